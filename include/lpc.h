@@ -1,0 +1,181 @@
+/*
+ * lpc.h -- C ABI of the MI355X (gfx950) implementation of the data-parallel
+ * hot path of LPC-SVRG / ALPC-SVRG (Yu, Wu, Huang, arXiv 1901.08924).
+ *
+ * The library solves the finite-sum composite problem of eq. (1),
+ *     min_w P(w) = (1/n) sum_i f_i(w) + h(w),   h(w) = lambda1*|w|_1 + (lambda2/2)*|w|^2,
+ * with N data-parallel workers simulated as shards on ONE GPU: the snapshot
+ * full-gradient pass (communication step 1), the workers' variance-reduced
+ * minibatch differences, the clipped low-precision stochastic quantizer with
+ * bit-packing, the receiver-side dequantize-and-average (communication step 2)
+ * and the proximal step, plus ALPC-SVRG's double sampling.
+ *
+ * Conventions
+ *  - Every pointer named "device" below is a DEVICE pointer owned by the caller
+ *    (for instance memory of a torch tensor); the library only borrows it.
+ *    Float/uint32 buffers must be 16-byte aligned, double buffers 8-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Every call except lpc_create, lpc_destroy, lpc_objective and
+ *    lpc_take_device_flags only enqueues work: no host synchronisation, no
+ *    allocation.  Scratch memory comes from the workspace given to lpc_create.
+ *  - Calls on one context must be issued on one stream at a time: they share
+ *    the context's scratch.
+ *  - Every call returns an lpc_status; nothing throws or aborts across the ABI.
+ *  - Results are a function of (problem, config, inputs, epoch, iter) only: all
+ *    randomness comes from a counter-based Philox4x32-10 stream with
+ *    key = (seed low, seed high) and counter = (index >> 2, tag << 24 | worker,
+ *    iter, epoch); word (index & 3) of the block belongs to `index`.
+ *  - d_pad = 32*ceil(d/32); a packed message has W = ceil(d/32)*bits 32-bit words.
+ */
+#ifndef LPC_H
+#define LPC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lpc_ctx lpc_ctx; /* opaque host object */
+
+typedef enum {
+  LPC_OK = 0,
+  LPC_EINVAL = -1,      /* a scalar argument or config field is out of range */
+  LPC_ENULL = -2,       /* a required pointer is NULL */
+  LPC_ESHAPE = -3,      /* sizes / leading dimensions / alignment do not fit */
+  LPC_EWORKSPACE = -4,  /* workspace missing, misaligned or too small */
+  LPC_ENONFINITE = -5,  /* a vector handed to the quantizer held NaN/Inf (see lpc_take_device_flags) */
+  LPC_EDEVICE = -6,     /* a HIP call failed */
+  LPC_EUNSUPPORTED = -7 /* valid in the paper, not built here */
+} lpc_status;
+
+typedef enum { LPC_LOSS_LOGISTIC = 0, LPC_LOSS_SQUARED = 1, LPC_LOSS_MLP_SOFTMAX = 2 } lpc_loss;
+typedef enum { LPC_ALGO_LPC = 0, LPC_ALGO_ALPC_SC = 1, LPC_ALGO_ALPC_GC = 2 } lpc_algo; /* Alg. 1 / 2 / 3 */
+typedef enum { LPC_CLIP_LAMBDA = 0, LPC_CLIP_CSIGMA = 1 } lpc_clip_mode;
+typedef enum { LPC_SCHEME_A = 0, LPC_SCHEME_B = 1, LPC_SCHEME_C = 2 } lpc_scheme; /* Sec. 4.2 (a), (b), (c) */
+typedef enum { LPC_BATCH_WORKER = 1, LPC_BATCH_SHARED = 2 } lpc_batch_kind;
+
+/* The data of eq. (1).  Exactly one of X (dense row-major, leading dimension
+ * ldx floats) or (row_ptr, col_idx, vals) (CSR, sorted int32 indices) is set.
+ * Losses: logistic f_i = log(1+exp(-y_i x_i'w)), y_i = +-1; squared
+ * f_i = (x_i'w - y_i)^2/2; MLP = ReLU multi-layer perceptron with softmax
+ * cross-entropy, X = inputs [n][mlp_dims[0]], y = class ids stored as floats,
+ * d = total parameter count, parameters laid out layer by layer as the weight
+ * matrix [in][out] row-major followed by the bias [out]. */
+typedef struct {
+  int64_t n, d;
+  int32_t loss;            /* lpc_loss */
+  const float *X;          /* device */
+  int64_t ldx;
+  const int32_t *row_ptr;  /* device, n+1 entries */
+  const int32_t *col_idx;  /* device */
+  const float *vals;       /* device */
+  int64_t nnz;
+  const float *y;          /* device, n entries */
+  const int32_t *mlp_dims; /* HOST, mlp_nlayers+1 entries (read during lpc_create only) */
+  int32_t mlp_nlayers;
+  float lambda1, lambda2;
+} lpc_problem;
+
+/* Inputs of Alg. 1 (S, m, lambda, B, eta) and Alg. 2/3 (tau1, tau2, alpha).
+ * bits in [2,16], or >= 32 for "quantization off" (u~ = plain average).
+ * clip: the paper's clipping parameter lambda in (0,1] (LPC_CLIP_LAMBDA), or c
+ * of the [-c*sigma, c*sigma] rule (LPC_CLIP_CSIGMA: lambda = min(1, c*sigma/|u|_inf),
+ * sigma = population standard deviation of the coordinates of u).
+ * ALPC fields left at 0 are derived: Theorem 3 for Alg. 2
+ * (tau1 = sqrt(m*sigma/(6L)) <= 1/2, alpha = 1/(6*tau1*L), tau2 = min(1/2, 5*zeta/3 + 1/(2B))),
+ * Alg. 3 step 3 for Alg. 3 (tau1 = 2/(s+4), alpha = 1/(6*L*tau1), or alpha/tau1 if alpha is given). */
+typedef struct {
+  int32_t algo;      /* lpc_algo */
+  int32_t N, B, m, bits;
+  int32_t clip_mode; /* lpc_clip_mode */
+  float clip;
+  int32_t scheme;    /* lpc_scheme; only (a) changes nothing on the wire format */
+  float eta, L, sigma, tau1, tau2, alpha;
+  uint64_t seed;
+  int64_t n_full;    /* rows used by the snapshot gradient (0 = all n) */
+} lpc_config;
+
+/* ---- context ------------------------------------------------------------ */
+
+/* Bytes of device scratch the context needs for this problem/config. */
+size_t lpc_workspace_bytes(const lpc_problem *problem, const lpc_config *config);
+
+/* Validates problem and config, copies both, and lays the scratch buffers out
+ * in `workspace` (device, 256-byte aligned, at least lpc_workspace_bytes long,
+ * owned by the caller and alive until lpc_destroy).  Clears the scratch's
+ * counters on the default stream and waits for that.  Errors: LPC_ENULL,
+ * LPC_EINVAL (bits = 1 divides by zero in eq. (3); N*B > n contradicts
+ * Theorem 1's N*B <= n), LPC_ESHAPE, LPC_EWORKSPACE, LPC_EUNSUPPORTED. */
+lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_config *config, void *workspace,
+                      size_t workspace_bytes);
+void lpc_destroy(lpc_ctx *ctx);
+const char *lpc_status_string(lpc_status s);
+int64_t lpc_d_pad(int64_t d);
+int64_t lpc_words_per_msg(int64_t d, int32_t bits);
+
+/* ---- the steps of Alg. 1 -------------------------------------------------- */
+
+/* Alg. 1 step 4 / Alg. 2 step 3 (communication step 1): the snapshot gradient
+ *   z = X w (n floats, may be NULL), mu = grad f(w) = (1/n) X' l'(z, y) (d floats),
+ *   f_out = f(w) (one device double, may be NULL),
+ * over the first n_full rows.  X is read from HBM once. */
+lpc_status lpc_full_grad(lpc_ctx *ctx, const float *w, float *mu, float *z, double *f_out, void *stream);
+
+/* Alg. 1 step 6 (Alg. 2 steps 7 and 11): for each worker i in
+ * [worker_begin, worker_end) draw B row indices uniformly, independently, with
+ * replacement from the worker's stream (kind = LPC_BATCH_WORKER) and form
+ *   u^i = (1/B) sum_{a in batch} [ grad f_a(w) - grad f_a(w_snap) ]
+ * into row i of U ([N][d_pad] floats, padding written as zero), with
+ * stats[i] = { |u^i|_inf, sum_j u_j, sum_j u_j^2, number of non-finite u_j }
+ * (4 doubles per worker, may be NULL).  kind = LPC_BATCH_SHARED draws the one
+ * batch J that ALPC-SVRG's double sampling shares between all workers and
+ * writes row worker_begin only.  z_snap (n floats: X w_snap, as produced by
+ * lpc_full_grad) lets each sampled row be read once; NULL recomputes it. */
+lpc_status lpc_worker_vr_grad(lpc_ctx *ctx, const float *w, const float *w_snap, const float *z_snap,
+                              uint32_t epoch, uint32_t iter, int32_t kind, int32_t worker_begin, int32_t worker_end,
+                              float *U, double *stats, void *stream);
+
+/* stats[v] (4 doubles, as above) for each of nvec rows of U ([nvec][d_pad]). */
+lpc_status lpc_vector_stats(lpc_ctx *ctx, const float *U, int32_t nvec, double *stats, void *stream);
+
+/* Alg. 1 step 7 (quantization step), Sec. 3.2 and eq. (3), all N workers:
+ *   delta_i = lambda*|u^i|_inf/(2^(bits-1)-1)  (or delta_in[i] if delta_in != NULL),
+ *   code_j  = stochastic rounding of u_j/delta_i onto {-2^(bits-1),...,2^(bits-1)-1}
+ *             after projection onto that range (gradient clipping),
+ * codes packed as bits-wide two's-complement fields of a little-endian bit
+ * stream (coordinate j in stream bits [j*bits, (j+1)*bits)), padding coded 0.
+ * stats may be NULL only if delta_in is given.  Outputs: packed [N][W],
+ * delta_out [N] (0 for an all-zero vector), n_clipped [N] (coordinates outside
+ * dom(delta,b): above lambda*|u|_inf or below -2^(bits-1)*delta; may be NULL). */
+lpc_status lpc_quantize_clip(lpc_ctx *ctx, const float *U, const double *stats, const float *delta_in,
+                             uint32_t epoch, uint32_t iter, uint32_t *packed, float *delta_out, uint32_t *n_clipped,
+                             void *stream);
+
+/* Communication step 2, scheme (a), eq. (4): u_avg_j = (1/N) sum_i delta_i*code^i_j,
+ * accumulated in worker order with one fused multiply-add per worker. */
+lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float *delta, float *u_avg, void *stream);
+
+/* Alg. 1 steps 9-10: v = u_avg + mu;  w <- prox_{step*h}(w - step*v), in place,
+ * prox(p)_j = sign(p_j)*max(|p_j| - step*lambda1, 0)/(1 + step*lambda2) (Sec. 3.3). */
+lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream);
+
+/* One epoch of Alg. 1 (algo LPC; y, z ignored) or of Alg. 2 / Alg. 3:
+ * snapshot gradient, m inner iterations, snapshot update.  w_snap: in x~^s, out
+ * x~^(s+1).  y, z: ALPC-SVRG's auxiliary iterates, in/out (d floats each; start
+ * them equal to x~^0).  epoch = s selects the random streams and Alg. 3's schedule. */
+lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, void *stream);
+
+/* P(w) of eq. (1) over all n rows, returned to the HOST (synchronises the stream). */
+lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void *stream);
+
+/* Reads and clears the context's device-side flags (synchronises the stream):
+ * returns LPC_ENONFINITE if any vector seen by the statistics pass since the last
+ * call held a NaN or Inf, else LPC_OK. */
+lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

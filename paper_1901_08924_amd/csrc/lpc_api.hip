@@ -1,0 +1,406 @@
+// C ABI of the library: argument checking, workspace layout, and the host-side
+// sequencing of the kernels for each call of include/lpc.h.  No arithmetic of
+// the method lives here except the scalar parameter rules of Alg. 2 / Alg. 3.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "lpc_internal.h"
+
+using namespace lpc;
+
+namespace {
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline lpc_status dev(hipError_t e) { return e == hipSuccess ? LPC_OK : LPC_EDEVICE; }
+inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
+
+bool is_csr(const lpc_problem &p) { return p.X == nullptr; }
+
+lpc_status check_problem(const lpc_problem *p) {
+  if (!p) return LPC_ENULL;
+  if (p->n <= 0 || p->d <= 0) return LPC_ESHAPE;
+  if (p->n > (int64_t)0xFFFFFFFFll) return LPC_ESHAPE;
+  if (!p->y) return LPC_ENULL;
+  if (p->loss != LPC_LOSS_LOGISTIC && p->loss != LPC_LOSS_SQUARED && p->loss != LPC_LOSS_MLP_SOFTMAX)
+    return LPC_EINVAL;
+  if (!(p->lambda1 >= 0.0f) || !(p->lambda2 >= 0.0f)) return LPC_EINVAL;
+  if (p->X) {
+    if (p->row_ptr || p->col_idx || p->vals) return LPC_EINVAL;  // exactly one storage format
+    if (!aligned(p->X, 4)) return LPC_ESHAPE;
+    if (p->loss != LPC_LOSS_MLP_SOFTMAX && p->ldx < p->d) return LPC_ESHAPE;
+  } else {
+    if (!p->row_ptr || !p->col_idx || !p->vals) return LPC_ENULL;
+    if (p->nnz < 0 || p->nnz > (int64_t)0x7FFFFFFFll) return LPC_ESHAPE;
+    if (p->loss == LPC_LOSS_MLP_SOFTMAX) return LPC_EINVAL;
+  }
+  if (p->loss == LPC_LOSS_MLP_SOFTMAX) {
+    if (!p->mlp_dims || p->mlp_nlayers < 1) return LPC_ENULL;
+    int64_t total = 0;
+    for (int32_t l = 0; l < p->mlp_nlayers; ++l) {
+      if (p->mlp_dims[l] <= 0 || p->mlp_dims[l + 1] <= 0) return LPC_ESHAPE;
+      total += (int64_t)p->mlp_dims[l] * p->mlp_dims[l + 1] + p->mlp_dims[l + 1];
+    }
+    if (total != p->d || p->ldx < p->mlp_dims[0]) return LPC_ESHAPE;
+  }
+  return LPC_OK;
+}
+
+lpc_status check_config(const lpc_problem *p, const lpc_config *c) {
+  if (!c) return LPC_ENULL;
+  if (c->algo != LPC_ALGO_LPC && c->algo != LPC_ALGO_ALPC_SC && c->algo != LPC_ALGO_ALPC_GC) return LPC_EINVAL;
+  if (c->N <= 0 || c->B <= 0 || c->m <= 0) return LPC_EINVAL;
+  if (c->N > 0xFFFFFE) return LPC_EINVAL;
+  // bits = 1 makes the denominator 2^(b-1)-1 of eq. (3) zero
+  if (c->bits < 2 || (c->bits > 16 && c->bits < 32)) return LPC_EINVAL;
+  if (c->clip_mode != LPC_CLIP_LAMBDA && c->clip_mode != LPC_CLIP_CSIGMA) return LPC_EINVAL;
+  if (!(c->clip > 0.0f)) return LPC_EINVAL;
+  if (c->clip_mode == LPC_CLIP_LAMBDA && c->clip > 1.0f) return LPC_EINVAL;  // lambda in (0,1]
+  if (c->scheme != LPC_SCHEME_A && c->scheme != LPC_SCHEME_B && c->scheme != LPC_SCHEME_C) return LPC_EINVAL;
+  if (!(c->eta > 0.0f)) return LPC_EINVAL;
+  if ((int64_t)c->N * c->B > p->n) return LPC_EINVAL;  // Theorem 1 assumes N*B <= n
+  if (c->n_full < 0 || c->n_full > p->n) return LPC_EINVAL;
+  if (c->algo != LPC_ALGO_LPC && !(c->L > 0.0f)) return LPC_EINVAL;
+  if (c->tau1 < 0.0f || c->tau2 < 0.0f || c->alpha < 0.0f || c->sigma < 0.0f) return LPC_EINVAL;
+  if (c->tau1 + c->tau2 > 1.0f) return LPC_EINVAL;
+  return LPC_OK;
+}
+
+// Computes sizes; when base != nullptr also assigns the scratch pointers.
+size_t layout(lpc_ctx *c, char *base) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) -> char * {
+    char *p = base ? base + off : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  };
+  const int64_t N1 = (int64_t)c->cfg.N + 1;
+  Scratch &s = c->s;
+  s.part = (float *)take(c->part_floats * sizeof(float));
+  s.part_loss = (double *)take((size_t)c->full_grad_wgs * sizeof(double));
+  s.stat_part = (double *)take((size_t)N1 * c->stat_slots * 4 * sizeof(double));
+  s.stats = (double *)take((size_t)N1 * 4 * sizeof(double));
+  s.qparams = (QParams *)take((size_t)N1 * sizeof(QParams));
+  s.counters = (uint32_t *)take((size_t)N1 * sizeof(uint32_t));
+  s.flags = (uint32_t *)take(4 * sizeof(uint32_t));
+  s.n_clipped = (uint32_t *)take((size_t)N1 * sizeof(uint32_t));
+  s.z_snap = (float *)take((size_t)c->n * sizeof(float));
+  s.mu = (float *)take((size_t)c->d * sizeof(float));
+  s.w = (float *)take((size_t)c->d * sizeof(float));
+  s.U = (float *)take((size_t)N1 * c->d_pad * sizeof(float));
+  s.packed = (uint32_t *)take((size_t)c->cfg.N * (c->quant ? c->W : 1) * sizeof(uint32_t));
+  s.delta = (float *)take((size_t)N1 * sizeof(float));
+  s.u_avg = (float *)take((size_t)c->d * sizeof(float));
+  s.ysum = (float *)take((size_t)c->d * sizeof(float));
+  s.f_scalar = (double *)take(sizeof(double));
+  return off;
+}
+
+lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
+  lpc_status st = check_problem(p);
+  if (st != LPC_OK) return st;
+  st = check_config(p, cfg);
+  if (st != LPC_OK) return st;
+  c->prob = *p;
+  c->cfg = *cfg;
+  if (p->loss == LPC_LOSS_MLP_SOFTMAX) {
+    c->mlp_dims.assign(p->mlp_dims, p->mlp_dims + p->mlp_nlayers + 1);
+    c->prob.mlp_dims = c->mlp_dims.data();
+  }
+  c->n = p->n;
+  c->d = p->d;
+  c->d_pad = lpc_d_pad(p->d);
+  c->quant = cfg->bits < 32;
+  c->W = c->quant ? lpc_words_per_msg(p->d, cfg->bits) : 0;
+  c->n_full = cfg->n_full > 0 ? cfg->n_full : p->n;
+  if (cfg->scheme != LPC_SCHEME_A) return LPC_EUNSUPPORTED;
+  // The gradient passes exist for dense linear models whose rows fit the register tiling; for any
+  // other problem the context still serves the quantizer / receiver / prox calls and the gradient
+  // calls answer LPC_EUNSUPPORTED.
+  c->grad_ok = p->loss != LPC_LOSS_MLP_SOFTMAX && !is_csr(*p) && dense_supported(p->d, p->ldx, p->X);
+  if (c->grad_ok) {
+    c->full_grad_wgs = dense_full_grad_wgs(c->n, c->d);
+    c->vr_parts = dense_vr_parts(c->d, cfg->B);
+    const size_t a1 = (size_t)c->full_grad_wgs * c->d;
+    const size_t a2 = (size_t)(cfg->N + 1) * c->vr_parts * c->d;
+    c->part_floats = a1 > a2 ? a1 : a2;
+  } else {
+    c->full_grad_wgs = 1;
+    c->vr_parts = 1;
+    c->part_floats = 64;
+  }
+  c->stat_slots = (int32_t)((c->d_pad + 63) / 64);
+  return LPC_OK;
+}
+
+StreamKey key_of(const lpc_ctx *c, uint32_t epoch, uint32_t iter) {
+  StreamKey k;
+  k.seed_lo = (uint32_t)(c->cfg.seed & 0xFFFFFFFFu);
+  k.seed_hi = (uint32_t)(c->cfg.seed >> 32);
+  k.epoch = epoch;
+  k.iter = iter;
+  return k;
+}
+
+// Alg. 1 step 4 into (mu, z), all on `st`
+lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, double *f_out, int64_t n_rows,
+                          hipStream_t st) {
+  if (!c->grad_ok) return LPC_EUNSUPPORTED;
+  hipError_t e = launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
+  if (e != hipSuccess) return LPC_EDEVICE;
+  e = launch_finish_full_grad(c, c->full_grad_wgs, (float)(1.0 / (double)n_rows), mu, f_out, f_out != nullptr, st);
+  return dev(e);
+}
+
+// Alg. 1 step 6 for workers [wb, we) (or the shared batch): U rows and statistics
+lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap, StreamKey key,
+                        uint32_t tag, int32_t wb, int32_t we, float *U_row0, double *stats_row0, bool want_stats,
+                        hipStream_t st) {
+  if (!c->grad_ok) return LPC_EUNSUPPORTED;
+  hipError_t e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
+  if (e != hipSuccess) return LPC_EDEVICE;
+  const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
+  e = launch_reduce_parts(c, c->s.part, c->vr_parts, (float)(1.0 / (double)c->cfg.B), U_row0, c->d_pad, slot0,
+                          we - wb, want_stats, stats_row0, st);
+  return dev(e);
+}
+
+struct AlpcParams {
+  float tau1, tau2, alpha, theta;
+};
+
+// Theorem 3 (Alg. 2) and Alg. 3 step 3; non-zero config fields override the rules.
+lpc_status alpc_params(const lpc_ctx *c, uint32_t epoch, AlpcParams *out) {
+  const lpc_config &g = c->cfg;
+  const double L = (double)g.L;
+  const double sigma = g.sigma > 0.0f ? (double)g.sigma : (double)c->prob.lambda2;
+  double zeta = 1.0 / ((double)g.N * (double)g.B);
+  if (c->quant) {
+    const double lam = g.clip_mode == LPC_CLIP_LAMBDA ? (double)g.clip : 1.0;
+    const double levels = (double)((1 << (g.bits - 1)) - 1);
+    zeta += (double)c->d * lam * lam / (4.0 * levels * levels);
+  }
+  double t2 = g.tau2 > 0.0f ? (double)g.tau2 : 5.0 * zeta / 3.0 + 1.0 / (2.0 * (double)g.B);
+  if (t2 > 0.5) t2 = 0.5;
+  double t1, a, th;
+  if (g.algo == LPC_ALGO_ALPC_SC) {
+    t1 = g.tau1 > 0.0f ? (double)g.tau1 : std::sqrt((double)g.m * sigma / (6.0 * L));
+    if (t1 > 0.5) t1 = 0.5;
+    if (!(t1 > 0.0)) return LPC_EINVAL;
+    a = g.alpha > 0.0f ? (double)g.alpha : 1.0 / (6.0 * t1 * L);
+    th = 1.0 + a * sigma;
+  } else {
+    t1 = 2.0 / ((double)epoch + 4.0);
+    a = g.alpha > 0.0f ? (double)g.alpha / t1 : 1.0 / (6.0 * L * t1);
+    th = 1.0;
+  }
+  out->tau1 = (float)t1; out->tau2 = (float)t2; out->alpha = (float)a; out->theta = (float)th;
+  return LPC_OK;
+}
+
+#define LPC_TRY(expr)                 \
+  do {                                \
+    lpc_status _s = (expr);           \
+    if (_s != LPC_OK) return _s;      \
+  } while (0)
+#define LPC_TRY_HIP(expr)                       \
+  do {                                          \
+    if ((expr) != hipSuccess) return LPC_EDEVICE; \
+  } while (0)
+
+// communication step 2 of one inner iteration followed by the update of Alg. 1
+lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st) {
+  Scratch &s = c->s;
+  if (c->quant) {
+    LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+    LPC_TRY_HIP(launch_dequantize_prox(c, s.packed, s.delta, s.mu, c->cfg.eta, w, nullptr, st));
+  } else {
+    LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
+    LPC_TRY_HIP(launch_prox(c, w, s.u_avg, s.mu, c->cfg.eta, st));
+  }
+  return LPC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t lpc_d_pad(int64_t d) { return (d + 31) / 32 * 32; }
+int64_t lpc_words_per_msg(int64_t d, int32_t bits) { return (d + 31) / 32 * (int64_t)bits; }
+
+const char *lpc_status_string(lpc_status s) {
+  switch (s) {
+    case LPC_OK: return "ok";
+    case LPC_EINVAL: return "invalid argument";
+    case LPC_ENULL: return "null pointer";
+    case LPC_ESHAPE: return "shape, leading dimension or alignment mismatch";
+    case LPC_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case LPC_ENONFINITE: return "non-finite value in a vector handed to the quantizer";
+    case LPC_EDEVICE: return "HIP call failed";
+    case LPC_EUNSUPPORTED: return "not supported by this build";
+  }
+  return "unknown status";
+}
+
+size_t lpc_workspace_bytes(const lpc_problem *problem, const lpc_config *config) {
+  lpc_ctx tmp{};
+  if (fill_ctx(&tmp, problem, config) != LPC_OK) return 0;
+  return layout(&tmp, nullptr);
+}
+
+lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_config *config, void *workspace,
+                      size_t workspace_bytes) {
+  if (!ctx_out) return LPC_ENULL;
+  *ctx_out = nullptr;
+  lpc_ctx *c = new (std::nothrow) lpc_ctx{};
+  if (!c) return LPC_EDEVICE;
+  lpc_status st = fill_ctx(c, problem, config);
+  if (st != LPC_OK) { delete c; return st; }
+  const size_t need = layout(c, nullptr);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < need) { delete c; return LPC_EWORKSPACE; }
+  layout(c, (char *)workspace);
+  c->workspace = workspace;
+  c->workspace_bytes = workspace_bytes;
+  // arrival counters, flags and clip counts start at zero (contiguous, see layout())
+  const size_t words = ((char *)c->s.z_snap - (char *)c->s.counters) / sizeof(uint32_t);
+  if (launch_fill_u32(c->s.counters, 0u, (int64_t)words, nullptr) != hipSuccess ||
+      hipStreamSynchronize(nullptr) != hipSuccess) {
+    delete c;
+    return LPC_EDEVICE;
+  }
+  *ctx_out = c;
+  return LPC_OK;
+}
+
+void lpc_destroy(lpc_ctx *ctx) { delete ctx; }
+
+lpc_status lpc_full_grad(lpc_ctx *ctx, const float *w, float *mu, float *z, double *f_out, void *stream) {
+  if (!ctx || !w || !mu) return LPC_ENULL;
+  if (!aligned(w, 16) || !aligned(mu, 16) || (z && !aligned(z, 4)) || (f_out && !aligned(f_out, 8)))
+    return LPC_ESHAPE;
+  return full_grad_impl(ctx, w, mu, z, f_out, ctx->n_full, as_stream(stream));
+}
+
+lpc_status lpc_worker_vr_grad(lpc_ctx *ctx, const float *w, const float *w_snap, const float *z_snap,
+                              uint32_t epoch, uint32_t iter, int32_t kind, int32_t worker_begin, int32_t worker_end,
+                              float *U, double *stats, void *stream) {
+  if (!ctx || !w || !w_snap || !U) return LPC_ENULL;
+  if (kind != LPC_BATCH_WORKER && kind != LPC_BATCH_SHARED) return LPC_EINVAL;
+  if (worker_begin < 0 || worker_end <= worker_begin || worker_end > ctx->cfg.N) return LPC_EINVAL;
+  if (!aligned(w, 16) || !aligned(w_snap, 16) || !aligned(U, 16) || (stats && !aligned(stats, 8)))
+    return LPC_ESHAPE;
+  const uint32_t tag = kind == LPC_BATCH_SHARED ? kTagShared : kTagBatch;
+  const int32_t we = kind == LPC_BATCH_SHARED ? worker_begin + 1 : worker_end;
+  return vr_grad_impl(ctx, w, w_snap, z_snap, key_of(ctx, epoch, iter), tag, worker_begin, we,
+                      U + (int64_t)worker_begin * ctx->d_pad, stats ? stats + 4 * (int64_t)worker_begin : nullptr,
+                      true, as_stream(stream));
+}
+
+lpc_status lpc_vector_stats(lpc_ctx *ctx, const float *U, int32_t nvec, double *stats, void *stream) {
+  if (!ctx || !U || !stats) return LPC_ENULL;
+  if (nvec <= 0 || nvec > ctx->cfg.N + 1) return LPC_EINVAL;
+  if (!aligned(U, 16) || !aligned(stats, 8)) return LPC_ESHAPE;
+  return dev(launch_vector_stats(ctx, U, ctx->d_pad, 0, nvec, stats, as_stream(stream)));
+}
+
+lpc_status lpc_quantize_clip(lpc_ctx *ctx, const float *U, const double *stats, const float *delta_in,
+                             uint32_t epoch, uint32_t iter, uint32_t *packed, float *delta_out, uint32_t *n_clipped,
+                             void *stream) {
+  if (!ctx || !U || !packed || !delta_out) return LPC_ENULL;
+  if (!stats && !delta_in) return LPC_ENULL;
+  if (!ctx->quant) return LPC_EINVAL;
+  if (!aligned(U, 16) || !aligned(packed, 16) || (stats && !aligned(stats, 8))) return LPC_ESHAPE;
+  hipStream_t st = as_stream(stream);
+  LPC_TRY_HIP(launch_prepare_qparams(ctx, stats, delta_in, ctx->cfg.N, st));
+  LPC_TRY_HIP(launch_quantize(ctx, U, key_of(ctx, epoch, iter), packed, delta_out, ctx->s.n_clipped, st));
+  if (n_clipped)
+    LPC_TRY_HIP(hipMemcpyAsync(n_clipped, ctx->s.n_clipped, sizeof(uint32_t) * (size_t)ctx->cfg.N,
+                               hipMemcpyDeviceToDevice, st));
+  return LPC_OK;
+}
+
+lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float *delta, float *u_avg, void *stream) {
+  if (!ctx || !packed || !delta || !u_avg) return LPC_ENULL;
+  if (!ctx->quant) return LPC_EINVAL;
+  if (!aligned(packed, 16) || !aligned(u_avg, 16)) return LPC_ESHAPE;
+  return dev(launch_dequantize_avg(ctx, packed, delta, u_avg, as_stream(stream)));
+}
+
+lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream) {
+  if (!ctx || !w || !u_avg || !mu) return LPC_ENULL;
+  if (!(step > 0.0f)) return LPC_EINVAL;
+  return dev(launch_prox(ctx, w, u_avg, mu, step, as_stream(stream)));
+}
+
+lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, void *stream) {
+  if (!ctx || !w_snap) return LPC_ENULL;
+  if (!aligned(w_snap, 16)) return LPC_ESHAPE;
+  lpc_ctx *c = ctx;
+  Scratch &s = c->s;
+  hipStream_t st = as_stream(stream);
+  const lpc_config &g = c->cfg;
+  // communication step 1
+  LPC_TRY(full_grad_impl(c, w_snap, s.mu, s.z_snap, nullptr, c->n_full, st));
+  const float *zs = (c->n_full == c->n) ? s.z_snap : nullptr;  // margins cached only when every row was visited
+  if (g.algo == LPC_ALGO_LPC) {
+    LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
+    for (int32_t t = 0; t < g.m; ++t) {
+      const StreamKey key = key_of(c, epoch, (uint32_t)t);
+      LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, c->quant, st));
+      LPC_TRY(exchange_and_prox(c, key, s.w, st));
+    }
+    LPC_TRY_HIP(launch_copy(w_snap, s.w, c->d, st));  // x~ <- x_m
+    return LPC_OK;
+  }
+  if (!y || !z) return LPC_ENULL;
+  if (!aligned(y, 16) || !aligned(z, 16)) return LPC_ESHAPE;
+  AlpcParams ap;
+  LPC_TRY(alpc_params(c, epoch, &ap));
+  const float step_y = (float)(1.0 / (4.0 * (double)g.L));
+  double weight = 1.0, wsum = 0.0;
+  float *u_hat = s.U + (int64_t)g.N * c->d_pad;
+  for (int32_t t = 0; t < g.m; ++t) {
+    const StreamKey key = key_of(c, epoch, (uint32_t)t);
+    LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
+    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, c->quant, st));
+    if (c->quant) {
+      LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+      LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
+    } else {
+      LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
+    }
+    // double sampling: the shared batch J, full precision
+    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagShared, 0, 1, u_hat, nullptr, false, st));
+    LPC_TRY_HIP(launch_alpc_update(c, s.w, s.u_avg, u_hat, s.mu, step_y, ap.alpha, (float)weight, t == 0, y, z,
+                                   s.ysum, st));
+    wsum += weight;
+    weight *= (double)ap.theta;
+  }
+  LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
+  return LPC_OK;
+}
+
+lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void *stream) {
+  if (!ctx || !w || !P_out_host) return LPC_ENULL;
+  hipStream_t st = as_stream(stream);
+  LPC_TRY(full_grad_impl(ctx, w, nullptr, nullptr, ctx->s.f_scalar, ctx->n, st));
+  LPC_TRY_HIP(launch_objective_reg(ctx, w, ctx->s.f_scalar, st));
+  LPC_TRY_HIP(hipMemcpyAsync(P_out_host, ctx->s.f_scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  LPC_TRY_HIP(hipStreamSynchronize(st));
+  return LPC_OK;
+}
+
+lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream) {
+  if (!ctx) return LPC_ENULL;
+  hipStream_t st = as_stream(stream);
+  uint32_t flags[4] = {0, 0, 0, 0};
+  LPC_TRY_HIP(hipMemcpyAsync(flags, ctx->s.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
+  LPC_TRY_HIP(hipStreamSynchronize(st));
+  LPC_TRY_HIP(launch_fill_u32(ctx->s.flags, 0u, 4, st));
+  return (flags[0] & 1u) ? LPC_ENONFINITE : LPC_OK;
+}
+
+}  // extern "C"

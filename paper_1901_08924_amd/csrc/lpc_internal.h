@@ -1,0 +1,123 @@
+// Internal declarations shared by the translation units of the HIP library.
+// Nothing here is part of the public ABI (include/lpc.h is).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "lpc.h"
+
+namespace lpc {
+
+constexpr uint32_t kTagQuant = 0, kTagBatch = 1, kTagShared = 2, kTagRequant = 3;
+constexpr uint32_t kSharedWorkerField = 0xFFFFFFu;
+
+// Per-vector quantizer parameters, produced on the device right after the
+// statistics of the vector are known (eq. (3)).
+struct QParams {
+  float delta;     // scale factor; 0 for an all-zero vector
+  float rdelta;    // float(1/delta); 0 when delta == 0
+  float thresh;    // positive clip threshold lambda*|u|_inf
+  float neg_edge;  // smallest codebook value -2^(b-1)*delta
+};
+
+struct StreamKey {
+  uint32_t seed_lo, seed_hi, epoch, iter;
+};
+
+// ---- device scratch owned by a context (all pointers into the workspace) ----
+struct Scratch {
+  float *part;          // partial gradient rows
+  double *part_loss;    // per-workgroup loss partials
+  double *stat_part;    // [(N+1)][stat_slots][4]
+  double *stats;        // [(N+1)][4]
+  QParams *qparams;     // [(N+1)]
+  uint32_t *counters;   // [(N+1)] arrival counters of the "last block finishes" reductions
+  uint32_t *flags;      // [4]: [0] = a non-finite value was seen
+  uint32_t *n_clipped;  // [N]
+  float *z_snap;        // [n]
+  float *mu;            // [d]
+  float *w;             // [d]   inner iterate x_t (Alg. 1) / x_{k+1} (Alg. 2, 3)
+  float *U;             // [(N+1)][d_pad]; row N holds the shared-batch difference
+  uint32_t *packed;     // [N][W]
+  float *delta;         // [N]
+  float *u_avg;         // [d]
+  float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
+  double *f_scalar;     // [1]
+};
+
+}  // namespace lpc
+
+struct lpc_ctx {
+  lpc_problem prob;
+  lpc_config cfg;
+  std::vector<int32_t> mlp_dims;
+  int64_t n, d, d_pad, W, n_full;
+  bool quant;             // bits < 32
+  bool grad_ok;           // the gradient passes are built for this problem
+  int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
+  int32_t vr_parts;       // partial rows per worker written by the worker pass
+  int32_t stat_slots;     // statistic partials per vector
+  size_t part_floats;
+  void *workspace;
+  size_t workspace_bytes;
+  lpc::Scratch s;
+};
+
+namespace lpc {
+
+// ---- launchers (each validates nothing: the ABI layer has done that) ----
+
+// Dense GLM passes (lpc_dense.hip)
+bool dense_supported(int64_t d, int64_t ldx, const void *X);
+int dense_full_grad_wgs(int64_t n, int64_t d);
+int dense_vr_parts(int64_t d, int32_t B);
+hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,
+                                  hipStream_t st);
+hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
+                                StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end,
+                                hipStream_t st);
+
+// CSR GLM passes (lpc_csr.hip)
+hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
+                                hipStream_t st);
+hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
+                              StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end, float *U,
+                              hipStream_t st);
+
+// Reductions, statistics, quantizer, receiver, prox (lpc_quant.hip)
+// out[v][0..d_pad) = scale * sum_p part[(v*parts + p)*d + j] (zero beyond d), then statistics of each
+// row and its quantizer parameters.  out / stats_out point at the first row of the launch; vec_begin
+// selects the scratch slots.
+hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t parts, float scale, float *out,
+                               int64_t ld_out, int32_t vec_begin, int32_t nvec, bool want_stats, double *stats_out,
+                               hipStream_t st);
+hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
+                               double *stats_out, hipStream_t st);
+hipError_t launch_prepare_qparams(const lpc_ctx *c, const double *stats, const float *delta_in, int32_t nvec,
+                                  hipStream_t st);
+hipError_t launch_quantize(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
+                           uint32_t *n_clipped, hipStream_t st);
+hipError_t launch_dequantize_avg(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg,
+                                 hipStream_t st);
+hipError_t launch_plain_avg(const lpc_ctx *c, const float *U, float *u_avg, hipStream_t st);
+hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const float *mu, float step, hipStream_t st);
+// fused receiver + prox of Alg. 1: w <- prox(w - eta*(avg + mu)); optionally also stores the average
+hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, const float *delta, const float *mu,
+                                  float step, float *w, float *u_avg_out, hipStream_t st);
+hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, float scale, float *mu, double *f_out,
+                                   bool want_loss, hipStream_t st);
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t st);
+hipError_t launch_fill_u32(uint32_t *dst, uint32_t v, int64_t n, hipStream_t st);
+// ALPC-SVRG element-wise steps (Alg. 2 steps 6, 13-15)
+hipError_t launch_alpc_couple(const lpc_ctx *c, const float *z, const float *w_snap, const float *y, float tau1,
+                              float tau2, float *x, hipStream_t st);
+hipError_t launch_alpc_update(const lpc_ctx *c, const float *x, const float *u_avg, const float *u_hat,
+                              const float *mu, float step_y, float alpha, float weight, bool first, float *y,
+                              float *z, float *ysum, hipStream_t st);
+hipError_t launch_scale_to(const lpc_ctx *c, const float *src, float scale, float *dst, hipStream_t st);
+hipError_t launch_objective_reg(const lpc_ctx *c, const float *w, double *acc, hipStream_t st);
+
+}  // namespace lpc

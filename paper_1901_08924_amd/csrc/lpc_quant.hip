@@ -1,0 +1,674 @@
+// Quantizer, message format, receiver-side averaging, proximal step and the
+// small reductions around them (gfx950).
+//
+// This translation unit is compiled with floating-point contraction OFF: the
+// quantizer's float arithmetic decides integer codes and must be the written
+// sequence of IEEE operations (Sec. 3.2, rules (1) and (2); eq. (3)).
+//
+// Data layout.  A worker's vector u (d_pad floats) is cut into segments of 32
+// consecutive coordinates; segment s becomes `bits` consecutive 32-bit words of
+// the message (coordinate j occupies bits [j*bits, (j+1)*bits) of a
+// little-endian bit stream, so a segment never straddles its words).  One
+// thread owns one segment: it needs 8 Philox blocks and emits whole words, so
+// no cross-lane traffic is needed for packing.  HBM accesses stay coalesced by
+// staging a tile of 256 segments through LDS with a row pitch of 36 floats
+// (pitch mod 32 banks = 4, so eight consecutive lanes reading 16 bytes each hit
+// disjoint banks).
+#include <hip/hip_runtime.h>
+
+#include "lpc_device.h"
+#include "lpc_internal.h"
+
+namespace lpc {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSegFloats = 32;
+constexpr int kPitch = 36;
+constexpr int kTileFloats = kThreads * kSegFloats;  // 8192 coordinates per workgroup
+
+struct QuantSpec {
+  int32_t bits;
+  int32_t clip_mode;
+  float clip;
+  int32_t enabled;
+};
+
+struct StatSinks {
+  double *stat_part;
+  double *stats;
+  QParams *qparams;
+  uint32_t *counters;
+  uint32_t *flags;
+  uint32_t *n_clipped;
+  double *stats_out;  // caller's buffer or nullptr
+  int32_t stat_slots;
+};
+
+// eq. (3): delta = lambda*|u|_inf/(2^(b-1)-1); in c*sigma mode
+// lambda = min(1, c*sigma/|u|_inf) with sigma the population standard deviation.
+__device__ inline QParams make_qparams(const QuantSpec &qs, double amax_d, double sum, double sumsq, int64_t d) {
+  QParams q;
+  const float amax = (float)amax_d;
+  float lambda;
+  if (qs.clip_mode == LPC_CLIP_LAMBDA) {
+    lambda = qs.clip;
+  } else if (amax > 0.0f) {
+    const double mean = sum / (double)d;
+    double var = sumsq / (double)d - mean * mean;
+    if (var < 0.0) var = 0.0;
+    const double ratio = (double)qs.clip * sqrt(var) / (double)amax;
+    lambda = ratio < 1.0 ? (float)ratio : 1.0f;
+  } else {
+    lambda = 1.0f;
+  }
+  const float thresh = lambda * amax;
+  const float levels = (float)((1 << (qs.bits - 1)) - 1);
+  const float delta = thresh / levels;
+  const float rdelta = (float)(1.0 / (double)delta);
+  const bool live = delta > 0.0f && isfinite(rdelta);
+  q.delta = live ? delta : 0.0f;
+  q.rdelta = live ? rdelta : 0.0f;
+  q.thresh = thresh;
+  q.neg_edge = -(float)(1 << (qs.bits - 1)) * delta;
+  return q;
+}
+
+__device__ inline QParams qparams_from_delta(const QuantSpec &qs, float delta) {
+  QParams q;
+  const float rdelta = (float)(1.0 / (double)delta);
+  const bool live = delta > 0.0f && isfinite(rdelta);
+  q.delta = live ? delta : 0.0f;
+  q.rdelta = live ? rdelta : 0.0f;
+  q.thresh = delta * (float)((1 << (qs.bits - 1)) - 1);
+  q.neg_edge = -(float)(1 << (qs.bits - 1)) * delta;
+  return q;
+}
+
+// Wave 0 of a workgroup publishes the statistics of its slice; the last
+// workgroup to arrive for a vector folds all slices in a fixed order, so the
+// result does not depend on scheduling.
+__device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, int32_t vec, int32_t rel, int32_t slot,
+                                     int32_t nslots, int64_t d, double amax, double sum, double sumsq, double bad,
+                                     bool *s_last) {
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    amax = wave_max(amax);
+    sum = wave_sum(sum);
+    sumsq = wave_sum(sumsq);
+    bad = wave_sum(bad);
+    if (tid == 0) {
+      double *p = sk.stat_part + ((int64_t)vec * sk.stat_slots + slot) * 4;
+      p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
+      __threadfence();
+      const uint32_t prev = atomicAdd(&sk.counters[vec], 1u);
+      *s_last = (prev == (uint32_t)nslots - 1u);
+    }
+  }
+  __syncthreads();
+  if (*s_last && tid < 64) {
+    __threadfence();
+    const volatile double *p = sk.stat_part + (int64_t)vec * sk.stat_slots * 4;
+    double a = 0.0, s = 0.0, s2 = 0.0, b = 0.0;
+    for (int32_t k = tid; k < nslots; k += 64) {
+      a = fmax(a, p[k * 4 + 0]);
+      s += p[k * 4 + 1];
+      s2 += p[k * 4 + 2];
+      b += p[k * 4 + 3];
+    }
+    a = wave_max(a); s = wave_sum(s); s2 = wave_sum(s2); b = wave_sum(b);
+    if (tid == 0) {
+      double *o = sk.stats + (int64_t)vec * 4;
+      o[0] = a; o[1] = s; o[2] = s2; o[3] = b;
+      if (sk.stats_out) {
+        double *u = sk.stats_out + (int64_t)rel * 4;
+        u[0] = a; u[1] = s; u[2] = s2; u[3] = b;
+      }
+      if (b > 0.0) atomicOr(&sk.flags[0], 1u);
+      if (qs.enabled) {
+        sk.qparams[vec] = make_qparams(qs, a, s, s2, d);
+        sk.n_clipped[vec] = 0u;
+      }
+      sk.counters[vec] = 0u;
+    }
+  }
+}
+
+// out[v][j] = scale * sum_p part[(v*parts + p)*d + j], j < d; zero for d <= j < d_pad.
+// 64 columns per workgroup; the 4 waves take interleaved parts and are combined in wave order.
+__global__ __launch_bounds__(kThreads) void reduce_parts_kernel(const float *__restrict__ part, int32_t parts,
+                                                                int64_t d, int64_t d_pad, float scale,
+                                                                float *__restrict__ out, int64_t ld_out,
+                                                                int32_t vec_begin, int32_t want_stats, StatSinks sk,
+                                                                QuantSpec qs) {
+  __shared__ float red[4][64];
+  __shared__ bool s_last;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int32_t vec = blockIdx.y;
+  const int64_t col = (int64_t)blockIdx.x * 64 + lane;
+  float acc = 0.0f;
+  if (col < d) {
+    const float *src = part + (int64_t)vec * parts * d + col;
+    for (int32_t p = wv; p < parts; p += 4) acc += src[(int64_t)p * d];
+  }
+  red[wv][lane] = acc;
+  __syncthreads();
+  double amax = 0.0, sum = 0.0, sumsq = 0.0, bad = 0.0;
+  if (wv == 0) {
+    float v = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    v = v * scale;
+    if (col >= d) v = 0.0f;
+    if (col < d_pad) out[(int64_t)vec * ld_out + col] = v;
+    if (isfinite(v)) {
+      amax = fabs((double)v); sum = (double)v; sumsq = (double)v * (double)v;
+    } else {
+      bad = 1.0;
+    }
+  }
+  if (want_stats)
+    publish_stats(sk, qs, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+}
+
+// statistics of rows of an existing matrix; each workgroup takes `chunk` columns
+__global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__restrict__ U, int64_t ld, int64_t d,
+                                                                int64_t chunk, int32_t vec_begin, StatSinks sk,
+                                                                QuantSpec qs) {
+  __shared__ double red[4][4];
+  __shared__ bool s_last;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int32_t vec = blockIdx.y;
+  const float *u = U + (int64_t)vec * ld;
+  const int64_t lo = (int64_t)blockIdx.x * chunk;
+  const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
+  double amax = 0.0, sum = 0.0, sumsq = 0.0, bad = 0.0;
+  for (int64_t j = lo + tid; j < hi; j += kThreads) {
+    const float v = u[j];
+    if (isfinite(v)) {
+      amax = fmax(amax, fabs((double)v)); sum += (double)v; sumsq += (double)v * (double)v;
+    } else {
+      bad += 1.0;
+    }
+  }
+  amax = wave_max(amax); sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
+  if (lane == 0) { red[wv][0] = amax; red[wv][1] = sum; red[wv][2] = sumsq; red[wv][3] = bad; }
+  __syncthreads();
+  amax = 0.0; sum = 0.0; sumsq = 0.0; bad = 0.0;
+  if (tid == 0) {
+    for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
+  }
+  publish_stats(sk, qs, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+}
+
+__global__ void prepare_qparams_kernel(const double *stats, const float *delta_in, int32_t nvec, int64_t d,
+                                       QuantSpec qs, QParams *qp, uint32_t *n_clipped, uint32_t *flags) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= nvec) return;
+  if (delta_in) {
+    qp[v] = qparams_from_delta(qs, delta_in[v]);
+  } else {
+    const double *s = stats + (int64_t)v * 4;
+    qp[v] = make_qparams(qs, s[0], s[1], s[2], d);
+  }
+  if (stats && stats[(int64_t)v * 4 + 3] > 0.0) atomicOr(&flags[0], 1u);
+  n_clipped[v] = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// Quantize + pack.  grid = (tiles of 8192 coordinates, N workers).
+template <int B>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad,
+                                                            const QParams *__restrict__ qp, StreamKey key,
+                                                            uint32_t *__restrict__ packed, int64_t W,
+                                                            float *__restrict__ delta_out,
+                                                            uint32_t *__restrict__ n_clipped) {
+  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
+  const int tid = threadIdx.x;
+  const uint32_t worker = blockIdx.y;
+  const int64_t tile_base = (int64_t)blockIdx.x * kTileFloats;
+  const float *u = U + (int64_t)worker * d_pad;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int e = r * kThreads + tid;
+    const int64_t j = tile_base + (int64_t)e * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < d_pad) {
+      v = *reinterpret_cast<const float4 *>(u + j);
+      if (j + 3 >= d) {  // the zero padding of the last segment carries code 0 whatever the buffer holds
+        if (j + 0 >= d) v.x = 0.f;
+        if (j + 1 >= d) v.y = 0.f;
+        if (j + 2 >= d) v.z = 0.f;
+        v.w = 0.f;
+      }
+    }
+    *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) = v;
+  }
+  __syncthreads();
+  const QParams q = qp[worker];
+  if (blockIdx.x == 0 && tid == 0) delta_out[worker] = q.delta;
+  const int64_t seg = tile_base / kSegFloats + tid;
+  const bool active = seg * kSegFloats < d_pad;
+  uint32_t clipped = 0;
+  if (active) {
+    const float hi = (float)((1 << (B - 1)) - 1);
+    const float lo = -(float)(1 << (B - 1));
+    constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
+    const bool count = q.delta > 0.0f;
+    uint32_t words[B];
+    uint64_t bitbuf = 0;
+    int nb = 0, wi = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float4 v4 = *reinterpret_cast<const float4 *>(&tile[tid * kPitch + k * 4]);
+      const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
+      float base[4], frac[4];
+      bool any = false;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float s = vals[t] * q.rdelta;        // position on the grid
+        s = fminf(fmaxf(s, lo), hi);         // rule (2): project onto the hull
+        base[t] = floorf(s);
+        frac[t] = s - base[t];               // exact
+        any = any || (frac[t] != 0.0f);
+        if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
+      }
+      uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+      if (any) {  // on-grid values (zeros in particular) need no random draw
+        const Philox4 blk = stream_block(key, kTagQuant, worker, (uint32_t)(seg * 8 + k));
+        rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
+        const int32_t code = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
+        bitbuf |= (uint64_t)((uint32_t)code & mask) << nb;
+        nb += B;
+        if (nb >= 32) {
+          words[wi++] = (uint32_t)bitbuf;
+          bitbuf >>= 32;
+          nb -= 32;
+        }
+      }
+    }
+    uint32_t *dst = packed + (int64_t)worker * W + seg * B;
+    if constexpr (B % 4 == 0) {
+#pragma unroll
+      for (int i = 0; i < B; i += 4)
+        *reinterpret_cast<uint4 *>(dst + i) = make_uint4(words[i], words[i + 1], words[i + 2], words[i + 3]);
+    } else if constexpr (B % 2 == 0) {
+#pragma unroll
+      for (int i = 0; i < B; i += 2) *reinterpret_cast<uint2 *>(dst + i) = make_uint2(words[i], words[i + 1]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < B; ++i) dst[i] = words[i];
+    }
+  }
+  if (n_clipped) {
+    clipped = wave_sum(clipped);
+    if ((tid & 63) == 0 && clipped) atomicAdd(&n_clipped[worker], clipped);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Receiver: unpack, eq. (4), optional fused proximal step.
+template <int B>
+__device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ src, float delta, float (&acc)[32]) {
+  uint32_t words[B];
+  if constexpr (B % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < B; i += 4) {
+      const uint4 t = *reinterpret_cast<const uint4 *>(src + i);
+      words[i] = t.x; words[i + 1] = t.y; words[i + 2] = t.z; words[i + 3] = t.w;
+    }
+  } else if constexpr (B % 2 == 0) {
+#pragma unroll
+    for (int i = 0; i < B; i += 2) {
+      const uint2 t = *reinterpret_cast<const uint2 *>(src + i);
+      words[i] = t.x; words[i + 1] = t.y;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < B; ++i) words[i] = src[i];
+  }
+#pragma unroll
+  for (int c = 0; c < 32; ++c) {
+    const int p = c * B, wi = p >> 5, sh = p & 31;
+    uint32_t field = words[wi] >> sh;
+    if (sh + B > 32) field |= words[wi + 1] << (32 - sh);
+    const int32_t code = (int32_t)(field << (32 - B)) >> (32 - B);  // sign-extend the B-bit field
+    acc[c] = __builtin_fmaf(delta, (float)code, acc[c]);
+  }
+}
+
+__device__ __forceinline__ float prox_scalar(float w, float v, float step, float thr, float shrink) {
+  const float p = w - step * v;
+  const float mag = fabsf(p) - thr;
+  return mag > 0.0f ? copysignf(mag * shrink, p) : 0.0f;
+}
+
+struct ProxArgs {
+  const float *mu;
+  float *w;
+  float step, thr, shrink;
+};
+
+template <int B, bool PROX>
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__restrict__ packed, int64_t W,
+                                                              const float *__restrict__ delta, int32_t N, int64_t d,
+                                                              int64_t d_pad, float *__restrict__ u_avg, ProxArgs pa) {
+  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
+  const int tid = threadIdx.x;
+  const int64_t tile_base = (int64_t)blockIdx.x * kTileFloats;
+  const int64_t seg = tile_base / kSegFloats + tid;
+  if (seg * kSegFloats < d_pad) {
+    float acc[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
+    for (int32_t i = 0; i < N; ++i) unpack_accumulate<B>(packed + (int64_t)i * W + seg * B, delta[i], acc);
+    const float inv_n = 1.0f / (float)N;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      *reinterpret_cast<float4 *>(&tile[tid * kPitch + k * 4]) =
+          make_float4(acc[4 * k] * inv_n, acc[4 * k + 1] * inv_n, acc[4 * k + 2] * inv_n, acc[4 * k + 3] * inv_n);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int e = r * kThreads + tid;
+    const int64_t j = tile_base + (int64_t)e * 4;
+    if (j >= d) continue;
+    const float4 a = *reinterpret_cast<const float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]);
+    const float av[4] = {a.x, a.y, a.z, a.w};
+    if (j + 4 <= d) {
+      if (u_avg) *reinterpret_cast<float4 *>(u_avg + j) = a;
+      if constexpr (PROX) {
+        const float4 m = *reinterpret_cast<const float4 *>(pa.mu + j);
+        float4 w = *reinterpret_cast<const float4 *>(pa.w + j);
+        w.x = prox_scalar(w.x, a.x + m.x, pa.step, pa.thr, pa.shrink);
+        w.y = prox_scalar(w.y, a.y + m.y, pa.step, pa.thr, pa.shrink);
+        w.z = prox_scalar(w.z, a.z + m.z, pa.step, pa.thr, pa.shrink);
+        w.w = prox_scalar(w.w, a.w + m.w, pa.step, pa.thr, pa.shrink);
+        *reinterpret_cast<float4 *>(pa.w + j) = w;
+      }
+    } else {
+      for (int t = 0; t < 4 && j + t < d; ++t) {
+        if (u_avg) u_avg[j + t] = av[t];
+        if constexpr (PROX) pa.w[j + t] = prox_scalar(pa.w[j + t], av[t] + pa.mu[j + t], pa.step, pa.thr, pa.shrink);
+      }
+    }
+  }
+}
+
+// quantization off: u_avg = (1/N) sum_i u^i, float adds in worker order
+__global__ void plain_avg_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad, int32_t N,
+                                 float *__restrict__ u_avg) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  float acc = 0.0f;
+  for (int32_t i = 0; i < N; ++i) acc = acc + U[(int64_t)i * d_pad + j];
+  u_avg[j] = acc * (1.0f / (float)N);
+}
+
+__global__ void prox_kernel(float *__restrict__ w, const float *__restrict__ u_avg, const float *__restrict__ mu,
+                            int64_t d, float step, float thr, float shrink) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  w[j] = prox_scalar(w[j], u_avg[j] + mu[j], step, thr, shrink);
+}
+
+__global__ void copy_kernel(float *__restrict__ dst, const float *__restrict__ src, int64_t n) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) dst[j] = src[j];
+}
+
+__global__ void fill_u32_kernel(uint32_t *dst, uint32_t v, int64_t n) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) dst[j] = v;
+}
+
+__global__ void scale_to_kernel(const float *__restrict__ src, float scale, float *__restrict__ dst, int64_t n) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < n) dst[j] = src[j] * scale;
+}
+
+// Alg. 2 step 6: x = tau1*z + tau2*x~ + (1 - tau1 - tau2)*y
+__global__ void alpc_couple_kernel(const float *__restrict__ z, const float *__restrict__ ws,
+                                   const float *__restrict__ y, float t1, float t2, float t3, float *__restrict__ x,
+                                   int64_t d) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < d) x[j] = (t1 * z[j] + t2 * ws[j]) + t3 * y[j];
+}
+
+// Alg. 2 steps 13-15: y <- prox_{h/(4L)}(x - v/(4L)), z <- prox_{alpha h}(z - alpha v^),
+// ysum <- ysum + theta^t * y
+__global__ void alpc_update_kernel(const float *__restrict__ x, const float *__restrict__ u_avg,
+                                   const float *__restrict__ u_hat, const float *__restrict__ mu, float step_y,
+                                   float thr_y, float shrink_y, float alpha, float thr_z, float shrink_z,
+                                   float weight, int first, float *__restrict__ y, float *__restrict__ z,
+                                   float *__restrict__ ysum, int64_t d) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  const float m = mu[j];
+  const float yn = prox_scalar(x[j], u_avg[j] + m, step_y, thr_y, shrink_y);
+  const float zn = prox_scalar(z[j], u_hat[j] + m, alpha, thr_z, shrink_z);
+  y[j] = yn;
+  z[j] = zn;
+  ysum[j] = first ? weight * yn : ysum[j] + weight * yn;
+}
+
+// f_out = scale * sum of the loss partials (one workgroup, fixed order)
+__global__ __launch_bounds__(kThreads) void sum_loss_kernel(const double *__restrict__ part, int32_t n, double scale,
+                                                            double *__restrict__ f_out) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  for (int32_t k = tid; k < n; k += kThreads) acc += part[k];
+  acc = wave_sum(acc);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) *f_out = (((red[0] + red[1]) + red[2]) + red[3]) * scale;
+}
+
+// acc += lambda1*|w|_1 + (lambda2/2)*|w|^2 (one workgroup)
+__global__ __launch_bounds__(1024) void objective_reg_kernel(const float *__restrict__ w, int64_t d, double l1,
+                                                             double l2, double *__restrict__ acc) {
+  __shared__ double red[16];
+  const int tid = threadIdx.x;
+  double a = 0.0;
+  for (int64_t j = tid; j < d; j += 1024) {
+    const double v = (double)w[j];
+    a += l1 * fabs(v) + 0.5 * l2 * v * v;
+  }
+  a = wave_sum(a);
+  if ((tid & 63) == 0) red[tid >> 6] = a;
+  __syncthreads();
+  if (tid == 0) {
+    double t = 0.0;
+    for (int k = 0; k < 16; ++k) t += red[k];
+    *acc += t;
+  }
+}
+
+QuantSpec spec_of(const lpc_ctx *c) {
+  QuantSpec qs;
+  qs.bits = c->cfg.bits;
+  qs.clip_mode = c->cfg.clip_mode;
+  qs.clip = c->cfg.clip;
+  qs.enabled = c->quant ? 1 : 0;
+  return qs;
+}
+
+StatSinks sinks_of(const lpc_ctx *c, double *stats_out) {
+  StatSinks sk;
+  sk.stat_part = c->s.stat_part;
+  sk.stats = c->s.stats;
+  sk.qparams = c->s.qparams;
+  sk.counters = c->s.counters;
+  sk.flags = c->s.flags;
+  sk.n_clipped = c->s.n_clipped;
+  sk.stats_out = stats_out;
+  sk.stat_slots = c->stat_slots;
+  return sk;
+}
+
+inline dim3 grid1d(int64_t n, int threads) { return dim3((unsigned)((n + threads - 1) / threads)); }
+
+}  // namespace
+
+hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t parts, float scale, float *out,
+                               int64_t ld_out, int32_t vec_begin, int32_t nvec, bool want_stats, double *stats_out,
+                               hipStream_t st) {
+  // `out` and `stats_out` point at the row of the first vector of this launch; vec_begin only selects
+  // the scratch slots (statistics, quantizer parameters, arrival counters).
+  const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
+  hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, part, parts, c->d, c->d_pad, scale, out,
+                     ld_out, vec_begin, want_stats ? 1 : 0, sinks_of(c, stats_out), spec_of(c));
+  return hipGetLastError();
+}
+
+hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
+                               double *stats_out, hipStream_t st) {
+  int64_t slots = (c->d + 4095) / 4096;
+  if (slots > c->stat_slots) slots = c->stat_slots;
+  if (slots < 1) slots = 1;
+  int64_t chunk = (c->d + slots - 1) / slots;
+  slots = (c->d + chunk - 1) / chunk;
+  const dim3 grid((unsigned)slots, (unsigned)nvec);
+  hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin,
+                     sinks_of(c, stats_out), spec_of(c));
+  return hipGetLastError();
+}
+
+hipError_t launch_prepare_qparams(const lpc_ctx *c, const double *stats, const float *delta_in, int32_t nvec,
+                                  hipStream_t st) {
+  hipLaunchKernelGGL(prepare_qparams_kernel, grid1d(nvec, 64), dim3(64), 0, st, stats, delta_in, nvec, c->d,
+                     spec_of(c), c->s.qparams, c->s.n_clipped, c->s.flags);
+  return hipGetLastError();
+}
+
+namespace {
+template <int B>
+void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
+                     uint32_t *n_clipped, hipStream_t st) {
+  const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats), (unsigned)c->cfg.N);
+  hipLaunchKernelGGL(quantize_kernel<B>, grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key, packed,
+                     c->W, delta_out, n_clipped);
+}
+
+template <int B, bool PROX>
+void dequantize_launch(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg, ProxArgs pa,
+                       hipStream_t st) {
+  const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats));
+  hipLaunchKernelGGL((dequantize_kernel<B, PROX>), grid, dim3(kThreads), 0, st, packed, c->W, delta, c->cfg.N, c->d,
+                     c->d_pad, u_avg, pa);
+}
+
+#define LPC_DISPATCH_BITS(bits, CALL)                                                                     \
+  switch (bits) {                                                                                         \
+    case 2: CALL(2); break;   case 3: CALL(3); break;   case 4: CALL(4); break;   case 5: CALL(5); break;   \
+    case 6: CALL(6); break;   case 7: CALL(7); break;   case 8: CALL(8); break;   case 9: CALL(9); break;   \
+    case 10: CALL(10); break; case 11: CALL(11); break; case 12: CALL(12); break; case 13: CALL(13); break; \
+    case 14: CALL(14); break; case 15: CALL(15); break; case 16: CALL(16); break;                          \
+    default: return hipErrorInvalidValue;                                                                 \
+  }
+}  // namespace
+
+hipError_t launch_quantize(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
+                           uint32_t *n_clipped, hipStream_t st) {
+#define CALL(BITS) quantize_launch<BITS>(c, U, key, packed, delta_out, n_clipped, st)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+hipError_t launch_dequantize_avg(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg,
+                                 hipStream_t st) {
+  ProxArgs pa{nullptr, nullptr, 0.f, 0.f, 0.f};
+#define CALL(BITS) dequantize_launch<BITS, false>(c, packed, delta, u_avg, pa, st)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+namespace {
+inline void prox_consts(const lpc_ctx *c, float step, float *thr, float *shrink) {
+  *thr = (float)((double)step * (double)c->prob.lambda1);
+  *shrink = (float)(1.0 / (1.0 + (double)step * (double)c->prob.lambda2));
+}
+}  // namespace
+
+hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, const float *delta, const float *mu,
+                                  float step, float *w, float *u_avg_out, hipStream_t st) {
+  ProxArgs pa{mu, w, step, 0.f, 0.f};
+  prox_consts(c, step, &pa.thr, &pa.shrink);
+#define CALL(BITS) dequantize_launch<BITS, true>(c, packed, delta, u_avg_out, pa, st)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+hipError_t launch_plain_avg(const lpc_ctx *c, const float *U, float *u_avg, hipStream_t st) {
+  hipLaunchKernelGGL(plain_avg_kernel, grid1d(c->d, 256), dim3(256), 0, st, U, c->d, c->d_pad, c->cfg.N, u_avg);
+  return hipGetLastError();
+}
+
+hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const float *mu, float step, hipStream_t st) {
+  float thr, shrink;
+  prox_consts(c, step, &thr, &shrink);
+  hipLaunchKernelGGL(prox_kernel, grid1d(c->d, 256), dim3(256), 0, st, w, u_avg, mu, c->d, step, thr, shrink);
+  return hipGetLastError();
+}
+
+hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, float scale, float *mu, double *f_out,
+                                   bool want_loss, hipStream_t st) {
+  if (mu) {
+    const dim3 grid((unsigned)((c->d + 63) / 64), 1u);
+    hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, (const float *)c->s.part, parts, c->d, c->d,
+                       scale, mu, c->d, 0, 0, sinks_of(c, nullptr), spec_of(c));
+  }
+  if (want_loss && f_out)
+    hipLaunchKernelGGL(sum_loss_kernel, dim3(1), dim3(kThreads), 0, st, (const double *)c->s.part_loss, parts,
+                       (double)scale, f_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(copy_kernel, grid1d(n, 256), dim3(256), 0, st, dst, src, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t *dst, uint32_t v, int64_t n, hipStream_t st) {
+  hipLaunchKernelGGL(fill_u32_kernel, grid1d(n, 256), dim3(256), 0, st, dst, v, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_alpc_couple(const lpc_ctx *c, const float *z, const float *w_snap, const float *y, float tau1,
+                              float tau2, float *x, hipStream_t st) {
+  const float t3 = (float)(1.0 - (double)tau1 - (double)tau2);
+  hipLaunchKernelGGL(alpc_couple_kernel, grid1d(c->d, 256), dim3(256), 0, st, z, w_snap, y, tau1, tau2, t3, x, c->d);
+  return hipGetLastError();
+}
+
+hipError_t launch_alpc_update(const lpc_ctx *c, const float *x, const float *u_avg, const float *u_hat,
+                              const float *mu, float step_y, float alpha, float weight, bool first, float *y,
+                              float *z, float *ysum, hipStream_t st) {
+  float thr_y, shrink_y, thr_z, shrink_z;
+  prox_consts(c, step_y, &thr_y, &shrink_y);
+  prox_consts(c, alpha, &thr_z, &shrink_z);
+  hipLaunchKernelGGL(alpc_update_kernel, grid1d(c->d, 256), dim3(256), 0, st, x, u_avg, u_hat, mu, step_y, thr_y,
+                     shrink_y, alpha, thr_z, shrink_z, weight, first ? 1 : 0, y, z, ysum, c->d);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_to(const lpc_ctx *c, const float *src, float scale, float *dst, hipStream_t st) {
+  hipLaunchKernelGGL(scale_to_kernel, grid1d(c->d, 256), dim3(256), 0, st, src, scale, dst, c->d);
+  return hipGetLastError();
+}
+
+hipError_t launch_objective_reg(const lpc_ctx *c, const float *w, double *acc, hipStream_t st) {
+  hipLaunchKernelGGL(objective_reg_kernel, dim3(1), dim3(1024), 0, st, w, c->d, (double)c->prob.lambda1,
+                     (double)c->prob.lambda2, acc);
+  return hipGetLastError();
+}
+
+}  // namespace lpc

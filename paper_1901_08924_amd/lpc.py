@@ -1,0 +1,189 @@
+"""Python binding of liblpc_hip.so: the same names as include/lpc.h, argument marshalling only.
+
+Every step of the path runs in the HIP kernels of the library; torch is used for device
+memory and streams.  There is no CPU fallback: if the library cannot be loaded this module
+raises at import time.
+"""
+import ctypes as C
+import os
+
+import torch  # imported first so that the process-wide HIP runtime is torch's
+
+from . import build as _build
+
+LOSS_LOGISTIC, LOSS_SQUARED, LOSS_MLP_SOFTMAX = 0, 1, 2
+ALGO_LPC, ALGO_ALPC_SC, ALGO_ALPC_GC = 0, 1, 2
+CLIP_LAMBDA, CLIP_CSIGMA = 0, 1
+SCHEME_A, SCHEME_B, SCHEME_C = 0, 1, 2
+BATCH_WORKER, BATCH_SHARED = 1, 2
+OK, EINVAL, ENULL, ESHAPE, EWORKSPACE, ENONFINITE, EDEVICE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6, -7
+
+_vp = C.c_void_p
+
+
+class Problem(C.Structure):
+    _fields_ = [("n", C.c_int64), ("d", C.c_int64), ("loss", C.c_int32),
+                ("X", _vp), ("ldx", C.c_int64),
+                ("row_ptr", _vp), ("col_idx", _vp), ("vals", _vp), ("nnz", C.c_int64),
+                ("y", _vp), ("mlp_dims", C.POINTER(C.c_int32)), ("mlp_nlayers", C.c_int32),
+                ("lambda1", C.c_float), ("lambda2", C.c_float)]
+
+
+class Config(C.Structure):
+    _fields_ = [("algo", C.c_int32), ("N", C.c_int32), ("B", C.c_int32), ("m", C.c_int32), ("bits", C.c_int32),
+                ("clip_mode", C.c_int32), ("clip", C.c_float), ("scheme", C.c_int32),
+                ("eta", C.c_float), ("L", C.c_float), ("sigma", C.c_float), ("tau1", C.c_float),
+                ("tau2", C.c_float), ("alpha", C.c_float), ("seed", C.c_uint64), ("n_full", C.c_int64)]
+
+
+EXPORTS = {
+    "lpc_workspace_bytes": (C.c_size_t, [C.POINTER(Problem), C.POINTER(Config)]),
+    "lpc_create": (C.c_int, [C.POINTER(_vp), C.POINTER(Problem), C.POINTER(Config), _vp, C.c_size_t]),
+    "lpc_destroy": (None, [_vp]),
+    "lpc_status_string": (C.c_char_p, [C.c_int]),
+    "lpc_d_pad": (C.c_int64, [C.c_int64]),
+    "lpc_words_per_msg": (C.c_int64, [C.c_int64, C.c_int32]),
+    "lpc_full_grad": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp]),
+    "lpc_worker_vr_grad": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, C.c_uint32, C.c_int32, C.c_int32, C.c_int32,
+                                     _vp, _vp, _vp]),
+    "lpc_vector_stats": (C.c_int, [_vp, _vp, C.c_int32, _vp, _vp]),
+    "lpc_quantize_clip": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
+    "lpc_dequantize_avg": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
+    "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
+    "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
+    "lpc_take_device_flags": (C.c_int, [_vp, _vp]),
+}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblpc_hip.so")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        _build.build()
+    lib = C.CDLL(LIB_PATH)
+    for name, (res, args) in EXPORTS.items():
+        fn = getattr(lib, name)   # AttributeError here means the library lacks a declared entry point
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+lib = _load()
+
+
+class LpcError(RuntimeError):
+    def __init__(self, code, where):
+        msg = lib.lpc_status_string(code).decode()
+        super().__init__("%s: %s (%d)" % (where, msg, code))
+        self.code = code
+
+
+def _chk(code, where):
+    if code != OK:
+        raise LpcError(code, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def d_pad(d):
+    return int(lib.lpc_d_pad(d))
+
+
+def words_per_msg(d, bits):
+    return int(lib.lpc_words_per_msg(d, bits))
+
+
+def make_config(algo=ALGO_LPC, N=1, B=1, m=1, bits=32, clip_mode=CLIP_LAMBDA, clip=1.0, scheme=SCHEME_A, eta=0.1,
+                L=0.0, sigma=0.0, tau1=0.0, tau2=0.0, alpha=0.0, seed=0, n_full=0):
+    return Config(algo, N, B, m, bits, clip_mode, clip, scheme, eta, L, sigma, tau1, tau2, alpha, seed, n_full)
+
+
+class Context:
+    """Owns an lpc_ctx and the torch tensors (data, workspace) it borrows."""
+
+    def __init__(self, loss, y, config, X=None, csr=None, d=None, mlp_dims=None, lambda1=0.0, lambda2=0.0):
+        self._keep = [y]
+        p = Problem()
+        p.loss, p.lambda1, p.lambda2 = loss, lambda1, lambda2
+        assert y.is_cuda and y.dtype == torch.float32 and y.is_contiguous()
+        p.y = y.data_ptr()
+        if X is not None:
+            assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2 and X.stride(1) == 1
+            self._keep.append(X)
+            p.n, p.X, p.ldx = X.shape[0], X.data_ptr(), X.stride(0)
+            p.d = X.shape[1] if d is None else d
+        else:
+            row_ptr, col_idx, vals, dd = csr
+            for t, dt in ((row_ptr, torch.int32), (col_idx, torch.int32), (vals, torch.float32)):
+                assert t.is_cuda and t.dtype == dt and t.is_contiguous()
+            self._keep += [row_ptr, col_idx, vals]
+            p.n, p.d, p.nnz = row_ptr.numel() - 1, dd, vals.numel()
+            p.row_ptr, p.col_idx, p.vals = row_ptr.data_ptr(), col_idx.data_ptr(), vals.data_ptr()
+        if mlp_dims is not None:
+            self._dims = (C.c_int32 * len(mlp_dims))(*mlp_dims)
+            p.mlp_dims, p.mlp_nlayers = self._dims, len(mlp_dims) - 1
+        self.problem, self.config = p, config
+        self.n, self.d, self.N, self.bits = int(p.n), int(p.d), config.N, config.bits
+        self.d_pad = d_pad(self.d)
+        self.W = words_per_msg(self.d, self.bits) if self.bits < 32 else 0
+        self.device = y.device
+        need = lib.lpc_workspace_bytes(C.byref(p), C.byref(config))
+        self.workspace = torch.empty(max(int(need), 256), dtype=torch.uint8, device=self.device)
+        handle = _vp()
+        _chk(lib.lpc_create(C.byref(handle), C.byref(p), C.byref(config), self.workspace.data_ptr(),
+                            self.workspace.numel()), "lpc_create")
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            torch.cuda.synchronize(self.device)
+            lib.lpc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the calls of include/lpc.h -------------------------------------------------------
+    def full_grad(self, w, mu, z=None, f_out=None, stream=None):
+        _chk(lib.lpc_full_grad(self._h, _ptr(w), _ptr(mu), _ptr(z), _ptr(f_out), _stream(stream)), "lpc_full_grad")
+
+    def worker_vr_grad(self, w, w_snap, z_snap, epoch, iter_, U, stats=None, kind=BATCH_WORKER, worker_begin=0,
+                       worker_end=None, stream=None):
+        we = self.N if worker_end is None else worker_end
+        _chk(lib.lpc_worker_vr_grad(self._h, _ptr(w), _ptr(w_snap), _ptr(z_snap), epoch, iter_, kind, worker_begin,
+                                    we, _ptr(U), _ptr(stats), _stream(stream)), "lpc_worker_vr_grad")
+
+    def vector_stats(self, U, nvec, stats, stream=None):
+        _chk(lib.lpc_vector_stats(self._h, _ptr(U), nvec, _ptr(stats), _stream(stream)), "lpc_vector_stats")
+
+    def quantize_clip(self, U, stats, delta_in, epoch, iter_, packed, delta_out, n_clipped=None, stream=None):
+        _chk(lib.lpc_quantize_clip(self._h, _ptr(U), _ptr(stats), _ptr(delta_in), epoch, iter_, _ptr(packed),
+                                   _ptr(delta_out), _ptr(n_clipped), _stream(stream)), "lpc_quantize_clip")
+
+    def dequantize_avg(self, packed, delta, u_avg, stream=None):
+        _chk(lib.lpc_dequantize_avg(self._h, _ptr(packed), _ptr(delta), _ptr(u_avg), _stream(stream)),
+             "lpc_dequantize_avg")
+
+    def prox_step(self, w, u_avg, mu, step, stream=None):
+        _chk(lib.lpc_prox_step(self._h, _ptr(w), _ptr(u_avg), _ptr(mu), step, _stream(stream)), "lpc_prox_step")
+
+    def epoch(self, w_snap, epoch, y=None, z=None, stream=None):
+        _chk(lib.lpc_epoch(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _stream(stream)), "lpc_epoch")
+
+    def objective(self, w, stream=None):
+        out = C.c_double()
+        _chk(lib.lpc_objective(self._h, _ptr(w), C.byref(out), _stream(stream)), "lpc_objective")
+        return out.value
+
+    def take_device_flags(self, stream=None):
+        return lib.lpc_take_device_flags(self._h, _stream(stream))

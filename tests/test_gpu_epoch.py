@@ -1,0 +1,77 @@
+"""GPU parity of whole epochs: Alg. 1 and Alg. 2/3 against the oracle, objective within 1e-4."""
+import numpy as np
+import pytest
+
+import lpc_synth
+from oracle import lpco
+from _common import gpu_context, oracle_config, oracle_problem, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_both(sp, epochs, **over):
+    ctx = gpu_context(sp, **over)
+    p, _k = oracle_problem(sp)
+    cfg = oracle_config(sp, **over)
+    alpc = cfg.algo != lpco.ALGO_LPC
+    w_o = sp.w0.copy()
+    y_o, z_o = (sp.w0.copy(), sp.w0.copy()) if alpc else (None, None)
+    w_g = to_dev(sp.w0)
+    y_g, z_g = (to_dev(sp.w0), to_dev(sp.w0)) if alpc else (None, None)
+    hist = []
+    for s in range(epochs):
+        lpco.epoch(p, cfg, w_o, s, y_o, z_o)
+        ctx.epoch(w_g, s, y_g, z_g)
+        hist.append((lpco.objective(p, w_o), ctx.objective(w_g), lpco.objective(p, w_g.cpu().numpy())))
+    assert ctx.take_device_flags() == 0
+    ctx.close()
+    return hist, w_o, w_g.cpu().numpy()
+
+
+def test_c1_ten_epochs_objective_parity():
+    sp = lpc_synth.make("c1")      # the full tiny config: n=1024, d=64, N=4, B=16, b=2, c*sigma clip, 10 epochs
+    hist, w_o, w_g = _run_both(sp, sp.epochs)
+    for P_o, P_g, P_og in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)       # spec tolerance
+        assert abs(P_g - P_og) <= 1e-5 * abs(P_og)     # the GPU objective of its own iterate
+    assert hist[-1][0] < hist[0][0]
+    assert np.abs(w_g - w_o).max() <= 1e-3 * max(1.0, np.abs(w_o).max())
+
+
+@pytest.mark.parametrize("bits,clip_mode,clip", [(32, 0, 1.0), (4, 0, 0.9), (3, 1, 2.0)])
+def test_lpc_epochs_small_dense(bits, clip_mode, clip):
+    sp = lpc_synth.make("c2", n=2048, d=512, N=4, B=16)
+    hist, w_o, w_g = _run_both(sp, 4, bits=bits, clip_mode=clip_mode, clip=clip)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    assert hist[-1][0] < hist[0][0]
+
+
+def test_quantization_off_tracks_the_oracle_closely():
+    # without stochastic rounding the two trajectories differ by float rounding only
+    sp = lpc_synth.make("c1", n=512, d=40, N=4, B=8)
+    hist, w_o, w_g = _run_both(sp, 5, bits=32)
+    assert np.abs(w_g - w_o).max() <= 2e-5 * max(1.0, np.abs(w_o).max())
+
+
+@pytest.mark.parametrize("algo", [lpco.ALGO_ALPC_SC, lpco.ALGO_ALPC_GC])
+@pytest.mark.parametrize("bits", [32, 3])
+def test_alpc_epochs_ridge(algo, bits):
+    sp = lpc_synth.make("c4", n=2048, d=256, N=4, B=16)
+    hist, w_o, w_g = _run_both(sp, 4, algo=algo, bits=bits, tau2=0.5)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    assert hist[-1][0] < hist[0][0]
+    if bits == 32:
+        assert np.abs(w_g - w_o).max() <= 5e-5 * max(1.0, np.abs(w_o).max())
+
+
+def test_epoch_is_reproducible():
+    import torch
+    sp = lpc_synth.make("c2", n=1024, d=256, N=4, B=16)
+    ctx = gpu_context(sp)
+    a, b = to_dev(sp.w0), to_dev(sp.w0)
+    ctx.epoch(a, 0); ctx.epoch(a, 1)
+    ctx.epoch(b, 0); ctx.epoch(b, 1)
+    assert torch.equal(a, b)
+    ctx.close()
