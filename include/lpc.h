@@ -157,6 +157,13 @@ lpc_status lpc_quantize_clip(lpc_ctx *ctx, const float *U, const double *stats, 
  * accumulated in worker order with one fused multiply-add per worker. */
 lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float *delta, float *u_avg, void *stream);
 
+/* Alg. 1 steps 7-8 in one call (quantization step + communication step 2, scheme (a)): statistics of
+ * the N rows of U, eq. (3), quantize + pack into packed [N][W] with delta_out [N], and the receiver's
+ * average u_avg (d floats) of eq. (4).  Same results, bit for bit, as lpc_vector_stats +
+ * lpc_quantize_clip + lpc_dequantize_avg in LPC_CLIP_LAMBDA mode; for small d it runs as two launches. */
+lpc_status lpc_exchange(lpc_ctx *ctx, const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed,
+                        float *delta_out, float *u_avg, void *stream);
+
 /* Alg. 1 steps 9-10: v = u_avg + mu;  w <- prox_{step*h}(w - step*v), in place,
  * prox(p)_j = sign(p_j)*max(|p_j| - step*lambda1, 0)/(1 + step*lambda2) (Sec. 3.3). */
 lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream);

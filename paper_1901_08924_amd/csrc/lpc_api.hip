@@ -80,6 +80,7 @@ size_t layout(lpc_ctx *c, char *base) {
   const int64_t N1 = (int64_t)c->cfg.N + 1;
   Scratch &s = c->s;
   s.part = (float *)take(c->part_floats * sizeof(float));
+  s.part2 = (float *)take((size_t)c->fold_slices * c->d * sizeof(float));
   s.part_loss = (double *)take((size_t)c->full_grad_wgs * sizeof(double));
   s.stat_part = (double *)take((size_t)N1 * c->stat_slots * 4 * sizeof(double));
   s.stats = (double *)take((size_t)N1 * 4 * sizeof(double));
@@ -121,9 +122,10 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   // other problem the context still serves the quantizer / receiver / prox calls and the gradient
   // calls answer LPC_EUNSUPPORTED.
   c->grad_ok = p->loss != LPC_LOSS_MLP_SOFTMAX && !is_csr(*p) && dense_supported(p->d, p->ldx, p->X);
+  c->cus = 256;  // MI355X
   if (c->grad_ok) {
-    c->full_grad_wgs = dense_full_grad_wgs(c->n, c->d);
-    c->vr_parts = dense_vr_parts(c->d, cfg->B);
+    c->full_grad_wgs = dense_full_grad_wgs(c->n_full, c->d, c->cus);
+    c->vr_parts = dense_vr_parts(c->d, cfg->N, cfg->B, c->cus);
     const size_t a1 = (size_t)c->full_grad_wgs * c->d;
     const size_t a2 = (size_t)(cfg->N + 1) * c->vr_parts * c->d;
     c->part_floats = a1 > a2 ? a1 : a2;
@@ -132,6 +134,7 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->vr_parts = 1;
     c->part_floats = 64;
   }
+  c->fold_slices = (c->full_grad_wgs >= 32 && c->full_grad_wgs % 16 == 0) ? 16 : 1;
   c->stat_slots = (int32_t)((c->d_pad + 63) / 64);
   return LPC_OK;
 }
@@ -157,14 +160,14 @@ lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, doubl
 
 // Alg. 1 step 6 for workers [wb, we) (or the shared batch): U rows and statistics
 lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap, StreamKey key,
-                        uint32_t tag, int32_t wb, int32_t we, float *U_row0, double *stats_row0, bool want_stats,
+                        uint32_t tag, int32_t wb, int32_t we, float *U_row0, double *stats_row0, int stats_mode,
                         hipStream_t st) {
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
   hipError_t e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
   if (e != hipSuccess) return LPC_EDEVICE;
   const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
   e = launch_reduce_parts(c, c->s.part, c->vr_parts, (float)(1.0 / (double)c->cfg.B), U_row0, c->d_pad, slot0,
-                          we - wb, want_stats, stats_row0, st);
+                          we - wb, stats_mode, stats_row0, st);
   return dev(e);
 }
 
@@ -296,14 +299,14 @@ lpc_status lpc_worker_vr_grad(lpc_ctx *ctx, const float *w, const float *w_snap,
   const int32_t we = kind == LPC_BATCH_SHARED ? worker_begin + 1 : worker_end;
   return vr_grad_impl(ctx, w, w_snap, z_snap, key_of(ctx, epoch, iter), tag, worker_begin, we,
                       U + (int64_t)worker_begin * ctx->d_pad, stats ? stats + 4 * (int64_t)worker_begin : nullptr,
-                      true, as_stream(stream));
+                      kStatsFinal, as_stream(stream));
 }
 
 lpc_status lpc_vector_stats(lpc_ctx *ctx, const float *U, int32_t nvec, double *stats, void *stream) {
   if (!ctx || !U || !stats) return LPC_ENULL;
   if (nvec <= 0 || nvec > ctx->cfg.N + 1) return LPC_EINVAL;
   if (!aligned(U, 16) || !aligned(stats, 8)) return LPC_ESHAPE;
-  return dev(launch_vector_stats(ctx, U, ctx->d_pad, 0, nvec, stats, as_stream(stream)));
+  return dev(launch_vector_stats(ctx, U, ctx->d_pad, 0, nvec, stats, kStatsFinal, nullptr, as_stream(stream)));
 }
 
 lpc_status lpc_quantize_clip(lpc_ctx *ctx, const float *U, const double *stats, const float *delta_in,
@@ -329,6 +332,25 @@ lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float 
   return dev(launch_dequantize_avg(ctx, packed, delta, u_avg, as_stream(stream)));
 }
 
+lpc_status lpc_exchange(lpc_ctx *ctx, const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed,
+                        float *delta_out, float *u_avg, void *stream) {
+  if (!ctx || !U || !packed || !delta_out || !u_avg) return LPC_ENULL;
+  if (!ctx->quant) return LPC_EINVAL;
+  if (!aligned(U, 16) || !aligned(packed, 16) || !aligned(u_avg, 16)) return LPC_ESHAPE;
+  hipStream_t st = as_stream(stream);
+  const StreamKey key = key_of(ctx, epoch, iter);
+  if (fused_exchange_supported(ctx)) {
+    int32_t slots = 0;
+    LPC_TRY_HIP(launch_vector_stats(ctx, U, ctx->d_pad, 0, ctx->cfg.N, nullptr, kStatsPartial, &slots, st));
+    LPC_TRY_HIP(launch_fused_exchange(ctx, U, slots, key, packed, delta_out, nullptr, 0.0f, nullptr, u_avg, st));
+    return LPC_OK;
+  }
+  LPC_TRY_HIP(launch_vector_stats(ctx, U, ctx->d_pad, 0, ctx->cfg.N, nullptr, kStatsFinal, nullptr, st));
+  LPC_TRY_HIP(launch_quantize(ctx, U, key, packed, delta_out, ctx->s.n_clipped, st));
+  LPC_TRY_HIP(launch_dequantize_avg(ctx, packed, delta_out, u_avg, st));
+  return LPC_OK;
+}
+
 lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream) {
   if (!ctx || !w || !u_avg || !mu) return LPC_ENULL;
   if (!(step > 0.0f)) return LPC_EINVAL;
@@ -347,10 +369,19 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   const float *zs = (c->n_full == c->n) ? s.z_snap : nullptr;  // margins cached only when every row was visited
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
+    const bool fused = fused_exchange_supported(c);
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
-      LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, c->quant, st));
-      LPC_TRY(exchange_and_prox(c, key, s.w, st));
+      if (fused) {
+        // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
+        LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st));
+        LPC_TRY_HIP(launch_fused_exchange(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, s.mu, g.eta,
+                                          s.w, nullptr, st));
+      } else {
+        LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
+                             c->quant ? kStatsFinal : kStatsNone, st));
+        LPC_TRY(exchange_and_prox(c, key, s.w, st));
+      }
     }
     LPC_TRY_HIP(launch_copy(w_snap, s.w, c->d, st));  // x~ <- x_m
     return LPC_OK;
@@ -365,7 +396,8 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   for (int32_t t = 0; t < g.m; ++t) {
     const StreamKey key = key_of(c, epoch, (uint32_t)t);
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
-    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, c->quant, st));
+    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
+                         c->quant ? kStatsFinal : kStatsNone, st));
     if (c->quant) {
       LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
       LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
@@ -373,7 +405,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
     }
     // double sampling: the shared batch J, full precision
-    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagShared, 0, 1, u_hat, nullptr, false, st));
+    LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagShared, 0, 1, u_hat, nullptr, kStatsNone, st));
     LPC_TRY_HIP(launch_alpc_update(c, s.w, s.u_avg, u_hat, s.mu, step_y, ap.alpha, (float)weight, t == 0, y, z,
                                    s.ysum, st));
     wsum += weight;

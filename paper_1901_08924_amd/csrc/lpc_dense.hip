@@ -132,6 +132,7 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
     bool rowlive[R];
     Chunk<VEC> x[R][K];
     float dot[R * NDOT];
+    float yv[R], zsv[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       rowlive[r] = g0 + r < pos_end;
@@ -140,6 +141,9 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
       } else {
         row[r] = rowlive[r] ? sample_row(a.key, a.tag, worker, (uint32_t)(g0 + r), a.n) : 0;
       }
+      // labels and cached margins are requested together with the rows, not after the reduction
+      yv[r] = rowlive[r] ? a.y[row[r]] : 0.0f;
+      zsv[r] = (MODE == 1 && rowlive[r]) ? a.z_snap[row[r]] : 0.0f;
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -187,7 +191,7 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
     for (int r = 0; r < R; ++r) {
       float coef = 0.0f;
       if (rowlive[r]) {
-        const float yr = a.y[row[r]];
+        const float yr = yv[r];
         const float z = dot[r * NDOT];
         if constexpr (MODE == 0) {
           coef = loss_slope(a.loss, z, yr);
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
             if (a.want_loss) loss_acc += (double)loss_value(a.loss, z, yr);
           }
         } else {
-          const float zs = (MODE == 2) ? dot[r * NDOT + (NDOT - 1)] : a.z_snap[row[r]];
+          const float zs = (MODE == 2) ? dot[r * NDOT + (NDOT - 1)] : zsv[r];
           coef = loss_slope(a.loss, z, yr) - loss_slope(a.loss, zs, yr);
         }
       }
@@ -237,28 +241,38 @@ bool pick_shape(int64_t d, int64_t ldx, const void *X, Shape *s) {
   return false;
 }
 
+// R rows are held in registers at once; the caller asks for rows_hint rows per group and gets the
+// largest instantiated R that does not exceed it (and fits the register budget of the tiling).
 template <int VEC, int K, int T, int MODE>
-void launch_shape(const DenseArgs &a, int grid, hipStream_t st) {
-  constexpr int R = (K >= 8) ? 1 : ((K * VEC >= 16 && MODE == 2) ? 2 : 4);
-  hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, R, MODE>), dim3((unsigned)grid), dim3(T), 0, st, a);
+void launch_shape(const DenseArgs &a, int grid, int rows_hint, hipStream_t st) {
+  constexpr int RMAX = (K >= 8) ? 1 : ((K * VEC >= 16 && MODE == 2) ? 2 : 4);
+  if (RMAX >= 4 && rows_hint >= 4) {
+    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, (RMAX >= 4 ? 4 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), 0,
+                       st, a);
+  } else if (RMAX >= 2 && rows_hint >= 2) {
+    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, (RMAX >= 2 ? 2 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), 0,
+                       st, a);
+  } else {
+    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, 1, MODE>), dim3((unsigned)grid), dim3(T), 0, st, a);
+  }
 }
 
 template <int VEC, int MODE>
-hipError_t dispatch_tk(const Shape &s, const DenseArgs &a, int grid, hipStream_t st) {
-  if (s.t == 64 && s.k == 1) launch_shape<VEC, 1, 64, MODE>(a, grid, st);
-  else if (s.t == 64 && s.k == 4) launch_shape<VEC, 4, 64, MODE>(a, grid, st);
-  else if (s.t == 256 && s.k == 2) launch_shape<VEC, 2, 256, MODE>(a, grid, st);
-  else if (s.t == 256 && s.k == 4) launch_shape<VEC, 4, 256, MODE>(a, grid, st);
-  else if (s.t == 512 && s.k == 4) launch_shape<VEC, 4, 512, MODE>(a, grid, st);
-  else if (s.t == 1024 && s.k == 4) launch_shape<VEC, 4, 1024, MODE>(a, grid, st);
-  else if (s.t == 1024 && s.k == 8) launch_shape<VEC, 8, 1024, MODE>(a, grid, st);
+hipError_t dispatch_tk(const Shape &s, const DenseArgs &a, int grid, int rows_hint, hipStream_t st) {
+  if (s.t == 64 && s.k == 1) launch_shape<VEC, 1, 64, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 64 && s.k == 4) launch_shape<VEC, 4, 64, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 256 && s.k == 2) launch_shape<VEC, 2, 256, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 256 && s.k == 4) launch_shape<VEC, 4, 256, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 512 && s.k == 4) launch_shape<VEC, 4, 512, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 1024 && s.k == 4) launch_shape<VEC, 4, 1024, MODE>(a, grid, rows_hint, st);
+  else if (s.t == 1024 && s.k == 8) launch_shape<VEC, 8, 1024, MODE>(a, grid, rows_hint, st);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
 template <int MODE>
-hipError_t dispatch(const Shape &s, const DenseArgs &a, int grid, hipStream_t st) {
-  return s.vec == 4 ? dispatch_tk<4, MODE>(s, a, grid, st) : dispatch_tk<1, MODE>(s, a, grid, st);
+hipError_t dispatch(const Shape &s, const DenseArgs &a, int grid, int rows_hint, hipStream_t st) {
+  return s.vec == 4 ? dispatch_tk<4, MODE>(s, a, grid, rows_hint, st) : dispatch_tk<1, MODE>(s, a, grid, rows_hint, st);
 }
 
 int rows_per_group(const Shape &s) { return s.k >= 8 ? 1 : 4; }
@@ -273,21 +287,23 @@ bool dense_supported(int64_t d, int64_t ldx, const void *X) {
 // Workgroups of the snapshot pass: enough to keep every CU busy with several
 // resident groups, few enough that the partial-gradient rows stay a small
 // fraction of the traffic of X.
-int dense_full_grad_wgs(int64_t n, int64_t d) {
+int dense_full_grad_wgs(int64_t n, int64_t d, int cus) {
   (void)d;
-  int64_t wgs = 1024;
+  int64_t wgs = (int64_t)cus * 3;         // three resident workgroups per CU, one scheduling round
   const int64_t by_rows = (n + 15) / 16;  // at least 16 rows per workgroup
   if (wgs > by_rows) wgs = by_rows;
   if (wgs < 1) wgs = 1;
+  if (wgs > 16) wgs = wgs / 16 * 16;      // the partial rows are folded in 16 equal slices
   return (int)wgs;
 }
 
-// Partial rows per worker in the worker pass: one workgroup per 4 sampled rows.
-int dense_vr_parts(int64_t d, int32_t B) {
+// Partial rows per worker in the worker pass.  The pass is latency-bound (a few MB per launch), so
+// the sampled rows are spread over about one workgroup per CU: 1, 2 or 4 rows per workgroup.
+int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus) {
   (void)d;
-  int parts = (B + 3) / 4;
-  if (parts < 1) parts = 1;
-  return parts;
+  int64_t rows = (int64_t)N * B / cus;
+  int rpw = rows >= 4 ? 4 : (rows >= 2 ? 2 : 1);
+  return (B + rpw - 1) / rpw;
 }
 
 hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,
@@ -303,7 +319,7 @@ hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bo
   int64_t rpw = (n_rows + wgs - 1) / wgs;
   rpw = ((rpw + rg - 1) / rg) * rg;
   a.rows_per_wg = rpw;
-  return dispatch<0>(s, a, wgs, st);
+  return dispatch<0>(s, a, wgs, 4, st);
 }
 
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
@@ -318,7 +334,7 @@ hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w
   a.B = c->cfg.B; a.parts = c->vr_parts;
   a.rows_per_part = (c->cfg.B + c->vr_parts - 1) / c->vr_parts;
   const int grid = (worker_end - worker_begin) * c->vr_parts;
-  return z_snap ? dispatch<1>(s, a, grid, st) : dispatch<2>(s, a, grid, st);
+  return z_snap ? dispatch<1>(s, a, grid, a.rows_per_part, st) : dispatch<2>(s, a, grid, a.rows_per_part, st);
 }
 
 }  // namespace lpc

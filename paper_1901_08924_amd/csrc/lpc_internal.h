@@ -30,6 +30,7 @@ struct StreamKey {
 // ---- device scratch owned by a context (all pointers into the workspace) ----
 struct Scratch {
   float *part;          // partial gradient rows
+  float *part2;         // second level of the snapshot pass's fold: [fold_slices][d]
   double *part_loss;    // per-workgroup loss partials
   double *stat_part;    // [(N+1)][stat_slots][4]
   double *stats;        // [(N+1)][4]
@@ -60,6 +61,8 @@ struct lpc_ctx {
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
   int32_t vr_parts;       // partial rows per worker written by the worker pass
   int32_t stat_slots;     // statistic partials per vector
+  int32_t cus;            // compute units of the device (256 on MI355X)
+  int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
   size_t part_floats;
   void *workspace;
   size_t workspace_bytes;
@@ -72,8 +75,8 @@ namespace lpc {
 
 // Dense GLM passes (lpc_dense.hip)
 bool dense_supported(int64_t d, int64_t ldx, const void *X);
-int dense_full_grad_wgs(int64_t n, int64_t d);
-int dense_vr_parts(int64_t d, int32_t B);
+int dense_full_grad_wgs(int64_t n, int64_t d, int cus);
+int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus);
 hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,
                                   hipStream_t st);
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
@@ -92,10 +95,16 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 // row and its quantizer parameters.  out / stats_out point at the first row of the launch; vec_begin
 // selects the scratch slots.
 hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t parts, float scale, float *out,
-                               int64_t ld_out, int32_t vec_begin, int32_t nvec, bool want_stats, double *stats_out,
+                               int64_t ld_out, int32_t vec_begin, int32_t nvec, int stats_mode, double *stats_out,
                                hipStream_t st);
+// stats_mode values of launch_reduce_parts
+constexpr int kStatsNone = 0, kStatsFinal = 1, kStatsPartial = 2;
+bool fused_exchange_supported(const lpc_ctx *c);
+hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key, uint32_t *packed,
+                                 float *delta_out, const float *mu, float step, float *w, float *u_avg_out,
+                                 hipStream_t st);
 hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
-                               double *stats_out, hipStream_t st);
+                               double *stats_out, int stats_mode, int32_t *slots_used, hipStream_t st);
 hipError_t launch_prepare_qparams(const lpc_ctx *c, const double *stats, const float *delta_in, int32_t nvec,
                                   hipStream_t st);
 hipError_t launch_quantize(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,

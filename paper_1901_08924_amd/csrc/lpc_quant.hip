@@ -86,12 +86,27 @@ __device__ inline QParams qparams_from_delta(const QuantSpec &qs, float delta) {
   return q;
 }
 
-// Wave 0 of a workgroup publishes the statistics of its slice; the last
-// workgroup to arrive for a vector folds all slices in a fixed order, so the
-// result does not depend on scheduling.
-__device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, int32_t vec, int32_t rel, int32_t slot,
-                                     int32_t nslots, int64_t d, double amax, double sum, double sumsq, double bad,
-                                     bool *s_last) {
+// Fold the statistic partials of one vector in a fixed order (lane k takes slots k, k+64, ...; then
+// a butterfly).  Called by one full wavefront; every lane returns the same four numbers.
+__device__ inline void fold_stat_slots(const volatile double *p, int32_t nslots, int lane, double &a, double &s,
+                                       double &s2, double &b) {
+  a = 0.0; s = 0.0; s2 = 0.0; b = 0.0;
+  for (int32_t k = lane; k < nslots; k += 64) {
+    a = fmax(a, p[k * 4 + 0]);
+    s += p[k * 4 + 1];
+    s2 += p[k * 4 + 2];
+    b += p[k * 4 + 3];
+  }
+  a = wave_max(a); s = wave_sum(s); s2 = wave_sum(s2); b = wave_sum(b);
+}
+
+// Wave 0 of a workgroup publishes the statistics of its slice.  In kStatsFinal mode the last
+// workgroup to arrive for a vector folds all slices in a fixed order, so the result does not depend
+// on scheduling; in kStatsPartial mode the consumer kernel does that fold itself (no fences, no
+// atomics on the critical path of a short kernel).
+__device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, int mode, int32_t vec, int32_t rel,
+                                     int32_t slot, int32_t nslots, int64_t d, double amax, double sum, double sumsq,
+                                     double bad, bool *s_last) {
   const int tid = threadIdx.x;
   if (tid < 64) {
     amax = wave_max(amax);
@@ -101,23 +116,19 @@ __device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, i
     if (tid == 0) {
       double *p = sk.stat_part + ((int64_t)vec * sk.stat_slots + slot) * 4;
       p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
-      __threadfence();
-      const uint32_t prev = atomicAdd(&sk.counters[vec], 1u);
-      *s_last = (prev == (uint32_t)nslots - 1u);
+      if (mode == kStatsFinal) {
+        __threadfence();
+        const uint32_t prev = atomicAdd(&sk.counters[vec], 1u);
+        *s_last = (prev == (uint32_t)nslots - 1u);
+      }
     }
   }
+  if (mode != kStatsFinal) return;
   __syncthreads();
   if (*s_last && tid < 64) {
     __threadfence();
-    const volatile double *p = sk.stat_part + (int64_t)vec * sk.stat_slots * 4;
-    double a = 0.0, s = 0.0, s2 = 0.0, b = 0.0;
-    for (int32_t k = tid; k < nslots; k += 64) {
-      a = fmax(a, p[k * 4 + 0]);
-      s += p[k * 4 + 1];
-      s2 += p[k * 4 + 2];
-      b += p[k * 4 + 3];
-    }
-    a = wave_max(a); s = wave_sum(s); s2 = wave_sum(s2); b = wave_sum(b);
+    double a, s, s2, b;
+    fold_stat_slots(sk.stat_part + (int64_t)vec * sk.stat_slots * 4, nslots, tid, a, s, s2, b);
     if (tid == 0) {
       double *o = sk.stats + (int64_t)vec * 4;
       o[0] = a; o[1] = s; o[2] = s2; o[3] = b;
@@ -166,14 +177,14 @@ __global__ __launch_bounds__(kThreads) void reduce_parts_kernel(const float *__r
       bad = 1.0;
     }
   }
-  if (want_stats)
-    publish_stats(sk, qs, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+  if (want_stats != kStatsNone)
+    publish_stats(sk, qs, want_stats, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
 }
 
 // statistics of rows of an existing matrix; each workgroup takes `chunk` columns
 __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__restrict__ U, int64_t ld, int64_t d,
-                                                                int64_t chunk, int32_t vec_begin, StatSinks sk,
-                                                                QuantSpec qs) {
+                                                                int64_t chunk, int32_t vec_begin, int32_t mode,
+                                                                StatSinks sk, QuantSpec qs) {
   __shared__ double red[4][4];
   __shared__ bool s_last;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -197,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__r
   if (tid == 0) {
     for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
   }
-  publish_stats(sk, qs, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+  publish_stats(sk, qs, mode, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
 }
 
 __global__ void prepare_qparams_kernel(const double *stats, const float *delta_in, int32_t nvec, int64_t d,
@@ -399,6 +410,130 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
   }
 }
 
+// ---------------------------------------------------------------------------
+// Small-d inner iteration: statistics fold -> eq. (3) -> quantize -> pack -> eq. (4) -> prox in ONE
+// launch.  When d is a few thousand the whole exchange moves a few hundred KB and is bound by
+// launch and dependency latency, not by HBM, so the work is spread as wide as possible: a
+// workgroup owns 128 coordinates (4 segments) of ALL workers, thread (g, l) quantizes the four
+// coordinates 4l..4l+3 of worker g, g+8, ..., codes meet in LDS, then words are assembled and the
+// average and proximal step are taken for the 128 coordinates.  Every workgroup folds the
+// statistic partials itself (same fixed order as the stand-alone fold), so no grid-wide
+// synchronisation is needed inside the launch.
+constexpr int kFusedCoords = 128;
+constexpr int kFusedMaxN = 64;
+
+struct FusedArgs {
+  const float *U;
+  int64_t d, d_pad, W;
+  int32_t N, bits, nslots, stat_slots;
+  const double *stat_part;
+  QuantSpec qs;
+  StreamKey key;
+  uint32_t *packed;
+  float *delta_out;
+  double *stats;
+  uint32_t *flags;
+  const float *mu;
+  float *w;
+  float *u_avg_out;
+  float step, thr, shrink;
+  int32_t do_prox;
+};
+
+__global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
+  __shared__ QParams qp[kFusedMaxN];
+  __shared__ int32_t codes[kFusedMaxN][kFusedCoords];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  for (int32_t i = wv; i < a.N; i += 4) {
+    double am, s, s2, b;
+    fold_stat_slots(a.stat_part + (int64_t)i * a.stat_slots * 4, a.nslots, lane, am, s, s2, b);
+    if (lane == 0) {
+      const QParams q = make_qparams(a.qs, am, s, s2, a.d);
+      qp[i] = q;
+      if (blockIdx.x == 0) {
+        a.delta_out[i] = q.delta;
+        double *o = a.stats + (int64_t)i * 4;
+        o[0] = am; o[1] = s; o[2] = s2; o[3] = b;
+        if (b > 0.0) atomicOr(&a.flags[0], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  const int64_t tile0 = (int64_t)blockIdx.x * kFusedCoords;
+  {
+    const int g = tid >> 5, l = tid & 31;
+    const int64_t j = tile0 + 4 * l;
+    const float hi = (float)((1 << (a.bits - 1)) - 1);
+    const float lo = -(float)(1 << (a.bits - 1));
+    for (int32_t i = g; i < a.N; i += 8) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < a.d_pad) {
+        v = *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + j);
+        if (j + 3 >= a.d) {
+          if (j + 0 >= a.d) v.x = 0.f;
+          if (j + 1 >= a.d) v.y = 0.f;
+          if (j + 2 >= a.d) v.z = 0.f;
+          v.w = 0.f;
+        }
+      }
+      const QParams q = qp[i];
+      const float vals[4] = {v.x, v.y, v.z, v.w};
+      float base[4], frac[4];
+      bool any = false;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        float s = vals[t] * q.rdelta;
+        s = fminf(fmaxf(s, lo), hi);
+        base[t] = floorf(s);
+        frac[t] = s - base[t];
+        any = any || (frac[t] != 0.0f);
+      }
+      uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+      if (any) {
+        const Philox4 blk = stream_block(a.key, kTagQuant, (uint32_t)i, (uint32_t)(j >> 2));
+        rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
+        codes[i][4 * l + t] = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);
+      }
+    }
+  }
+  __syncthreads();
+  // pack: one thread per output word of the tile
+  {
+    const int32_t bits = a.bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    const int32_t words_per_worker = 4 * bits;
+    const int64_t seg0 = tile0 / kSegFloats;
+    for (int32_t idx = tid; idx < a.N * words_per_worker; idx += kThreads) {
+      const int32_t i = idx / words_per_worker, rem = idx % words_per_worker;
+      const int32_t sgm = rem / bits, wd = rem % bits;
+      if ((seg0 + sgm) * kSegFloats >= a.d_pad) continue;
+      const int32_t bit0 = 32 * wd;
+      uint32_t word = 0u;
+      for (int32_t c = bit0 / bits; c < 32 && c * bits < bit0 + 32; ++c) {
+        const uint32_t field = (uint32_t)codes[i][32 * sgm + c] & mask;
+        const int32_t sh = c * bits - bit0;
+        word |= sh >= 0 ? (field << sh) : (field >> (-sh));
+      }
+      a.packed[(int64_t)i * a.W + (seg0 + sgm) * bits + wd] = word;
+    }
+  }
+  // eq. (4) in worker order, then Alg. 1 steps 9-10
+  if (tid < kFusedCoords) {
+    const int64_t j = tile0 + tid;
+    if (j < a.d) {
+      float acc = 0.0f;
+      for (int32_t i = 0; i < a.N; ++i) acc = __builtin_fmaf(qp[i].delta, (float)codes[i][tid], acc);
+      const float avg = acc * (1.0f / (float)a.N);
+      if (a.u_avg_out) a.u_avg_out[j] = avg;
+      if (a.do_prox) a.w[j] = prox_scalar(a.w[j], avg + a.mu[j], a.step, a.thr, a.shrink);
+    }
+  }
+}
+
 // quantization off: u_avg = (1/N) sum_i u^i, float adds in worker order
 __global__ void plain_avg_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad, int32_t N,
                                  float *__restrict__ u_avg) {
@@ -516,26 +651,27 @@ inline dim3 grid1d(int64_t n, int threads) { return dim3((unsigned)((n + threads
 }  // namespace
 
 hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t parts, float scale, float *out,
-                               int64_t ld_out, int32_t vec_begin, int32_t nvec, bool want_stats, double *stats_out,
+                               int64_t ld_out, int32_t vec_begin, int32_t nvec, int stats_mode, double *stats_out,
                                hipStream_t st) {
   // `out` and `stats_out` point at the row of the first vector of this launch; vec_begin only selects
   // the scratch slots (statistics, quantizer parameters, arrival counters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
   hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, part, parts, c->d, c->d_pad, scale, out,
-                     ld_out, vec_begin, want_stats ? 1 : 0, sinks_of(c, stats_out), spec_of(c));
+                     ld_out, vec_begin, stats_mode, sinks_of(c, stats_out), spec_of(c));
   return hipGetLastError();
 }
 
 hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
-                               double *stats_out, hipStream_t st) {
-  int64_t slots = (c->d + 4095) / 4096;
+                               double *stats_out, int stats_mode, int32_t *slots_used, hipStream_t st) {
+  int64_t slots = (c->d + 1023) / 1024;
   if (slots > c->stat_slots) slots = c->stat_slots;
   if (slots < 1) slots = 1;
   int64_t chunk = (c->d + slots - 1) / slots;
   slots = (c->d + chunk - 1) / chunk;
   const dim3 grid((unsigned)slots, (unsigned)nvec);
-  hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin,
+  hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin, stats_mode,
                      sinks_of(c, stats_out), spec_of(c));
+  if (slots_used) *slots_used = (int32_t)slots;
   return hipGetLastError();
 }
 
@@ -607,6 +743,27 @@ hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, cons
   return hipGetLastError();
 }
 
+bool fused_exchange_supported(const lpc_ctx *c) {
+  return c->quant && c->cfg.N <= kFusedMaxN && c->stat_slots <= 256;
+}
+
+// One launch for eq. (3), quantize, pack, eq. (4) and (optionally) the proximal step; reads the statistic
+// partials left by launch_reduce_parts(..., kStatsPartial, ...) for vectors 0..N-1.
+hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key, uint32_t *packed,
+                                 float *delta_out, const float *mu, float step, float *w, float *u_avg_out,
+                                 hipStream_t st) {
+  FusedArgs a{};
+  a.U = U; a.d = c->d; a.d_pad = c->d_pad; a.W = c->W;
+  a.N = c->cfg.N; a.bits = c->cfg.bits; a.nslots = nslots; a.stat_slots = c->stat_slots;
+  a.stat_part = c->s.stat_part; a.qs = spec_of(c); a.key = key;
+  a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
+  a.mu = mu; a.w = w; a.u_avg_out = u_avg_out; a.step = step; a.do_prox = w != nullptr ? 1 : 0;
+  prox_consts(c, step > 0.0f ? step : 1.0f, &a.thr, &a.shrink);
+  const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords));
+  hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_plain_avg(const lpc_ctx *c, const float *U, float *u_avg, hipStream_t st) {
   hipLaunchKernelGGL(plain_avg_kernel, grid1d(c->d, 256), dim3(256), 0, st, U, c->d, c->d_pad, c->cfg.N, u_avg);
   return hipGetLastError();
@@ -622,9 +779,19 @@ hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const flo
 hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, float scale, float *mu, double *f_out,
                                    bool want_loss, hipStream_t st) {
   if (mu) {
+    const float *src = c->s.part;
+    int32_t left = parts;
+    if (c->fold_slices > 1 && parts % c->fold_slices == 0) {
+      // first level: fold_slices groups of consecutive partial rows, all columns in parallel
+      const dim3 grid1((unsigned)((c->d + 63) / 64), (unsigned)c->fold_slices);
+      hipLaunchKernelGGL(reduce_parts_kernel, grid1, dim3(kThreads), 0, st, src, parts / c->fold_slices, c->d, c->d,
+                         1.0f, c->s.part2, c->d, 0, kStatsNone, sinks_of(c, nullptr), spec_of(c));
+      src = c->s.part2;
+      left = c->fold_slices;
+    }
     const dim3 grid((unsigned)((c->d + 63) / 64), 1u);
-    hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, (const float *)c->s.part, parts, c->d, c->d,
-                       scale, mu, c->d, 0, 0, sinks_of(c, nullptr), spec_of(c));
+    hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, src, left, c->d, c->d, scale, mu, c->d, 0,
+                       kStatsNone, sinks_of(c, nullptr), spec_of(c));
   }
   if (want_loss && f_out)
     hipLaunchKernelGGL(sum_loss_kernel, dim3(1), dim3(kThreads), 0, st, (const double *)c->s.part_loss, parts,

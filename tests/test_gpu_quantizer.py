@@ -146,3 +146,25 @@ def test_prox_step(d, l1, l2):
     assert np.allclose(got, ref, rtol=0, atol=2e-7 * max(1.0, np.abs(ref).max()))
     assert np.array_equal(got == 0, ref == 0) or np.mean((got == 0) != (ref == 0)) < 1e-4
     ctx.close()
+
+
+@pytest.mark.parametrize("d,N,bits,clip", [(64, 4, 2, 1.0), (4096, 8, 4, 0.9), (8192, 16, 3, 1.0), (1000, 5, 7, 0.5),
+                                           (4100, 64, 16, 1.0), (16384, 3, 5, 1.0),     # small-d single-launch path
+                                           (20_000, 4, 4, 0.9), (4096, 70, 2, 1.0)])    # large-d / many-worker path
+def test_exchange_one_call_bit_exact(d, N, bits, clip):
+    """lpc_exchange = statistics + eq. (3) + quantize/pack + eq. (4); every output bit-exact (lambda mode)."""
+    import torch
+    ctx, _ = _ctx(d, N, bits, 0, clip, seed=5)
+    U = _u(N, d, seed=3 * d + bits)
+    U[N - 1] = 0.0                                   # an all-zero worker
+    dU = to_dev(U)
+    for epoch, it in [(0, 0), (2, 9)]:
+        packed = torch.full((N, ctx.W), -1, dtype=torch.int32, device="cuda")
+        delta = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        avg = torch.full((d,), -1.0, dtype=torch.float32, device="cuda")
+        ctx.exchange(dU, epoch, it, packed, delta, avg)
+        po, do, _, _ = lpco.quantize_clip(U, d, bits, 0, clip, seed=5, epoch=epoch, iter_=it)
+        assert np.array_equal(delta.cpu().numpy(), do)
+        assert np.array_equal(packed.cpu().numpy().view(np.uint32), po)
+        assert np.array_equal(avg.cpu().numpy(), lpco.dequantize_avg(po, do, d, bits))
+    ctx.close()
