@@ -8,9 +8,10 @@ differences -> clip/quantize/pack -> dequantize+average -> prox).  Inputs are sy
 and resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` = inner iterations per second over whole steps (the snapshot pass
-included).  `roofline` covers the kernel that dominates the step; its duration is measured here
-with HIP events on the stream the library launches on.  `cpu_baseline` is the CPU oracle timed on
-a bounded sample of the same workload.
+included).  After the timed region the same steps are run once more with the library's event
+profiling on (HIP events on the launch stream around each kernel class); `kernels` lists every
+class, `roofline` is the class with the largest share of the step.  `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -24,19 +25,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 
-
-def event_time_ms(fn, reps, torch):
-    """Average duration of fn() in ms, HIP events on the current stream around `reps` back-to-back calls."""
-    start = torch.cuda.Event(enable_timing=True)
-    stop = torch.cuda.Event(enable_timing=True)
-    fn()
-    torch.cuda.synchronize()
-    start.record()
-    for _ in range(reps):
-        fn()
-    stop.record()
-    stop.synchronize()
-    return start.elapsed_time(stop) / reps
+KERNEL_NAMES = {
+    "full_rows": "dense_rows_kernel<mode 0> (lpc_full_grad: z = Xw and X'l' in one read of X)",
+    "full_fold": "reduce_parts_kernel x2 (fold of the snapshot pass's partial gradients)",
+    "vr_rows": "dense_rows_kernel<mode 1> (lpc_worker_vr_grad, all N workers in one launch)",
+    "vr_fold": "reduce_parts_kernel (fold of the workers' partials + statistics)",
+    "exchange": "fused_exchange_kernel (eq. 3 + quantize + pack + eq. 4 + prox)",
+}
 
 
 def main():
@@ -46,14 +41,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--small", action="store_true", help="scaled-down C2 (for a quick functional run)")
+    ap.add_argument("--small", action="store_true", help="scaled-down problem (quick functional run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the N workers are shards on one device); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     import lpc_synth
     from paper_1901_08924_amd import lpc
@@ -68,6 +62,7 @@ def main():
     y = torch.from_numpy(sp.y).to(dev)
     ctx = lpc.Context(sp.loss, y, lpc.make_config(**cfgkw), X=X, lambda1=sp.lambda1, lambda2=sp.lambda2)
     n, d, N, B, m, bits = sp.n, sp.d, sp.N, sp.B, sp.m, sp.bits
+    dp = lpc.d_pad(d)
     alpc = sp.algo != lpc.ALGO_LPC
     w = torch.from_numpy(sp.w0).to(dev)
     ya, za = (w.clone(), w.clone()) if alpc else (None, None)
@@ -90,37 +85,39 @@ def main():
     iters_per_sec = m * args.steps / elapsed
     P_end = ctx.objective(w)
 
-    # ---- per-call timings with HIP events (same stream as the library's launches) ----------
-    dp = lpc.d_pad(d)
-    mu = torch.zeros(d, device=dev)
-    z = torch.zeros(n, device=dev)
-    w2 = (w + 0.01 * torch.randn(d, device=dev)).contiguous()
-    U = torch.zeros(N, dp, device=dev)
-    stats = torch.zeros(N, 4, dtype=torch.float64, device=dev)
-    packed = torch.zeros(N, max(ctx.W, 1), dtype=torch.int32, device=dev)
-    delta = torch.zeros(N, device=dev)
-    uavg = torch.zeros(d, device=dev)
-    t_full = event_time_ms(lambda: ctx.full_grad(w, mu, z, None), 20, torch)
-    t_vr = event_time_ms(lambda: ctx.worker_vr_grad(w2, w, z, 0, 1, U, stats), 200, torch)
-    t_q = event_time_ms(lambda: ctx.quantize_clip(U, stats, None, 0, 1, packed, delta, None), 200, torch)
-    t_dq = event_time_ms(lambda: ctx.dequantize_avg(packed, delta, uavg), 200, torch)
-    t_px = event_time_ms(lambda: ctx.prox_step(w2, uavg, mu, 1e-9), 200, torch)
-    full_bytes = 4.0 * n * d + 4.0 * n + 4.0 * d + 4.0 * n + 4.0 * d     # X, y, w in; z, mu out
-    vr_bytes = 4.0 * N * B * d + 4.0 * N * d                             # sampled rows once + U
-    q_bytes = N * (4.0 * dp + bits * dp / 8.0 + 4.0)
-    t_inner_ms = ms_per_step - t_full
-    # the m inner iterations dominate the step; inside them the workers' gradient pass moves the bytes
-    roofline = {
-        "kernel": "lpc_full_grad (dense_rows_kernel mode 0 + partial reduction)",
-        "bound": "hbm",
-        "achieved": full_bytes / (t_full * 1e-3) / 1e9,
-        "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s",
-        "frac": full_bytes / (t_full * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "traffic": None,
-        "bytes_per_launch": full_bytes,
-        "ms_per_launch": t_full,
+    # ---- the same steps again with HIP events around every kernel class ---------------------
+    ctx.profile_enable(True)
+    s0 = args.warmup + args.steps
+    for s in range(s0, s0 + args.steps):
+        ctx.epoch(w, s, ya, za)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    # algorithmic bytes one launch of each class must move
+    algo_bytes = {
+        "full_rows": 4.0 * sp.n * d + 4.0 * n + 4.0 * d + 4.0 * n + 4.0 * d,   # X, y, w in; z, mu out
+        "vr_rows": 4.0 * N * B * d + 4.0 * N * d,                              # each sampled row once; U out
+        "exchange": N * (4.0 * dp + bits * dp / 8.0 + 4.0) + 12.0 * d + 4.0 * d,
     }
+    kernels = {}
+    for k, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        avg_ms = ms / cnt
+        ent = {"name": KERNEL_NAMES[k], "launches_per_step": cnt / args.steps, "avg_us": 1e3 * avg_ms,
+               "share_of_step": (ms / args.steps) / ms_per_step}
+        if k in algo_bytes:
+            gbps = algo_bytes[k] / (avg_ms * 1e-3) / 1e9
+            ent.update({"algorithmic_bytes": algo_bytes[k], "GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS})
+        kernels[k] = ent
+    rated = [k for k in kernels if "GBps" in kernels[k]]
+    dom = max(rated, key=lambda k: kernels[k]["share_of_step"])
+    roofline = {"kernel": kernels[dom]["name"], "bound": "hbm", "achieved": kernels[dom]["GBps"],
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": None,
+                "bytes_per_launch": kernels[dom]["algorithmic_bytes"], "us_per_launch": kernels[dom]["avg_us"],
+                "note": "a launch moves only 4*N*B*d bytes, so it is bound by launch and dependency latency, "
+                        "not by HBM; the HBM-bound kernel of the step is full_rows (see kernels)"
+                        if dom == "vr_rows" else ""}
+    t_full_ms = (prof["full_rows"][0] + prof["full_fold"][0]) / max(1, prof["full_rows"][1])
     out = {
         "metric": "svrg_inner_iters_per_sec",
         "value": iters_per_sec,
@@ -137,14 +134,12 @@ def main():
         "config": {"workload": "%s: dense %s n=%d d=%d N=%d B=%d bits=%d m=%d clip=%g"
                    % (sp.name, "logistic" if sp.loss == 0 else "squared", n, d, N, B, bits, m, sp.clip),
                    "step": "one lpc_epoch = full-gradient pass + m inner iterations"},
-        "full_grad_pass": {"ms": t_full, "algorithmic_GBps": full_bytes / (t_full * 1e-3) / 1e9,
-                           "frac_of_hbm_peak": full_bytes / (t_full * 1e-3) / 1e9 / HBM_PEAK_GBPS},
-        "inner_iters_per_sec_excluding_full_grad": m / (t_inner_ms * 1e-3) if t_inner_ms > 0 else None,
-        "per_call_ms": {"full_grad": t_full, "worker_vr_grad": t_vr, "quantize_clip": t_q,
-                        "dequantize_avg": t_dq, "prox_step": t_px},
-        "per_call_algorithmic_GBps": {"worker_vr_grad": vr_bytes / (t_vr * 1e-3) / 1e9,
-                                      "quantize_clip": q_bytes / (t_q * 1e-3) / 1e9},
+        "full_grad_pass": {"ms": t_full_ms, "algorithmic_GBps": algo_bytes["full_rows"] / (t_full_ms * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": algo_bytes["full_rows"] / (t_full_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                           "note": "rows kernel + fold kernels"},
+        "inner_iters_per_sec_excluding_full_grad": m / ((ms_per_step - t_full_ms) * 1e-3),
         "objective": {"start": P0, "end": P_end},
+        "kernels": kernels,
         "roofline": roofline,
     }
 
@@ -155,7 +150,7 @@ def main():
         ocfg = lpco.make_config(**cfgkw)
         wo = sp.w0.copy()
         yo, zo = (wo.copy(), wo.copy()) if alpc else (None, None)
-        n_ep = 3
+        n_ep = 16
         t0 = time.perf_counter()
         for s in range(n_ep):
             lpco.epoch(p, ocfg, wo, s, yo, zo)

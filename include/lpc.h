@@ -182,6 +182,23 @@ lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void 
  * call held a NaN or Inf, else LPC_OK. */
 lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream);
 
+/* ---- measurement aid (benchmarks; no passage of the paper) ------------------------------
+ * While enabled, every launch of the kernel classes below made by this context is bracketed by
+ * two HIP events on its stream (this allocates events and perturbs the pipeline slightly, so it
+ * is off by default).  lpc_profile_read synchronises the stream, returns per class the summed
+ * duration in milliseconds and the number of launches since the last read (two HOST arrays of
+ * LPC_PROF_NCLASS entries), and clears the records. */
+typedef enum {
+  LPC_PROF_FULL_ROWS = 0, /* snapshot pass: rows kernel                         */
+  LPC_PROF_FULL_FOLD = 1, /* snapshot pass: fold of the partial gradient rows   */
+  LPC_PROF_VR_ROWS = 2,   /* worker pass: rows kernel (all workers, one launch) */
+  LPC_PROF_VR_FOLD = 3,   /* worker pass: fold + statistics                     */
+  LPC_PROF_EXCHANGE = 4,  /* quantize/pack + dequantize/average + prox          */
+  LPC_PROF_NCLASS = 5
+} lpc_prof_class;
+lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on);
+lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

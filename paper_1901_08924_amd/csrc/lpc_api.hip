@@ -20,6 +20,26 @@ inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 
 bool is_csr(const lpc_problem &p) { return p.X == nullptr; }
 
+// Optional timing of kernel classes with HIP events on the launch stream (benchmarks only; the
+// events cost a little pipeline time, so the hot path leaves this off).
+struct ProfScope {
+  lpc_ctx *c;
+  hipStream_t st;
+  hipEvent_t stop = nullptr;
+  ProfScope(lpc_ctx *ctx, int cls, hipStream_t s) : c(ctx), st(s) {
+    if (!c->prof_on) return;
+    hipEvent_t start = nullptr;
+    if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
+    c->prof_start.push_back(start);
+    c->prof_stop.push_back(stop);
+    c->prof_cls.push_back(cls);
+    (void)hipEventRecord(start, st);
+  }
+  ~ProfScope() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
+
 lpc_status check_problem(const lpc_problem *p) {
   if (!p) return LPC_ENULL;
   if (p->n <= 0 || p->d <= 0) return LPC_ESHAPE;
@@ -152,8 +172,13 @@ StreamKey key_of(const lpc_ctx *c, uint32_t epoch, uint32_t iter) {
 lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, double *f_out, int64_t n_rows,
                           hipStream_t st) {
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
-  hipError_t e = launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
+  hipError_t e;
+  {
+    ProfScope ps(c, LPC_PROF_FULL_ROWS, st);
+    e = launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
+  }
   if (e != hipSuccess) return LPC_EDEVICE;
+  ProfScope ps(c, LPC_PROF_FULL_FOLD, st);
   e = launch_finish_full_grad(c, c->full_grad_wgs, (float)(1.0 / (double)n_rows), mu, f_out, f_out != nullptr, st);
   return dev(e);
 }
@@ -163,8 +188,13 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
                         uint32_t tag, int32_t wb, int32_t we, float *U_row0, double *stats_row0, int stats_mode,
                         hipStream_t st) {
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
-  hipError_t e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
+  hipError_t e;
+  {
+    ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+    e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
+  }
   if (e != hipSuccess) return LPC_EDEVICE;
+  ProfScope ps(c, LPC_PROF_VR_FOLD, st);
   const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
   e = launch_reduce_parts(c, c->s.part, c->vr_parts, (float)(1.0 / (double)c->cfg.B), U_row0, c->d_pad, slot0,
                           we - wb, stats_mode, stats_row0, st);
@@ -217,6 +247,7 @@ lpc_status alpc_params(const lpc_ctx *c, uint32_t epoch, AlpcParams *out) {
 // communication step 2 of one inner iteration followed by the update of Alg. 1
 lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st) {
   Scratch &s = c->s;
+  ProfScope ps(c, LPC_PROF_EXCHANGE, st);
   if (c->quant) {
     LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
     LPC_TRY_HIP(launch_dequantize_prox(c, s.packed, s.delta, s.mu, c->cfg.eta, w, nullptr, st));
@@ -278,7 +309,35 @@ lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_c
   return LPC_OK;
 }
 
-void lpc_destroy(lpc_ctx *ctx) { delete ctx; }
+void lpc_destroy(lpc_ctx *ctx) {
+  if (!ctx) return;
+  for (hipEvent_t e : ctx->prof_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ctx->prof_stop) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on) {
+  if (!ctx) return LPC_ENULL;
+  ctx->prof_on = on != 0;
+  return LPC_OK;
+}
+
+lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, void *stream) {
+  if (!ctx || !ms_total || !launches) return LPC_ENULL;
+  LPC_TRY_HIP(hipStreamSynchronize(as_stream(stream)));
+  for (int k = 0; k < LPC_PROF_NCLASS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
+  for (size_t i = 0; i < ctx->prof_cls.size(); ++i) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, ctx->prof_start[i], ctx->prof_stop[i]) == hipSuccess) {
+      ms_total[ctx->prof_cls[i]] += (double)ms;
+      launches[ctx->prof_cls[i]] += 1;
+    }
+    (void)hipEventDestroy(ctx->prof_start[i]);
+    (void)hipEventDestroy(ctx->prof_stop[i]);
+  }
+  ctx->prof_start.clear(); ctx->prof_stop.clear(); ctx->prof_cls.clear();
+  return LPC_OK;
+}
 
 lpc_status lpc_full_grad(lpc_ctx *ctx, const float *w, float *mu, float *z, double *f_out, void *stream) {
   if (!ctx || !w || !mu) return LPC_ENULL;
@@ -375,6 +434,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       if (fused) {
         // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st));
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
         LPC_TRY_HIP(launch_fused_exchange(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, s.mu, g.eta,
                                           s.w, nullptr, st));
       } else {

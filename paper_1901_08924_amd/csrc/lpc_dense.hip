@@ -34,6 +34,7 @@ struct DenseArgs {
   int64_t n_rows;       // snapshot pass
   int32_t loss;
   int32_t want_loss;
+  int32_t stream_loads;
   // worker pass
   StreamKey key;
   uint32_t tag;
@@ -67,6 +68,20 @@ __device__ __forceinline__ Chunk<VEC> load_chunk(const float *p) {
     c.v[0] = t.x; c.v[1] = t.y; c.v[2] = t.z; c.v[3] = t.w;
   } else {
     c.v[0] = *p;
+  }
+  return c;
+}
+
+// streamed-once data: non-temporal loads keep it from displacing what the caches should hold
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+template <int VEC>
+__device__ __forceinline__ Chunk<VEC> load_chunk_stream(const float *p) {
+  Chunk<VEC> c;
+  if constexpr (VEC == 4) {
+    const floatx4 t = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(p));
+    c.v[0] = t.x; c.v[1] = t.y; c.v[2] = t.z; c.v[3] = t.w;
+  } else {
+    c.v[0] = __builtin_nontemporal_load(p);
   }
   return c;
 }
@@ -151,7 +166,10 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         if (rowlive[r] && live[k]) {
-          x[r][k] = load_chunk<VEC>(xr + ((int64_t)k * T + tid) * VEC);
+          if (MODE == 0 && a.stream_loads)
+            x[r][k] = load_chunk_stream<VEC>(xr + ((int64_t)k * T + tid) * VEC);
+          else
+            x[r][k] = load_chunk<VEC>(xr + ((int64_t)k * T + tid) * VEC);
         } else {
 #pragma unroll
           for (int v = 0; v < VEC; ++v) x[r][k].v[v] = 0.0f;
@@ -287,9 +305,18 @@ bool dense_supported(int64_t d, int64_t ldx, const void *X) {
 // Workgroups of the snapshot pass: enough to keep every CU busy with several
 // resident groups, few enough that the partial-gradient rows stay a small
 // fraction of the traffic of X.
+// Measured on MI355X: the pass streams fastest with about 64 KB of rows in flight per workgroup and
+// about 128 KB per CU (two such workgroups); more resident workgroups lower the achieved bandwidth.
+int snapshot_rows_in_flight(int64_t d) {
+  const int64_t r = 65536 / (4 * d);
+  return r >= 4 ? 4 : (r >= 2 ? 2 : 1);
+}
+
 int dense_full_grad_wgs(int64_t n, int64_t d, int cus) {
-  (void)d;
-  int64_t wgs = (int64_t)cus * 3;         // three resident workgroups per CU, one scheduling round
+  const int64_t group_bytes = (int64_t)snapshot_rows_in_flight(d) * 4 * d;
+  int64_t per_cu = 131072 / group_bytes;
+  per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+  int64_t wgs = (int64_t)cus * per_cu;
   const int64_t by_rows = (n + 15) / 16;  // at least 16 rows per workgroup
   if (wgs > by_rows) wgs = by_rows;
   if (wgs < 1) wgs = 1;
@@ -315,11 +342,13 @@ hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bo
   a.w = w; a.z_out = z; a.part = c->s.part; a.part_loss = c->s.part_loss;
   a.n_rows = n_rows; a.loss = c->prob.loss; a.want_loss = want_loss ? 1 : 0;
   const int wgs = c->full_grad_wgs;
+  const int rows_hint = snapshot_rows_in_flight(c->d);
+  a.stream_loads = 1;  // X is read once per pass
   const int rg = rows_per_group(s);
   int64_t rpw = (n_rows + wgs - 1) / wgs;
   rpw = ((rpw + rg - 1) / rg) * rg;
   a.rows_per_wg = rpw;
-  return dispatch<0>(s, a, wgs, 4, st);
+  return dispatch<0>(s, a, wgs, rows_hint, st);
 }
 
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,

@@ -66,6 +66,9 @@ struct lpc_ctx {
   size_t part_floats;
   void *workspace;
   size_t workspace_bytes;
+  bool prof_on = false;   // kernel-class timing (lpc_profile_enable)
+  std::vector<hipEvent_t> prof_start, prof_stop;
+  std::vector<int> prof_cls;
   lpc::Scratch s;
 };
 

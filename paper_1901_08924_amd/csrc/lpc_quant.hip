@@ -444,6 +444,17 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
   __shared__ QParams qp[kFusedMaxN];
   __shared__ int32_t codes[kFusedMaxN][kFusedCoords];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int64_t tile0 = (int64_t)blockIdx.x * kFusedCoords;
+  // everything this thread will need from memory is requested before the statistics fold, so the three
+  // dependent round trips (statistics, U, w/mu) overlap
+  float4 v_first = make_float4(0.f, 0.f, 0.f, 0.f);
+  if ((tid >> 5) < a.N && tile0 + 4 * (tid & 31) < a.d_pad)
+    v_first = *reinterpret_cast<const float4 *>(a.U + (int64_t)(tid >> 5) * a.d_pad + tile0 + 4 * (tid & 31));
+  float w_old = 0.0f, mu_j = 0.0f;
+  if (a.do_prox && tid < kFusedCoords && tile0 + tid < a.d) {
+    w_old = a.w[tile0 + tid];
+    mu_j = a.mu[tile0 + tid];
+  }
   for (int32_t i = wv; i < a.N; i += 4) {
     double am, s, s2, b;
     fold_stat_slots(a.stat_part + (int64_t)i * a.stat_slots * 4, a.nslots, lane, am, s, s2, b);
@@ -459,7 +470,6 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
     }
   }
   __syncthreads();
-  const int64_t tile0 = (int64_t)blockIdx.x * kFusedCoords;
   {
     const int g = tid >> 5, l = tid & 31;
     const int64_t j = tile0 + 4 * l;
@@ -468,7 +478,7 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
     for (int32_t i = g; i < a.N; i += 8) {
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j < a.d_pad) {
-        v = *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + j);
+        v = (i == g) ? v_first : *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + j);
         if (j + 3 >= a.d) {
           if (j + 0 >= a.d) v.x = 0.f;
           if (j + 1 >= a.d) v.y = 0.f;
@@ -529,7 +539,7 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
       for (int32_t i = 0; i < a.N; ++i) acc = __builtin_fmaf(qp[i].delta, (float)codes[i][tid], acc);
       const float avg = acc * (1.0f / (float)a.N);
       if (a.u_avg_out) a.u_avg_out[j] = avg;
-      if (a.do_prox) a.w[j] = prox_scalar(a.w[j], avg + a.mu[j], a.step, a.thr, a.shrink);
+      if (a.do_prox) a.w[j] = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
     }
   }
 }

@@ -54,7 +54,10 @@ EXPORTS = {
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "lpc_take_device_flags": (C.c_int, [_vp, _vp]),
+    "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
+    "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), _vp]),
 }
+PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblpc_hip.so")
 
@@ -189,6 +192,16 @@ class Context:
         out = C.c_double()
         _chk(lib.lpc_objective(self._h, _ptr(w), C.byref(out), _stream(stream)), "lpc_objective")
         return out.value
+
+    def profile_enable(self, on):
+        _chk(lib.lpc_profile_enable(self._h, 1 if on else 0), "lpc_profile_enable")
+
+    def profile_read(self, stream=None):
+        """{class: (total ms, launches)} since the last read."""
+        ms = (C.c_double * len(PROF_CLASSES))()
+        cnt = (C.c_int64 * len(PROF_CLASSES))()
+        _chk(lib.lpc_profile_read(self._h, ms, cnt, _stream(stream)), "lpc_profile_read")
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_CLASSES)}
 
     def take_device_flags(self, stream=None):
         return lib.lpc_take_device_flags(self._h, _stream(stream))
