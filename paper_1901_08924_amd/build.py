@@ -20,6 +20,7 @@ SOURCES = [
     ("lpc_api.hip", []),
     ("lpc_quant.hip", ["-ffp-contract=off"]),
     ("lpc_dense.hip", []),
+    ("lpc_csr.hip", []),
 ]
 HEADERS = ["lpc_internal.h", "lpc_device.h"]
 

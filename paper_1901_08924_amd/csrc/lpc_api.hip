@@ -117,6 +117,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.u_avg = (float *)take((size_t)c->d * sizeof(float));
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
+  s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
   return off;
 }
 
@@ -143,7 +144,13 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   // calls answer LPC_EUNSUPPORTED.
   c->grad_ok = p->loss != LPC_LOSS_MLP_SOFTMAX && !is_csr(*p) && dense_supported(p->d, p->ldx, p->X);
   c->cus = 256;  // MI355X
-  if (c->grad_ok) {
+  c->csr = is_csr(*p);
+  if (c->csr && p->loss != LPC_LOSS_MLP_SOFTMAX) {
+    c->grad_ok = true;
+    c->full_grad_wgs = csr_full_grad_wgs(c->n_full);
+    c->vr_parts = 1;
+    c->part_floats = (size_t)c->full_grad_wgs * csr_head_columns(c->d);
+  } else if (c->grad_ok) {
     c->full_grad_wgs = dense_full_grad_wgs(c->n_full, c->d, c->cus);
     c->vr_parts = dense_vr_parts(c->d, cfg->N, cfg->B, c->cus);
     const size_t a1 = (size_t)c->full_grad_wgs * c->d;
@@ -175,29 +182,44 @@ lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, doubl
   hipError_t e;
   {
     ProfScope ps(c, LPC_PROF_FULL_ROWS, st);
-    e = launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
+    e = c->csr ? launch_csr_full_grad(c, w, mu, z, f_out != nullptr, n_rows, st)
+               : launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
   }
   if (e != hipSuccess) return LPC_EDEVICE;
   ProfScope ps(c, LPC_PROF_FULL_FOLD, st);
-  e = launch_finish_full_grad(c, c->full_grad_wgs, (float)(1.0 / (double)n_rows), mu, f_out, f_out != nullptr, st);
+  // dense: every column comes from the fold; CSR: the privatised head columns do
+  const int64_t cols = c->csr ? csr_head_columns(c->d) : c->d;
+  e = launch_finish_full_grad(c, c->full_grad_wgs, cols, (float)(1.0 / (double)n_rows), mu, f_out,
+                              f_out != nullptr, st);
   return dev(e);
 }
 
 // Alg. 1 step 6 for workers [wb, we) (or the shared batch): U rows and statistics
 lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap, StreamKey key,
                         uint32_t tag, int32_t wb, int32_t we, float *U_row0, double *stats_row0, int stats_mode,
-                        hipStream_t st) {
+                        hipStream_t st, int32_t *stat_slots_used = nullptr) {
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
   hipError_t e;
+  const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
+  if (c->csr) {
+    {
+      ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+      e = launch_csr_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, U_row0, st);
+    }
+    if (e != hipSuccess) return LPC_EDEVICE;
+    if (stats_mode == kStatsNone) return LPC_OK;
+    ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+    return dev(launch_vector_stats(c, U_row0, c->d_pad, slot0, we - wb, stats_row0, stats_mode, stat_slots_used, st));
+  }
   {
     ProfScope ps(c, LPC_PROF_VR_ROWS, st);
     e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
   }
   if (e != hipSuccess) return LPC_EDEVICE;
   ProfScope ps(c, LPC_PROF_VR_FOLD, st);
-  const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
   e = launch_reduce_parts(c, c->s.part, c->vr_parts, (float)(1.0 / (double)c->cfg.B), U_row0, c->d_pad, slot0,
                           we - wb, stats_mode, stats_row0, st);
+  if (stat_slots_used) *stat_slots_used = (int32_t)((c->d_pad + 63) / 64);
   return dev(e);
 }
 
@@ -433,10 +455,10 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       if (fused) {
         // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
-        LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st));
+        int32_t slots = 0;
+        LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st, &slots));
         ProfScope ps(c, LPC_PROF_EXCHANGE, st);
-        LPC_TRY_HIP(launch_fused_exchange(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, s.mu, g.eta,
-                                          s.w, nullptr, st));
+        LPC_TRY_HIP(launch_fused_exchange(c, s.U, slots, key, s.packed, s.delta, s.mu, g.eta, s.w, nullptr, st));
       } else {
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
                              c->quant ? kStatsFinal : kStatsNone, st));

@@ -47,6 +47,7 @@ struct Scratch {
   float *u_avg;         // [d]
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
+  float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
 };
 
 }  // namespace lpc
@@ -58,6 +59,7 @@ struct lpc_ctx {
   int64_t n, d, d_pad, W, n_full;
   bool quant;             // bits < 32
   bool grad_ok;           // the gradient passes are built for this problem
+  bool csr;               // rows are stored in CSR
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
   int32_t vr_parts;       // partial rows per worker written by the worker pass
   int32_t stat_slots;     // statistic partials per vector
@@ -87,6 +89,9 @@ hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w
                                 hipStream_t st);
 
 // CSR GLM passes (lpc_csr.hip)
+int csr_head_columns(int64_t d);
+int csr_full_grad_wgs(int64_t n);
+hipError_t launch_zero(float *dst, int64_t n, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
 hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
@@ -119,8 +124,8 @@ hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const flo
 // fused receiver + prox of Alg. 1: w <- prox(w - eta*(avg + mu)); optionally also stores the average
 hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, const float *delta, const float *mu,
                                   float step, float *w, float *u_avg_out, hipStream_t st);
-hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, float scale, float *mu, double *f_out,
-                                   bool want_loss, hipStream_t st);
+hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, int64_t cols, float scale, float *mu,
+                                   double *f_out, bool want_loss, hipStream_t st);
 hipError_t launch_copy(float *dst, const float *src, int64_t n, hipStream_t st);
 hipError_t launch_fill_u32(uint32_t *dst, uint32_t v, int64_t n, hipStream_t st);
 // ALPC-SVRG element-wise steps (Alg. 2 steps 6, 13-15)

@@ -786,21 +786,22 @@ hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const flo
   return hipGetLastError();
 }
 
-hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, float scale, float *mu, double *f_out,
-                                   bool want_loss, hipStream_t st) {
+hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, int64_t cols, float scale, float *mu,
+                                   double *f_out, bool want_loss, hipStream_t st) {
+  // the partial rows are `cols` floats long; mu[0..cols) = scale * their sum
   if (mu) {
     const float *src = c->s.part;
     int32_t left = parts;
+    const dim3 grid((unsigned)((cols + 63) / 64), 1u);
     if (c->fold_slices > 1 && parts % c->fold_slices == 0) {
       // first level: fold_slices groups of consecutive partial rows, all columns in parallel
-      const dim3 grid1((unsigned)((c->d + 63) / 64), (unsigned)c->fold_slices);
-      hipLaunchKernelGGL(reduce_parts_kernel, grid1, dim3(kThreads), 0, st, src, parts / c->fold_slices, c->d, c->d,
-                         1.0f, c->s.part2, c->d, 0, kStatsNone, sinks_of(c, nullptr), spec_of(c));
+      const dim3 grid1(grid.x, (unsigned)c->fold_slices);
+      hipLaunchKernelGGL(reduce_parts_kernel, grid1, dim3(kThreads), 0, st, src, parts / c->fold_slices, cols, cols,
+                         1.0f, c->s.part2, cols, 0, kStatsNone, sinks_of(c, nullptr), spec_of(c));
       src = c->s.part2;
       left = c->fold_slices;
     }
-    const dim3 grid((unsigned)((c->d + 63) / 64), 1u);
-    hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, src, left, c->d, c->d, scale, mu, c->d, 0,
+    hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, src, left, cols, cols, scale, mu, cols, 0,
                        kStatsNone, sinks_of(c, nullptr), spec_of(c));
   }
   if (want_loss && f_out)

@@ -75,3 +75,13 @@ def test_epoch_is_reproducible():
     ctx.epoch(b, 0); ctx.epoch(b, 1)
     assert torch.equal(a, b)
     ctx.close()
+
+
+@pytest.mark.parametrize("d,bits", [(2048, 2), (40_000, 2), (40_000, 32)])
+def test_lpc_epochs_csr(d, bits):
+    # sparse rows: small-d single-launch exchange and the large-d path
+    sp = lpc_synth.make("c3", n=4096, d=d, nnz_mean=20, N=4, B=16)
+    hist, w_o, w_g = _run_both(sp, 3, bits=bits)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    assert hist[-1][0] < hist[0][0]

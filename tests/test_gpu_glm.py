@@ -100,3 +100,61 @@ def test_worker_vr_gradient(name, n, d, N, B, cached):
         ctx.worker_vr_grad(dws, dws, None, 0, 0, U, None)
         assert not U.any().item()
     ctx.close()
+
+
+# ---------------------------------------------------------------- CSR rows (sparse text-like design)
+
+CSR_SHAPES = [(2000, 512, 12), (5000, 20_000, 30), (3000, 100_000, 50), (700, 33, 5)]
+
+
+@pytest.mark.parametrize("n,d,nnz", CSR_SHAPES)
+def test_csr_full_gradient(n, d, nnz):
+    import torch
+    sp = lpc_synth.make("c3", n=n, d=d, nnz_mean=nnz, N=2, B=8)
+    ctx = gpu_context(sp)
+    p, _k = oracle_problem(sp)
+    w = (np.random.default_rng(1).standard_normal(d) * 2.0).astype(np.float32)
+    mu = torch.full((d,), 7.0, device="cuda")
+    z = torch.zeros(n, device="cuda")
+    f = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.full_grad(to_dev(w), mu, z, f)
+    mu_o, z_o, f_o = lpco.full_grad(p, w)
+    assert np.abs(mu.cpu().numpy() - mu_o).max() <= 1e-5 * np.abs(mu_o).max()
+    assert np.abs(z.cpu().numpy() - z_o).max() <= 1e-5 * max(1.0, np.abs(z_o).max())
+    assert abs(f.item() - f_o) <= 1e-5 * abs(f_o)
+    assert abs(ctx.objective(to_dev(w)) - lpco.objective(p, w)) <= 1e-5 * abs(lpco.objective(p, w))
+    ctx.close()
+
+
+@pytest.mark.parametrize("n,d,nnz", CSR_SHAPES)
+@pytest.mark.parametrize("cached", [True, False])
+def test_csr_worker_vr_gradient(n, d, nnz, cached):
+    import torch
+    N, B = 4, 16
+    sp = lpc_synth.make("c3", n=n, d=d, nnz_mean=nnz, N=N, B=B)
+    ctx = gpu_context(sp)
+    p, _k = oracle_problem(sp)
+    cfg = oracle_config(sp)
+    rng = np.random.default_rng(3)
+    ws = (rng.standard_normal(d) * 2.0).astype(np.float32)
+    w = (ws + 0.2 * rng.standard_normal(d)).astype(np.float32)
+    dw, dws = to_dev(w), to_dev(ws)
+    zs = None
+    if cached:
+        zs = torch.zeros(n, device="cuda")
+        ctx.full_grad(dws, torch.zeros(d, device="cuda"), zs, None)
+    dp = lpco.d_pad(d)
+    for kind, tag, rows in [(1, lpco.TAG_BATCH, N), (2, lpco.TAG_SHARED, 1)]:
+        U = torch.full((N, dp), 9.0, device="cuda")
+        stats = torch.zeros(N, 4, dtype=torch.float64, device="cuda")
+        ctx.worker_vr_grad(dw, dws, zs, 1, 3, U, stats, kind=kind)
+        U_o, st_o = lpco.worker_vr_grad(p, cfg, w, ws, 1, 3, tag=tag)
+        gB, _ = lpco.worker_vr_grad(p, cfg, w, np.zeros_like(ws), 1, 3, tag=tag)
+        got = U.cpu().numpy()[:rows]
+        for i in range(rows):
+            ref_scale = max(np.abs(gB[i]).max(), np.abs(U_o[i]).max())
+            assert np.abs(got[i] - U_o[i]).max() <= 2e-5 * ref_scale
+            assert np.array_equal(got[i] != 0, U_o[i] != 0) or np.abs(got[i][(got[i] != 0) != (U_o[i] != 0)]).max() < 1e-6 * ref_scale
+        sg = stats.cpu().numpy()[:rows]
+        assert np.array_equal(sg[:, 0], np.abs(got[:, :d]).max(axis=1).astype(np.float64))
+    ctx.close()
