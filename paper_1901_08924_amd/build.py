@@ -21,6 +21,8 @@ SOURCES = [
     ("lpc_quant.hip", ["-ffp-contract=off"]),
     ("lpc_dense.hip", []),
     ("lpc_csr.hip", []),
+    ("lpc_gemm.hip", []),
+    ("lpc_mlp.hip", []),
 ]
 HEADERS = ["lpc_internal.h", "lpc_device.h"]
 

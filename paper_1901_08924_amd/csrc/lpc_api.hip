@@ -118,6 +118,13 @@ size_t layout(lpc_ctx *c, char *base) {
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
   s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
+  if (c->mlp) {
+    s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
+    s.mlp_yb = (float *)take((size_t)c->mlp_rows * sizeof(float));
+    s.mlp_act = (float *)take((size_t)c->mlp_act_floats * sizeof(float));
+    s.mlp_del = (float *)take((size_t)c->mlp_act_floats * sizeof(float));
+    s.mlp_loss = (double *)take((size_t)c->mlp_rows * sizeof(double));
+  }
   return off;
 }
 
@@ -145,7 +152,14 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   c->grad_ok = p->loss != LPC_LOSS_MLP_SOFTMAX && !is_csr(*p) && dense_supported(p->d, p->ldx, p->X);
   c->cus = 256;  // MI355X
   c->csr = is_csr(*p);
-  if (c->csr && p->loss != LPC_LOSS_MLP_SOFTMAX) {
+  c->mlp = p->loss == LPC_LOSS_MLP_SOFTMAX;
+  if (c->mlp) {
+    mlp_plan(c);
+    c->grad_ok = true;
+    c->full_grad_wgs = 1;
+    c->vr_parts = 1;
+    c->part_floats = 64;
+  } else if (c->csr) {
     c->grad_ok = true;
     c->full_grad_wgs = csr_full_grad_wgs(c->n_full);
     c->vr_parts = 1;
@@ -182,6 +196,7 @@ lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, doubl
   hipError_t e;
   {
     ProfScope ps(c, LPC_PROF_FULL_ROWS, st);
+    if (c->mlp) return dev(launch_mlp_full_grad(c, w, mu, f_out, n_rows, st));
     e = c->csr ? launch_csr_full_grad(c, w, mu, z, f_out != nullptr, n_rows, st)
                : launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
   }
@@ -201,10 +216,11 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
   hipError_t e;
   const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
-  if (c->csr) {
+  if (c->csr || c->mlp) {
     {
       ProfScope ps(c, LPC_PROF_VR_ROWS, st);
-      e = launch_csr_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, U_row0, st);
+      e = c->mlp ? launch_mlp_vr_grad(c, w, w_snap, key, tag, wb, we, U_row0, st)
+                 : launch_csr_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, U_row0, st);
     }
     if (e != hipSuccess) return LPC_EDEVICE;
     if (stats_mode == kStatsNone) return LPC_OK;

@@ -1,0 +1,180 @@
+// fp32 matrix-core GEMM for the MLP instance of eq. (1) (gfx950).
+//
+//   C[m][n] (+)= alpha * sum_{segments} sum_k opA(m,k) * opB(k,n)   (+ bias[n], ReLU, ReLU-mask)
+//
+// The only dense contractions of the hot path are the MLP's layer products, so
+// this is where MFMA is used: v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate.
+// A workgroup of 4 wavefronts owns a 128x128 tile of C; each wavefront owns a
+// 64x64 quadrant = 2x2 MFMA tiles (64 accumulator registers).  The K loop runs
+// in slabs of 16: the next slab is fetched from global memory into registers
+// while the current one is consumed from LDS (stored k-major so that the 32
+// lanes of an MFMA operand read consecutive words).  Operands may be given
+// transposed (weight gradients A'D and data gradients D W' need it) and the K
+// range may consist of two segments with their own base pointers (the
+// difference of two weight gradients is one contraction over stacked rows).
+#include <hip/hip_runtime.h>
+
+#include "lpc_internal.h"
+
+namespace lpc {
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int LDT = BM + 4;  // LDS row pitch (floats)
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// element (r, c) of a row-major matrix with leading dimension ld, zero outside [0,R)x[0,C)
+__device__ __forceinline__ float guarded(const float *p, int64_t ld, int r, int c, int R, int C) {
+  return (r < R && c < C) ? p[(int64_t)r * ld + c] : 0.0f;
+}
+
+// Fetch this thread's share of a 128 x 16 operand slab into 8 registers.
+//   TRANS == false: the operand is stored [mn][k] (k contiguous).  Thread t takes rows (t/4) and (t/4)+64,
+//                   columns k0 + 4*(t%4) .. +3.
+//   TRANS == true : the operand is stored [k][mn] (mn contiguous).  Thread t takes rows k0 + t/32 and
+//                   k0 + t/32 + 8, columns 4*(t%32) .. +3.
+template <bool TRANS>
+__device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t ld, int mn0, int k0, int MN, int K,
+                                           bool vec_ok, int tid, float (&r)[8]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    int row, col, R, C;
+    if (!TRANS) { row = mn0 + (tid >> 2) + 64 * h; col = k0 + 4 * (tid & 3); R = MN; C = K; }
+    else        { row = k0 + (tid >> 5) + 8 * h;   col = mn0 + 4 * (tid & 31); R = K;  C = MN; }
+    if (vec_ok && row < R && col + 3 < C) {
+      const float4 v = *reinterpret_cast<const float4 *>(p + (int64_t)row * ld + col);
+      r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[4 * h + i] = guarded(p, ld, row, col + i, R, C);
+    }
+  }
+}
+
+// Store the registers k-major into an LDS slab T[k][mn].
+template <bool TRANS>
+__device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float (&r)[8]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    if (!TRANS) {
+      const int mn = (tid >> 2) + 64 * h, k = 4 * (tid & 3);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) T[k + i][mn] = r[4 * h + i];
+    } else {
+      const int k = (tid >> 5) + 8 * h, mn = 4 * (tid & 31);
+      *reinterpret_cast<float4 *>(&T[k][mn]) = make_float4(r[4 * h], r[4 * h + 1], r[4 * h + 2], r[4 * h + 3]);
+    }
+  }
+}
+
+template <bool TA, bool TB>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) float As[2][BK][LDT];
+  __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int64_t bz = blockIdx.z;
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  float ra[8], rb[8];
+  for (int s = 0; s < g.nseg; ++s) {
+    const float *A = g.A[s] + bz * g.strideA[s];
+    const float *B = g.B[s] + bz * g.strideB[s];
+    const int64_t lda = g.lda[s], ldb = g.ldb[s];
+    const bool va = (lda % 4 == 0) && (((uintptr_t)A & 15u) == 0);
+    const bool vb = (ldb % 4 == 0) && (((uintptr_t)B & 15u) == 0);
+    const int K = g.K;
+    const int nslab = (K + BK - 1) / BK;
+    fetch_slab<TA>(A, lda, m0, 0, g.M, K, va, tid, ra);
+    fetch_slab<!TB>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
+    __syncthreads();  // the previous segment's last slab has been consumed
+    stash_slab<TA>(As[0], tid, ra);
+    stash_slab<!TB>(Bs[0], tid, rb);
+    __syncthreads();
+    for (int t = 0; t < nslab; ++t) {
+      const int cur = t & 1;
+      if (t + 1 < nslab) {
+        fetch_slab<TA>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
+        fetch_slab<!TB>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
+      }
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 2) {
+        const int kr = kk + (lane >> 5), c = lane & 31;
+        const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
+        const float b0 = Bs[cur][kr][wn + c], b1 = Bs[cur][kr][wn + 32 + c];
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      }
+      if (t + 1 < nslab) {
+        // the other buffer was last read in iteration t-1, and every wave has passed the barrier since
+        stash_slab<TA>(As[cur ^ 1], tid, ra);
+        stash_slab<!TB>(Bs[cur ^ 1], tid, rb);
+      }
+      __syncthreads();
+    }
+  }
+
+  // Accumulator layout of the 32x32 MFMA: lane l holds column (l % 32); register v holds row
+  // 8*(v/4) + 4*(l/32) + (v%4).
+  float *C = g.C + bz * g.strideC;
+  const float *mask = g.relu_mask ? g.relu_mask + bz * g.strideC : nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = n0 + wn + 32 * j + (lane & 31);
+      if (col >= g.N) continue;
+      const float bias = g.bias ? g.bias[col] : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        const int64_t off = (int64_t)row * g.ldc + col;
+        float val = g.alpha * acc[i][j][v] + bias;
+        if (g.relu) val = val > 0.0f ? val : 0.0f;
+        if (mask) val = mask[off] > 0.0f ? val : 0.0f;
+        if (g.accumulate) val += C[off];
+        C[off] = val;
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// Validates shapes on the host (every access in the kernel is guarded by M, N, K).
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.nseg < 1 || g.nseg > 2 || g.batch < 1) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
+  if (!g.transA && !g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(256), 0, st, g);
+  else if (!g.transA && g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(256), 0, st, g);
+  else if (g.transA && !g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(256), 0, st, g);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(256), 0, st, g);
+  return hipGetLastError();
+}
+
+}  // namespace lpc
+
+// Exported for the unit test of the contraction itself (not part of include/lpc.h): all pointers are
+// device pointers, row-major, C is M x N.
+extern "C" int lpc_debug_gemm(const float *A, const float *B, float *C, int M, int N, int K, int64_t lda, int64_t ldb,
+                              int64_t ldc, int transA, int transB, float alpha, const float *bias, int relu,
+                              int accumulate, void *stream) {
+  lpc::GemmArgs g{};
+  g.A[0] = A; g.B[0] = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda[0] = lda; g.ldb[0] = ldb; g.ldc = ldc;
+  g.transA = transA; g.transB = transB; g.alpha = alpha; g.bias = bias; g.relu = relu; g.accumulate = accumulate;
+  g.nseg = 1; g.batch = 1;
+  return lpc::launch_gemm(g, (hipStream_t)stream) == hipSuccess ? 0 : -6;
+}

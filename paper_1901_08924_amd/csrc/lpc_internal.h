@@ -27,6 +27,25 @@ struct StreamKey {
   uint32_t seed_lo, seed_hi, epoch, iter;
 };
 
+// One (possibly batched, possibly two-segment) contraction on the matrix cores, see lpc_gemm.hip:
+//   C[m][n] (+)= alpha * sum_s sum_k opA_s(m,k) * opB_s(k,n)  (+ bias[n]) (ReLU) (masked by relu_mask > 0)
+// transA: A is stored [k][m] instead of [m][k]; transB: B is stored [n][k] instead of [k][n].
+struct GemmArgs {
+  const float *A[2];
+  const float *B[2];
+  int64_t lda[2], ldb[2], strideA[2], strideB[2];
+  float *C;
+  int64_t ldc, strideC;
+  int M, N, K;
+  int transA, transB;
+  float alpha;
+  const float *bias;
+  int relu;
+  const float *relu_mask;  // same layout as C
+  int accumulate;
+  int nseg, batch;
+};
+
 // ---- device scratch owned by a context (all pointers into the workspace) ----
 struct Scratch {
   float *part;          // partial gradient rows
@@ -48,6 +67,12 @@ struct Scratch {
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
   float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
+  // MLP instance: gathered inputs/labels and per-layer activations / deltas for the two parameter sets
+  float *mlp_xb;        // [rows][dims[0]]
+  float *mlp_yb;        // [rows]
+  float *mlp_act;       // layer l (1..L) at mlp_act + act_off[l]: [2][rows][dims[l]]
+  float *mlp_del;       // same layout as mlp_act
+  double *mlp_loss;     // [rows] per-row losses of the snapshot pass
 };
 
 }  // namespace lpc
@@ -60,6 +85,10 @@ struct lpc_ctx {
   bool quant;             // bits < 32
   bool grad_ok;           // the gradient passes are built for this problem
   bool csr;               // rows are stored in CSR
+  bool mlp;               // multi-layer perceptron instance
+  int64_t mlp_rows;       // rows per pass (N*B)
+  std::vector<int64_t> mlp_woff, mlp_boff, mlp_act_off;  // per layer offsets
+  int64_t mlp_act_floats;
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
   int32_t vr_parts;       // partial rows per worker written by the worker pass
   int32_t stat_slots;     // statistic partials per vector
@@ -97,6 +126,14 @@ hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, flo
 hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                               StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end, float *U,
                               hipStream_t st);
+
+// MLP instance (lpc_gemm.hip, lpc_mlp.hip)
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
+void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
+hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
+                                hipStream_t st);
+hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, StreamKey key, uint32_t tag,
+                              int32_t worker_begin, int32_t worker_end, float *U, hipStream_t st);
 
 // Reductions, statistics, quantizer, receiver, prox (lpc_quant.hip)
 // out[v][0..d_pad) = scale * sum_p part[(v*parts + p)*d + j] (zero beyond d), then statistics of each

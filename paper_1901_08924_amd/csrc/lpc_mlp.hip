@@ -1,0 +1,254 @@
+// ReLU multi-layer perceptron with softmax cross-entropy as an instance of
+// eq. (1) (gfx950): the snapshot gradient of Alg. 1 step 4 and the workers'
+// variance-reduced differences of Alg. 1 step 6 over the whole flattened
+// parameter vector (one scale factor per worker, Sec. 3.2 last paragraph).
+//
+// Parameter vector: layer by layer, weight matrix [in][out] row-major, then the
+// bias [out].  All contractions run on the matrix cores (lpc_gemm.hip):
+//   forward        H_l = relu(H_{l-1} W_l + b_l)                (rows x in) (in x out)
+//   data gradient  D_{l-1} = (D_l W_l') masked by H_{l-1} > 0   (rows x out) (out x in)
+//   weight grad    G_l = H_{l-1}' D_l                           (in x rows) (rows x out)
+// For the workers' differences the two parameter sets (x and the snapshot)
+// share the sampled rows: both forward/backward passes run over all N*B rows
+// at once (the weights are shared by the workers), the snapshot's deltas are
+// produced negated, and each worker's difference of weight gradients is ONE
+// contraction over its 2B stacked rows (for the first layer, whose input is the
+// same for both sets, over B rows with the two deltas added first).
+#include <hip/hip_runtime.h>
+
+#include "lpc_device.h"
+#include "lpc_internal.h"
+
+namespace lpc {
+
+namespace {
+
+// rows of X (and labels) for positions [0, rows): position r belongs to worker worker_begin + r/B
+__global__ void gather_rows_kernel(const float *__restrict__ X, int64_t ldx, const float *__restrict__ y, int64_t n,
+                                   int32_t in0, StreamKey key, uint32_t tag, int32_t worker_begin, int32_t B,
+                                   float *__restrict__ xb, float *__restrict__ yb) {
+  const int r = blockIdx.x;
+  const uint32_t worker = (tag == kTagShared) ? kSharedWorkerField : (uint32_t)(worker_begin + r / B);
+  const int64_t src = sample_row(key, tag, worker, (uint32_t)(r % B), n);
+  const float *xs = X + src * ldx;
+  float *xd = xb + (int64_t)r * in0;
+  for (int j = threadIdx.x; j < in0; j += blockDim.x) xd[j] = xs[j];
+  if (threadIdx.x == 0) yb[r] = y[src];
+}
+
+// delta = sign * (softmax(logits) - onehot(label)); optionally the row's loss
+__global__ void softmax_delta_kernel(const float *__restrict__ logits, const float *__restrict__ labels, int rows,
+                                     int classes, float sign, float *__restrict__ delta,
+                                     double *__restrict__ row_loss) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  const float *z = logits + (int64_t)r * classes;
+  float mx = z[0];
+  for (int c = 1; c < classes; ++c) mx = fmaxf(mx, z[c]);
+  float sum = 0.0f;
+  for (int c = 0; c < classes; ++c) sum += expf(z[c] - mx);
+  const int label = (int)labels[r];
+  const float inv = 1.0f / sum;
+  for (int c = 0; c < classes; ++c)
+    delta[(int64_t)r * classes + c] = sign * (expf(z[c] - mx) * inv - (c == label ? 1.0f : 0.0f));
+  if (row_loss) row_loss[r] = (double)(logf(sum) + mx - z[label]);
+}
+
+__global__ void add_inplace_kernel(float *__restrict__ a, const float *__restrict__ b, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) a[i] += b[i];
+}
+
+// out[b][c] (+)= alpha * sum over the K rows of batch item b of (D0[row][c] + D1[row][c])
+__global__ void colsum_kernel(const float *__restrict__ D0, const float *__restrict__ D1, int K, int cols,
+                              float alpha, int accumulate, float *__restrict__ out, int64_t out_stride) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  const int b = blockIdx.y;
+  if (c >= cols) return;
+  const float *p0 = D0 + (int64_t)b * K * cols + c;
+  const float *p1 = D1 ? D1 + (int64_t)b * K * cols + c : nullptr;
+  float s = 0.0f;
+  for (int k = 0; k < K; ++k) s += p0[(int64_t)k * cols] + (p1 ? p1[(int64_t)k * cols] : 0.0f);
+  float *o = out + (int64_t)b * out_stride + c;
+  *o = accumulate ? *o + alpha * s : alpha * s;
+}
+
+__global__ void sum_rows_loss_kernel(const double *__restrict__ row_loss, int rows, double scale, int accumulate,
+                                     double *__restrict__ f_out) {
+  __shared__ double red[4];
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  for (int r = tid; r < rows; r += 256) acc += row_loss[r];
+  acc = wave_sum(acc);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    const double t = (((red[0] + red[1]) + red[2]) + red[3]) * scale;
+    *f_out = accumulate ? *f_out + t : t;
+  }
+}
+
+__global__ void zero_tail_kernel(float *__restrict__ U, int64_t d, int64_t d_pad, int nvec) {
+  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t pad = d_pad - d;
+  if (k < pad * nvec) U[(k / pad) * d_pad + d + (k % pad)] = 0.0f;
+}
+
+struct Net {
+  int L;
+  const int32_t *dims;
+  const lpc_ctx *c;
+  int64_t rows_cap;  // rows the activation buffers were sized for
+  float *act(int l, int set) const { return c->s.mlp_act + c->mlp_act_off[l] + (int64_t)set * rows_cap * dims[l]; }
+  float *del(int l, int set) const { return c->s.mlp_del + c->mlp_act_off[l] + (int64_t)set * rows_cap * dims[l]; }
+};
+
+// forward pass of `rows` rows whose inputs start at in0 (leading dimension ld0) with parameters W into set `set`
+hipError_t forward(const Net &nn, const float *W, const float *in0, int64_t ld0, int rows, int set, hipStream_t st) {
+  for (int l = 0; l < nn.L; ++l) {
+    GemmArgs g{};
+    g.A[0] = l == 0 ? in0 : nn.act(l, set);
+    g.lda[0] = l == 0 ? ld0 : nn.dims[l];
+    g.B[0] = W + nn.c->mlp_woff[l];
+    g.ldb[0] = nn.dims[l + 1];
+    g.C = nn.act(l + 1, set);
+    g.ldc = nn.dims[l + 1];
+    g.M = rows; g.N = nn.dims[l + 1]; g.K = nn.dims[l];
+    g.alpha = 1.0f; g.bias = W + nn.c->mlp_boff[l]; g.relu = (l + 1 < nn.L) ? 1 : 0;
+    g.nseg = 1; g.batch = 1;
+    hipError_t e = launch_gemm(g, st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// deltas of every layer from the logits down; sign = -1 produces the negated deltas of the snapshot set
+hipError_t backward_data(const Net &nn, const float *W, const float *labels, int rows, int set, float sign,
+                         double *row_loss, hipStream_t st) {
+  const int classes = nn.dims[nn.L];
+  hipLaunchKernelGGL(softmax_delta_kernel, dim3((unsigned)((rows + 127) / 128)), dim3(128), 0, st,
+                     (const float *)nn.act(nn.L, set), labels, rows, classes, sign, nn.del(nn.L, set), row_loss);
+  for (int l = nn.L - 1; l >= 1; --l) {
+    GemmArgs g{};
+    g.A[0] = nn.del(l + 1, set); g.lda[0] = nn.dims[l + 1];
+    g.B[0] = W + nn.c->mlp_woff[l]; g.ldb[0] = nn.dims[l + 1]; g.transB = 1;  // W_l is [in][out]; we need W_l'
+    g.C = nn.del(l, set); g.ldc = nn.dims[l];
+    g.M = rows; g.N = nn.dims[l]; g.K = nn.dims[l + 1];
+    g.alpha = 1.0f; g.relu_mask = nn.act(l, set);
+    g.nseg = 1; g.batch = 1;
+    hipError_t e = launch_gemm(g, st);
+    if (e != hipSuccess) return e;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+void mlp_plan(lpc_ctx *c) {
+  const int L = c->prob.mlp_nlayers;
+  const int32_t *dims = c->mlp_dims.data();
+  c->mlp_rows = (int64_t)c->cfg.N * c->cfg.B;
+  c->mlp_woff.assign(L, 0);
+  c->mlp_boff.assign(L, 0);
+  c->mlp_act_off.assign(L + 1, 0);
+  int64_t off = 0, aoff = 0;
+  for (int l = 0; l < L; ++l) {
+    c->mlp_woff[l] = off; off += (int64_t)dims[l] * dims[l + 1];
+    c->mlp_boff[l] = off; off += dims[l + 1];
+  }
+  for (int l = 1; l <= L; ++l) {
+    c->mlp_act_off[l] = aoff;
+    aoff += 2 * c->mlp_rows * dims[l];
+    aoff = (aoff + 63) / 64 * 64;
+  }
+  c->mlp_act_floats = aoff;
+}
+
+// Alg. 1 step 4 for the MLP: mean gradient (and loss) over the first n_rows samples, in chunks of N*B rows.
+hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
+                                hipStream_t st) {
+  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_rows};
+  const float alpha = (float)(1.0 / (double)n_rows);
+  for (int64_t r0 = 0; r0 < n_rows; r0 += c->mlp_rows) {
+    const int rows = (int)((n_rows - r0 < c->mlp_rows) ? n_rows - r0 : c->mlp_rows);
+    const float *in0 = c->prob.X + r0 * c->prob.ldx;
+    const float *labels = c->prob.y + r0;
+    hipError_t e = forward(nn, w, in0, c->prob.ldx, rows, 0, st);
+    if (e != hipSuccess) return e;
+    e = backward_data(nn, w, labels, rows, 0, 1.0f, f_out ? c->s.mlp_loss : nullptr, st);
+    if (e != hipSuccess) return e;
+    if (f_out)
+      hipLaunchKernelGGL(sum_rows_loss_kernel, dim3(1), dim3(256), 0, st, (const double *)c->s.mlp_loss, rows,
+                         (double)alpha, r0 > 0 ? 1 : 0, f_out);
+    if (!mu) continue;
+    for (int l = 0; l < nn.L; ++l) {
+      GemmArgs g{};
+      g.A[0] = l == 0 ? in0 : nn.act(l, 0); g.lda[0] = l == 0 ? c->prob.ldx : nn.dims[l]; g.transA = 1;
+      g.B[0] = nn.del(l + 1, 0); g.ldb[0] = nn.dims[l + 1];
+      g.C = mu + c->mlp_woff[l]; g.ldc = nn.dims[l + 1];
+      g.M = nn.dims[l]; g.N = nn.dims[l + 1]; g.K = rows;
+      g.alpha = alpha; g.accumulate = r0 > 0 ? 1 : 0; g.nseg = 1; g.batch = 1;
+      e = launch_gemm(g, st);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((nn.dims[l + 1] + 127) / 128), 1u), dim3(128), 0, st,
+                         (const float *)nn.del(l + 1, 0), (const float *)nullptr, rows, nn.dims[l + 1], alpha,
+                         r0 > 0 ? 1 : 0, mu + c->mlp_boff[l], (int64_t)0);
+    }
+  }
+  return hipGetLastError();
+}
+
+// Alg. 1 step 6 for the MLP: u^i = grad f_{B_i}(w) - grad f_{B_i}(w_snap) for workers [worker_begin, worker_end)
+// (or the one shared batch), written to consecutive rows of U (row stride d_pad).
+hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, StreamKey key, uint32_t tag,
+                              int32_t worker_begin, int32_t worker_end, float *U, hipStream_t st) {
+  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_rows};
+  const int nw = worker_end - worker_begin, B = c->cfg.B, rows = nw * B;
+  const int in0 = nn.dims[0];
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, c->prob.X, c->prob.ldx, c->prob.y,
+                     c->n, in0, key, tag, worker_begin, B, c->s.mlp_xb, c->s.mlp_yb);
+  hipError_t e;
+  for (int set = 0; set < 2; ++set) {
+    const float *W = set == 0 ? w : w_snap;
+    e = forward(nn, W, c->s.mlp_xb, in0, rows, set, st);
+    if (e != hipSuccess) return e;
+    e = backward_data(nn, W, c->s.mlp_yb, rows, set, set == 0 ? 1.0f : -1.0f, nullptr, st);
+    if (e != hipSuccess) return e;
+  }
+  const float alpha = (float)(1.0 / (double)B);
+  for (int l = nn.L - 1; l >= 0; --l) {
+    const int out = nn.dims[l + 1], in = nn.dims[l];
+    // bias: column sums of the two delta sets over the worker's rows
+    hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 127) / 128), (unsigned)nw), dim3(128), 0, st,
+                       (const float *)nn.del(l + 1, 0), (const float *)nn.del(l + 1, 1), B, out, alpha, 0,
+                       U + c->mlp_boff[l], c->d_pad);
+    GemmArgs g{};
+    g.transA = 1;
+    g.C = U + c->mlp_woff[l]; g.ldc = out; g.strideC = c->d_pad;
+    g.M = in; g.N = out; g.K = B; g.alpha = alpha; g.batch = nw;
+    if (l == 0) {
+      // same input rows for both sets: add the deltas first, contract once
+      const int64_t cnt = (int64_t)rows * out;
+      hipLaunchKernelGGL(add_inplace_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, nn.del(1, 0),
+                         (const float *)nn.del(1, 1), cnt);
+      g.nseg = 1;
+      g.A[0] = c->s.mlp_xb; g.lda[0] = in; g.strideA[0] = (int64_t)B * in;
+      g.B[0] = nn.del(1, 0); g.ldb[0] = out; g.strideB[0] = (int64_t)B * out;
+    } else {
+      g.nseg = 2;
+      for (int set = 0; set < 2; ++set) {
+        g.A[set] = nn.act(l, set); g.lda[set] = in; g.strideA[set] = (int64_t)B * in;
+        g.B[set] = nn.del(l + 1, set); g.ldb[set] = out; g.strideB[set] = (int64_t)B * out;
+      }
+    }
+    e = launch_gemm(g, st);
+    if (e != hipSuccess) return e;
+  }
+  if (c->d_pad > c->d) {
+    const int64_t cnt = (c->d_pad - c->d) * nw;
+    hipLaunchKernelGGL(zero_tail_kernel, dim3((unsigned)((cnt + 63) / 64)), dim3(64), 0, st, U, c->d, c->d_pad, nw);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lpc
