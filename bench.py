@@ -1,17 +1,18 @@
 #!/usr/bin/env python3
-"""Benchmark of the LPC-SVRG hot path on one MI355X.
+"""Benchmark of the LPC-SVRG / ALPC-SVRG hot path on one MI355X.
 
-A "step" is one pass of the whole hot path: one lpc_epoch on configuration C2 (dense L1+L2
-logistic regression, n=65536, d=4096, N=8 simulated workers, minibatch 64 per worker, b=4 bits,
-m=128 inner iterations) = the snapshot full-gradient pass, then 128 x (workers' variance-reduced
-differences -> clip/quantize/pack -> dequantize+average -> prox).  Inputs are synthetic, seeded,
-and resident in HBM before the timed region.
+A "step" is one pass of the whole hot path: one lpc_epoch = the snapshot full-gradient pass, then
+m inner iterations of (workers' variance-reduced differences -> clip/quantize/pack ->
+dequantize+average -> prox [+ ALPC double sampling]).  The default workload is configuration C2
+(dense L1+L2 logistic regression, n=65536, d=4096, N=8 workers, minibatch 64 per worker, b=4 bits,
+m=128); --workload c1|c3|c4|c5 selects the other configurations.  Inputs are synthetic, seeded, and
+resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` = inner iterations per second over whole steps (the snapshot pass
 included).  After the timed region the same steps are run once more with the library's event
 profiling on (HIP events on the launch stream around each kernel class); `kernels` lists every
-class, `roofline` is the class with the largest share of the step.  `cpu_baseline` is the CPU oracle
-timed on a bounded sample of the same workload.
+class with its algorithmic bytes (or flops) per launch, `roofline` is the class with the largest
+share of the step.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -23,23 +24,82 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published peak
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 
 KERNEL_NAMES = {
-    "full_rows": "dense_rows_kernel<mode 0> (lpc_full_grad: z = Xw and X'l' in one read of X)",
-    "full_fold": "reduce_parts_kernel x2 (fold of the snapshot pass's partial gradients)",
-    "vr_rows": "dense_rows_kernel<mode 1> (lpc_worker_vr_grad, all N workers in one launch)",
-    "vr_fold": "reduce_parts_kernel (fold of the workers' partials + statistics)",
-    "exchange": "fused_exchange_kernel (eq. 3 + quantize + pack + eq. 4 + prox)",
+    "full_rows": "snapshot pass (lpc_full_grad): rows kernel(s)",
+    "full_fold": "snapshot pass: fold of the partial gradient rows",
+    "vr_rows": "worker pass (lpc_worker_vr_grad): all workers' sampled rows",
+    "vr_fold": "worker pass: fold / statistics of U",
+    "exchange": "exchange: eq. (3) + quantize + pack + eq. (4) + prox",
 }
+
+
+def algorithmic_work(sp, dp, nnz):
+    """Per launch of each kernel class: (amount, 'bytes' | 'flops'), as counted from what the method must move."""
+    n, d, N, B, bits = sp.n, sp.d, sp.N, sp.B, sp.bits
+    n_full = sp.n_full or n
+    msg = N * (4.0 * dp + (bits * dp / 8.0 if bits < 32 else 0.0) + 4.0) + 16.0 * d
+    if sp.loss == 2:      # MLP: contractions on the matrix cores
+        dims = sp.mlp_dims
+        mac = sum(dims[l] * dims[l + 1] for l in range(len(dims) - 1))
+        fwd_bwd_w = 2.0 * mac * 3            # forward, weight gradient, data gradient (first layer has none)
+        bwd_first = 2.0 * dims[0] * dims[1]
+        rows = N * B
+        vr = rows * (2 * (fwd_bwd_w - bwd_first)) - rows * 2.0 * dims[0] * dims[1]   # layer-1 weight grad once
+        return {"full_rows": (n_full * (fwd_bwd_w - bwd_first), "flops"), "vr_rows": (vr, "flops"),
+                "exchange": (msg, "bytes")}
+    if sp.csr is not None:
+        return {"full_rows": (8.0 * nnz * n_full / n + 4.0 * (n_full + 1) + 8.0 * n_full + 8.0 * d, "bytes"),
+                "vr_rows": (8.0 * N * B * nnz / n + 8.0 * N * dp, "bytes"),     # rows + zero and write U
+                "exchange": (msg, "bytes")}
+    return {"full_rows": (4.0 * n_full * d + 8.0 * n_full + 8.0 * d, "bytes"),  # X, y, w in; z, mu out
+            "vr_rows": (4.0 * N * B * d + 4.0 * N * d, "bytes"),               # each sampled row once; U out
+            "exchange": (msg, "bytes")}
+
+
+def cpu_baseline(sp, cfgkw, alpc):
+    """The oracle as it stands, one host thread, on a bounded sample of the workload."""
+    from oracle import lpco
+    sample = dict(cfgkw)
+    scale, note = 1.0, ""
+    if sp.name == "c5":       # one inner iteration of the full size is ~1 minute of plain loops: shrink the batch
+        sample.update(N=2, B=4, m=1, n_full=8)
+        scale = (sample["N"] * sample["B"]) / float(sp.N * sp.B)
+        note = " with N=2, B=4, snapshot over 8 rows; rate scaled by sampled rows per iteration"
+        epochs = 1
+    elif sp.name == "c3":
+        sample.update(m=16)
+        epochs = 1
+    elif sp.name == "c4":
+        sample.update(m=64)
+        epochs = 1
+    else:
+        epochs = 16 if sp.name == "c2" else 200
+    if sp.csr is not None:
+        p, _keep = lpco.make_problem(sp.loss, sp.y, sp.lambda1, sp.lambda2, csr=(*sp.csr, sp.d))
+    else:
+        p, _keep = lpco.make_problem(sp.loss, sp.y, sp.lambda1, sp.lambda2, X=sp.X, d=sp.d, mlp_dims=sp.mlp_dims)
+    ocfg = lpco.make_config(**sample)
+    wo = sp.w0.copy()
+    yo, zo = (wo.copy(), wo.copy()) if alpc else (None, None)
+    t0 = time.perf_counter()
+    for s in range(epochs):
+        lpco.epoch(p, ocfg, wo, s, yo, zo)
+    tc = time.perf_counter() - t0
+    iters = sample["m"] * epochs
+    return {"value": iters / tc * scale, "unit": "inner iterations/s", "cores": 1, "kind": "oracle",
+            "sample": "%d epoch(s) of %d inner iterations (snapshot pass included)%s: %.1f s"
+                      % (epochs, sample["m"], note, tc)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="scaled-down problem (quick functional run)")
     args = ap.parse_args()
@@ -47,6 +107,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the N workers are shards on one device); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    default_steps = {"c1": 50, "c2": 20, "c3": 3, "c4": 5, "c5": 3}[args.workload]
+    steps = args.steps if args.steps is not None else default_steps
+    warmup = args.warmup if args.warmup is not None else (3 if args.workload in ("c1", "c2") else 1)
 
     import torch
     import lpc_synth
@@ -54,15 +117,15 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    over = dict(n=4096, d=1024) if args.small else {}
-    sp = lpc_synth.make(args.workload, **over)
+    small = {"c1": {}, "c2": dict(n=4096, d=1024), "c3": dict(n=1 << 14, d=1 << 14), "c4": dict(n=4096, d=1024),
+             "c5": dict(n=2048, dims=(256, 128, 128, 10), n_full=512, m=4)}[args.workload]
+    sp = lpc_synth.make(args.workload, **(small if args.small else {}))
     cfgkw = dict(algo=sp.algo, N=sp.N, B=sp.B, m=sp.m, bits=sp.bits, clip_mode=sp.clip_mode, clip=sp.clip,
                  eta=sp.eta, L=sp.L, seed=sp.seed, n_full=sp.n_full)
-    X = torch.from_numpy(sp.X).to(dev)
-    y = torch.from_numpy(sp.y).to(dev)
-    ctx = lpc.Context(sp.loss, y, lpc.make_config(**cfgkw), X=X, lambda1=sp.lambda1, lambda2=sp.lambda2)
+    ctx = lpc.context_from_problem(sp)
     n, d, N, B, m, bits = sp.n, sp.d, sp.N, sp.B, sp.m, sp.bits
     dp = lpc.d_pad(d)
+    nnz = int(sp.csr[2].size) if sp.csr is not None else 0
     alpc = sp.algo != lpc.ALGO_LPC
     w = torch.from_numpy(sp.w0).to(dev)
     ya, za = (w.clone(), w.clone()) if alpc else (None, None)
@@ -73,91 +136,88 @@ def main():
 
     # ---- the timed region: K whole epochs --------------------------------------------------
     P0 = ctx.objective(w)
-    for s in range(args.warmup):
+    for s in range(warmup):
         ctx.epoch(w, s, ya, za)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for s in range(args.warmup, args.warmup + args.steps):
+    for s in range(warmup, warmup + steps):
         ctx.epoch(w, s, ya, za)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
-    iters_per_sec = m * args.steps / elapsed
+    ms_per_step = 1e3 * elapsed / steps
+    iters_per_sec = m * steps / elapsed
     P_end = ctx.objective(w)
 
     # ---- the same steps again with HIP events around every kernel class ---------------------
     ctx.profile_enable(True)
-    s0 = args.warmup + args.steps
-    for s in range(s0, s0 + args.steps):
+    s0 = warmup + steps
+    for s in range(s0, s0 + steps):
         ctx.epoch(w, s, ya, za)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    # algorithmic bytes one launch of each class must move
-    algo_bytes = {
-        "full_rows": 4.0 * sp.n * d + 4.0 * n + 4.0 * d + 4.0 * n + 4.0 * d,   # X, y, w in; z, mu out
-        "vr_rows": 4.0 * N * B * d + 4.0 * N * d,                              # each sampled row once; U out
-        "exchange": N * (4.0 * dp + bits * dp / 8.0 + 4.0) + 12.0 * d + 4.0 * d,
-    }
+    work = algorithmic_work(sp, dp, nnz)
     kernels = {}
     for k, (ms, cnt) in prof.items():
         if cnt == 0:
             continue
         avg_ms = ms / cnt
-        ent = {"name": KERNEL_NAMES[k], "launches_per_step": cnt / args.steps, "avg_us": 1e3 * avg_ms,
-               "share_of_step": (ms / args.steps) / ms_per_step}
-        if k in algo_bytes:
-            gbps = algo_bytes[k] / (avg_ms * 1e-3) / 1e9
-            ent.update({"algorithmic_bytes": algo_bytes[k], "GBps": gbps, "frac_of_hbm_peak": gbps / HBM_PEAK_GBPS})
+        ent = {"name": KERNEL_NAMES[k], "launches_per_step": cnt / steps, "avg_us": 1e3 * avg_ms,
+               "share_of_step": (ms / steps) / ms_per_step}
+        if k in work:
+            amount, kind = work[k]
+            rate = amount / (avg_ms * 1e-3)
+            if kind == "bytes":
+                ent.update({"bound": "hbm", "algorithmic_bytes": amount, "achieved": rate / 1e9, "unit": "GB/s",
+                            "peak": HBM_PEAK_GBPS, "frac": rate / 1e9 / HBM_PEAK_GBPS})
+            else:
+                ent.update({"bound": "mfma", "algorithmic_flops": amount, "achieved": rate / 1e12, "unit": "TFLOP/s",
+                            "peak": MFMA_FP32_PEAK_TFLOPS, "frac": rate / 1e12 / MFMA_FP32_PEAK_TFLOPS})
         kernels[k] = ent
-    rated = [k for k in kernels if "GBps" in kernels[k]]
+    rated = [k for k in kernels if "frac" in kernels[k]]
     dom = max(rated, key=lambda k: kernels[k]["share_of_step"])
-    roofline = {"kernel": kernels[dom]["name"], "bound": "hbm", "achieved": kernels[dom]["GBps"],
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": kernels[dom]["frac_of_hbm_peak"], "traffic": None,
-                "bytes_per_launch": kernels[dom]["algorithmic_bytes"], "us_per_launch": kernels[dom]["avg_us"],
-                "note": "a launch moves only 4*N*B*d bytes, so it is bound by launch and dependency latency, "
-                        "not by HBM; the HBM-bound kernel of the step is full_rows (see kernels)"
-                        if dom == "vr_rows" else ""}
+    kd = kernels[dom]
+    roofline = {"kernel": kd["name"], "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": None, "us_per_launch": kd["avg_us"],
+                "launches_per_step": kd["launches_per_step"]}
+    if dom == "vr_rows" and kd["bound"] == "hbm" and kd["avg_us"] < 20:
+        roofline["note"] = ("one launch moves only %.1f MB, so it is bound by launch and dependency latency, not by "
+                            "HBM; the HBM-bound kernel of the step is the snapshot pass (kernels.full_rows)"
+                            % (kd["algorithmic_bytes"] / 1e6))
     t_full_ms = (prof["full_rows"][0] + prof["full_fold"][0]) / max(1, prof["full_rows"][1])
     out = {
         "metric": "svrg_inner_iters_per_sec",
         "value": iters_per_sec,
         "unit": "inner iterations/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: dense %s n=%d d=%d N=%d B=%d bits=%d m=%d clip=%g"
-                   % (sp.name, "logistic" if sp.loss == 0 else "squared", n, d, N, B, bits, m, sp.clip),
-                   "step": "one lpc_epoch = full-gradient pass + m inner iterations"},
-        "full_grad_pass": {"ms": t_full_ms, "algorithmic_GBps": algo_bytes["full_rows"] / (t_full_ms * 1e-3) / 1e9,
-                           "frac_of_hbm_peak": algo_bytes["full_rows"] / (t_full_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                           "note": "rows kernel + fold kernels"},
+        "config": {"workload": "%s%s: %s n=%d d=%d%s N=%d B=%d bits=%d m=%d clip=%s%g algo=%s"
+                   % (sp.name, " (scaled down)" if args.small else "",
+                      {0: "logistic", 1: "squared loss", 2: "MLP softmax"}[sp.loss] + (" CSR" if sp.csr else " dense"),
+                      n, d, " nnz=%d" % nnz if nnz else "", N, B, bits, m, "c*sigma " if sp.clip_mode else "lambda ",
+                      sp.clip, {0: "LPC-SVRG", 1: "ALPC-SVRG (Alg. 2)", 2: "ALPC-SVRG (Alg. 3)"}[sp.algo]),
+                   "step": "one lpc_epoch = snapshot full-gradient pass + m inner iterations"},
+        "full_grad_pass": {"ms": t_full_ms, "note": "rows kernel(s) + fold"},
         "inner_iters_per_sec_excluding_full_grad": m / ((ms_per_step - t_full_ms) * 1e-3),
         "objective": {"start": P0, "end": P_end},
         "kernels": kernels,
         "roofline": roofline,
     }
-
-    # ---- the CPU oracle on a bounded sample of the same workload ---------------------------
+    if "frac" in kernels.get("full_rows", {}):
+        amount, kind = work["full_rows"]
+        rate = amount / (t_full_ms * 1e-3)
+        out["full_grad_pass"].update({"achieved": rate / (1e9 if kind == "bytes" else 1e12),
+                                      "unit": "GB/s" if kind == "bytes" else "TFLOP/s",
+                                      "frac_of_peak": rate / (1e9 * HBM_PEAK_GBPS if kind == "bytes"
+                                                              else 1e12 * MFMA_FP32_PEAK_TFLOPS)})
     if not args.no_cpu_baseline:
-        from oracle import lpco
-        p, _keep = lpco.make_problem(sp.loss, sp.y, sp.lambda1, sp.lambda2, X=sp.X)
-        ocfg = lpco.make_config(**cfgkw)
-        wo = sp.w0.copy()
-        yo, zo = (wo.copy(), wo.copy()) if alpc else (None, None)
-        n_ep = 16
-        t0 = time.perf_counter()
-        for s in range(n_ep):
-            lpco.epoch(p, ocfg, wo, s, yo, zo)
-        tc = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": m * n_ep / tc, "unit": "inner iterations/s", "cores": 1, "kind": "oracle",
-                               "sample": "%d whole epochs of the same workload (%d inner iterations), %.1f s"
-                                         % (n_ep, m * n_ep, tc)}
+        out["cpu_baseline"] = cpu_baseline(sp, cfgkw, alpc)
     ctx.close()
     print(json.dumps(out))
 

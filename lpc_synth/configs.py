@@ -125,14 +125,20 @@ def make_c3(seed=0, n=1 << 20, d=1 << 20, nnz_mean=50, N=16, B=256, bits=2, epoc
 
 def make_c4(seed=0, n=262144, d=8192, rho=0.5, N=16, B=64, bits=3, epochs=5, clip=2.0, algo=ALGO_ALPC_GC):
     """Ridge least squares with AR(1)-correlated columns for the accelerated variant."""
+    from scipy.signal import lfilter
     rng = np.random.default_rng(seed)
-    X = rng.standard_normal((n, d), dtype=np.float32)
-    s = np.float32(np.sqrt(1.0 - rho * rho))
-    for j in range(1, d):                       # x_j = rho x_{j-1} + sqrt(1-rho^2) eps_j
-        X[:, j] = np.float32(rho) * X[:, j - 1] + s * X[:, j]
+    X = np.empty((n, d), dtype=np.float32)
+    s = float(np.sqrt(1.0 - rho * rho))
+    L = 0.0
+    block = max(1, (1 << 25) // d)              # x_0 = eps_0, x_j = rho x_{j-1} + sqrt(1-rho^2) eps_j, row by row
+    for r0 in range(0, n, block):
+        eps = rng.standard_normal((min(block, n - r0), d), dtype=np.float32)
+        eps[:, 0] /= np.float32(s)
+        xb = lfilter([s], [1.0, -rho], eps, axis=1).astype(np.float32)
+        X[r0:r0 + xb.shape[0]] = xb
+        L = max(L, float(np.max(np.einsum("ij,ij->i", xb, xb, dtype=np.float64))))
     w_star = (rng.standard_normal(d) / np.sqrt(d)).astype(np.float32)
     y = (X @ w_star + 0.1 * rng.standard_normal(n).astype(np.float32)).astype(np.float32)
-    L = float(np.max(np.einsum("ij,ij->i", X, X, dtype=np.float64)))
     return SynthProblem(name="c4", loss=LOSS_SQUARED, n=n, d=d, X=X, y=y, w0=np.zeros(d, np.float32),
                         lambda1=0.0, lambda2=1e-3, algo=algo, N=N, B=B, m=max(1, n // (N * B)), bits=bits,
                         clip_mode=CLIP_CSIGMA, clip=clip, eta=0.1 / L, L=L, epochs=epochs, seed=seed,

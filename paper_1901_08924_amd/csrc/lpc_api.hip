@@ -229,7 +229,7 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
   }
   {
     ProfScope ps(c, LPC_PROF_VR_ROWS, st);
-    e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, st);
+    e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, false, st);
   }
   if (e != hipSuccess) return LPC_EDEVICE;
   ProfScope ps(c, LPC_PROF_VR_FOLD, st);
@@ -491,16 +491,48 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   const float step_y = (float)(1.0 / (4.0 * (double)g.L));
   double weight = 1.0, wsum = 0.0;
   float *u_hat = s.U + (int64_t)g.N * c->d_pad;
+  if (!c->csr && !c->mlp && fused_exchange_supported(c)) {
+    // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
+    // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
+    LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
+    for (int32_t t = 0; t < g.m; ++t) {
+      const StreamKey key = key_of(c, epoch, (uint32_t)t);
+      {
+        ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+        LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, true, st));
+      }
+      {
+        ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+        LPC_TRY_HIP(launch_reduce_parts(c, s.part, c->vr_parts, (float)(1.0 / (double)g.B), s.U, c->d_pad, 0,
+                                        g.N + 1, kStatsPartial, nullptr, st));
+      }
+      AlpcStep al{};
+      al.x = s.w; al.u_hat = u_hat; al.w_snap = w_snap; al.mu = s.mu;
+      al.y = y; al.z = z; al.ysum = s.ysum; al.x_next = s.w;
+      al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
+      al.first = t == 0 ? 1 : 0;
+      ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+      LPC_TRY_HIP(launch_fused_exchange_alpc(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, al,
+                                             st));
+      wsum += weight;
+      weight *= (double)ap.theta;
+    }
+    LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
+    return LPC_OK;
+  }
   for (int32_t t = 0; t < g.m; ++t) {
     const StreamKey key = key_of(c, epoch, (uint32_t)t);
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
     LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
                          c->quant ? kStatsFinal : kStatsNone, st));
-    if (c->quant) {
-      LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
-      LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
-    } else {
-      LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
+    {
+      ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+      if (c->quant) {
+        LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+        LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
+      } else {
+        LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
+      }
     }
     // double sampling: the shared batch J, full precision
     LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagShared, 0, 1, u_hat, nullptr, kStatsNone, st));

@@ -40,6 +40,7 @@ struct DenseArgs {
   uint32_t tag;
   int32_t worker_begin;
   int32_t B, parts, rows_per_part;
+  int32_t shared_rel;  // relative worker index that draws the shared batch J instead (-1: none)
 };
 
 __device__ __forceinline__ float loss_slope(int32_t loss, float z, float y) {
@@ -127,14 +128,15 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
   }
 
   int64_t pos_begin, pos_end;
-  uint32_t worker = 0;
+  uint32_t worker = 0, tag = a.tag;
   if constexpr (MODE == 0) {
     pos_begin = (int64_t)blockIdx.x * a.rows_per_wg;
     pos_end = pos_begin + a.rows_per_wg;
     if (pos_end > a.n_rows) pos_end = a.n_rows;
   } else {
     const int32_t wrel = blockIdx.x / a.parts, part = blockIdx.x % a.parts;
-    worker = (a.tag == kTagShared) ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
+    if (wrel == a.shared_rel) tag = kTagShared;
+    worker = (tag == kTagShared) ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
     pos_begin = (int64_t)part * a.rows_per_part;
     pos_end = pos_begin + a.rows_per_part;
     if (pos_end > a.B) pos_end = a.B;
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
       if constexpr (MODE == 0) {
         row[r] = g0 + r;
       } else {
-        row[r] = rowlive[r] ? sample_row(a.key, a.tag, worker, (uint32_t)(g0 + r), a.n) : 0;
+        row[r] = rowlive[r] ? sample_row(a.key, tag, worker, (uint32_t)(g0 + r), a.n) : 0;
       }
       // labels and cached margins are requested together with the rows, not after the reduction
       yv[r] = rowlive[r] ? a.y[row[r]] : 0.0f;
@@ -353,7 +355,7 @@ hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bo
 
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                                 StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end,
-                                hipStream_t st) {
+                                bool plus_shared, hipStream_t st) {
   Shape s;
   if (!pick_shape(c->d, c->prob.ldx, c->prob.X, &s)) return hipErrorInvalidValue;
   DenseArgs a{};
@@ -362,7 +364,8 @@ hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w
   a.loss = c->prob.loss; a.key = key; a.tag = tag; a.worker_begin = worker_begin;
   a.B = c->cfg.B; a.parts = c->vr_parts;
   a.rows_per_part = (c->cfg.B + c->vr_parts - 1) / c->vr_parts;
-  const int grid = (worker_end - worker_begin) * c->vr_parts;
+  a.shared_rel = plus_shared ? worker_end - worker_begin : -1;
+  const int grid = (worker_end - worker_begin + (plus_shared ? 1 : 0)) * c->vr_parts;
   return z_snap ? dispatch<1>(s, a, grid, a.rows_per_part, st) : dispatch<2>(s, a, grid, a.rows_per_part, st);
 }
 

@@ -113,9 +113,10 @@ int dense_full_grad_wgs(int64_t n, int64_t d, int cus);
 int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus);
 hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,
                                   hipStream_t st);
+// plus_shared: one more vector after the workers', drawn from the shared batch J (double sampling)
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                                 StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end,
-                                hipStream_t st);
+                                bool plus_shared, hipStream_t st);
 
 // CSR GLM passes (lpc_csr.hip)
 int csr_head_columns(int64_t d);
@@ -148,6 +149,15 @@ bool fused_exchange_supported(const lpc_ctx *c);
 hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key, uint32_t *packed,
                                  float *delta_out, const float *mu, float step, float *w, float *u_avg_out,
                                  hipStream_t st);
+// Alg. 2 steps 13-15 and the next step 6 as the epilogue of the exchange launch
+struct AlpcStep {
+  const float *x, *u_hat, *w_snap, *mu;
+  float *y, *z, *ysum, *x_next;
+  float step_y, alpha, weight, tau1, tau2;
+  int first;
+};
+hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key,
+                                      uint32_t *packed, float *delta_out, const AlpcStep &al, hipStream_t st);
 hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
                                double *stats_out, int stats_mode, int32_t *slots_used, hipStream_t st);
 hipError_t launch_prepare_qparams(const lpc_ctx *c, const double *stats, const float *delta_in, int32_t nvec,

@@ -193,14 +193,26 @@ __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__r
   const int64_t lo = (int64_t)blockIdx.x * chunk;
   const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
   double amax = 0.0, sum = 0.0, sumsq = 0.0, bad = 0.0;
-  for (int64_t j = lo + tid; j < hi; j += kThreads) {
-    const float v = u[j];
-    if (isfinite(v)) {
-      amax = fmax(amax, fabs((double)v)); sum += (double)v; sumsq += (double)v * (double)v;
+  float fmx = 0.0f;
+  // chunk is a multiple of 4 and rows are 16-byte aligned: 16-byte loads, scalar tail at the end of the row
+  for (int64_t j = lo + 4 * (int64_t)tid; j < hi; j += 4 * kThreads) {
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (j + 4 <= hi) {
+      const float4 t = *reinterpret_cast<const float4 *>(u + j);
+      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
-      bad += 1.0;
+      for (int k = 0; k < 4 && j + k < hi; ++k) v[k] = u[j + k];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (isfinite(v[k])) {
+        fmx = fmaxf(fmx, fabsf(v[k])); sum += (double)v[k]; sumsq += (double)v[k] * (double)v[k];
+      } else {
+        bad += 1.0;
+      }
     }
   }
+  amax = (double)fmx;
   amax = wave_max(amax); sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
   if (lane == 0) { red[wv][0] = amax; red[wv][1] = sum; red[wv][2] = sumsq; red[wv][3] = bad; }
   __syncthreads();
@@ -438,6 +450,12 @@ struct FusedArgs {
   float *u_avg_out;
   float step, thr, shrink;
   int32_t do_prox;
+  // ALPC-SVRG epilogue (Alg. 2 steps 13-15 and the next step 6) instead of the plain proximal step
+  int32_t do_alpc;
+  const float *x, *u_hat, *w_snap;
+  float *y, *z, *ysum, *x_next;
+  float step_y, thr_y, shrink_y, alpha, thr_z, shrink_z, weight, t1, t2, t3;
+  int32_t first;
 };
 
 __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
@@ -540,6 +558,15 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
       const float avg = acc * (1.0f / (float)a.N);
       if (a.u_avg_out) a.u_avg_out[j] = avg;
       if (a.do_prox) a.w[j] = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
+      if (a.do_alpc) {
+        const float m = a.mu[j];
+        const float yn = prox_scalar(a.x[j], avg + m, a.step_y, a.thr_y, a.shrink_y);   // low-precision gradient
+        const float zn = prox_scalar(a.z[j], a.u_hat[j] + m, a.alpha, a.thr_z, a.shrink_z);  // full precision
+        a.y[j] = yn;
+        a.z[j] = zn;
+        a.ysum[j] = a.first ? a.weight * yn : a.ysum[j] + a.weight * yn;
+        a.x_next[j] = (a.t1 * zn + a.t2 * a.w_snap[j]) + a.t3 * yn;
+      }
     }
   }
 }
@@ -673,11 +700,16 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
 
 hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
                                double *stats_out, int stats_mode, int32_t *slots_used, hipStream_t st) {
-  int64_t slots = (c->d + 1023) / 1024;
-  if (slots > c->stat_slots) slots = c->stat_slots;
-  if (slots < 1) slots = 1;
-  int64_t chunk = (c->d + slots - 1) / slots;
-  slots = (c->d + chunk - 1) / chunk;
+  // 1K..32K coordinates per workgroup: short vectors spread wide (latency), long ones keep the number of
+  // statistic partials (and of fenced arrivals) small
+  int64_t chunk = ((c->d / 64 + 1023) / 1024) * 1024;
+  chunk = chunk < 1024 ? 1024 : (chunk > 32768 ? 32768 : chunk);
+  int64_t slots = (c->d + chunk - 1) / chunk;
+  if (slots > c->stat_slots) {  // cannot happen for chunk >= 64, kept as a guard for the scratch layout
+    slots = c->stat_slots;
+    chunk = (((c->d + slots - 1) / slots) + 3) / 4 * 4;
+    slots = (c->d + chunk - 1) / chunk;
+  }
   const dim3 grid((unsigned)slots, (unsigned)nvec);
   hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin, stats_mode,
                      sinks_of(c, stats_out), spec_of(c));
@@ -769,6 +801,24 @@ hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslot
   a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
   a.mu = mu; a.w = w; a.u_avg_out = u_avg_out; a.step = step; a.do_prox = w != nullptr ? 1 : 0;
   prox_consts(c, step > 0.0f ? step : 1.0f, &a.thr, &a.shrink);
+  const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords));
+  hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key,
+                                      uint32_t *packed, float *delta_out, const AlpcStep &al, hipStream_t st) {
+  FusedArgs a{};
+  a.U = U; a.d = c->d; a.d_pad = c->d_pad; a.W = c->W;
+  a.N = c->cfg.N; a.bits = c->cfg.bits; a.nslots = nslots; a.stat_slots = c->stat_slots;
+  a.stat_part = c->s.stat_part; a.qs = spec_of(c); a.key = key;
+  a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
+  a.mu = al.mu; a.do_alpc = 1;
+  a.x = al.x; a.u_hat = al.u_hat; a.w_snap = al.w_snap; a.y = al.y; a.z = al.z; a.ysum = al.ysum; a.x_next = al.x_next;
+  a.step_y = al.step_y; a.alpha = al.alpha; a.weight = al.weight; a.first = al.first;
+  a.t1 = al.tau1; a.t2 = al.tau2; a.t3 = (float)(1.0 - (double)al.tau1 - (double)al.tau2);
+  prox_consts(c, al.step_y, &a.thr_y, &a.shrink_y);
+  prox_consts(c, al.alpha, &a.thr_z, &a.shrink_z);
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords));
   hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kThreads), 0, st, a);
   return hipGetLastError();

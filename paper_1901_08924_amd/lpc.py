@@ -205,3 +205,22 @@ class Context:
 
     def take_device_flags(self, stream=None):
         return lib.lpc_take_device_flags(self._h, _stream(stream))
+
+
+def context_from_problem(sp, **over):
+    """Upload a synthetic problem description (fields as in lpc_synth.SynthProblem) and create its context.
+
+    `over` overrides run parameters (N, B, m, bits, clip_mode, clip, eta, ...).
+    """
+    import numpy as np
+    dev = torch.device("cuda:0")
+    kw = dict(algo=sp.algo, N=sp.N, B=sp.B, m=sp.m, bits=sp.bits, clip_mode=sp.clip_mode, clip=sp.clip, eta=sp.eta,
+              L=sp.L, seed=sp.seed, n_full=sp.n_full)
+    kw.update(over)
+    cfg = make_config(**kw)
+    y = torch.from_numpy(sp.y).to(dev)
+    if sp.csr is not None:
+        rp, ci, va = (torch.from_numpy(np.ascontiguousarray(a)).to(dev) for a in sp.csr)
+        return Context(sp.loss, y, cfg, csr=(rp, ci, va, sp.d), lambda1=sp.lambda1, lambda2=sp.lambda2)
+    X = torch.from_numpy(sp.X).to(dev)
+    return Context(sp.loss, y, cfg, X=X, d=sp.d, mlp_dims=sp.mlp_dims, lambda1=sp.lambda1, lambda2=sp.lambda2)
