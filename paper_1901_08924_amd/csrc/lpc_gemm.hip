@@ -35,14 +35,16 @@ __device__ __forceinline__ float guarded(const float *p, int64_t ld, int r, int 
 //                   columns k0 + 4*(t%4) .. +3.
 //   TRANS == true : the operand is stored [k][mn] (mn contiguous).  Thread t takes rows k0 + t/32 and
 //                   k0 + t/32 + 8, columns 4*(t%32) .. +3.
-template <bool TRANS>
+// TILE (128 or 64) is the slab's extent along m (or n); a 64-wide slab needs one 16-byte load per thread.
+template <bool TRANS, int TILE>
 __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t ld, int mn0, int k0, int MN, int K,
                                            bool vec_ok, int tid, float (&r)[8]) {
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
+  for (int h = 0; h < TILE / 64; ++h) {
     int row, col, R, C;
     if (!TRANS) { row = mn0 + (tid >> 2) + 64 * h; col = k0 + 4 * (tid & 3); R = MN; C = K; }
-    else        { row = k0 + (tid >> 5) + 8 * h;   col = mn0 + 4 * (tid & 31); R = K;  C = MN; }
+    else if (TILE == 128) { row = k0 + (tid >> 5) + 8 * h; col = mn0 + 4 * (tid & 31); R = K; C = MN; }
+    else { row = k0 + (tid >> 4); col = mn0 + 4 * (tid & 15); R = K; C = MN; }
     if (vec_ok && row < R && col + 3 < C) {
       const float4 v = *reinterpret_cast<const float4 *>(p + (int64_t)row * ld + col);
       r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
@@ -54,35 +56,39 @@ __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t 
 }
 
 // Store the registers k-major into an LDS slab T[k][mn].
-template <bool TRANS>
+template <bool TRANS, int TILE>
 __device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float (&r)[8]) {
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
+  for (int h = 0; h < TILE / 64; ++h) {
     if (!TRANS) {
       const int mn = (tid >> 2) + 64 * h, k = 4 * (tid & 3);
 #pragma unroll
       for (int i = 0; i < 4; ++i) T[k + i][mn] = r[4 * h + i];
     } else {
-      const int k = (tid >> 5) + 8 * h, mn = 4 * (tid & 31);
+      const int k = TILE == 128 ? (tid >> 5) + 8 * h : (tid >> 4);
+      const int mn = TILE == 128 ? 4 * (tid & 31) : 4 * (tid & 15);
       *reinterpret_cast<float4 *>(&T[k][mn]) = make_float4(r[4 * h], r[4 * h + 1], r[4 * h + 2], r[4 * h + 3]);
     }
   }
 }
 
-template <bool TA, bool TB>
+// TN = 128: 128x128 tile, each wavefront 64x64 (2x2 MFMA tiles).  TN = 64: 128x64 tile, each wavefront
+// 64x32 (2x1) -- twice as many workgroups for outputs too small to fill the chip with 128x128 tiles.
+template <bool TA, bool TB, int TN>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
+  constexpr int NJ = TN / 64;
   __shared__ __attribute__((aligned(16))) float As[2][BK][LDT];
   __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int wm = (wave >> 1) * 64, wn = (wave & 1) * (TN / 2);
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * TN;
   const int64_t bz = blockIdx.z;
 
-  floatx16 acc[2][2];
+  floatx16 acc[2][NJ];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
@@ -95,32 +101,35 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const bool vb = (ldb % 4 == 0) && (((uintptr_t)B & 15u) == 0);
     const int K = g.K;
     const int nslab = (K + BK - 1) / BK;
-    fetch_slab<TA>(A, lda, m0, 0, g.M, K, va, tid, ra);
-    fetch_slab<!TB>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
+    fetch_slab<TA, BM>(A, lda, m0, 0, g.M, K, va, tid, ra);
+    fetch_slab<!TB, TN>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
     __syncthreads();  // the previous segment's last slab has been consumed
-    stash_slab<TA>(As[0], tid, ra);
-    stash_slab<!TB>(Bs[0], tid, rb);
+    stash_slab<TA, BM>(As[0], tid, ra);
+    stash_slab<!TB, TN>(Bs[0], tid, rb);
     __syncthreads();
     for (int t = 0; t < nslab; ++t) {
       const int cur = t & 1;
       if (t + 1 < nslab) {
-        fetch_slab<TA>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
-        fetch_slab<!TB>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
+        fetch_slab<TA, BM>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
+        fetch_slab<!TB, TN>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
       }
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
         const int kr = kk + (lane >> 5), c = lane & 31;
         const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
-        const float b0 = Bs[cur][kr][wn + c], b1 = Bs[cur][kr][wn + 32 + c];
+        const float b0 = Bs[cur][kr][wn + c];
         acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
         acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        if constexpr (NJ == 2) {
+          const float b1 = Bs[cur][kr][wn + 32 + c];
+          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
       }
       if (t + 1 < nslab) {
         // the other buffer was last read in iteration t-1, and every wave has passed the barrier since
-        stash_slab<TA>(As[cur ^ 1], tid, ra);
-        stash_slab<!TB>(Bs[cur ^ 1], tid, rb);
+        stash_slab<TA, BM>(As[cur ^ 1], tid, ra);
+        stash_slab<!TB, TN>(Bs[cur ^ 1], tid, rb);
       }
       __syncthreads();
     }
@@ -133,7 +142,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + (lane & 31);
       if (col >= g.N) continue;
       const float bias = g.bias ? g.bias[col] : 0.0f;
@@ -157,11 +166,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 // Validates shapes on the host (every access in the kernel is guarded by M, N, K).
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.nseg < 1 || g.nseg > 2 || g.batch < 1) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
-  if (!g.transA && !g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(256), 0, st, g);
-  else if (!g.transA && g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(256), 0, st, g);
-  else if (g.transA && !g.transB) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(256), 0, st, g);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(256), 0, st, g);
+  const int64_t tiles128 = (int64_t)((g.N + 127) / 128) * ((g.M + BM - 1) / BM) * g.batch;
+  const bool narrow = tiles128 < 512 || g.N <= 64;   // fewer than two 128x128 tiles per CU: halve the tile
+  const int tn = narrow ? 64 : 128;
+  const dim3 grid((unsigned)((g.N + tn - 1) / tn), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
+#define LPC_GEMM_LAUNCH(TA_, TB_)                                                                          \
+  do {                                                                                                     \
+    if (narrow) hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 64>), grid, dim3(256), 0, st, g);            \
+    else hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 128>), grid, dim3(256), 0, st, g);                  \
+  } while (0)
+  if (!g.transA && !g.transB) LPC_GEMM_LAUNCH(false, false);
+  else if (!g.transA && g.transB) LPC_GEMM_LAUNCH(false, true);
+  else if (g.transA && !g.transB) LPC_GEMM_LAUNCH(true, false);
+  else LPC_GEMM_LAUNCH(true, true);
+#undef LPC_GEMM_LAUNCH
   return hipGetLastError();
 }
 

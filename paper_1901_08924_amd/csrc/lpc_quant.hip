@@ -100,13 +100,12 @@ __device__ inline void fold_stat_slots(const volatile double *p, int32_t nslots,
   a = wave_max(a); s = wave_sum(s); s2 = wave_sum(s2); b = wave_sum(b);
 }
 
-// Wave 0 of a workgroup publishes the statistics of its slice.  In kStatsFinal mode the last
-// workgroup to arrive for a vector folds all slices in a fixed order, so the result does not depend
-// on scheduling; in kStatsPartial mode the consumer kernel does that fold itself (no fences, no
-// atomics on the critical path of a short kernel).
-__device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, int mode, int32_t vec, int32_t rel,
-                                     int32_t slot, int32_t nslots, int64_t d, double amax, double sum, double sumsq,
-                                     double bad, bool *s_last) {
+// Wave 0 of a workgroup publishes the statistics of its slice as one partial.  The fold of the partials
+// is done by the consumer: the finalize kernel below, or the small-d exchange kernel itself.  (A
+// "last workgroup folds" scheme needs a device-scope fence per workgroup, which on a multi-XCD part
+// costs an L2 write-back each time; a tiny second launch is cheaper and just as deterministic.)
+__device__ inline void publish_stats(const StatSinks &sk, int32_t vec, int32_t slot, double amax, double sum,
+                                     double sumsq, double bad) {
   const int tid = threadIdx.x;
   if (tid < 64) {
     amax = wave_max(amax);
@@ -116,32 +115,27 @@ __device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, i
     if (tid == 0) {
       double *p = sk.stat_part + ((int64_t)vec * sk.stat_slots + slot) * 4;
       p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
-      if (mode == kStatsFinal) {
-        __threadfence();
-        const uint32_t prev = atomicAdd(&sk.counters[vec], 1u);
-        *s_last = (prev == (uint32_t)nslots - 1u);
-      }
     }
   }
-  if (mode != kStatsFinal) return;
-  __syncthreads();
-  if (*s_last && tid < 64) {
-    __threadfence();
-    double a, s, s2, b;
-    fold_stat_slots(sk.stat_part + (int64_t)vec * sk.stat_slots * 4, nslots, tid, a, s, s2, b);
-    if (tid == 0) {
-      double *o = sk.stats + (int64_t)vec * 4;
-      o[0] = a; o[1] = s; o[2] = s2; o[3] = b;
-      if (sk.stats_out) {
-        double *u = sk.stats_out + (int64_t)rel * 4;
-        u[0] = a; u[1] = s; u[2] = s2; u[3] = b;
-      }
-      if (b > 0.0) atomicOr(&sk.flags[0], 1u);
-      if (qs.enabled) {
-        sk.qparams[vec] = make_qparams(qs, a, s, s2, d);
-        sk.n_clipped[vec] = 0u;
-      }
-      sk.counters[vec] = 0u;
+}
+
+// one wavefront per vector: fold its partials, store the statistics and the quantizer parameters
+__global__ __launch_bounds__(64) void finalize_stats_kernel(StatSinks sk, QuantSpec qs, int32_t vec_begin,
+                                                            int32_t nslots, int64_t d) {
+  const int32_t rel = blockIdx.x, vec = vec_begin + rel;
+  double a, s, s2, b;
+  fold_stat_slots(sk.stat_part + (int64_t)vec * sk.stat_slots * 4, nslots, threadIdx.x, a, s, s2, b);
+  if (threadIdx.x == 0) {
+    double *o = sk.stats + (int64_t)vec * 4;
+    o[0] = a; o[1] = s; o[2] = s2; o[3] = b;
+    if (sk.stats_out) {
+      double *u = sk.stats_out + (int64_t)rel * 4;
+      u[0] = a; u[1] = s; u[2] = s2; u[3] = b;
+    }
+    if (b > 0.0) atomicOr(&sk.flags[0], 1u);
+    if (qs.enabled) {
+      sk.qparams[vec] = make_qparams(qs, a, s, s2, d);
+      sk.n_clipped[vec] = 0u;
     }
   }
 }
@@ -151,10 +145,8 @@ __device__ inline void publish_stats(const StatSinks &sk, const QuantSpec &qs, i
 __global__ __launch_bounds__(kThreads) void reduce_parts_kernel(const float *__restrict__ part, int32_t parts,
                                                                 int64_t d, int64_t d_pad, float scale,
                                                                 float *__restrict__ out, int64_t ld_out,
-                                                                int32_t vec_begin, int32_t want_stats, StatSinks sk,
-                                                                QuantSpec qs) {
+                                                                int32_t vec_begin, int32_t want_stats, StatSinks sk) {
   __shared__ float red[4][64];
-  __shared__ bool s_last;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t vec = blockIdx.y;
   const int64_t col = (int64_t)blockIdx.x * 64 + lane;
@@ -177,16 +169,13 @@ __global__ __launch_bounds__(kThreads) void reduce_parts_kernel(const float *__r
       bad = 1.0;
     }
   }
-  if (want_stats != kStatsNone)
-    publish_stats(sk, qs, want_stats, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+  if (want_stats != kStatsNone) publish_stats(sk, vec_begin + vec, blockIdx.x, amax, sum, sumsq, bad);
 }
 
 // statistics of rows of an existing matrix; each workgroup takes `chunk` columns
 __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__restrict__ U, int64_t ld, int64_t d,
-                                                                int64_t chunk, int32_t vec_begin, int32_t mode,
-                                                                StatSinks sk, QuantSpec qs) {
+                                                                int64_t chunk, int32_t vec_begin, StatSinks sk) {
   __shared__ double red[4][4];
-  __shared__ bool s_last;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t vec = blockIdx.y;
   const float *u = U + (int64_t)vec * ld;
@@ -220,7 +209,7 @@ __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__r
   if (tid == 0) {
     for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
   }
-  publish_stats(sk, qs, mode, vec_begin + vec, vec, blockIdx.x, gridDim.x, d, amax, sum, sumsq, bad, &s_last);
+  publish_stats(sk, vec_begin + vec, blockIdx.x, amax, sum, sumsq, bad);
 }
 
 __global__ void prepare_qparams_kernel(const double *stats, const float *delta_in, int32_t nvec, int64_t d,
@@ -694,7 +683,10 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
   // the scratch slots (statistics, quantizer parameters, arrival counters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
   hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, part, parts, c->d, c->d_pad, scale, out,
-                     ld_out, vec_begin, stats_mode, sinks_of(c, stats_out), spec_of(c));
+                     ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
+  if (stats_mode == kStatsFinal)
+    hipLaunchKernelGGL(finalize_stats_kernel, dim3((unsigned)nvec), dim3(64), 0, st, sinks_of(c, stats_out),
+                       spec_of(c), vec_begin, (int32_t)grid.x, c->d);
   return hipGetLastError();
 }
 
@@ -711,8 +703,11 @@ hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int
     slots = (c->d + chunk - 1) / chunk;
   }
   const dim3 grid((unsigned)slots, (unsigned)nvec);
-  hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin, stats_mode,
-                     sinks_of(c, stats_out), spec_of(c));
+  hipLaunchKernelGGL(vector_stats_kernel, grid, dim3(kThreads), 0, st, U, ld, c->d, chunk, vec_begin,
+                     sinks_of(c, stats_out));
+  if (stats_mode == kStatsFinal)
+    hipLaunchKernelGGL(finalize_stats_kernel, dim3((unsigned)nvec), dim3(64), 0, st, sinks_of(c, stats_out),
+                       spec_of(c), vec_begin, (int32_t)slots, c->d);
   if (slots_used) *slots_used = (int32_t)slots;
   return hipGetLastError();
 }
@@ -847,12 +842,12 @@ hipError_t launch_finish_full_grad(const lpc_ctx *c, int32_t parts, int64_t cols
       // first level: fold_slices groups of consecutive partial rows, all columns in parallel
       const dim3 grid1(grid.x, (unsigned)c->fold_slices);
       hipLaunchKernelGGL(reduce_parts_kernel, grid1, dim3(kThreads), 0, st, src, parts / c->fold_slices, cols, cols,
-                         1.0f, c->s.part2, cols, 0, kStatsNone, sinks_of(c, nullptr), spec_of(c));
+                         1.0f, c->s.part2, cols, 0, kStatsNone, sinks_of(c, nullptr));
       src = c->s.part2;
       left = c->fold_slices;
     }
     hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, src, left, cols, cols, scale, mu, cols, 0,
-                       kStatsNone, sinks_of(c, nullptr), spec_of(c));
+                       kStatsNone, sinks_of(c, nullptr));
   }
   if (want_loss && f_out)
     hipLaunchKernelGGL(sum_loss_kernel, dim3(1), dim3(kThreads), 0, st, (const double *)c->s.part_loss, parts,
