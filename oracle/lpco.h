@@ -135,6 +135,9 @@ int lpco_full_grad(const lpco_problem *p, const float *w, int64_t n_rows, float 
 int lpco_worker_vr_grad(const lpco_problem *p, const lpco_config *c, const float *w, const float *w_snap,
                         uint32_t epoch, uint32_t iter, uint32_t tag, int32_t worker_begin, int32_t worker_end,
                         float *U, double *stats);
+/* MLP only: the smallest |pre-activation| of a hidden ReLU unit over the B given rows (the gradient is
+ * discontinuous at zero, so parity with a float implementation is only meaningful away from it) */
+int lpco_mlp_relu_margin(const lpco_problem *p, const float *w, const int64_t *idx, int32_t B, double *margin_out);
 /* P(w) of eq. (1) */
 int lpco_objective(const lpco_problem *p, const float *w, double *P_out);
 

@@ -70,6 +70,7 @@ def _load():
         "lpco_worker_vr_grad": (C.c_int, [P, K, _f32p, _f32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int32,
                                           C.c_int32, _f32p, _f64p]),
         "lpco_objective": (C.c_int, [P, _f32p, _f64p]),
+        "lpco_mlp_relu_margin": (C.c_int, [P, _f32p, _i64p, C.c_int32, _f64p]),
         "lpco_alpc_params": (C.c_int, [P, K, C.c_uint32, _f32p, _f32p, _f32p, _f32p]),
         "lpco_epoch": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _u64p]),
         "lpco_bits_per_message": (C.c_uint64, [C.c_int64, C.c_int32]),
@@ -277,6 +278,14 @@ def objective(problem, w):
     w = _f32(w)
     out = C.c_double()
     _chk(lib.lpco_objective(C.byref(problem), _p(w, _f32p), C.byref(out)))
+    return out.value
+
+
+def mlp_relu_margin(problem, w, idx):
+    w = _f32(w)
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    out = C.c_double()
+    _chk(lib.lpco_mlp_relu_margin(C.byref(problem), _p(w, _f32p), _p(idx, _i64p), idx.size, C.byref(out)))
     return out.value
 
 

@@ -93,6 +93,38 @@ double sample_grad(const lpco_problem *p, const Shape &s, const float *w, int64_
 
 }  // namespace
 
+// Smallest |pre-activation| of any hidden (ReLU) unit over the given rows.  The gradient of a ReLU
+// network is discontinuous where a pre-activation is zero; a float implementation may land on either
+// side of such a kink, so the parity tests only demand tight agreement for batches whose margin is
+// well above float rounding (and say so).
+extern "C" int lpco_mlp_relu_margin(const lpco_problem *p, const float *w, const int64_t *idx, int32_t B,
+                                    double *margin_out) {
+  Shape s;
+  if (!p || !w || !idx || !margin_out) return LPCO_ENULL;
+  if (!p->X || !shape_of(p, s)) return LPCO_ESHAPE;
+  double margin = 1e300;
+  std::vector<double> h, hn;
+  for (int32_t a = 0; a < B; ++a) {
+    const float *x = p->X + idx[a] * p->ldx;
+    h.assign(x, x + s.dims[0]);
+    for (int32_t l = 0; l + 1 < s.nl; ++l) {
+      const int64_t in = s.dims[(size_t)l], out = s.dims[(size_t)l + 1];
+      const float *W = w + s.woff[(size_t)l];
+      const float *b = w + s.boff[(size_t)l];
+      hn.assign((size_t)out, 0.0);
+      for (int64_t o = 0; o < out; ++o) {
+        double acc = (double)b[o];
+        for (int64_t k = 0; k < in; ++k) acc += h[(size_t)k] * (double)W[k * out + o];
+        if (std::fabs(acc) < margin) margin = std::fabs(acc);
+        hn[(size_t)o] = acc > 0.0 ? acc : 0.0;
+      }
+      h.swap(hn);
+    }
+  }
+  *margin_out = margin;
+  return LPCO_OK;
+}
+
 // mean gradient over the first n_rows samples (the snapshot pass)
 int lpco_mlp_full_grad(const lpco_problem *p, const float *w, int64_t n_rows, float *mu, double *f_out) {
   Shape s;
