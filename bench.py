@@ -59,6 +59,19 @@ def algorithmic_work(sp, dp, nnz):
             "exchange": (msg, "bytes")}
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch and kernel class from the stored rocprofv3 counter summary of this workload
+    (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel), or {} when no summary is kept for it."""
+    path = os.path.join(ROOT, "profiles", "%s_hbm_traffic.md" % workload)
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 8 and cells[0] in KERNEL_NAMES:
+                out[cells[0]] = float(cells[6])
+    return out
+
+
 def cpu_baseline(sp, cfgkw, alpc):
     """The oracle as it stands, one host thread, on a bounded sample of the workload."""
     from oracle import lpco
@@ -102,7 +115,20 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="scaled-down problem (quick functional run)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run ten 1 GiB device-to-device copies (a kernel of known traffic: 1 GiB read, "
+                         "1 GiB written) so that rocprofv3's FETCH_SIZE / WRITE_SIZE counters can be scaled")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": 4 * src.numel(), "bytes_written": 4 * src.numel(),
+                                               "launches": 10}}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the N workers are shards on one device); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -173,11 +199,15 @@ def main():
                 ent.update({"bound": "mfma", "algorithmic_flops": amount, "achieved": rate / 1e12, "unit": "TFLOP/s",
                             "peak": MFMA_FP32_PEAK_TFLOPS, "frac": rate / 1e12 / MFMA_FP32_PEAK_TFLOPS})
         kernels[k] = ent
+    traffic = {} if args.small else measured_traffic(args.workload)
+    for k in kernels:
+        if k in traffic:
+            kernels[k]["traffic_bytes"] = traffic[k]
     rated = [k for k in kernels if "frac" in kernels[k]]
     dom = max(rated, key=lambda k: kernels[k]["share_of_step"])
     kd = kernels[dom]
     roofline = {"kernel": kd["name"], "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": None, "us_per_launch": kd["avg_us"],
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": kd.get("traffic_bytes"), "us_per_launch": kd["avg_us"],
                 "launches_per_step": kd["launches_per_step"]}
     if dom == "vr_rows" and kd["bound"] == "hbm" and kd["avg_us"] < 20:
         roofline["note"] = ("one launch moves only %.1f MB, so it is bound by launch and dependency latency, not by "
