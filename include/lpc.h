@@ -91,7 +91,7 @@ typedef struct {
   int32_t N, B, m, bits;
   int32_t clip_mode; /* lpc_clip_mode */
   float clip;
-  int32_t scheme;    /* lpc_scheme; only (a) changes nothing on the wire format */
+  int32_t scheme;    /* lpc_scheme: per-worker delta (a), or shared delta with integer sums (b) / re-quantizing (c) */
   float eta, L, sigma, tau1, tau2, alpha;
   uint64_t seed;
   int64_t n_full;    /* rows used by the snapshot gradient (0 = all n) */
@@ -156,6 +156,14 @@ lpc_status lpc_quantize_clip(lpc_ctx *ctx, const float *U, const double *stats, 
 /* Communication step 2, scheme (a), eq. (4): u_avg_j = (1/N) sum_i delta_i*code^i_j,
  * accumulated in worker order with one fused multiply-add per worker. */
 lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float *delta, float *u_avg, void *stream);
+
+/* Communication step 2, schemes (b) and (c) of Sec. 4.2: all N messages were quantized with the same
+ * scale factor delta[0] = max_i delta_i (pass that value as every entry of delta_in to lpc_quantize_clip),
+ * so the receiver adds the codes as integers and scales once: u_avg_j = delta * (sum_i code^i_j)/N.  With
+ * requantize != 0 the average is rounded once more, without bias, onto dom(delta, bits) (eq. (5)) using
+ * stream tag 3.  lpc_epoch applies (b)/(c) when config.scheme says so. */
+lpc_status lpc_dequantize_shared(lpc_ctx *ctx, const uint32_t *packed, const float *delta, int32_t requantize,
+                                 uint32_t epoch, uint32_t iter, float *u_avg, void *stream);
 
 /* Alg. 1 steps 7-8 in one call (quantization step + communication step 2, scheme (a)): statistics of
  * the N rows of U, eq. (3), quantize + pack into packed [N][W] with delta_out [N], and the receiver's

@@ -145,7 +145,6 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   c->quant = cfg->bits < 32;
   c->W = c->quant ? lpc_words_per_msg(p->d, cfg->bits) : 0;
   c->n_full = cfg->n_full > 0 ? cfg->n_full : p->n;
-  if (cfg->scheme != LPC_SCHEME_A) return LPC_EUNSUPPORTED;
   // The gradient passes exist for dense linear models whose rows fit the register tiling; for any
   // other problem the context still serves the quantizer / receiver / prox calls and the gradient
   // calls answer LPC_EUNSUPPORTED.
@@ -286,7 +285,13 @@ lpc_status alpc_params(const lpc_ctx *c, uint32_t epoch, AlpcParams *out) {
 lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st) {
   Scratch &s = c->s;
   ProfScope ps(c, LPC_PROF_EXCHANGE, st);
-  if (c->quant) {
+  if (c->quant && c->cfg.scheme != LPC_SCHEME_A) {
+    // schemes (b), (c): delta = max_i delta_i for every worker, integer sum at the receiver
+    LPC_TRY_HIP(launch_share_delta(c, c->cfg.N, nullptr, st));
+    LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+    LPC_TRY_HIP(launch_dequantize_shared(c, s.packed, s.delta, c->cfg.scheme == LPC_SCHEME_C, key, s.u_avg, st));
+    LPC_TRY_HIP(launch_prox(c, w, s.u_avg, s.mu, c->cfg.eta, st));
+  } else if (c->quant) {
     LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
     LPC_TRY_HIP(launch_dequantize_prox(c, s.packed, s.delta, s.mu, c->cfg.eta, w, nullptr, st));
   } else {
@@ -429,6 +434,15 @@ lpc_status lpc_dequantize_avg(lpc_ctx *ctx, const uint32_t *packed, const float 
   return dev(launch_dequantize_avg(ctx, packed, delta, u_avg, as_stream(stream)));
 }
 
+lpc_status lpc_dequantize_shared(lpc_ctx *ctx, const uint32_t *packed, const float *delta, int32_t requantize,
+                                 uint32_t epoch, uint32_t iter, float *u_avg, void *stream) {
+  if (!ctx || !packed || !delta || !u_avg) return LPC_ENULL;
+  if (!ctx->quant) return LPC_EINVAL;
+  if (!aligned(packed, 16) || !aligned(u_avg, 16)) return LPC_ESHAPE;
+  return dev(launch_dequantize_shared(ctx, packed, delta, requantize != 0, key_of(ctx, epoch, iter), u_avg,
+                                      as_stream(stream)));
+}
+
 lpc_status lpc_exchange(lpc_ctx *ctx, const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed,
                         float *delta_out, float *u_avg, void *stream) {
   if (!ctx || !U || !packed || !delta_out || !u_avg) return LPC_ENULL;
@@ -466,7 +480,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   const float *zs = (c->n_full == c->n) ? s.z_snap : nullptr;  // margins cached only when every row was visited
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
-    const bool fused = fused_exchange_supported(c);
+    const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A;
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       if (fused) {
@@ -491,7 +505,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   const float step_y = (float)(1.0 / (4.0 * (double)g.L));
   double weight = 1.0, wsum = 0.0;
   float *u_hat = s.U + (int64_t)g.N * c->d_pad;
-  if (!c->csr && !c->mlp && fused_exchange_supported(c)) {
+  if (!c->csr && !c->mlp && fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A) {
     // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
     // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
@@ -527,7 +541,11 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
                          c->quant ? kStatsFinal : kStatsNone, st));
     {
       ProfScope ps(c, LPC_PROF_EXCHANGE, st);
-      if (c->quant) {
+      if (c->quant && g.scheme != LPC_SCHEME_A) {
+        LPC_TRY_HIP(launch_share_delta(c, g.N, nullptr, st));
+        LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+        LPC_TRY_HIP(launch_dequantize_shared(c, s.packed, s.delta, g.scheme == LPC_SCHEME_C, key, s.u_avg, st));
+      } else if (c->quant) {
         LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
         LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
       } else {

@@ -167,6 +167,10 @@ hipError_t launch_quantize(const lpc_ctx *c, const float *U, StreamKey key, uint
 hipError_t launch_dequantize_avg(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg,
                                  hipStream_t st);
 hipError_t launch_plain_avg(const lpc_ctx *c, const float *U, float *u_avg, hipStream_t st);
+// schemes (b)/(c): unify the scale factors of vectors 0..nvec-1 to their maximum; integer-sum receiver
+hipError_t launch_share_delta(const lpc_ctx *c, int32_t nvec, float *delta_out, hipStream_t st);
+hipError_t launch_dequantize_shared(const lpc_ctx *c, const uint32_t *packed, const float *delta, bool requant,
+                                    StreamKey key, float *u_avg, hipStream_t st);
 hipError_t launch_prox(const lpc_ctx *c, float *w, const float *u_avg, const float *mu, float step, hipStream_t st);
 // fused receiver + prox of Alg. 1: w <- prox(w - eta*(avg + mu)); optionally also stores the average
 hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, const float *delta, const float *mu,

@@ -560,6 +560,94 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------
+// Schemes (b) and (c) of Sec. 4.2: every worker quantized with the same delta = max_i delta_i, so the
+// codes add as integers (ceil(log2 N) overflow bits) and one scaling recovers the average.  With
+// REQUANT the average is stochastically rounded once more onto dom(delta, b) (eq. (5)); it lies inside
+// the hull, so this second rounding is unbiased.
+
+// all vectors take the largest delta among them
+__global__ void share_delta_kernel(QParams *qp, int32_t nvec, QuantSpec qs, float *delta_out) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  float dmax = 0.0f;
+  for (int32_t i = 0; i < nvec; ++i) dmax = fmaxf(dmax, qp[i].delta);
+  const QParams q = qparams_from_delta(qs, dmax);
+  for (int32_t i = 0; i < nvec; ++i) qp[i] = q;
+  if (delta_out) delta_out[0] = q.delta;
+}
+
+template <int B>
+__device__ __forceinline__ void unpack_add(const uint32_t *__restrict__ src, int32_t (&acc)[32]) {
+  uint32_t words[B];
+#pragma unroll
+  for (int i = 0; i < B; ++i) words[i] = src[i];
+#pragma unroll
+  for (int c = 0; c < 32; ++c) {
+    const int p = c * B, wi = p >> 5, sh = p & 31;
+    uint32_t field = words[wi] >> sh;
+    if (sh + B > 32) field |= words[wi + 1] << (32 - sh);
+    acc[c] += (int32_t)(field << (32 - B)) >> (32 - B);
+  }
+}
+
+template <int B, bool REQUANT>
+__global__ __launch_bounds__(kThreads) void dequantize_shared_kernel(const uint32_t *__restrict__ packed, int64_t W,
+                                                                     const float *__restrict__ delta, int32_t N,
+                                                                     int64_t d, int64_t d_pad, StreamKey key,
+                                                                     float *__restrict__ u_avg) {
+  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
+  const int tid = threadIdx.x;
+  const int64_t tile_base = (int64_t)blockIdx.x * kTileFloats;
+  const int64_t seg = tile_base / kSegFloats + tid;
+  if (seg * kSegFloats < d_pad) {
+    int32_t acc[32];
+#pragma unroll
+    for (int c = 0; c < 32; ++c) acc[c] = 0;
+    for (int32_t i = 0; i < N; ++i) unpack_add<B>(packed + (int64_t)i * W + seg * B, acc);
+    const float dl = delta[0];
+    const float inv_n = 1.0f / (float)N;
+    const float hi = (float)((1 << (B - 1)) - 1), lo = -(float)(1 << (B - 1));
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      float out[4];
+      uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+      if (REQUANT) {
+        const Philox4 blk = stream_block(key, kTagRequant, 0u, (uint32_t)(seg * 8 + k));
+        rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float mean_code = (float)acc[4 * k + t] * inv_n;  // position of the average on the grid
+        if (!REQUANT) {
+          out[t] = dl * mean_code;
+        } else {
+          float s = mean_code * 1.0f;
+          s = fminf(fmaxf(s, lo), hi);
+          const float base = floorf(s);
+          const float frac = s - base;
+          const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
+          out[t] = dl * (float)((int32_t)base + ((unif < frac) ? 1 : 0));
+        }
+      }
+      *reinterpret_cast<float4 *>(&tile[tid * kPitch + k * 4]) = make_float4(out[0], out[1], out[2], out[3]);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int e = r * kThreads + tid;
+    const int64_t j = tile_base + (int64_t)e * 4;
+    if (j >= d) continue;
+    const float4 a = *reinterpret_cast<const float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]);
+    if (j + 4 <= d) {
+      *reinterpret_cast<float4 *>(u_avg + j) = a;
+    } else {
+      const float av[4] = {a.x, a.y, a.z, a.w};
+      for (int t = 0; t < 4 && j + t < d; ++t) u_avg[j + t] = av[t];
+    }
+  }
+}
+
 // quantization off: u_avg = (1/N) sum_i u^i, float adds in worker order
 __global__ void plain_avg_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad, int32_t N,
                                  float *__restrict__ u_avg) {
@@ -816,6 +904,33 @@ hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t 
   prox_consts(c, al.alpha, &a.thr_z, &a.shrink_z);
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords));
   hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_share_delta(const lpc_ctx *c, int32_t nvec, float *delta_out, hipStream_t st) {
+  hipLaunchKernelGGL(share_delta_kernel, dim3(1), dim3(64), 0, st, c->s.qparams, nvec, spec_of(c), delta_out);
+  return hipGetLastError();
+}
+
+namespace {
+template <int B>
+void dequantize_shared_launch(const lpc_ctx *c, const uint32_t *packed, const float *delta, bool requant,
+                              StreamKey key, float *u_avg, hipStream_t st) {
+  const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats));
+  if (requant)
+    hipLaunchKernelGGL((dequantize_shared_kernel<B, true>), grid, dim3(kThreads), 0, st, packed, c->W, delta,
+                       c->cfg.N, c->d, c->d_pad, key, u_avg);
+  else
+    hipLaunchKernelGGL((dequantize_shared_kernel<B, false>), grid, dim3(kThreads), 0, st, packed, c->W, delta,
+                       c->cfg.N, c->d, c->d_pad, key, u_avg);
+}
+}  // namespace
+
+hipError_t launch_dequantize_shared(const lpc_ctx *c, const uint32_t *packed, const float *delta, bool requant,
+                                    StreamKey key, float *u_avg, hipStream_t st) {
+#define CALL(BITS) dequantize_shared_launch<BITS>(c, packed, delta, requant, key, u_avg, st)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
   return hipGetLastError();
 }
 

@@ -49,6 +49,7 @@ EXPORTS = {
     "lpc_vector_stats": (C.c_int, [_vp, _vp, C.c_int32, _vp, _vp]),
     "lpc_quantize_clip": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
     "lpc_dequantize_avg": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "lpc_dequantize_shared": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_uint32, C.c_uint32, _vp, _vp]),
     "lpc_exchange": (C.c_int, [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
@@ -177,6 +178,10 @@ class Context:
     def dequantize_avg(self, packed, delta, u_avg, stream=None):
         _chk(lib.lpc_dequantize_avg(self._h, _ptr(packed), _ptr(delta), _ptr(u_avg), _stream(stream)),
              "lpc_dequantize_avg")
+
+    def dequantize_shared(self, packed, delta, requantize, epoch, iter_, u_avg, stream=None):
+        _chk(lib.lpc_dequantize_shared(self._h, _ptr(packed), _ptr(delta), 1 if requantize else 0, epoch, iter_,
+                                       _ptr(u_avg), _stream(stream)), "lpc_dequantize_shared")
 
     def exchange(self, U, epoch, iter_, packed, delta_out, u_avg, stream=None):
         _chk(lib.lpc_exchange(self._h, _ptr(U), epoch, iter_, _ptr(packed), _ptr(delta_out), _ptr(u_avg),

@@ -85,3 +85,15 @@ def test_lpc_epochs_csr(d, bits):
     for P_o, P_g, _ in hist:
         assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
     assert hist[-1][0] < hist[0][0]
+
+
+@pytest.mark.parametrize("scheme", [lpco.SCHEME_B, lpco.SCHEME_C])
+@pytest.mark.parametrize("algo", [lpco.ALGO_LPC, lpco.ALGO_ALPC_GC])
+def test_shared_scale_schemes_epochs(scheme, algo):
+    # Sec. 4.2 (b), (c): parameter-server style exchange with one scale factor for all workers
+    name = "c2" if algo == lpco.ALGO_LPC else "c4"
+    sp = lpc_synth.make(name, n=2048, d=512, N=4, B=16)
+    hist, w_o, w_g = _run_both(sp, 3, algo=algo, scheme=scheme, bits=4, clip_mode=0, clip=1.0, tau2=0.5)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    assert hist[-1][0] < hist[0][0]

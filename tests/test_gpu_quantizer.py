@@ -168,3 +168,26 @@ def test_exchange_one_call_bit_exact(d, N, bits, clip):
         assert np.array_equal(packed.cpu().numpy().view(np.uint32), po)
         assert np.array_equal(avg.cpu().numpy(), lpco.dequantize_avg(po, do, d, bits))
     ctx.close()
+
+
+@pytest.mark.parametrize("d,N,bits", [(1000, 8, 3), (4096, 16, 4), (30_000, 5, 2), (70, 3, 9)])
+def test_shared_scale_receiver_bit_exact(d, N, bits):
+    """Schemes (b)/(c): every worker quantized with delta = max_i delta_i; integer code sums; eq. (5)."""
+    import torch
+    ctx, _ = _ctx(d, N, bits, 0, 1.0, seed=9)
+    U = _u(N, d, seed=d + N)
+    deltas = [lpco.delta_from_stats(lpco.vector_stats(U[i, :d]), d, bits, lpco.CLIP_LAMBDA, 1.0)[0] for i in range(N)]
+    shared = np.full(N, max(deltas), dtype=np.float32)
+    po, do, _, _ = lpco.quantize_clip(U, d, bits, seed=9, epoch=1, iter_=4, delta_in=shared)
+    packed = torch.zeros(N, ctx.W, dtype=torch.int32, device="cuda")
+    delta = torch.zeros(N, device="cuda")
+    stats = torch.zeros(N, 4, dtype=torch.float64, device="cuda")
+    ctx.vector_stats(to_dev(U), N, stats)
+    ctx.quantize_clip(to_dev(U), stats, to_dev(shared), 1, 4, packed, delta, None)
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), po) and np.array_equal(delta.cpu().numpy(), do)
+    for requant in (False, True):
+        avg = torch.full((d,), -1.0, device="cuda")
+        ctx.dequantize_shared(packed, delta, requant, 1, 4, avg)
+        ref, _sums = lpco.dequantize_shared(po, float(do[0]), d, bits, requantize=requant, seed=9, epoch=1, iter_=4)
+        assert np.array_equal(avg.cpu().numpy(), ref)
+    ctx.close()
