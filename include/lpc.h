@@ -15,8 +15,8 @@
  *    (for instance memory of a torch tensor); the library only borrows it.
  *    Float/uint32 buffers must be 16-byte aligned, double buffers 8-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Every call except lpc_create, lpc_destroy, lpc_objective and
- *    lpc_take_device_flags only enqueues work: no host synchronisation, no
+ *    Every call except lpc_create, lpc_destroy, lpc_objective,
+ *    lpc_gradient_mapping and lpc_take_device_flags only enqueues work: no host synchronisation, no
  *    allocation.  Scratch memory comes from the workspace given to lpc_create.
  *  - Calls on one context must be issued on one stream at a time: they share
  *    the context's scratch.
@@ -189,6 +189,32 @@ lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void 
  * returns LPC_ENONFINITE if any vector seen by the statistics pass since the last
  * call held a NaN or Inf, else LPC_OK. */
 lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream);
+
+/* ---- evaluators (outside the timed path) --------------------------------------------------
+ * |G_eta(w)|^2 with G_eta(w) = (w - prox_{eta*h}(w - eta*grad f(w)))/eta, the convergence metric
+ * of Sec. 3.3 (Theorems 1 and 2 bound its expectation), over all n rows; fp64 accumulation.
+ * w: device, d floats.  Returned to the HOST (synchronises the stream).  Uses the context's
+ * scratch; the snapshot state kept by lpc_epoch is not touched.  eta > 0 else LPC_EINVAL. */
+lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double *gm2_out_host, void *stream);
+
+/* Left-hand side of Theorem 2's step-size condition,
+ *   8 m^2 rho^2 [ c*d*lambda^2/(2^(bits-1)-1)^2 + d_lambda*(1-lambda)^2 + 1/(N*B) ] + rho,
+ * c = 1/4 for schemes (a), (b) (eq. (6)) and 3/8 for scheme (c) (eq. (7)); rho = eta*L, d_lambda =
+ * the number of clipped coordinates (Sec. 3.2).  The theorem needs the value <= 1 and rho < 1/2.
+ * Host arithmetic only; out_host receives the value.  LPC_EINVAL for bits outside [2,16]. */
+lpc_status lpc_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambda, int32_t N, int32_t B,
+                            int32_t m, double rho, int32_t scheme, double *out_host);
+
+/* Entropy coding of the messages (Sec. 6.1 applies Huffman coding to the code stream).
+ * lpc_code_histogram: counts[k] = number of the first d coordinates of ONE packed message whose
+ * code is k - 2^(bits-1); packed: device, W words; counts: device, 2^bits uint64, overwritten.
+ * lpc_huffman_bits: HOST arithmetic; from nsym counts, the lengths of an optimal prefix code
+ * (lens_out_host, nsym int32, may be NULL; unused symbols get 0; a lone used symbol gets 1) and
+ * the encoded size sum_k counts[k]*len[k] in bits (bits_out_host).  The size is unique; the
+ * lengths are one valid optimum when weights tie. */
+lpc_status lpc_code_histogram(lpc_ctx *ctx, const uint32_t *packed, uint64_t *counts, void *stream);
+lpc_status lpc_huffman_bits(const uint64_t *counts_host, int32_t nsym, int32_t *lens_out_host,
+                            uint64_t *bits_out_host);
 
 /* ---- measurement aid (benchmarks; no passage of the paper) ------------------------------
  * While enabled, every launch of the kernel classes below made by this context is bracketed by

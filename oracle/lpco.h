@@ -150,6 +150,17 @@ int lpco_alpc_params(const lpco_problem *p, const lpco_config *c, uint32_t epoch
 int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc, uint32_t epoch,
                uint64_t *bits_sent /* may be NULL; communication step 2 only, Table 1 */);
 
+/* ---- evaluators ---- */
+/* |G_eta(w)|^2, the gradient-mapping metric of Sec. 3.3 */
+int lpco_gradient_mapping(const lpco_problem *p, const float *w, float eta, double *gm2_out);
+/* left-hand side of eq. (6) (schemes a, b) / eq. (7) (scheme c) of Theorem 2 */
+double lpco_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambda, int32_t N, int32_t B, int32_t m,
+                         double rho, int32_t scheme);
+/* entropy (Huffman) coding of the code stream, Sec. 6.1: optimal prefix-code lengths from the counts
+ * of the 2^b code values; returns the encoded size in bits */
+uint64_t lpco_huffman_bits(const uint64_t *counts, int32_t nsym, int32_t *lens_out);
+int lpco_code_histogram(const uint32_t *words, int64_t d, int32_t bits, uint64_t *counts);
+
 /* ---- message accounting (Table 1) ---- */
 uint64_t lpco_bits_per_message(int64_t d, int32_t bits);
 uint64_t lpco_bits_per_iteration(int64_t d, int32_t bits, int32_t N, int32_t scheme);

@@ -71,6 +71,11 @@ def _load():
                                           C.c_int32, _f32p, _f64p]),
         "lpco_objective": (C.c_int, [P, _f32p, _f64p]),
         "lpco_mlp_relu_margin": (C.c_int, [P, _f32p, _i64p, C.c_int32, _f64p]),
+        "lpco_gradient_mapping": (C.c_int, [P, _f32p, C.c_float, _f64p]),
+        "lpco_theorem2_lhs": (C.c_double, [C.c_int64, C.c_int32, C.c_double, C.c_int64, C.c_int32, C.c_int32,
+                                           C.c_int32, C.c_double, C.c_int32]),
+        "lpco_huffman_bits": (C.c_uint64, [_u64p, C.c_int32, _i32p]),
+        "lpco_code_histogram": (C.c_int, [_u32p, C.c_int64, C.c_int32, _u64p]),
         "lpco_alpc_params": (C.c_int, [P, K, C.c_uint32, _f32p, _f32p, _f32p, _f32p]),
         "lpco_epoch": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _u64p]),
         "lpco_bits_per_message": (C.c_uint64, [C.c_int64, C.c_int32]),
@@ -287,6 +292,31 @@ def mlp_relu_margin(problem, w, idx):
     out = C.c_double()
     _chk(lib.lpco_mlp_relu_margin(C.byref(problem), _p(w, _f32p), _p(idx, _i64p), idx.size, C.byref(out)))
     return out.value
+
+
+def gradient_mapping(problem, w, eta):
+    w = _f32(w)
+    out = C.c_double()
+    _chk(lib.lpco_gradient_mapping(C.byref(problem), _p(w, _f32p), eta, C.byref(out)))
+    return out.value
+
+
+def theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme=SCHEME_A):
+    return float(lib.lpco_theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme))
+
+
+def huffman_bits(counts):
+    counts = np.ascontiguousarray(counts, dtype=np.uint64)
+    lens = np.zeros(counts.size, dtype=np.int32)
+    bits = lib.lpco_huffman_bits(_p(counts, _u64p), counts.size, _p(lens, _i32p))
+    return int(bits), lens
+
+
+def code_histogram(words, d, bits):
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    counts = np.zeros(1 << bits, dtype=np.uint64)
+    _chk(lib.lpco_code_histogram(_p(words, _u32p), d, bits, _p(counts, _u64p)))
+    return counts
 
 
 def alpc_params(problem, config, epoch):

@@ -221,3 +221,38 @@ extern "C" int lpco_objective(const lpco_problem *p, const float *w, double *P_o
   *P_out = f + (double)p->lambda1 * l1 + 0.5 * (double)p->lambda2 * l2;
   return LPCO_OK;
 }
+
+// Convergence metric for nonconvex / nonsmooth problems (Sec. 3.3): the gradient mapping
+//   G_eta(x) = (1/eta) [ x - prox_{eta h}(x - eta grad f(x)) ];  returns |G_eta(x)|^2.
+extern "C" int lpco_gradient_mapping(const lpco_problem *p, const float *w, float eta, double *gm2_out) {
+  int rc = check_problem(p);
+  if (rc != LPCO_OK) return rc;
+  if (!w || !gm2_out) return LPCO_ENULL;
+  if (!(eta > 0.0f)) return LPCO_EINVAL;
+  std::vector<float> mu((size_t)p->d);
+  rc = lpco_full_grad(p, w, 0, mu.data(), nullptr, nullptr);
+  if (rc != LPCO_OK) return rc;
+  const double thr = (double)eta * (double)p->lambda1, shrink = 1.0 / (1.0 + (double)eta * (double)p->lambda2);
+  double acc = 0.0;
+  for (int64_t j = 0; j < p->d; ++j) {
+    const double pt = (double)w[j] - (double)eta * (double)mu[j];
+    const double mag = std::fabs(pt) - thr;
+    const double px = mag > 0.0 ? (pt > 0.0 ? mag : -mag) * shrink : 0.0;
+    const double g = ((double)w[j] - px) / (double)eta;
+    acc += g * g;
+  }
+  *gm2_out = acc;
+  return LPCO_OK;
+}
+
+// Left-hand side of the step-size conditions of Theorem 2 (eq. (6) for schemes (a)/(b), eq. (7) for (c)):
+//   8 m^2 rho^2 [ c * d lambda^2/(2^(b-1)-1)^2 + d_lambda (1-lambda)^2 + 1/(N B) ] + rho,  c = 1/4 or 3/8.
+// The theorem asks for a value <= 1 (and rho < 1/2).
+extern "C" double lpco_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambda, int32_t N, int32_t B,
+                                    int32_t m, double rho, int32_t scheme) {
+  const double levels = (double)((1 << (bits - 1)) - 1);
+  const double c = scheme == LPCO_SCHEME_C ? 3.0 / 8.0 : 1.0 / 4.0;
+  const double bracket = c * (double)d * lambda * lambda / (levels * levels) +
+                         (double)d_lambda * (1.0 - lambda) * (1.0 - lambda) + 1.0 / ((double)N * (double)B);
+  return 8.0 * (double)m * (double)m * rho * rho * bracket + rho;
+}

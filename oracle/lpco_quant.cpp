@@ -7,9 +7,11 @@
 //
 // Arithmetic that decides an integer code is written out in float, one
 // operation per statement, and this file is compiled with contraction off.
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <limits>
+#include <utility>
 #include <vector>
 
 #include "lpco.h"
@@ -263,5 +265,68 @@ extern "C" int lpco_dequantize_shared(int64_t d, int32_t N, int32_t bits, const 
       u_avg[j] = delta_shared * (float)k;
     }
   }
+  return LPCO_OK;
+}
+
+// Entropy coding of the code stream (Sec. 6.1: "adopt the entropy encoding scheme [Huffman 1952] to
+// further reduce the communication overhead").  Given the counts of the 2^b code values, the length
+// of an optimal prefix code for each value by Huffman's merging of the two least frequent subtrees;
+// returns the number of bits of the encoded message, sum_k count_k * len_k (a lone symbol costs 1
+// bit per coordinate).  lens_out may be NULL.
+extern "C" uint64_t lpco_huffman_bits(const uint64_t *counts, int32_t nsym, int32_t *lens_out) {
+  if (!counts || nsym <= 0) return 0;
+  struct Node { uint64_t w; int32_t left, right; };
+  std::vector<Node> nodes;
+  std::vector<int32_t> alive;
+  for (int32_t k = 0; k < nsym; ++k) {
+    nodes.push_back(Node{counts[k], -1, -1});
+    if (counts[k] > 0) alive.push_back(k);
+  }
+  std::vector<int32_t> lens((size_t)nsym, 0);
+  if (alive.size() == 1) lens[(size_t)alive[0]] = 1;
+  while (alive.size() > 1) {
+    // two smallest weights (ties: lowest index first); plain selection, the alphabet is tiny
+    size_t a = 0, b = 1;
+    if (nodes[(size_t)alive[b]].w < nodes[(size_t)alive[a]].w) std::swap(a, b);
+    for (size_t t = 2; t < alive.size(); ++t) {
+      const uint64_t wt = nodes[(size_t)alive[t]].w;
+      if (wt < nodes[(size_t)alive[a]].w) { b = a; a = t; }
+      else if (wt < nodes[(size_t)alive[b]].w) { b = t; }
+    }
+    const int32_t ia = alive[a], ib = alive[b];
+    nodes.push_back(Node{nodes[(size_t)ia].w + nodes[(size_t)ib].w, ia, ib});
+    const int32_t merged = (int32_t)nodes.size() - 1;
+    if (a > b) std::swap(a, b);
+    alive.erase(alive.begin() + (long)b);
+    alive.erase(alive.begin() + (long)a);
+    alive.push_back(merged);
+  }
+  if (!alive.empty() && alive.size() == 1 && nodes.size() > (size_t)nsym) {
+    // depth of every leaf below the root
+    std::vector<std::pair<int32_t, int32_t>> stack{{alive[0], 0}};
+    while (!stack.empty()) {
+      const auto [id, depth] = stack.back();
+      stack.pop_back();
+      if (nodes[(size_t)id].left < 0) { lens[(size_t)id] = depth; continue; }
+      stack.push_back({nodes[(size_t)id].left, depth + 1});
+      stack.push_back({nodes[(size_t)id].right, depth + 1});
+    }
+  }
+  uint64_t bits = 0;
+  for (int32_t k = 0; k < nsym; ++k) {
+    bits += counts[k] * (uint64_t)lens[(size_t)k];
+    if (lens_out) lens_out[k] = lens[(size_t)k];
+  }
+  return bits;
+}
+
+// counts of the 2^b code values of one packed message (coordinates 0..d-1); bin k holds code k - 2^(b-1)
+extern "C" int lpco_code_histogram(const uint32_t *words, int64_t d, int32_t bits, uint64_t *counts) {
+  if (!words || !counts) return LPCO_ENULL;
+  if (!bits_ok(bits) || d < 0) return LPCO_EINVAL;
+  std::vector<int32_t> codes((size_t)d);
+  lpco_unpack(words, d, bits, codes.data());
+  for (int32_t k = 0; k < (1 << bits); ++k) counts[k] = 0;
+  for (int64_t j = 0; j < d; ++j) counts[codes[(size_t)j] + (1 << (bits - 1))] += 1;
   return LPCO_OK;
 }

@@ -23,6 +23,7 @@ SOURCES = [
     ("lpc_csr.hip", []),
     ("lpc_gemm.hip", []),
     ("lpc_mlp.hip", []),
+    ("lpc_eval.hip", []),
 ]
 HEADERS = ["lpc_internal.h", "lpc_device.h"]
 

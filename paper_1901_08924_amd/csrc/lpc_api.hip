@@ -573,6 +573,47 @@ lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void 
   return LPC_OK;
 }
 
+lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double *gm2_out_host, void *stream) {
+  if (!ctx || !w || !gm2_out_host) return LPC_ENULL;
+  if (!(eta > 0.0f)) return LPC_EINVAL;
+  hipStream_t st = as_stream(stream);
+  float *grad = ctx->s.u_avg;   // free outside an epoch
+  LPC_TRY(full_grad_impl(ctx, w, grad, nullptr, nullptr, ctx->n, st));
+  LPC_TRY_HIP(launch_gradient_mapping(ctx, w, grad, (double)eta, ctx->s.f_scalar, st));
+  LPC_TRY_HIP(hipMemcpyAsync(gm2_out_host, ctx->s.f_scalar, sizeof(double), hipMemcpyDeviceToHost, st));
+  LPC_TRY_HIP(hipStreamSynchronize(st));
+  return LPC_OK;
+}
+
+lpc_status lpc_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambda, int32_t N, int32_t B,
+                            int32_t m, double rho, int32_t scheme, double *out_host) {
+  if (!out_host) return LPC_ENULL;
+  if (bits < 2 || bits > 16 || d < 0 || d_lambda < 0 || N < 1 || B < 1 || m < 1) return LPC_EINVAL;
+  if (scheme != LPC_SCHEME_A && scheme != LPC_SCHEME_B && scheme != LPC_SCHEME_C) return LPC_EINVAL;
+  const double steps = (double)((1 << (bits - 1)) - 1);   // delta = lambda*|u|_inf/steps, eq. (3)
+  const double rounding = (scheme == LPC_SCHEME_C ? 0.375 : 0.25) * (double)d * (lambda / steps) * (lambda / steps);
+  const double clipping = (double)d_lambda * (1.0 - lambda) * (1.0 - lambda);
+  const double sampling = 1.0 / ((double)N * (double)B);
+  const double mr = (double)m * rho;
+  *out_host = 8.0 * mr * mr * (rounding + clipping + sampling) + rho;
+  return LPC_OK;
+}
+
+lpc_status lpc_code_histogram(lpc_ctx *ctx, const uint32_t *packed, uint64_t *counts, void *stream) {
+  if (!ctx || !packed || !counts) return LPC_ENULL;
+  if (!ctx->quant) return LPC_EINVAL;
+  LPC_TRY_HIP(launch_code_histogram(packed, ctx->d, ctx->cfg.bits, counts, as_stream(stream)));
+  return LPC_OK;
+}
+
+lpc_status lpc_huffman_bits(const uint64_t *counts_host, int32_t nsym, int32_t *lens_out_host,
+                            uint64_t *bits_out_host) {
+  if (!counts_host || !bits_out_host) return LPC_ENULL;
+  if (nsym < 1 || nsym > (1 << 16)) return LPC_EINVAL;
+  *bits_out_host = huffman_code_lengths(counts_host, nsym, lens_out_host);
+  return LPC_OK;
+}
+
 lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream) {
   if (!ctx) return LPC_ENULL;
   hipStream_t st = as_stream(stream);

@@ -187,5 +187,10 @@ hipError_t launch_alpc_update(const lpc_ctx *c, const float *x, const float *u_a
                               float *z, float *ysum, hipStream_t st);
 hipError_t launch_scale_to(const lpc_ctx *c, const float *src, float scale, float *dst, hipStream_t st);
 hipError_t launch_objective_reg(const lpc_ctx *c, const float *w, double *acc, hipStream_t st);
+// evaluators (Sec. 3.3 gradient mapping; Sec. 6.1 entropy coding of the code stream)
+hipError_t launch_gradient_mapping(const lpc_ctx *c, const float *w, const float *grad, double eta, double *out,
+                                   hipStream_t st);
+hipError_t launch_code_histogram(const uint32_t *words, int64_t d, int32_t bits, uint64_t *counts, hipStream_t st);
+uint64_t huffman_code_lengths(const uint64_t *counts, int32_t nsym, int32_t *lens);
 
 }  // namespace lpc

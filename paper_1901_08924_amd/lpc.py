@@ -55,6 +55,11 @@ EXPORTS = {
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "lpc_take_device_flags": (C.c_int, [_vp, _vp]),
+    "lpc_gradient_mapping": (C.c_int, [_vp, _vp, C.c_float, C.POINTER(C.c_double), _vp]),
+    "lpc_theorem2_lhs": (C.c_int, [C.c_int64, C.c_int32, C.c_double, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                   C.c_double, C.c_int32, C.POINTER(C.c_double)]),
+    "lpc_code_histogram": (C.c_int, [_vp, _vp, _vp, _vp]),
+    "lpc_huffman_bits": (C.c_int, [_vp, C.c_int32, _vp, C.POINTER(C.c_uint64)]),
     "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
     "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), _vp]),
 }
@@ -103,6 +108,22 @@ def d_pad(d):
 
 def words_per_msg(d, bits):
     return int(lib.lpc_words_per_msg(d, bits))
+
+
+def theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme=SCHEME_A):
+    out = C.c_double()
+    _chk(lib.lpc_theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme, C.byref(out)), "lpc_theorem2_lhs")
+    return out.value
+
+
+def huffman_bits(counts):
+    """counts: host sequence of symbol counts -> (encoded bits, list of code lengths)."""
+    n = len(counts)
+    arr = (C.c_uint64 * n)(*[int(c) for c in counts])
+    lens = (C.c_int32 * n)()
+    out = C.c_uint64()
+    _chk(lib.lpc_huffman_bits(arr, n, lens, C.byref(out)), "lpc_huffman_bits")
+    return int(out.value), list(lens)
 
 
 def make_config(algo=ALGO_LPC, N=1, B=1, m=1, bits=32, clip_mode=CLIP_LAMBDA, clip=1.0, scheme=SCHEME_A, eta=0.1,
@@ -197,6 +218,18 @@ class Context:
         out = C.c_double()
         _chk(lib.lpc_objective(self._h, _ptr(w), C.byref(out), _stream(stream)), "lpc_objective")
         return out.value
+
+    def gradient_mapping(self, w, eta, stream=None):
+        out = C.c_double()
+        _chk(lib.lpc_gradient_mapping(self._h, _ptr(w), eta, C.byref(out), _stream(stream)), "lpc_gradient_mapping")
+        return out.value
+
+    def code_histogram(self, packed, counts=None, stream=None):
+        """packed: one message (W uint32 words on the device) -> 2^bits int64 counts on the device."""
+        if counts is None:
+            counts = torch.empty(1 << self.config.bits, dtype=torch.int64, device=packed.device)
+        _chk(lib.lpc_code_histogram(self._h, _ptr(packed), _ptr(counts), _stream(stream)), "lpc_code_histogram")
+        return counts
 
     def profile_enable(self, on):
         _chk(lib.lpc_profile_enable(self._h, 1 if on else 0), "lpc_profile_enable")

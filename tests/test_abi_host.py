@@ -109,3 +109,23 @@ def test_calls_reject_null_handles(lpc):
     assert lpc.lib.lpc_prox_step(None, None, None, None, 0.1, None) == lpc.ENULL
     out = C.c_double()
     assert lpc.lib.lpc_objective(None, None, C.byref(out), None) == lpc.ENULL
+
+
+def test_theorem2_and_huffman_host_entry_points():
+    """Host arithmetic inside the HIP library (no GPU needed): eq. (6)/(7) and optimal prefix-code sizes."""
+    from fractions import Fraction
+    from paper_1901_08924_amd import lpc
+    exact = Fraction(8 * 4, 100) * (Fraction(64, 4 * 49) + Fraction(1, 64)) + Fraction(1, 10)
+    assert abs(lpc.theorem2_lhs(64, 4, 1.0, 0, 4, 16, 2, 0.1, lpc.SCHEME_A) - float(exact)) < 1e-12
+    exact_c = Fraction(8 * 4, 100) * (Fraction(3 * 64, 8 * 49) + Fraction(1, 64)) + Fraction(1, 10)
+    assert abs(lpc.theorem2_lhs(64, 4, 1.0, 0, 4, 16, 2, 0.1, lpc.SCHEME_C) - float(exact_c)) < 1e-12
+    exact_l = Fraction(8 * 4, 100) * (Fraction(64, 4 * 49) / 4 + Fraction(3, 4) + Fraction(1, 64)) + Fraction(1, 10)
+    assert abs(lpc.theorem2_lhs(64, 4, 0.5, 3, 4, 16, 2, 0.1, lpc.SCHEME_B) - float(exact_l)) < 1e-12
+    with pytest.raises(lpc.LpcError):
+        lpc.theorem2_lhs(64, 1, 1.0, 0, 4, 16, 2, 0.1, lpc.SCHEME_A)
+    bits, lens = lpc.huffman_bits([45, 13, 12, 16, 9, 5])
+    assert bits == 224 and sorted(lens) == [1, 3, 3, 3, 4, 4]
+    assert lpc.huffman_bits([0, 9, 0]) == (9, [0, 1, 0])
+    assert lpc.huffman_bits([0, 0]) == (0, [0, 0])
+    bits, lens = lpc.huffman_bits([3] * 8)
+    assert bits == 72 and lens == [3] * 8
