@@ -118,6 +118,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
   s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
+  s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
     s.mlp_yb = (float *)take((size_t)c->mlp_rows * sizeof(float));
@@ -163,6 +164,17 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->full_grad_wgs = csr_full_grad_wgs(c->n_full);
     c->vr_parts = 1;
     c->part_floats = (size_t)c->full_grad_wgs * csr_head_columns(c->d);
+    // Alg. 1 with per-worker scale factors keeps u^i sparse when a worker's batch touches a small part of the
+    // d columns (about B*nnz/n entries against d coordinates)
+    c->sparse_head = csr_head_columns(c->d);
+    c->bitmap_words = (c->d_pad / 32 + 31) / 32;
+    const double touched = (double)cfg->B * (double)p->nnz / (double)p->n;
+    c->csr_sparse = c->quant && cfg->algo == LPC_ALGO_LPC && cfg->scheme == LPC_SCHEME_A &&
+                    p->d >= 4 * (int64_t)c->sparse_head && touched * 8.0 <= (double)p->d;
+    if (c->csr_sparse) {
+      const size_t head_parts = (size_t)cfg->N * csr_sparse_parts(cfg->B) * c->sparse_head;
+      if (head_parts > c->part_floats) c->part_floats = head_parts;
+    }
   } else if (c->grad_ok) {
     c->full_grad_wgs = dense_full_grad_wgs(c->n_full, c->d, c->cus);
     c->vr_parts = dense_vr_parts(c->d, cfg->N, cfg->B, c->cus);
@@ -481,9 +493,27 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
     const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A;
+    if (c->csr_sparse) {
+      // the sparse passes rely on U, the bitmap and the packed words being zero where nothing was written
+      LPC_TRY_HIP(launch_zero(s.U, (int64_t)g.N * c->d_pad, st));
+      LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
+      LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
+    }
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
-      if (fused) {
+      if (c->csr_sparse) {
+        {
+          ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+          LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, st));
+        }
+        {
+          ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+          LPC_TRY_HIP(launch_sparse_stats(c, st));
+        }
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        LPC_TRY_HIP(launch_sparse_quantize(c, key, st));
+        LPC_TRY_HIP(launch_sparse_receive_prox(c, s.mu, g.eta, s.w, st));
+      } else if (fused) {
         // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
         int32_t slots = 0;
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st, &slots));

@@ -51,6 +51,9 @@ struct CsrArgs {
   float *part;        // snapshot pass: [workgroup][head] partial rows
   double *part_loss;  // snapshot pass
   float *U;           // worker pass: [N][d_pad], zeroed
+  uint32_t *touched;  // sparse worker pass: [N][bitmap_words], one bit per 32-coordinate segment
+  int64_t bitmap_words;
+  int32_t parts, rows_per_part;  // sparse worker pass: workgroups per worker, sampled rows per workgroup
   int64_t n, d, d_pad, n_rows;
   int32_t head;       // columns [0, head) are privatised in LDS (snapshot pass)
   int32_t loss, want_loss;
@@ -62,9 +65,8 @@ struct CsrArgs {
 
 // sum over the 16 lanes of a group; every lane of the group returns it
 __device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-  for (int off = kGroup / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kGroup);
-  return v;
+  static_assert(kGroup == 16, "a group is one row of 16 lanes");
+  return row16_sum(v);
 }
 
 // Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kGroups-th row.
@@ -142,6 +144,80 @@ __global__ __launch_bounds__(kThreads) void csr_vr_kernel(CsrArgs a, int32_t nwo
   for (int32_t e = lo + gl; e < hi; e += kGroup) atomicAdd(&u[a.col_idx[e]], coef * a.vals[e]);
 }
 
+// Worker pass that keeps u^i sparse.  A workgroup takes rows_per_part sampled rows of one worker, sixteen
+// lanes per row.  Head columns accumulate in LDS and leave as one partial row per workgroup (a.part, folded by
+// the statistics pass); a tail column is added to the worker's row of U, which is all zero outside the
+// segments touched in this iteration, and its 32-coordinate segment is marked in the bitmap so that the
+// statistics, quantizer and receiver passes visit only marked segments (an unmarked segment codes to zero).
+constexpr int kSparseThreads = 1024;
+constexpr int kSparseGroups = kSparseThreads / kGroup;
+
+template <bool CACHED>
+__global__ __launch_bounds__(kSparseThreads) void csr_vr_sparse_kernel(CsrArgs a) {
+  extern __shared__ float head_acc[];
+  const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
+  for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
+  __syncthreads();
+  const int32_t wrel = blockIdx.x / a.parts, part = blockIdx.x % a.parts;
+  const uint32_t worker = (uint32_t)(a.worker_begin + wrel);
+  const int32_t pos0 = part * a.rows_per_part;
+  const int32_t pos1 = pos0 + a.rows_per_part < a.B ? pos0 + a.rows_per_part : a.B;
+  float *u = a.U + (int64_t)wrel * a.d_pad;
+  uint32_t *bm = a.touched + (int64_t)wrel * a.bitmap_words;
+  for (int32_t pos = pos0 + grp; pos < pos1; pos += kSparseGroups) {
+    const int64_t r = sample_row(a.key, a.tag, worker, (uint32_t)pos, a.n);
+    const int32_t lo = a.row_ptr[r], hi = a.row_ptr[r + 1];
+    const float yr = a.y[r];
+    const float zc = CACHED ? a.z_snap[r] : 0.0f;
+    // 64 entries of the row per step, all loads of a step in flight together (most rows need one step)
+    float s = 0.0f, s2 = 0.0f;
+    int32_t c[4];
+    float v[4];
+    for (int32_t base = lo; base < hi; base += 4 * kGroup) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t e = base + q * kGroup + gl;
+        const bool ok = e < hi;
+        c[q] = ok ? a.col_idx[e] : 0;
+        v[q] = ok ? a.vals[e] : 0.0f;
+      }
+      float wv[4], wsv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        wv[q] = a.w[c[q]];
+        wsv[q] = CACHED ? 0.0f : a.w_snap[c[q]];
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        s = fmaf(v[q], wv[q], s);
+        if (!CACHED) s2 = fmaf(v[q], wsv[q], s2);
+      }
+    }
+    const float z = group_sum(s);
+    const float zs = CACHED ? zc : group_sum(s2);
+    const float coef = (loss_slope(a.loss, z, yr) - loss_slope(a.loss, zs, yr)) * a.scale;
+    const bool one_step = hi - lo <= 4 * kGroup;  // then c[], v[] still hold the whole row
+    for (int32_t base = lo; base < hi; base += 4 * kGroup) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t e = base + q * kGroup + gl;
+        if (e >= hi) continue;
+        const int32_t col = one_step ? c[q] : a.col_idx[e];
+        const float g = coef * (one_step ? v[q] : a.vals[e]);
+        if (col < a.head) {
+          atomicAdd(&head_acc[col], g);
+        } else {
+          atomicAdd(&u[col], g);
+          atomicOr(&bm[col >> 10], 1u << ((col >> 5) & 31));
+        }
+      }
+    }
+  }
+  __syncthreads();
+  float *dst = a.part + (int64_t)blockIdx.x * a.head;
+  for (int32_t j = tid; j < a.head; j += kSparseThreads) dst[j] = head_acc[j];
+}
+
 __global__ void zero_kernel(float4 *__restrict__ dst, int64_t n4) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n4) dst[i] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -209,6 +285,28 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const dim3 grid((unsigned)((slots + kGroups - 1) / kGroups));
   if (z_snap) hipLaunchKernelGGL(csr_vr_kernel<true>, grid, dim3(kThreads), 0, st, a, nworkers);
   else hipLaunchKernelGGL(csr_vr_kernel<false>, grid, dim3(kThreads), 0, st, a, nworkers);
+  return hipGetLastError();
+}
+
+// Sparse worker pass (all N workers).  s.U rows and the bitmap must be zero outside what this call adds.
+int csr_sparse_parts(int32_t B) { return (B + kSparseGroups - 1) / kSparseGroups; }
+
+hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
+                                StreamKey key, hipStream_t st) {
+  CsrArgs a{};
+  a.row_ptr = c->prob.row_ptr; a.col_idx = c->prob.col_idx; a.vals = c->prob.vals; a.y = c->prob.y;
+  a.w = w; a.w_snap = w_snap; a.z_snap = z_snap; a.U = c->s.U; a.part = c->s.part;
+  a.touched = c->s.touched; a.bitmap_words = c->bitmap_words;
+  a.n = c->n; a.d = c->d; a.d_pad = c->d_pad; a.loss = c->prob.loss;
+  a.head = c->sparse_head;
+  a.key = key; a.tag = kTagBatch; a.worker_begin = 0; a.B = c->cfg.B;
+  a.scale = (float)(1.0 / (double)c->cfg.B);
+  a.parts = csr_sparse_parts(c->cfg.B);
+  a.rows_per_part = (c->cfg.B + a.parts - 1) / a.parts;
+  const dim3 grid((unsigned)(c->cfg.N * a.parts));
+  const size_t lds = (size_t)a.head * sizeof(float);
+  if (z_snap) hipLaunchKernelGGL(csr_vr_sparse_kernel<true>, grid, dim3(kSparseThreads), lds, st, a);
+  else hipLaunchKernelGGL(csr_vr_sparse_kernel<false>, grid, dim3(kSparseThreads), lds, st, a);
   return hipGetLastError();
 }
 

@@ -67,6 +67,7 @@ struct Scratch {
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
   float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
+  uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
   // MLP instance: gathered inputs/labels and per-layer activations / deltas for the two parameter sets
   float *mlp_xb;        // [rows][dims[0]]
   float *mlp_yb;        // [rows]
@@ -94,6 +95,9 @@ struct lpc_ctx {
   int32_t stat_slots;     // statistic partials per vector
   int32_t cus;            // compute units of the device (256 on MI355X)
   int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
+  bool csr_sparse = false; // inner iterations of Alg. 1 keep u^i sparse (CSR rows that touch few columns)
+  int32_t sparse_head = 0; // leading columns that every sparse pass visits densely
+  int64_t bitmap_words = 0; // words per worker of the touched-segment bitmap
   size_t part_floats;
   void *workspace;
   size_t workspace_bytes;
@@ -124,6 +128,12 @@ int csr_full_grad_wgs(int64_t n);
 hipError_t launch_zero(float *dst, int64_t n, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
+int csr_sparse_parts(int32_t B);
+hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
+                                StreamKey key, hipStream_t st);
+hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st);
+hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st);
+hipError_t launch_sparse_receive_prox(const lpc_ctx *c, const float *mu, float step, float *w, hipStream_t st);
 hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                               StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end, float *U,
                               hipStream_t st);

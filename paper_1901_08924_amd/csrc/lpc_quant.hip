@@ -88,14 +88,16 @@ __device__ inline QParams qparams_from_delta(const QuantSpec &qs, float delta) {
 
 // Fold the statistic partials of one vector in a fixed order (lane k takes slots k, k+64, ...; then
 // a butterfly).  Called by one full wavefront; every lane returns the same four numbers.
-__device__ inline void fold_stat_slots(const volatile double *p, int32_t nslots, int lane, double &a, double &s,
+__device__ inline void fold_stat_slots(const double *p, int32_t nslots, int lane, double &a, double &s,
                                        double &s2, double &b) {
   a = 0.0; s = 0.0; s2 = 0.0; b = 0.0;
   for (int32_t k = lane; k < nslots; k += 64) {
-    a = fmax(a, p[k * 4 + 0]);
-    s += p[k * 4 + 1];
-    s2 += p[k * 4 + 2];
-    b += p[k * 4 + 3];
+    const double2 lo = *reinterpret_cast<const double2 *>(p + k * 4);
+    const double2 hi = *reinterpret_cast<const double2 *>(p + k * 4 + 2);
+    a = fmax(a, lo.x);
+    s += lo.y;
+    s2 += hi.x;
+    b += hi.y;
   }
   a = wave_max(a); s = wave_sum(s); s2 = wave_sum(s2); b = wave_sum(b);
 }
@@ -226,6 +228,69 @@ __global__ void prepare_qparams_kernel(const double *stats, const float *delta_i
   n_clipped[v] = 0u;
 }
 
+// Quantize the 32 coordinates of segment `seg` of one worker's vector (Sec. 3.2 rules (1), (2) with the
+// scale of eq. (3)) and store its B packed words at dst.  load4(k) returns coordinates 4k..4k+3.  Returns
+// the number of coordinates outside dom(delta, b).  All arithmetic is fp32 without contraction:
+//   s = u*(1/delta), clamp to [-2^(b-1), 2^(b-1)-1], lo = floor(s), frac = s - lo (exact),
+//   U = (word >> 8)*2^-24 from the Philox block of the coordinate's group of four, code = lo + (U < frac).
+template <int B, class Load4>
+__device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams &q, const StreamKey &key,
+                                                     uint32_t worker, int64_t seg, uint32_t *__restrict__ dst) {
+  const float hi = (float)((1 << (B - 1)) - 1);
+  const float lo = -(float)(1 << (B - 1));
+  constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
+  const bool count = q.delta > 0.0f;
+  uint32_t clipped = 0;
+  uint32_t words[B];
+  uint64_t bitbuf = 0;
+  int nb = 0, wi = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const float4 v4 = load4(k);
+    const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
+    float base[4], frac[4];
+    bool any = false;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      float s = vals[t] * q.rdelta;        // position on the grid
+      s = fminf(fmaxf(s, lo), hi);         // rule (2): project onto the hull
+      base[t] = floorf(s);
+      frac[t] = s - base[t];               // exact
+      any = any || (frac[t] != 0.0f);
+      if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
+    }
+    uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+    if (any) {  // on-grid values (zeros in particular) need no random draw
+      const Philox4 blk = stream_block(key, kTagQuant, worker, (uint32_t)(seg * 8 + k));
+      rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
+      const int32_t code = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
+      bitbuf |= (uint64_t)((uint32_t)code & mask) << nb;
+      nb += B;
+      if (nb >= 32) {
+        words[wi++] = (uint32_t)bitbuf;
+        bitbuf >>= 32;
+        nb -= 32;
+      }
+    }
+  }
+  if constexpr (B % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < B; i += 4)
+      *reinterpret_cast<uint4 *>(dst + i) = make_uint4(words[i], words[i + 1], words[i + 2], words[i + 3]);
+  } else if constexpr (B % 2 == 0) {
+#pragma unroll
+    for (int i = 0; i < B; i += 2) *reinterpret_cast<uint2 *>(dst + i) = make_uint2(words[i], words[i + 1]);
+  } else {
+#pragma unroll
+    for (int i = 0; i < B; ++i) dst[i] = words[i];
+  }
+  return clipped;
+}
+
 // ---------------------------------------------------------------------------
 // Quantize + pack.  grid = (tiles of 8192 coordinates, N workers).
 template <int B>
@@ -262,58 +327,9 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
   const bool active = seg * kSegFloats < d_pad;
   uint32_t clipped = 0;
   if (active) {
-    const float hi = (float)((1 << (B - 1)) - 1);
-    const float lo = -(float)(1 << (B - 1));
-    constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
-    const bool count = q.delta > 0.0f;
-    uint32_t words[B];
-    uint64_t bitbuf = 0;
-    int nb = 0, wi = 0;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const float4 v4 = *reinterpret_cast<const float4 *>(&tile[tid * kPitch + k * 4]);
-      const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
-      float base[4], frac[4];
-      bool any = false;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        float s = vals[t] * q.rdelta;        // position on the grid
-        s = fminf(fmaxf(s, lo), hi);         // rule (2): project onto the hull
-        base[t] = floorf(s);
-        frac[t] = s - base[t];               // exact
-        any = any || (frac[t] != 0.0f);
-        if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
-      }
-      uint32_t rnd[4] = {0u, 0u, 0u, 0u};
-      if (any) {  // on-grid values (zeros in particular) need no random draw
-        const Philox4 blk = stream_block(key, kTagQuant, worker, (uint32_t)(seg * 8 + k));
-        rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
-      }
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
-        const int32_t code = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
-        bitbuf |= (uint64_t)((uint32_t)code & mask) << nb;
-        nb += B;
-        if (nb >= 32) {
-          words[wi++] = (uint32_t)bitbuf;
-          bitbuf >>= 32;
-          nb -= 32;
-        }
-      }
-    }
-    uint32_t *dst = packed + (int64_t)worker * W + seg * B;
-    if constexpr (B % 4 == 0) {
-#pragma unroll
-      for (int i = 0; i < B; i += 4)
-        *reinterpret_cast<uint4 *>(dst + i) = make_uint4(words[i], words[i + 1], words[i + 2], words[i + 3]);
-    } else if constexpr (B % 2 == 0) {
-#pragma unroll
-      for (int i = 0; i < B; i += 2) *reinterpret_cast<uint2 *>(dst + i) = make_uint2(words[i], words[i + 1]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < B; ++i) dst[i] = words[i];
-    }
+    const float *mine = &tile[tid * kPitch];
+    clipped = quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key, worker,
+                                  seg, packed + (int64_t)worker * W + seg * B);
   }
   if (n_clipped) {
     clipped = wave_sum(clipped);
@@ -324,8 +340,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
 // ---------------------------------------------------------------------------
 // Receiver: unpack, eq. (4), optional fused proximal step.
 template <int B>
-__device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ src, float delta, float (&acc)[32]) {
-  uint32_t words[B];
+__device__ __forceinline__ void load_words(const uint32_t *__restrict__ src, uint32_t (&words)[B]) {
   if constexpr (B % 4 == 0) {
 #pragma unroll
     for (int i = 0; i < B; i += 4) {
@@ -342,6 +357,14 @@ __device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ s
 #pragma unroll
     for (int i = 0; i < B; ++i) words[i] = src[i];
   }
+}
+
+// acc[c] = fma(delta, code_c, acc[c]) for the 32 codes of one segment; returns the OR of the words
+template <int B>
+__device__ __forceinline__ uint32_t accumulate_words(const uint32_t (&words)[B], float delta, float (&acc)[32]) {
+  uint32_t any = 0u;
+#pragma unroll
+  for (int i = 0; i < B; ++i) any |= words[i];
 #pragma unroll
   for (int c = 0; c < 32; ++c) {
     const int p = c * B, wi = p >> 5, sh = p & 31;
@@ -350,6 +373,14 @@ __device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ s
     const int32_t code = (int32_t)(field << (32 - B)) >> (32 - B);  // sign-extend the B-bit field
     acc[c] = __builtin_fmaf(delta, (float)code, acc[c]);
   }
+  return any;
+}
+
+template <int B>
+__device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ src, float delta, float (&acc)[32]) {
+  uint32_t words[B];
+  load_words<B>(src, words);
+  accumulate_words<B>(words, delta, acc);
 }
 
 __device__ __forceinline__ float prox_scalar(float w, float v, float step, float thr, float shrink) {
@@ -362,10 +393,15 @@ struct ProxArgs {
   const float *mu;
   float *w;
   float step, thr, shrink;
+  // sparse inner iteration: consumed non-zero words are set back to zero (rezero aliases the packed
+  // messages, N <= 64) and the touched-segment bitmap is cleared
+  uint32_t *rezero;
+  uint32_t *touched;
+  int64_t bitmap_words;
 };
 
 template <int B, bool PROX>
-__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__restrict__ packed, int64_t W,
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *packed, int64_t W,
                                                               const float *__restrict__ delta, int32_t N, int64_t d,
                                                               int64_t d_pad, float *__restrict__ u_avg, ProxArgs pa) {
   __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
@@ -376,7 +412,38 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
     float acc[32];
 #pragma unroll
     for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
-    for (int32_t i = 0; i < N; ++i) unpack_accumulate<B>(packed + (int64_t)i * W + seg * B, delta[i], acc);
+    // four messages in flight at a time; accumulation stays in worker order
+    uint64_t nonzero = 0;
+    int32_t i = 0;
+    for (; i + 4 <= N; i += 4) {
+      uint32_t w0[B], w1[B], w2[B], w3[B];
+      const uint32_t *src = packed + (int64_t)i * W + seg * B;
+      load_words<B>(src, w0); load_words<B>(src + W, w1); load_words<B>(src + 2 * W, w2); load_words<B>(src + 3 * W, w3);
+      const float d0 = delta[i], d1 = delta[i + 1], d2 = delta[i + 2], d3 = delta[i + 3];
+      if (accumulate_words<B>(w0, d0, acc)) nonzero |= 1ull << (i & 63);
+      if (accumulate_words<B>(w1, d1, acc)) nonzero |= 1ull << ((i + 1) & 63);
+      if (accumulate_words<B>(w2, d2, acc)) nonzero |= 1ull << ((i + 2) & 63);
+      if (accumulate_words<B>(w3, d3, acc)) nonzero |= 1ull << ((i + 3) & 63);
+    }
+    for (; i < N; ++i) {
+      uint32_t w0[B];
+      load_words<B>(packed + (int64_t)i * W + seg * B, w0);
+      if (accumulate_words<B>(w0, delta[i], acc)) nonzero |= 1ull << (i & 63);
+    }
+    if constexpr (PROX) {
+      if (pa.rezero) {
+        while (nonzero) {
+          const int k = __builtin_ctzll(nonzero);
+          nonzero &= nonzero - 1;
+          uint32_t *z = pa.rezero + (int64_t)k * W + seg * B;
+#pragma unroll
+          for (int q = 0; q < B; ++q) z[q] = 0u;
+        }
+        // the 32 segments of one bitmap word belong to this wavefront, and no pass reads the bitmap here
+        if ((seg & 31) == 0)
+          for (int32_t k = 0; k < N; ++k) pa.touched[(int64_t)k * pa.bitmap_words + (seg >> 5)] = 0u;
+      }
+    }
     const float inv_n = 1.0f / (float)N;
 #pragma unroll
     for (int k = 0; k < 8; ++k)
@@ -409,6 +476,195 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------
+// Sparse inner iteration (CSR rows): u^i is non-zero only in the always-visited head columns and in the
+// 32-coordinate segments marked in the worker's bitmap.  A zero coordinate adds nothing to the statistics,
+// quantizes to code 0 without a random draw and is never clipped, so visiting only the marked segments gives
+// the results of the dense passes.  One thread per (segment, worker) in all three kernels.
+struct SparseArgs {
+  float *U;                 // [N][d_pad]
+  const float *head_part;   // [N][parts][head]: partial head rows of the worker pass
+  uint32_t *touched;        // [N][bitmap_words]
+  int64_t d_pad, W, bitmap_words;
+  int32_t head, parts, N;
+};
+
+__device__ __forceinline__ bool segment_marked(const uint32_t *bm, int64_t seg) {
+  return (bm[seg >> 5] >> (seg & 31)) & 1u;
+}
+
+// A wavefront owns kWaveWords words of a worker's bitmap, first_word + k*stride for k < kWaveWords (strided so
+// that every wavefront gets its share of the frequent low columns), i.e. kWaveSegs tail segments.  The marked
+// ones are compacted into `list` (LDS, kWaveSegs entries per wavefront) so that the lanes share them evenly;
+// returns their number.
+// A segment is one 128-byte line: it is always moved by eight adjacent lanes with 16 bytes each (one request
+// per line); a lane that walks a line of its own costs a request per 16 bytes.
+constexpr int kWaveWords = 32;
+constexpr int kWaveSegs = kWaveWords * 32;
+
+__device__ __forceinline__ int32_t compact_marked(const uint32_t *__restrict__ bm, int64_t bitmap_words,
+                                                  int64_t first_word, int64_t stride, int64_t total_segs, int lane,
+                                                  int32_t *__restrict__ list) {
+  const int64_t wi = first_word + lane * stride;
+  const uint32_t word = (lane < kWaveWords && wi < bitmap_words) ? bm[wi] : 0u;
+  int32_t n = 0;
+#pragma unroll 4
+  for (int c = 0; c < kWaveWords / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
+    const int k = 2 * c + (lane >> 5);
+    const uint32_t w = __shfl(word, k, 64);
+    const int64_t seg = (first_word + k * stride) * 32 + (lane & 31);
+    const bool marked = ((w >> (lane & 31)) & 1u) && seg < total_segs;
+    const uint64_t m = __ballot(marked);
+    if (marked) list[n + __popcll(m & ((1ull << lane) - 1ull))] = (int32_t)seg;
+    n += __popcll(m);
+  }
+  return n;
+}
+
+// Statistic partials of u^i.  Workgroups [0, head/1024) of a worker fold the head columns from the partial rows
+// of the worker pass (fixed order, one float4 per thread, coalesced) into U; in the others every wavefront
+// visits the marked ones of its kWaveSegs tail segments.
+__global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, StatSinks sk) {
+  __shared__ double red[4][4];
+  __shared__ int32_t list[4][kWaveSegs];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int32_t worker = blockIdx.y;
+  const int32_t head_wgs = a.head / (4 * kThreads);
+  float *urow = a.U + (int64_t)worker * a.d_pad;
+  double sum = 0.0, sumsq = 0.0, bad = 0.0;
+  float fmx = 0.0f;
+  auto take = [&](float x) {
+    if (isfinite(x)) {
+      fmx = fmaxf(fmx, fabsf(x)); sum += (double)x; sumsq += (double)x * (double)x;
+    } else {
+      bad += 1.0;
+    }
+  };
+  if ((int32_t)blockIdx.x < head_wgs) {
+    const int64_t j = ((int64_t)blockIdx.x * kThreads + tid) * 4;
+    const float *src = a.head_part + (int64_t)worker * a.parts * a.head + j;
+    float4 v = *reinterpret_cast<const float4 *>(src);
+    for (int32_t p = 1; p < a.parts; ++p) {
+      const float4 t = *reinterpret_cast<const float4 *>(src + (int64_t)p * a.head);
+      v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+    *reinterpret_cast<float4 *>(urow + j) = v;
+    take(v.x); take(v.y); take(v.z); take(v.w);
+  } else {
+    const int64_t stride = (int64_t)(gridDim.x - head_wgs) * 4;  // tail wavefronts of this worker
+    const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - head_wgs) * 4 + wv;
+    const int32_t n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
+                                     a.d_pad / kSegFloats, lane, list[wv]);
+    __builtin_amdgcn_wave_barrier();
+    // eight lanes per segment, 32 segments (four independent loads per lane) per step
+    for (int32_t i0 = 0; i0 < n; i0 += 32) {
+      float4 v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t i = i0 + q * 8 + (lane >> 3);
+        v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < n) v[q] = *reinterpret_cast<const float4 *>(urow + (int64_t)list[wv][i] * kSegFloats + (lane & 7) * 4);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { take(v[q].x); take(v[q].y); take(v[q].z); take(v[q].w); }
+    }
+  }
+  fmx = wave_max(fmx);
+  sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
+  if (lane == 0) { red[wv][0] = (double)fmx; red[wv][1] = sum; red[wv][2] = sumsq; red[wv][3] = bad; }
+  __syncthreads();
+  if (tid == 0) {
+    double amax = 0.0;
+    sum = 0.0; sumsq = 0.0; bad = 0.0;
+    for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
+    double *p = sk.stat_part + ((int64_t)worker * sk.stat_slots + blockIdx.x) * 4;
+    p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
+    if (blockIdx.x == 0) sk.n_clipped[worker] = 0u;  // the quantizer pass adds to it
+  }
+}
+
+// eq. (3) + quantize + pack over the visited segments; a marked tail segment of U is set back to zero for the
+// next iteration.  Every workgroup folds its worker's statistic partials itself (the fixed order of
+// fold_stat_slots, so all of them derive the same scale); workgroup 0 of a worker records the results.
+// Workgroup 0 of a worker takes the head (one dense tile, transposed through LDS like the dense quantizer);
+// in the others every wavefront visits the marked ones of its kWaveSegs tail segments.
+template <int B>
+__global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a, StatSinks sk, QuantSpec qs,
+                                                                   int32_t nslots, int64_t d, StreamKey key,
+                                                                   uint32_t *__restrict__ packed,
+                                                                   float *__restrict__ delta_out) {
+  // the head workgroup uses the whole tile; a tail wavefront uses its quarter (64 segments) and its list
+  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
+  __shared__ int32_t lists[4][kWaveSegs];
+  __shared__ QParams q_sh;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const uint32_t worker = blockIdx.y;
+  const bool head = blockIdx.x == 0;
+  float *urow = a.U + (int64_t)worker * a.d_pad;
+  int32_t *list = lists[wv];
+  int32_t n = 0;
+  if (head) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int e = r * kThreads + tid;
+      *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) =
+          *reinterpret_cast<const float4 *>(urow + (int64_t)e * 4);
+    }
+  } else {
+    const int64_t stride = (int64_t)(gridDim.x - 1) * 4;  // tail wavefronts of this worker
+    const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - 1) * 4 + wv;
+    n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
+                       a.d_pad / kSegFloats, lane, list);
+  }
+  if (tid < 64) {
+    double amax, sum, sumsq, bad;
+    fold_stat_slots(sk.stat_part + (int64_t)worker * sk.stat_slots * 4, nslots, tid, amax, sum, sumsq, bad);
+    if (tid == 0) {
+      const QParams q = make_qparams(qs, amax, sum, sumsq, d);
+      q_sh = q;
+      if (blockIdx.x == 0) {
+        double *o = sk.stats + (int64_t)worker * 4;
+        o[0] = amax; o[1] = sum; o[2] = sumsq; o[3] = bad;
+        sk.qparams[worker] = q;
+        delta_out[worker] = q.delta;
+        if (bad > 0.0) atomicOr(&sk.flags[0], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  const QParams q = q_sh;
+  uint32_t clipped = 0;
+  if (head) {
+    const float *mine = &tile[tid * kPitch];
+    clipped = quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key, worker,
+                                  (int64_t)tid, packed + (int64_t)worker * a.W + (int64_t)tid * B);
+  } else {
+    float *wtile = tile + wv * 64 * kPitch;
+    for (int32_t i0 = 0; i0 < n; i0 += 64) {
+      // 64 segments per step: eight lanes move one segment in and, zeroed, back out
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int32_t local = r * 8 + (lane >> 3);
+        if (i0 + local < n) {
+          float *u = urow + (int64_t)list[i0 + local] * kSegFloats + (lane & 7) * 4;
+          *reinterpret_cast<float4 *>(&wtile[local * kPitch + (lane & 7) * 4]) = *reinterpret_cast<const float4 *>(u);
+          *reinterpret_cast<float4 *>(u) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (i0 + lane < n) {
+        const int64_t seg = list[i0 + lane];
+        const float *mine = &wtile[lane * kPitch];
+        clipped += quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key,
+                                       worker, seg, packed + (int64_t)worker * a.W + seg * B);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+  clipped = wave_sum(clipped);
+  if (lane == 0 && clipped) atomicAdd(&sk.n_clipped[worker], clipped);
 }
 
 // ---------------------------------------------------------------------------
@@ -844,7 +1100,7 @@ hipError_t launch_quantize(const lpc_ctx *c, const float *U, StreamKey key, uint
 
 hipError_t launch_dequantize_avg(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg,
                                  hipStream_t st) {
-  ProxArgs pa{nullptr, nullptr, 0.f, 0.f, 0.f};
+  ProxArgs pa{nullptr, nullptr, 0.f, 0.f, 0.f, nullptr, nullptr, 0};
 #define CALL(BITS) dequantize_launch<BITS, false>(c, packed, delta, u_avg, pa, st)
   LPC_DISPATCH_BITS(c->cfg.bits, CALL)
 #undef CALL
@@ -860,9 +1116,55 @@ inline void prox_consts(const lpc_ctx *c, float step, float *thr, float *shrink)
 
 hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, const float *delta, const float *mu,
                                   float step, float *w, float *u_avg_out, hipStream_t st) {
-  ProxArgs pa{mu, w, step, 0.f, 0.f};
+  ProxArgs pa{mu, w, step, 0.f, 0.f, nullptr, nullptr, 0};
   prox_consts(c, step, &pa.thr, &pa.shrink);
 #define CALL(BITS) dequantize_launch<BITS, true>(c, packed, delta, u_avg_out, pa, st)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+namespace {
+SparseArgs sparse_args_of(const lpc_ctx *c) {
+  SparseArgs a{};
+  a.U = c->s.U; a.head_part = c->s.part; a.touched = c->s.touched;
+  a.d_pad = c->d_pad; a.W = c->W; a.bitmap_words = c->bitmap_words;
+  a.head = c->sparse_head; a.parts = csr_sparse_parts(c->cfg.B); a.N = c->cfg.N;
+  return a;
+}
+}  // namespace
+
+namespace {
+// workgroups per worker that cover the tail: four wavefronts of kWaveSegs segments each
+int32_t sparse_tail_wgs(const lpc_ctx *c) {
+  const int64_t tail_segs = (c->d_pad - c->sparse_head) / kSegFloats;
+  return (int32_t)((tail_segs + 4 * kWaveSegs - 1) / (4 * kWaveSegs));  // four wavefronts per workgroup
+}
+int32_t sparse_stat_slots(const lpc_ctx *c) { return c->sparse_head / (4 * kThreads) + sparse_tail_wgs(c); }
+}  // namespace
+
+// statistic partials of the N sparse vectors left by launch_csr_vr_sparse
+hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st) {
+  hipLaunchKernelGGL(sparse_stats_kernel, dim3((unsigned)sparse_stat_slots(c), (unsigned)c->cfg.N), dim3(kThreads), 0,
+                     st, sparse_args_of(c), sinks_of(c, nullptr));
+  return hipGetLastError();
+}
+
+hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st) {
+  const dim3 grid((unsigned)(1 + sparse_tail_wgs(c)), (unsigned)c->cfg.N);
+  const int32_t slots = sparse_stat_slots(c);
+#define CALL(BITS)                                                                                             \
+  hipLaunchKernelGGL(sparse_quantize_kernel<BITS>, grid, dim3(kThreads), 0, st, sparse_args_of(c), sinks_of(c, nullptr), \
+                     spec_of(c), slots, c->d, key, c->s.packed, c->s.delta)
+  LPC_DISPATCH_BITS(c->cfg.bits, CALL)
+#undef CALL
+  return hipGetLastError();
+}
+
+hipError_t launch_sparse_receive_prox(const lpc_ctx *c, const float *mu, float step, float *w, hipStream_t st) {
+  ProxArgs pa{mu, w, step, 0.f, 0.f, c->s.packed, c->s.touched, c->bitmap_words};
+  prox_consts(c, step, &pa.thr, &pa.shrink);
+#define CALL(BITS) dequantize_launch<BITS, true>(c, c->s.packed, c->s.delta, nullptr, pa, st)
   LPC_DISPATCH_BITS(c->cfg.bits, CALL)
 #undef CALL
   return hipGetLastError();
