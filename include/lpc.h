@@ -105,7 +105,8 @@ size_t lpc_workspace_bytes(const lpc_problem *problem, const lpc_config *config)
 /* Validates problem and config, copies both, and lays the scratch buffers out
  * in `workspace` (device, 256-byte aligned, at least lpc_workspace_bytes long,
  * owned by the caller and alive until lpc_destroy).  Clears the scratch's
- * counters on the default stream and waits for that.  Errors: LPC_ENULL,
+ * counters and, for CSR data, builds a column-major copy of the rarely used
+ * columns' entries in the scratch, on the default stream, and waits for that.  Errors: LPC_ENULL,
  * LPC_EINVAL (bits = 1 divides by zero in eq. (3); N*B > n contradicts
  * Theorem 1's N*B <= n), LPC_ESHAPE, LPC_EWORKSPACE, LPC_EUNSUPPORTED. */
 lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_config *config, void *workspace,

@@ -54,6 +54,7 @@ lpc_status check_problem(const lpc_problem *p) {
     if (p->loss != LPC_LOSS_MLP_SOFTMAX && p->ldx < p->d) return LPC_ESHAPE;
   } else {
     if (!p->row_ptr || !p->col_idx || !p->vals) return LPC_ENULL;
+    if (!aligned(p->col_idx, 16) || !aligned(p->vals, 16) || !aligned(p->row_ptr, 4)) return LPC_ESHAPE;
     if (p->nnz < 0 || p->nnz > (int64_t)0x7FFFFFFFll) return LPC_ESHAPE;
     if (p->loss == LPC_LOSS_MLP_SOFTMAX) return LPC_EINVAL;
   }
@@ -118,6 +119,11 @@ size_t layout(lpc_ctx *c, char *base) {
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
   s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
+  s.csc_ptr = (int32_t *)take((c->csr ? (size_t)c->d + 4 : 4) * sizeof(int32_t));
+  s.csc_cursor = (int32_t *)take((c->csr ? (size_t)c->d + 1 : 4) * sizeof(int32_t));
+  s.csc_rows = (int32_t *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(int32_t));
+  s.csc_vals = (float *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(float));
+  s.csc_coef = (float *)take((c->csr ? (size_t)c->n : 4) * sizeof(float));
   s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
@@ -357,6 +363,10 @@ lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_c
   const size_t words = ((char *)c->s.z_snap - (char *)c->s.counters) / sizeof(uint32_t);
   if (launch_fill_u32(c->s.counters, 0u, (int64_t)words, nullptr) != hipSuccess ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
+    delete c;
+    return LPC_EDEVICE;
+  }
+  if (c->csr && build_csc_tail(c, nullptr) != hipSuccess) {
     delete c;
     return LPC_EDEVICE;
   }

@@ -4,14 +4,18 @@
 //
 // Sixteen lanes own one row at a time (a wavefront works on four rows at once):
 // the row's (column, value) pairs are read as contiguous spans, w is gathered
-// (it stays cache resident), the dot product is closed with a 16-lane
-// butterfly, and the row is scattered back as coef * value into the gradient.
+// (it stays cache resident), the dot product is closed inside the row of 16
+// lanes, and the row is scattered back as coef * value into the gradient.
 // A row costs three dependent memory round trips (row_ptr -> pairs -> w), so
-// small groups keep many rows in flight per CU.
+// small groups keep many rows in flight per CU and the next row's data is
+// requested while the current row is worked on.
 // Text-like data has Zipf-distributed column ids, so a handful of "head"
 // columns receive most of the scatter: each workgroup accumulates the first
 // kHead columns privately in LDS and writes them once as a partial row that is
-// folded in a fixed order; only the rare tail columns use global float atomics.
+// folded in a fixed order.  The rare tail columns are summed column by column
+// from a column-major copy of the tail entries built when the context is
+// created (a gather of the per-row slopes, no atomics, fixed order); when that
+// copy is not available they fall back to global float atomics.
 #include <hip/hip_runtime.h>
 
 #include "lpc_device.h"
@@ -47,6 +51,7 @@ struct CsrArgs {
   const float *w_snap;
   const float *z_snap;
   float *z_out;
+  float *coef;        // snapshot pass with the column-major tail: per-row loss slopes
   float *tail;        // snapshot pass: d floats, zeroed; tail columns accumulate here
   float *part;        // snapshot pass: [workgroup][head] partial rows
   double *part_loss;  // snapshot pass
@@ -54,9 +59,9 @@ struct CsrArgs {
   uint32_t *touched;  // sparse worker pass: [N][bitmap_words], one bit per 32-coordinate segment
   int64_t bitmap_words;
   int32_t parts, rows_per_part;  // sparse worker pass: workgroups per worker, sampled rows per workgroup
-  int64_t n, d, d_pad, n_rows;
+  int64_t n, d, d_pad, n_rows, nnz;
   int32_t head;       // columns [0, head) are privatised in LDS (snapshot pass)
-  int32_t loss, want_loss;
+  int32_t loss, want_loss, want_grad;
   StreamKey key;
   uint32_t tag;
   int32_t worker_begin, B;
@@ -69,47 +74,297 @@ __device__ __forceinline__ float group_sum(float v) {
   return row16_sum(v);
 }
 
-// Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kGroups-th row.
-__global__ __launch_bounds__(kThreads) void csr_full_kernel(CsrArgs a, int64_t rows_per_wg) {
+// Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kFullGroups-th row.
+// Built to keep many rows in flight: 1024 threads (64 row groups) share one LDS head, two such workgroups
+// fit a CU, the first 64 pairs of a row (most rows have no more) are requested one row ahead and the extent
+// of a row two rows ahead.
+constexpr int kFullThreads = 1024;
+constexpr int kFullGroups = kFullThreads / kGroup;
+
+struct RowExtent {
+  int32_t lo, hi;
+  float y;
+};
+
+__device__ __forceinline__ RowExtent load_extent(const CsrArgs &a, int64_t r, int64_t r1) {
+  const int64_t rc = r < r1 ? r : r1 - 1;
+  RowExtent x;
+  x.lo = a.row_ptr[rc];
+  x.hi = a.row_ptr[rc + 1];
+  x.y = a.y[rc];
+  if (r >= r1) x.hi = x.lo;  // past the end: an empty row
+  return x;
+}
+
+// the first 64 pairs of a row, four per lane; entries past the row come back as (column 0, value 0)
+__device__ __forceinline__ void load_pairs(const CsrArgs &a, const RowExtent &x, int gl, int32_t (&c)[4],
+                                           float (&v)[4]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int32_t e = x.lo + q * kGroup + gl;
+    const bool ok = e < x.hi;
+    // streamed once: non-temporal, so that the pairs do not displace w in the caches
+    c[q] = ok ? __builtin_nontemporal_load(a.col_idx + e) : 0;
+    v[q] = ok ? __builtin_nontemporal_load(a.vals + e) : 0.0f;
+  }
+}
+
+template <bool CSC>
+__global__ __launch_bounds__(kFullThreads) void csr_full_kernel(CsrArgs a, int64_t rows_per_wg) {
+  // LDS: the head of the gradient accumulator, then a copy of the head of w.  Most entries fall into the
+  // head columns; a 4-byte gather from memory costs a cache-line lookup per lane, and that lookup rate, not
+  // HBM, is what bounds this pass.
   extern __shared__ float head_acc[];
-  __shared__ double loss_red[kGroups];
+  float *w_head = head_acc + a.head;
+  __shared__ double loss_red[kFullGroups];
   const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
-  for (int32_t j = tid; j < a.head; j += kThreads) head_acc[j] = 0.0f;
+  for (int32_t j = tid; j < a.head; j += kFullThreads) {
+    head_acc[j] = 0.0f;
+    w_head[j] = a.w[j];
+  }
   __syncthreads();
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_wg;
   int64_t r1 = r0 + rows_per_wg;
   if (r1 > a.n_rows) r1 = a.n_rows;
   double loss_acc = 0.0;
-  for (int64_t r = r0 + grp; r < r1; r += kGroups) {
-    const int32_t lo = a.row_ptr[r], hi = a.row_ptr[r + 1];
-    const float yr = a.y[r];
-    float s = 0.0f;
-    for (int32_t e = lo + gl; e < hi; e += kGroup) s = fmaf(a.vals[e], a.w[a.col_idx[e]], s);
-    const float z = group_sum(s);
-    const float coef = loss_slope(a.loss, z, yr);
-    if (gl == 0) {
-      if (a.z_out) a.z_out[r] = z;
-      if (a.want_loss) loss_acc += (double)loss_value(a.loss, z, yr);
-    }
-    for (int32_t e = lo + gl; e < hi; e += kGroup) {
-      const int32_t c = a.col_idx[e];
-      const float g = coef * a.vals[e];
-      if (c < a.head) atomicAdd(&head_acc[c], g);   // LDS
-      else atomicAdd(&a.tail[c], g);                // rare columns
+  if (r0 < r1) {  // uniform over the workgroup
+    int64_t r = r0 + grp;
+    RowExtent cur = load_extent(a, r, r1);
+    RowExtent nxt = load_extent(a, r + kFullGroups, r1);
+    int32_t c[4];
+    float v[4];
+    load_pairs(a, cur, gl, c, v);
+    while (r < r1) {
+      // the gathers of this row go out first: the wait for them then leaves the prefetches below in
+      // flight (memory operations complete in issue order as far as the wait counter is concerned)
+      float wv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        wv[q] = w_head[c[q] < a.head ? c[q] : 0];
+        if (c[q] >= a.head && v[q] != 0.0f) wv[q] = a.w[c[q]];  // only the lanes that need memory ask for it
+      }
+      const RowExtent nxt2 = load_extent(a, r + 2 * kFullGroups, r1);
+      int32_t cn[4];
+      float vn[4];
+      load_pairs(a, nxt, gl, cn, vn);
+      float s = 0.0f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) s = fmaf(v[q], wv[q], s);
+      for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {  // rows longer than 64 entries
+        const int32_t col = a.col_idx[e];
+        s = fmaf(a.vals[e], col < a.head ? w_head[col] : a.w[col], s);
+      }
+      const float z = group_sum(s);
+      const float coef = loss_slope(a.loss, z, cur.y);
+      if (gl == 0) {
+        if (a.z_out) a.z_out[r] = z;
+        if (CSC) a.coef[r] = coef;
+        if (a.want_loss) loss_acc += (double)loss_value(a.loss, z, cur.y);
+      }
+      if (a.want_grad) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float g = coef * v[q];
+          if (v[q] == 0.0f) continue;  // outside the row (a stored zero adds nothing either)
+          if (c[q] < a.head) atomicAdd(&head_acc[c[q]], g);  // LDS
+          else if (!CSC) atomicAdd(&a.tail[c[q]], g);
+        }
+        for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {
+          const int32_t col = a.col_idx[e];
+          const float g = coef * a.vals[e];
+          if (col < a.head) atomicAdd(&head_acc[col], g);
+          else if (!CSC) atomicAdd(&a.tail[col], g);
+        }
+      }
+      r += kFullGroups;
+      cur = nxt; nxt = nxt2;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { c[q] = cn[q]; v[q] = vn[q]; }
     }
   }
   __syncthreads();
-  float *dst = a.part + (int64_t)blockIdx.x * a.head;
-  for (int32_t j = tid; j < a.head; j += kThreads) dst[j] = head_acc[j];
+  if (a.want_grad) {
+    float *dst = a.part + (int64_t)blockIdx.x * a.head;
+    for (int32_t j = tid; j < a.head; j += kFullThreads) dst[j] = head_acc[j];
+  }
   if (a.want_loss) {
     if (gl == 0) loss_red[grp] = loss_acc;
     __syncthreads();
     if (tid == 0) {
       double t = 0.0;
-      for (int k = 0; k < kGroups; ++k) t += loss_red[k];
+      for (int k = 0; k < kFullGroups; ++k) t += loss_red[k];
       a.part_loss[blockIdx.x] = t;
     }
   }
+}
+
+// Tail columns from the column-major copy: mu[c] = scale * sum_k coef[row_k] * val_k over the column's
+// entries, each column summed in a fixed order.  Columns are served by length so that no lane walks a long
+// column alone: up to kCscShort entries one thread per column (all tail columns in index order, so that
+// neighbouring lanes read neighbouring entries; longer ones are skipped here), up to kCscMedium a row of 16
+// lanes per column, beyond that a wavefront per column; the two longer classes come from lists made at
+// build time.  One launch: the workgroup index selects the class.
+constexpr int kCscShort = 16;
+constexpr int kCscMedium = 128;
+
+struct CscArgs {
+  const int32_t *ptr, *rows;
+  const float *vals, *coef;
+  const int32_t *medium, *longc;  // column lists
+  int32_t n_medium, n_long;
+  int32_t wgs_short, wgs_medium;
+  int64_t head, d, n_rows;
+  float scale;
+  float *mu;
+};
+
+// partial sum of entries lo + lane, lo + lane + stride, ... (four entries per step, all loads in flight)
+__device__ __forceinline__ float csc_column_part(const CscArgs &a, int32_t lo, int32_t hi, int lane, int stride) {
+  float acc = 0.0f;
+  for (int32_t k = lo + lane; k < hi; k += 4 * stride) {
+    int32_t rr[4];
+    float vv[4], cc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const bool ok = k + q * stride < hi;
+      rr[q] = ok ? a.rows[k + q * stride] : 0;
+      vv[q] = ok ? a.vals[k + q * stride] : 0.0f;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) cc[q] = (k + q * stride < hi && rr[q] < a.n_rows) ? a.coef[rr[q]] : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc = fmaf(cc[q], vv[q], acc);
+  }
+  return acc;
+}
+
+__global__ __launch_bounds__(kThreads) void csc_tail_kernel(CscArgs a) {
+  const int tid = threadIdx.x;
+  int32_t b = blockIdx.x;
+  if (b < a.wgs_short) {
+    const int64_t c = a.head + (int64_t)b * kThreads + tid;
+    if (c >= a.d) return;
+    const int32_t lo = a.ptr[c], hi = a.ptr[c + 1];
+    if (hi - lo > kCscShort) return;
+    a.mu[c] = csc_column_part(a, lo, hi, 0, 1) * a.scale;
+    return;
+  }
+  b -= a.wgs_short;
+  if (b < a.wgs_medium) {
+    const int32_t i = b * (kThreads / kGroup) + tid / kGroup;
+    if (i >= a.n_medium) return;  // whole rows of 16 lanes leave together
+    const int32_t c = a.medium[i];
+    const float t = group_sum(csc_column_part(a, a.ptr[c], a.ptr[c + 1], tid & (kGroup - 1), kGroup));
+    if ((tid & (kGroup - 1)) == 0) a.mu[c] = t * a.scale;
+    return;
+  }
+  b -= a.wgs_medium;
+  const int32_t i = b * (kThreads / 64) + tid / 64;
+  if (i >= a.n_long) return;  // whole wavefronts leave together
+  const int32_t c = a.longc[i];
+  const float t = wave_sum(csc_column_part(a, a.ptr[c], a.ptr[c + 1], tid & 63, 64));
+  if ((tid & 63) == 0) a.mu[c] = t * a.scale;
+}
+
+// build: number of medium / long tail columns (cls[0], cls[1]), then their lists
+__global__ void csc_classify_kernel(const int32_t *__restrict__ ptr, int64_t head, int64_t d, int32_t *cls,
+                                    int32_t *__restrict__ medium, int32_t *__restrict__ longc) {
+  const int64_t c = head + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  const int32_t len = ptr[c + 1] - ptr[c];
+  if (len <= kCscShort) return;
+  if (len <= kCscMedium) {
+    const int32_t k = atomicAdd(&cls[0], 1);
+    if (medium) medium[k] = (int32_t)c;
+  } else {
+    const int32_t k = atomicAdd(&cls[1], 1);
+    if (longc) longc[k] = (int32_t)c;
+  }
+}
+
+// ---- column-major copy of the tail entries, built once per context --------------------------------
+__global__ void csc_count_kernel(const int32_t *__restrict__ col_idx, int64_t nnz, int32_t head,
+                                 int32_t *__restrict__ count) {
+  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e < nnz && col_idx[e] >= head) atomicAdd(&count[col_idx[e]], 1);
+}
+
+// exclusive prefix sum of count[0..d) into ptr[0..d], one workgroup walking 1024-element blocks; also the
+// largest count (max_out)
+__global__ __launch_bounds__(1024) void csc_scan_kernel(const int32_t *__restrict__ count, int64_t d,
+                                                        int32_t *__restrict__ ptr, int32_t *__restrict__ max_out) {
+  __shared__ int32_t buf[1024];
+  __shared__ int32_t carry_sh;
+  const int tid = threadIdx.x;
+  if (tid == 0) carry_sh = 0;
+  int32_t mx = 0;
+  __syncthreads();
+  for (int64_t base = 0; base < d; base += 1024) {
+    const int64_t j = base + tid;
+    const int32_t x = j < d ? count[j] : 0;
+    mx = x > mx ? x : mx;
+    buf[tid] = x;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {  // Hillis-Steele inclusive scan
+      const int32_t t = tid >= off ? buf[tid - off] : 0;
+      __syncthreads();
+      buf[tid] += t;
+      __syncthreads();
+    }
+    const int32_t carry = carry_sh;
+    if (j < d) ptr[j] = carry + buf[tid] - x;
+    __syncthreads();
+    if (tid == 1023) carry_sh = carry + buf[1023];
+    __syncthreads();
+  }
+  if (tid == 0) ptr[d] = carry_sh;
+  buf[tid] = mx;
+  __syncthreads();
+  for (int off = 512; off > 0; off >>= 1) {
+    if (tid < off) buf[tid] = buf[tid] > buf[tid + off] ? buf[tid] : buf[tid + off];
+    __syncthreads();
+  }
+  if (tid == 0) *max_out = buf[0];
+}
+
+// thread per row: append the row's tail entries to their columns (any order inside a column)
+__global__ void csc_fill_kernel(const int32_t *__restrict__ row_ptr, const int32_t *__restrict__ col_idx,
+                                const float *__restrict__ vals, int64_t n, int32_t head,
+                                int32_t *__restrict__ cursor, int32_t *__restrict__ rows, float *__restrict__ cvals) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n) return;
+  for (int32_t e = row_ptr[r]; e < row_ptr[r + 1]; ++e) {
+    const int32_t c = col_idx[e];
+    if (c < head) continue;
+    const int32_t k = atomicAdd(&cursor[c], 1);
+    rows[k] = (int32_t)r;
+    cvals[k] = vals[e];
+  }
+}
+
+// thread per column: order the column's entries by row (insertion sort; the build refuses long tail columns)
+__global__ void csc_sort_kernel(const int32_t *__restrict__ ptr, int64_t head, int64_t d, int32_t *__restrict__ rows,
+                                float *__restrict__ cvals) {
+  const int64_t c = head + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  const int32_t lo = ptr[c], hi = ptr[c + 1];
+  for (int32_t i = lo + 1; i < hi; ++i) {
+    const int32_t rk = rows[i];
+    const float vk = cvals[i];
+    int32_t j = i - 1;
+    while (j >= lo && rows[j] > rk) {
+      rows[j + 1] = rows[j];
+      cvals[j + 1] = cvals[j];
+      --j;
+    }
+    rows[j + 1] = rk;
+    cvals[j + 1] = vk;
+  }
+}
+
+__global__ void fill_i32_kernel(int32_t *dst, int32_t v, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = v;
 }
 
 // mu[j] = scale * tail[j] for the tail columns (the head comes from the fold of the partial rows)
@@ -231,7 +486,7 @@ __global__ void zero_kernel(float4 *__restrict__ dst, int64_t n4) {
 int csr_head_columns(int64_t d) { return (int)(d < 8192 ? d : 8192); }
 
 int csr_full_grad_wgs(int64_t n) {
-  int64_t wgs = 1024;  // 4 resident workgroups per CU (LDS)
+  int64_t wgs = 512;  // two resident 1024-thread workgroups per CU
   const int64_t by_rows = (n + 63) / 64;
   if (wgs > by_rows) wgs = by_rows;
   if (wgs >= 32) wgs = wgs / 16 * 16;
@@ -246,25 +501,96 @@ hipError_t launch_zero(float *dst, int64_t n, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Longest tail column the column-major copy accepts (its build sorts a column with one thread).
+constexpr int32_t kCscMaxColumn = 4096;
+
+// Builds the column-major copy of the tail entries in the context's scratch on `st` and waits for it.
+// Sets c->csc_ready; leaves it false (the snapshot pass then uses atomics) when a tail column is too long.
+hipError_t build_csc_tail(lpc_ctx *c, hipStream_t st) {
+  c->csc_ready = false;
+  const int32_t head = csr_head_columns(c->d);
+  if (c->d <= head || c->prob.nnz <= 0) return hipSuccess;
+  const int64_t d = c->d, nnz = c->prob.nnz;
+  int32_t *count = c->s.csc_cursor;  // reused: counts, then insertion cursors
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((d + 1 + 255) / 256)), dim3(256), 0, st, count, 0, d + 1);
+  hipLaunchKernelGGL(csc_count_kernel, dim3((unsigned)((nnz + 255) / 256)), dim3(256), 0, st, c->prob.col_idx, nnz, head,
+                     count);
+  hipLaunchKernelGGL(csc_scan_kernel, dim3(1), dim3(1024), 0, st, (const int32_t *)count, d, c->s.csc_ptr,
+                     c->s.csc_ptr + d + 1);
+  int32_t tail_info[1] = {0};
+  hipError_t e = hipMemcpyAsync(tail_info, c->s.csc_ptr + d + 1, sizeof(int32_t), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return e;
+  if (tail_info[0] > kCscMaxColumn) return hipSuccess;
+  e = hipMemcpyAsync(count, c->s.csc_ptr, sizeof(int32_t) * (size_t)d, hipMemcpyDeviceToDevice, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(csc_fill_kernel, dim3((unsigned)((c->n + 255) / 256)), dim3(256), 0, st, c->prob.row_ptr,
+                     c->prob.col_idx, c->prob.vals, c->n, head, count, c->s.csc_rows, c->s.csc_vals);
+  hipLaunchKernelGGL(csc_sort_kernel, dim3((unsigned)((d - head + 255) / 256)), dim3(256), 0, st,
+                     (const int32_t *)c->s.csc_ptr, (int64_t)head, d, c->s.csc_rows, c->s.csc_vals);
+  // column lists by length: count, then fill (the cursor array is free again and holds both lists)
+  int32_t *cls = c->s.csc_ptr + d + 2;
+  int32_t counts[2] = {0, 0};
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, st, cls, 0, (int64_t)2);
+  hipLaunchKernelGGL(csc_classify_kernel, dim3((unsigned)((d - head + 255) / 256)), dim3(256), 0, st,
+                     (const int32_t *)c->s.csc_ptr, (int64_t)head, d, cls, (int32_t *)nullptr, (int32_t *)nullptr);
+  e = hipMemcpyAsync(counts, cls, sizeof(counts), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return e;
+  c->csc_medium = counts[0];
+  c->csc_long = counts[1];
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, st, cls, 0, (int64_t)2);
+  hipLaunchKernelGGL(csc_classify_kernel, dim3((unsigned)((d - head + 255) / 256)), dim3(256), 0, st,
+                     (const int32_t *)c->s.csc_ptr, (int64_t)head, d, cls, c->s.csc_cursor,
+                     c->s.csc_cursor + c->csc_medium);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = hipStreamSynchronize(st);
+  if (e == hipSuccess) c->csc_ready = true;
+  return e;
+}
+
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st) {
   CsrArgs a{};
   a.row_ptr = c->prob.row_ptr; a.col_idx = c->prob.col_idx; a.vals = c->prob.vals; a.y = c->prob.y;
   a.w = w; a.z_out = z; a.tail = c->s.csr_tail; a.part = c->s.part; a.part_loss = c->s.part_loss;
-  a.n = c->n; a.d = c->d; a.d_pad = c->d_pad; a.n_rows = n_rows;
+  a.coef = c->s.csc_coef;
+  a.n = c->n; a.d = c->d; a.d_pad = c->d_pad; a.n_rows = n_rows; a.nnz = c->prob.nnz;
   a.head = csr_head_columns(c->d); a.loss = c->prob.loss; a.want_loss = want_loss ? 1 : 0;
+  a.want_grad = mu != nullptr ? 1 : 0;
+  const bool csc = c->csc_ready && mu != nullptr;
   const int wgs = c->full_grad_wgs;
   const int64_t rpw = (n_rows + wgs - 1) / wgs;
-  hipError_t e = launch_zero(c->s.csr_tail, c->d_pad, st);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(csr_full_kernel, dim3((unsigned)wgs), dim3(kThreads), (size_t)a.head * sizeof(float), st, a,
-                     rpw);
+  hipError_t e;
+  if (!csc && mu) {
+    e = launch_zero(c->s.csr_tail, c->d_pad, st);
+    if (e != hipSuccess) return e;
+  }
+  const size_t lds = 2 * (size_t)a.head * sizeof(float);
+  if (csc) hipLaunchKernelGGL(csr_full_kernel<true>, dim3((unsigned)wgs), dim3(kFullThreads), lds, st, a, rpw);
+  else hipLaunchKernelGGL(csr_full_kernel<false>, dim3((unsigned)wgs), dim3(kFullThreads), lds, st, a, rpw);
   e = hipGetLastError();
   if (e != hipSuccess || !mu) return e;
   if (c->d > a.head) {
     const int64_t tail_n = c->d - a.head;
-    hipLaunchKernelGGL(csr_tail_kernel, dim3((unsigned)((tail_n + 255) / 256)), dim3(256), 0, st,
-                       (const float *)c->s.csr_tail, (float)(1.0 / (double)n_rows), (int64_t)a.head, c->d, mu);
+    const float scale = (float)(1.0 / (double)n_rows);
+    if (csc) {
+      CscArgs ca{};
+      ca.ptr = c->s.csc_ptr; ca.rows = c->s.csc_rows; ca.vals = c->s.csc_vals; ca.coef = c->s.csc_coef;
+      ca.medium = c->s.csc_cursor; ca.longc = c->s.csc_cursor + c->csc_medium;
+      ca.n_medium = c->csc_medium; ca.n_long = c->csc_long;
+      ca.wgs_short = (int32_t)((tail_n + kThreads - 1) / kThreads);
+      ca.wgs_medium = (c->csc_medium + kThreads / kGroup - 1) / (kThreads / kGroup);
+      const int32_t wgs_long = (c->csc_long + kThreads / 64 - 1) / (kThreads / 64);
+      ca.head = a.head; ca.d = c->d; ca.n_rows = n_rows; ca.scale = scale; ca.mu = mu;
+      hipLaunchKernelGGL(csc_tail_kernel, dim3((unsigned)(ca.wgs_short + ca.wgs_medium + wgs_long)), dim3(kThreads), 0,
+                         st, ca);
+    } else
+      hipLaunchKernelGGL(csr_tail_kernel, dim3((unsigned)((tail_n + 255) / 256)), dim3(256), 0, st,
+                         (const float *)c->s.csr_tail, scale, (int64_t)a.head, c->d, mu);
   }
   return hipGetLastError();
 }

@@ -67,6 +67,12 @@ struct Scratch {
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
   float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
+  // column-major copy of the CSR entries whose column is not in the head (built by lpc_create)
+  int32_t *csc_ptr;     // [d+4]: column extents (head columns are empty), the longest column, two build counters
+  int32_t *csc_cursor;  // [d+1] build scratch, then the lists of medium and long tail columns
+  int32_t *csc_rows;    // [nnz] row index per entry, ascending inside a column
+  float *csc_vals;      // [nnz]
+  float *csc_coef;      // [n] per-row loss slopes of the snapshot pass
   uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
   // MLP instance: gathered inputs/labels and per-layer activations / deltas for the two parameter sets
   float *mlp_xb;        // [rows][dims[0]]
@@ -95,6 +101,8 @@ struct lpc_ctx {
   int32_t stat_slots;     // statistic partials per vector
   int32_t cus;            // compute units of the device (256 on MI355X)
   int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
+  bool csc_ready = false;  // the column-major tail copy exists (CSR snapshot pass without atomics)
+  int32_t csc_medium = 0, csc_long = 0;  // tail columns served by 16 lanes / by a wavefront
   bool csr_sparse = false; // inner iterations of Alg. 1 keep u^i sparse (CSR rows that touch few columns)
   int32_t sparse_head = 0; // leading columns that every sparse pass visits densely
   int64_t bitmap_words = 0; // words per worker of the touched-segment bitmap
@@ -126,6 +134,7 @@ hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w
 int csr_head_columns(int64_t d);
 int csr_full_grad_wgs(int64_t n);
 hipError_t launch_zero(float *dst, int64_t n, hipStream_t st);
+hipError_t build_csc_tail(lpc_ctx *c, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
 int csr_sparse_parts(int32_t B);
