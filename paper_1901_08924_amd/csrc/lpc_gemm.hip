@@ -14,6 +14,7 @@
 // difference of two weight gradients is one contraction over stacked rows).
 #include <hip/hip_runtime.h>
 
+#include "lpc_device.h"
 #include "lpc_internal.h"
 
 namespace lpc {
@@ -36,7 +37,9 @@ __device__ __forceinline__ float guarded(const float *p, int64_t ld, int r, int 
 //   TRANS == true : the operand is stored [k][mn] (mn contiguous).  Thread t takes rows k0 + t/32 and
 //                   k0 + t/32 + 8, columns 4*(t%32) .. +3.
 // TILE (128 or 64) is the slab's extent along m (or n); a 64-wide slab needs one 16-byte load per thread.
-template <bool TRANS, int TILE>
+// FULL: the whole slab lies inside the operand and is 16-byte aligned (the launcher checks): plain vector
+// loads with no branches between them, so all of a slab's loads are in flight together.
+template <bool TRANS, int TILE, bool FULL>
 __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t ld, int mn0, int k0, int MN, int K,
                                            bool vec_ok, int tid, float (&r)[8]) {
 #pragma unroll
@@ -45,7 +48,10 @@ __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t 
     if (!TRANS) { row = mn0 + (tid >> 2) + 64 * h; col = k0 + 4 * (tid & 3); R = MN; C = K; }
     else if (TILE == 128) { row = k0 + (tid >> 5) + 8 * h; col = mn0 + 4 * (tid & 31); R = K; C = MN; }
     else { row = k0 + (tid >> 4); col = mn0 + 4 * (tid & 15); R = K; C = MN; }
-    if (vec_ok && row < R && col + 3 < C) {
+    if constexpr (FULL) {
+      const float4 v = *reinterpret_cast<const float4 *>(p + (int64_t)row * ld + col);
+      r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
+    } else if (vec_ok && row < R && col + 3 < C) {
       const float4 v = *reinterpret_cast<const float4 *>(p + (int64_t)row * ld + col);
       r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
     } else {
@@ -74,7 +80,7 @@ __device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float
 
 // TN = 128: 128x128 tile, each wavefront 64x64 (2x2 MFMA tiles).  TN = 64: 128x64 tile, each wavefront
 // 64x32 (2x1) -- twice as many workgroups for outputs too small to fill the chip with 128x128 tiles.
-template <bool TA, bool TB, int TN>
+template <bool TA, bool TB, int TN, bool FULL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int NJ = TN / 64;
   __shared__ __attribute__((aligned(16))) float As[2][BK][LDT];
@@ -101,8 +107,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const bool vb = (ldb % 4 == 0) && (((uintptr_t)B & 15u) == 0);
     const int K = g.K;
     const int nslab = (K + BK - 1) / BK;
-    fetch_slab<TA, BM>(A, lda, m0, 0, g.M, K, va, tid, ra);
-    fetch_slab<!TB, TN>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
+    fetch_slab<TA, BM, FULL>(A, lda, m0, 0, g.M, K, va, tid, ra);
+    fetch_slab<!TB, TN, FULL>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
     __syncthreads();  // the previous segment's last slab has been consumed
     stash_slab<TA, BM>(As[0], tid, ra);
     stash_slab<!TB, TN>(Bs[0], tid, rb);
@@ -110,8 +116,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     for (int t = 0; t < nslab; ++t) {
       const int cur = t & 1;
       if (t + 1 < nslab) {
-        fetch_slab<TA, BM>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
-        fetch_slab<!TB, TN>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
+        fetch_slab<TA, BM, FULL>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
+        fetch_slab<!TB, TN, FULL>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
       }
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
@@ -145,7 +151,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + (lane & 31);
       if (col >= g.N) continue;
-      const float bias = g.bias ? g.bias[col] : 0.0f;
+      const float bias = g.bias ? g.bias[bz * g.strideBias + col] : 0.0f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -161,25 +167,192 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
+// ---- outputs with at most 16 columns (the last layer of the MLP) -------------------------------------
+// A 128-wide matrix-core tile would be 90 % padding and the long K loop of the few tiles is pure latency,
+// so these products run on the vector units with B (at most K x 16) staged in LDS.
+constexpr int kSkinnyN = 16;
+constexpr int kSkinnyLdsFloats = 16384;  // 64 KB
+
+__device__ __forceinline__ void skinny_store(const GemmArgs &g, float *C, int64_t bz, int row, int col, float acc) {
+  const int64_t off = (int64_t)row * g.ldc + col;
+  float val = g.alpha * acc + (g.bias ? g.bias[bz * g.strideBias + col] : 0.0f);
+  if (g.relu) val = val > 0.0f ? val : 0.0f;
+  if (g.relu_mask) val = g.relu_mask[off + (C - g.C)] > 0.0f ? val : 0.0f;
+  if (g.accumulate) val += C[off];
+  C[off] = val;
+}
+
+// C = A*B, A [M][K] row-major.  A wavefront takes one row of A at a time (16 rows per workgroup): its lanes
+// split K in groups of four, read B transposed from LDS (Bt[c][k], k contiguous) and close each of the N dot
+// products with a wavefront reduction.  K is walked in chunks of kc <= kSkinnyLdsFloats / N rows of B.
+__global__ __launch_bounds__(256) void gemm_skinny_nn_kernel(GemmArgs g, int kc) {
+  extern __shared__ float Bt[];  // [N][kc + 4]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t bz = blockIdx.y;
+  const int pitch = kc + 4;
+  const int row0 = blockIdx.x * 16;
+  float acc[4][kSkinnyN];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int c = 0; c < kSkinnyN; ++c) acc[r][c] = 0.0f;
+  for (int s = 0; s < g.nseg; ++s) {
+    const float *A = g.A[s] + bz * g.strideA[s];
+    const float *B = g.B[s] + bz * g.strideB[s];
+    for (int k0 = 0; k0 < g.K; k0 += kc) {
+      const int kn = g.K - k0 < kc ? g.K - k0 : kc;
+      __syncthreads();  // the previous chunk has been consumed
+      for (int i = tid; i < kn * g.N; i += 256) {
+        const int k = i / g.N, c = i - k * g.N;
+        Bt[c * pitch + k] = B[(int64_t)(k0 + k) * g.ldb[s] + c];
+      }
+      for (int i = tid; i < 4 * g.N; i += 256) Bt[(i >> 2) * pitch + kn + (i & 3)] = 0.0f;  // pad of the last group
+      __syncthreads();
+      for (int k = 4 * lane; k < kn; k += 256) {
+        // the wavefront's four rows are requested together, then consumed
+        float av[4][4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = row0 + wave * 4 + r;
+          const float *a = A + (int64_t)(row < g.M ? row : g.M - 1) * g.lda[s] + k0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) av[r][j] = (row < g.M && k + j < kn) ? a[k + j] : 0.0f;
+        }
+#pragma unroll
+        for (int c = 0; c < kSkinnyN; ++c) {
+          if (c < g.N) {
+            const float4 b = *reinterpret_cast<const float4 *>(&Bt[c * pitch + k]);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              acc[r][c] = fmaf(av[r][0], b.x, fmaf(av[r][1], b.y, fmaf(av[r][2], b.z, fmaf(av[r][3], b.w, acc[r][c]))));
+          }
+        }
+      }
+    }
+  }
+  float *C = g.C + bz * g.strideC;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = row0 + wave * 4 + r;
+#pragma unroll
+    for (int c = 0; c < kSkinnyN; ++c) {
+      if (c < g.N) {  // uniform
+        const float t = wave_sum(acc[r][c]);
+        if (lane == 0 && row < g.M) skinny_store(g, C, bz, row, c, t);
+      }
+    }
+  }
+}
+
+// C = A'*B, A stored [K][M].  A wavefront owns 64 consecutive rows m of C (one per lane: the loads of A are
+// coalesced along m); the four wavefronts of a workgroup split K and are combined through LDS in wavefront
+// order.  B rows (N values, the same for every lane) come from LDS in chunks of kc rows.
+__global__ __launch_bounds__(256) void gemm_skinny_tn_kernel(GemmArgs g, int kc) {
+  extern __shared__ float Bs[];  // [kc][16], then the reduction buffer [4][64][16]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t bz = blockIdx.y;
+  const int m = blockIdx.x * 64 + lane;
+  float acc[kSkinnyN];
+#pragma unroll
+  for (int c = 0; c < kSkinnyN; ++c) acc[c] = 0.0f;
+  for (int s = 0; s < g.nseg; ++s) {
+    const float *A = g.A[s] + bz * g.strideA[s];
+    const float *B = g.B[s] + bz * g.strideB[s];
+    for (int k0 = 0; k0 < g.K; k0 += kc) {
+      const int kn = g.K - k0 < kc ? g.K - k0 : kc;
+      __syncthreads();
+      for (int i = tid; i < kn * kSkinnyN; i += 256) {
+        const int k = i >> 4, c = i & 15;
+        Bs[i] = c < g.N ? B[(int64_t)(k0 + k) * g.ldb[s] + c] : 0.0f;
+      }
+      __syncthreads();
+      if (m < g.M) {
+        for (int k = wave; k < kn; k += 32) {
+          // eight rows of A in flight per step
+          float a[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) a[j] = k + 4 * j < kn ? A[(int64_t)(k0 + k + 4 * j) * g.lda[s] + m] : 0.0f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int kk = k + 4 * j < kn ? k + 4 * j : 0;  // a[j] is zero past the end
+            const float4 *b = reinterpret_cast<const float4 *>(&Bs[kk * kSkinnyN]);
+            const float4 b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
+            acc[0] = fmaf(a[j], b0.x, acc[0]); acc[1] = fmaf(a[j], b0.y, acc[1]);
+            acc[2] = fmaf(a[j], b0.z, acc[2]); acc[3] = fmaf(a[j], b0.w, acc[3]);
+            acc[4] = fmaf(a[j], b1.x, acc[4]); acc[5] = fmaf(a[j], b1.y, acc[5]);
+            acc[6] = fmaf(a[j], b1.z, acc[6]); acc[7] = fmaf(a[j], b1.w, acc[7]);
+            acc[8] = fmaf(a[j], b2.x, acc[8]); acc[9] = fmaf(a[j], b2.y, acc[9]);
+            acc[10] = fmaf(a[j], b2.z, acc[10]); acc[11] = fmaf(a[j], b2.w, acc[11]);
+            acc[12] = fmaf(a[j], b3.x, acc[12]); acc[13] = fmaf(a[j], b3.y, acc[13]);
+            acc[14] = fmaf(a[j], b3.z, acc[14]); acc[15] = fmaf(a[j], b3.w, acc[15]);
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  float *red = Bs;  // [4][64][16]
+#pragma unroll
+  for (int c = 0; c < kSkinnyN; ++c) red[(wave * 64 + lane) * kSkinnyN + c] = acc[c];
+  __syncthreads();
+  float *C = g.C + bz * g.strideC;
+  for (int i = tid; i < 64 * kSkinnyN; i += 256) {
+    const int l = i >> 4, c = i & 15, row = blockIdx.x * 64 + l;
+    if (row < g.M && c < g.N) {
+      const float t = ((red[(0 * 64 + l) * kSkinnyN + c] + red[(1 * 64 + l) * kSkinnyN + c]) +
+                       red[(2 * 64 + l) * kSkinnyN + c]) + red[(3 * 64 + l) * kSkinnyN + c];
+      skinny_store(g, C, bz, row, c, t);
+    }
+  }
+}
+
 }  // namespace
 
 // Validates shapes on the host (every access in the kernel is guarded by M, N, K).
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.nseg < 1 || g.nseg > 2 || g.batch < 1) return hipErrorInvalidValue;
+  if (g.N <= kSkinnyN && !g.transB && g.M >= 64) {
+    if (!g.transA) {
+      int kc = kSkinnyLdsFloats / g.N - 4;
+      kc = kc / 4 * 4;
+      if (kc > g.K) kc = (g.K + 3) / 4 * 4;
+      const size_t lds = (size_t)g.N * (kc + 4) * sizeof(float);
+      hipLaunchKernelGGL(gemm_skinny_nn_kernel, dim3((unsigned)((g.M + 15) / 16), (unsigned)g.batch), dim3(256), lds, st,
+                         g, kc);
+    } else {
+      int kc = 768;  // 48 KB of B rows; the reduction buffer needs 16 KB
+      if (kc > g.K) kc = g.K;
+      const size_t floats = (size_t)kc * kSkinnyN > 4u * 64 * kSkinnyN ? (size_t)kc * kSkinnyN : 4u * 64 * kSkinnyN;
+      hipLaunchKernelGGL(gemm_skinny_tn_kernel, dim3((unsigned)((g.M + 63) / 64), (unsigned)g.batch), dim3(256),
+                         floats * sizeof(float), st, g, kc);
+    }
+    return hipGetLastError();
+  }
   const int64_t tiles128 = (int64_t)((g.N + 127) / 128) * ((g.M + BM - 1) / BM) * g.batch;
   const bool narrow = tiles128 < 512 || g.N <= 64;   // fewer than two 128x128 tiles per CU: halve the tile
   const int tn = narrow ? 64 : 128;
   const dim3 grid((unsigned)((g.N + tn - 1) / tn), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
-#define LPC_GEMM_LAUNCH(TA_, TB_)                                                                          \
+  // whole tiles and slabs, 16-byte aligned rows: the branch-free fetch
+  bool full = g.M % BM == 0 && g.N % tn == 0 && g.K % BK == 0;
+  for (int s = 0; s < g.nseg; ++s)
+    full = full && g.lda[s] % 4 == 0 && g.ldb[s] % 4 == 0 && ((uintptr_t)g.A[s] & 15u) == 0 &&
+           ((uintptr_t)g.B[s] & 15u) == 0 && g.strideA[s] % 4 == 0 && g.strideB[s] % 4 == 0;
+#define LPC_GEMM_LAUNCH2(TA_, TB_, FULL_)                                                                  \
   do {                                                                                                     \
-    if (narrow) hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 64>), grid, dim3(256), 0, st, g);            \
-    else hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 128>), grid, dim3(256), 0, st, g);                  \
+    if (narrow) hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 64, FULL_>), grid, dim3(256), 0, st, g);     \
+    else hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 128, FULL_>), grid, dim3(256), 0, st, g);           \
+  } while (0)
+#define LPC_GEMM_LAUNCH(TA_, TB_)                 \
+  do {                                            \
+    if (full) LPC_GEMM_LAUNCH2(TA_, TB_, true);   \
+    else LPC_GEMM_LAUNCH2(TA_, TB_, false);       \
   } while (0)
   if (!g.transA && !g.transB) LPC_GEMM_LAUNCH(false, false);
   else if (!g.transA && g.transB) LPC_GEMM_LAUNCH(false, true);
   else if (g.transA && !g.transB) LPC_GEMM_LAUNCH(true, false);
   else LPC_GEMM_LAUNCH(true, true);
 #undef LPC_GEMM_LAUNCH
+#undef LPC_GEMM_LAUNCH2
   return hipGetLastError();
 }
 

@@ -40,6 +40,7 @@ struct GemmArgs {
   int transA, transB;
   float alpha;
   const float *bias;
+  int64_t strideBias;  // per batch element
   int relu;
   const float *relu_mask;  // same layout as C
   int accumulate;

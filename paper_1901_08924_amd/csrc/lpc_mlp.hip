@@ -72,7 +72,17 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ D
   if (c < cols) {
     const float *p0 = D0 + (int64_t)b * K * cols + c;
     const float *p1 = D1 ? D1 + (int64_t)b * K * cols + c : nullptr;
-    for (int k = wv; k < K; k += 4) s += p0[(int64_t)k * cols] + (p1 ? p1[(int64_t)k * cols] : 0.0f);
+    for (int k = wv; k < K; k += 32) {  // eight rows of each set in flight per step
+      float v0[8], v1[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool ok = k + 4 * j < K;
+        v0[j] = ok ? p0[(int64_t)(k + 4 * j) * cols] : 0.0f;
+        v1[j] = (ok && p1) ? p1[(int64_t)(k + 4 * j) * cols] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s += v0[j] + v1[j];
+    }
   }
   red[wv][lane] = s;
   __syncthreads();
@@ -113,39 +123,48 @@ struct Net {
   float *del(int l, int set) const { return c->s.mlp_del + c->mlp_act_off[l] + (int64_t)set * rows_cap * dims[l]; }
 };
 
-// forward pass of `rows` rows whose inputs start at in0 (leading dimension ld0) with parameters W into set `set`
-hipError_t forward(const Net &nn, const float *W, const float *in0, int64_t ld0, int rows, int set, hipStream_t st) {
+// Forward pass of `rows` rows whose inputs start at in0 (leading dimension ld0) into activation sets
+// 0..nsets-1: set s uses the parameters at W + s*wstride (one batched product per layer).
+hipError_t forward(const Net &nn, const float *W, int64_t wstride, int nsets, const float *in0, int64_t ld0, int rows,
+                   hipStream_t st) {
   for (int l = 0; l < nn.L; ++l) {
     GemmArgs g{};
-    g.A[0] = l == 0 ? in0 : nn.act(l, set);
+    g.A[0] = l == 0 ? in0 : nn.act(l, 0);
     g.lda[0] = l == 0 ? ld0 : nn.dims[l];
+    g.strideA[0] = l == 0 ? 0 : nn.rows_cap * nn.dims[l];
     g.B[0] = W + nn.c->mlp_woff[l];
     g.ldb[0] = nn.dims[l + 1];
-    g.C = nn.act(l + 1, set);
+    g.strideB[0] = wstride;
+    g.C = nn.act(l + 1, 0);
     g.ldc = nn.dims[l + 1];
+    g.strideC = nn.rows_cap * nn.dims[l + 1];
     g.M = rows; g.N = nn.dims[l + 1]; g.K = nn.dims[l];
-    g.alpha = 1.0f; g.bias = W + nn.c->mlp_boff[l]; g.relu = (l + 1 < nn.L) ? 1 : 0;
-    g.nseg = 1; g.batch = 1;
+    g.alpha = 1.0f; g.bias = W + nn.c->mlp_boff[l]; g.strideBias = wstride; g.relu = (l + 1 < nn.L) ? 1 : 0;
+    g.nseg = 1; g.batch = nsets;
     hipError_t e = launch_gemm(g, st);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
-// deltas of every layer from the logits down; sign = -1 produces the negated deltas of the snapshot set
-hipError_t backward_data(const Net &nn, const float *W, const float *labels, int rows, int set, float sign,
+// Deltas of every layer from the logits down for sets 0..nsets-1; set 1 (the snapshot parameters) gets
+// negated deltas, so that the weight gradients of the two sets add up to the variance-reduced difference.
+hipError_t backward_data(const Net &nn, const float *W, int64_t wstride, int nsets, const float *labels, int rows,
                          double *row_loss, hipStream_t st) {
   const int classes = nn.dims[nn.L];
-  hipLaunchKernelGGL(softmax_delta_kernel, dim3((unsigned)((rows + 127) / 128)), dim3(128), 0, st,
-                     (const float *)nn.act(nn.L, set), labels, rows, classes, sign, nn.del(nn.L, set), row_loss);
+  for (int set = 0; set < nsets; ++set)
+    hipLaunchKernelGGL(softmax_delta_kernel, dim3((unsigned)((rows + 127) / 128)), dim3(128), 0, st,
+                       (const float *)nn.act(nn.L, set), labels, rows, classes, set == 0 ? 1.0f : -1.0f,
+                       nn.del(nn.L, set), set == 0 ? row_loss : nullptr);
   for (int l = nn.L - 1; l >= 1; --l) {
     GemmArgs g{};
-    g.A[0] = nn.del(l + 1, set); g.lda[0] = nn.dims[l + 1];
+    g.A[0] = nn.del(l + 1, 0); g.lda[0] = nn.dims[l + 1]; g.strideA[0] = nn.rows_cap * nn.dims[l + 1];
     g.B[0] = W + nn.c->mlp_woff[l]; g.ldb[0] = nn.dims[l + 1]; g.transB = 1;  // W_l is [in][out]; we need W_l'
-    g.C = nn.del(l, set); g.ldc = nn.dims[l];
+    g.strideB[0] = wstride;
+    g.C = nn.del(l, 0); g.ldc = nn.dims[l]; g.strideC = nn.rows_cap * nn.dims[l];
     g.M = rows; g.N = nn.dims[l]; g.K = nn.dims[l + 1];
-    g.alpha = 1.0f; g.relu_mask = nn.act(l, set);
-    g.nseg = 1; g.batch = 1;
+    g.alpha = 1.0f; g.relu_mask = nn.act(l, 0);
+    g.nseg = 1; g.batch = nsets;
     hipError_t e = launch_gemm(g, st);
     if (e != hipSuccess) return e;
   }
@@ -183,9 +202,9 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
     const int rows = (int)((n_rows - r0 < c->mlp_rows) ? n_rows - r0 : c->mlp_rows);
     const float *in0 = c->prob.X + r0 * c->prob.ldx;
     const float *labels = c->prob.y + r0;
-    hipError_t e = forward(nn, w, in0, c->prob.ldx, rows, 0, st);
+    hipError_t e = forward(nn, w, 0, 1, in0, c->prob.ldx, rows, st);
     if (e != hipSuccess) return e;
-    e = backward_data(nn, w, labels, rows, 0, 1.0f, f_out ? c->s.mlp_loss : nullptr, st);
+    e = backward_data(nn, w, 0, 1, labels, rows, f_out ? c->s.mlp_loss : nullptr, st);
     if (e != hipSuccess) return e;
     if (f_out)
       hipLaunchKernelGGL(sum_rows_loss_kernel, dim3(1), dim3(256), 0, st, (const double *)c->s.mlp_loss, rows,
@@ -217,14 +236,12 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const int in0 = nn.dims[0];
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, c->prob.X, c->prob.ldx, c->prob.y,
                      c->n, in0, key, tag, worker_begin, B, c->s.mlp_xb, c->s.mlp_yb);
-  hipError_t e;
-  for (int set = 0; set < 2; ++set) {
-    const float *W = set == 0 ? w : w_snap;
-    e = forward(nn, W, c->s.mlp_xb, in0, rows, set, st);
-    if (e != hipSuccess) return e;
-    e = backward_data(nn, W, c->s.mlp_yb, rows, set, set == 0 ? 1.0f : -1.0f, nullptr, st);
-    if (e != hipSuccess) return e;
-  }
+  // both parameter sets ride in one batched product per layer (set 1 = the snapshot, w_snap - w floats away)
+  const int64_t wstride = w_snap - w;
+  hipError_t e = forward(nn, w, wstride, 2, c->s.mlp_xb, in0, rows, st);
+  if (e != hipSuccess) return e;
+  e = backward_data(nn, w, wstride, 2, c->s.mlp_yb, rows, nullptr, st);
+  if (e != hipSuccess) return e;
   const float alpha = (float)(1.0 / (double)B);
   for (int l = nn.L - 1; l >= 0; --l) {
     const int out = nn.dims[l + 1], in = nn.dims[l];

@@ -155,7 +155,13 @@ __global__ __launch_bounds__(kThreads) void reduce_parts_kernel(const float *__r
   float acc = 0.0f;
   if (col < d) {
     const float *src = part + (int64_t)vec * parts * d + col;
-    for (int32_t p = wv; p < parts; p += 4) acc += src[(int64_t)p * d];
+    for (int32_t p = wv; p < parts; p += 32) {  // eight partial rows in flight per step
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = p + 4 * j < parts ? src[(int64_t)(p + 4 * j) * d] : 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc += v[j];
+    }
   }
   red[wv][lane] = acc;
   __syncthreads();

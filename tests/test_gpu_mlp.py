@@ -13,7 +13,9 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("M,N,K,tA,tB", [(128, 128, 16, 0, 0), (64, 32, 8, 0, 0), (130, 257, 35, 0, 0),
                                           (200, 100, 77, 1, 0), (96, 300, 64, 0, 1), (33, 10, 1024, 1, 1),
-                                          (2048, 10, 1024, 0, 0), (3, 5, 6, 0, 0), (512, 384, 256, 1, 0)])
+                                          (2048, 10, 1024, 0, 0), (3, 5, 6, 0, 0), (512, 384, 256, 1, 0),
+                                          (1024, 10, 256, 1, 0), (100, 7, 333, 1, 0), (77, 16, 100, 0, 0),
+                                          (300, 3, 2051, 0, 0), (130, 13, 2000, 1, 0)])
 def test_matrix_core_contraction(M, N, K, tA, tB):
     import torch
     from paper_1901_08924_amd import lpc
