@@ -51,8 +51,17 @@ def algorithmic_work(sp, dp, nnz):
         return {"full_rows": (n_full * (fwd_bwd_w - bwd_first), "flops"), "vr_rows": (vr, "flops"),
                 "exchange": (msg, "bytes")}
     if sp.csr is not None:
-        return {"full_rows": (8.0 * nnz * n_full / n + 4.0 * (n_full + 1) + 8.0 * n_full + 8.0 * d, "bytes"),
-                "vr_rows": (8.0 * N * B * nnz / n + 8.0 * N * dp, "bytes"),     # rows + zero and write U
+        full = (8.0 * nnz * n_full / n + 4.0 * (n_full + 1) + 8.0 * n_full + 8.0 * d, "bytes")
+        entries = float(N) * B * nnz / n
+        sparse = (bits < 32 and sp.algo == 0 and getattr(sp, "scheme", 0) == 0 and d >= 4 * 8192
+                  and 8.0 * B * nnz / n <= d)
+        if sparse:
+            # u^i stays sparse: the pairs of the sampled rows in, one contribution per entry out; the exchange
+            # must still read every worker's packed message and update all d coordinates (w, mu in; w out)
+            return {"full_rows": full, "vr_rows": (12.0 * entries, "bytes"),
+                    "exchange": (N * bits * dp / 8.0 + 16.0 * d, "bytes")}
+        return {"full_rows": full,
+                "vr_rows": (8.0 * entries + 8.0 * N * dp, "bytes"),     # rows + zero and write U
                 "exchange": (msg, "bytes")}
     return {"full_rows": (4.0 * n_full * d + 8.0 * n_full + 8.0 * d, "bytes"),  # X, y, w in; z, mu out
             "vr_rows": (4.0 * N * B * d + 4.0 * N * d, "bytes"),               # each sampled row once; U out

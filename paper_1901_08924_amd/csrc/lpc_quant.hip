@@ -716,25 +716,51 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
   const int64_t tile0 = (int64_t)blockIdx.x * kFusedCoords;
   // everything this thread will need from memory is requested before the statistics fold, so the three
   // dependent round trips (statistics, U, w/mu) overlap
-  float4 v_first = make_float4(0.f, 0.f, 0.f, 0.f);
-  if ((tid >> 5) < a.N && tile0 + 4 * (tid & 31) < a.d_pad)
-    v_first = *reinterpret_cast<const float4 *>(a.U + (int64_t)(tid >> 5) * a.d_pad + tile0 + 4 * (tid & 31));
+  float4 v_all[kFusedMaxN / 8];  // this thread's four coordinates of workers g, g+8, ...
+#pragma unroll
+  for (int q = 0; q < kFusedMaxN / 8; ++q) {
+    const int32_t i = (tid >> 5) + 8 * q;
+    v_all[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < a.N && tile0 + 4 * (tid & 31) < a.d_pad)
+      v_all[q] = *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + tile0 + 4 * (tid & 31));
+  }
   float w_old = 0.0f, mu_j = 0.0f;
   if (a.do_prox && tid < kFusedCoords && tile0 + tid < a.d) {
     w_old = a.w[tile0 + tid];
     mu_j = a.mu[tile0 + tid];
   }
-  for (int32_t i = wv; i < a.N; i += 4) {
-    double am, s, s2, b;
-    fold_stat_slots(a.stat_part + (int64_t)i * a.stat_slots * 4, a.nslots, lane, am, s, s2, b);
-    if (lane == 0) {
-      const QParams q = make_qparams(a.qs, am, s, s2, a.d);
-      qp[i] = q;
-      if (blockIdx.x == 0) {
-        a.delta_out[i] = q.delta;
-        double *o = a.stats + (int64_t)i * 4;
-        o[0] = am; o[1] = s; o[2] = s2; o[3] = b;
-        if (b > 0.0) atomicOr(&a.flags[0], 1u);
+  // wavefront wv folds the statistics of vectors wv, wv+4, ...; four vectors at a time so that their partials
+  // are requested together (the lane-wise sums and the butterflies keep fold_stat_slots' order)
+  for (int32_t i0 = wv; i0 < a.N; i0 += 16) {
+    double am[4], s[4], s2[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { am[q] = 0.0; s[q] = 0.0; s2[q] = 0.0; b[q] = 0.0; }
+    for (int32_t k = lane; k < a.nslots; k += 64) {
+      double2 lo[4], hi[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t i = i0 + 4 * q < a.N ? i0 + 4 * q : i0;
+        const double *p = a.stat_part + ((int64_t)i * a.stat_slots + k) * 4;
+        lo[q] = *reinterpret_cast<const double2 *>(p);
+        hi[q] = *reinterpret_cast<const double2 *>(p + 2);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { am[q] = fmax(am[q], lo[q].x); s[q] += lo[q].y; s2[q] += hi[q].x; b[q] += hi[q].y; }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int32_t i = i0 + 4 * q;
+      if (i >= a.N) break;  // uniform over the wavefront
+      const double am_w = wave_max(am[q]), s_w = wave_sum(s[q]), s2_w = wave_sum(s2[q]), b_w = wave_sum(b[q]);
+      if (lane == 0) {
+        const QParams q_i = make_qparams(a.qs, am_w, s_w, s2_w, a.d);
+        qp[i] = q_i;
+        if (blockIdx.x == 0) {
+          a.delta_out[i] = q_i.delta;
+          double *o = a.stats + (int64_t)i * 4;
+          o[0] = am_w; o[1] = s_w; o[2] = s2_w; o[3] = b_w;
+          if (b_w > 0.0) atomicOr(&a.flags[0], 1u);
+        }
       }
     }
   }
@@ -744,10 +770,13 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
     const int64_t j = tile0 + 4 * l;
     const float hi = (float)((1 << (a.bits - 1)) - 1);
     const float lo = -(float)(1 << (a.bits - 1));
-    for (int32_t i = g; i < a.N; i += 8) {
+#pragma unroll
+    for (int qi = 0; qi < kFusedMaxN / 8; ++qi) {
+      const int32_t i = g + 8 * qi;
+      if (i >= a.N) break;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (j < a.d_pad) {
-        v = (i == g) ? v_first : *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + j);
+        v = v_all[qi];
         if (j + 3 >= a.d) {
           if (j + 0 >= a.d) v.x = 0.f;
           if (j + 1 >= a.d) v.y = 0.f;
