@@ -98,7 +98,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  float ra[8], rb[8];
+  // Two register sets per operand: while slab t is consumed from LDS, slab t+1 waits in registers and slab t+2
+  // is in flight, so a slab's loads have two slabs' worth of matrix-unit time to arrive.
+  float ra[2][8], rb[2][8];
+  auto consume = [&](int cur) {
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      const int kr = kk + (lane >> 5), c = lane & 31;
+      const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
+      const float b0 = Bs[cur][kr][wn + c];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      if constexpr (NJ == 2) {
+        const float b1 = Bs[cur][kr][wn + 32 + c];
+        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      }
+    }
+  };
   for (int s = 0; s < g.nseg; ++s) {
     const float *A = g.A[s] + bz * g.strideA[s];
     const float *B = g.B[s] + bz * g.strideB[s];
@@ -107,38 +124,37 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const bool vb = (ldb % 4 == 0) && (((uintptr_t)B & 15u) == 0);
     const int K = g.K;
     const int nslab = (K + BK - 1) / BK;
-    fetch_slab<TA, BM, FULL>(A, lda, m0, 0, g.M, K, va, tid, ra);
-    fetch_slab<!TB, TN, FULL>(B, ldb, n0, 0, g.N, K, vb, tid, rb);
-    __syncthreads();  // the previous segment's last slab has been consumed
-    stash_slab<TA, BM>(As[0], tid, ra);
-    stash_slab<!TB, TN>(Bs[0], tid, rb);
-    __syncthreads();
-    for (int t = 0; t < nslab; ++t) {
-      const int cur = t & 1;
-      if (t + 1 < nslab) {
-        fetch_slab<TA, BM, FULL>(A, lda, m0, (t + 1) * BK, g.M, K, va, tid, ra);
-        fetch_slab<!TB, TN, FULL>(B, ldb, n0, (t + 1) * BK, g.N, K, vb, tid, rb);
-      }
-#pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        const int kr = kk + (lane >> 5), c = lane & 31;
-        const float a0 = As[cur][kr][wm + c], a1 = As[cur][kr][wm + 32 + c];
-        const float b0 = Bs[cur][kr][wn + c];
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-        if constexpr (NJ == 2) {
-          const float b1 = Bs[cur][kr][wn + 32 + c];
-          acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-          acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
-        }
-      }
-      if (t + 1 < nslab) {
-        // the other buffer was last read in iteration t-1, and every wave has passed the barrier since
-        stash_slab<TA, BM>(As[cur ^ 1], tid, ra);
-        stash_slab<!TB, TN>(Bs[cur ^ 1], tid, rb);
-      }
-      __syncthreads();
+    fetch_slab<TA, BM, FULL>(A, lda, m0, 0, g.M, K, va, tid, ra[0]);
+    fetch_slab<!TB, TN, FULL>(B, ldb, n0, 0, g.N, K, vb, tid, rb[0]);
+    if (nslab > 1) {
+      fetch_slab<TA, BM, FULL>(A, lda, m0, BK, g.M, K, va, tid, ra[1]);
+      fetch_slab<!TB, TN, FULL>(B, ldb, n0, BK, g.N, K, vb, tid, rb[1]);
     }
+    __syncthreads();  // the previous segment's last slab has been consumed
+    stash_slab<TA, BM>(As[0], tid, ra[0]);
+    stash_slab<!TB, TN>(Bs[0], tid, rb[0]);
+    __syncthreads();
+    // step p of a pair handles slab t+p, which sits in LDS buffer p; registers [1-p] hold slab t+p+1 and
+    // registers [p] are free for slab t+p+2
+#define LPC_GEMM_STEP(P)                                                                        \
+    {                                                                                           \
+      const int slab = t + (P);                                                                 \
+      if (slab + 2 < nslab) {                                                                   \
+        fetch_slab<TA, BM, FULL>(A, lda, m0, (slab + 2) * BK, g.M, K, va, tid, ra[(P)]);        \
+        fetch_slab<!TB, TN, FULL>(B, ldb, n0, (slab + 2) * BK, g.N, K, vb, tid, rb[(P)]);       \
+      }                                                                                         \
+      consume((P));                                                                             \
+      if (slab + 1 < nslab) {                                                                   \
+        stash_slab<TA, BM>(As[1 - (P)], tid, ra[1 - (P)]);                                      \
+        stash_slab<!TB, TN>(Bs[1 - (P)], tid, rb[1 - (P)]);                                     \
+      }                                                                                         \
+      __syncthreads();                                                                          \
+    }
+    for (int t = 0; t < nslab; t += 2) {
+      LPC_GEMM_STEP(0)
+      if (t + 1 < nslab) LPC_GEMM_STEP(1)
+    }
+#undef LPC_GEMM_STEP
   }
 
   // Accumulator layout of the 32x32 MFMA: lane l holds column (l % 32); register v holds row
@@ -202,9 +218,18 @@ __global__ __launch_bounds__(256) void gemm_skinny_nn_kernel(GemmArgs g, int kc)
     for (int k0 = 0; k0 < g.K; k0 += kc) {
       const int kn = g.K - k0 < kc ? g.K - k0 : kc;
       __syncthreads();  // the previous chunk has been consumed
-      for (int i = tid; i < kn * g.N; i += 256) {
-        const int k = i / g.N, c = i - k * g.N;
-        Bt[c * pitch + k] = B[(int64_t)(k0 + k) * g.ldb[s] + c];
+      for (int i0 = tid; i0 < kn * g.N; i0 += 8 * 256) {  // eight elements in flight per thread
+        float t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int i = i0 + j * 256, k = i / g.N, c = i - k * g.N;
+          t[j] = i < kn * g.N ? B[(int64_t)(k0 + k) * g.ldb[s] + c] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int i = i0 + j * 256, k = i / g.N, c = i - k * g.N;
+          if (i < kn * g.N) Bt[c * pitch + k] = t[j];
+        }
       }
       for (int i = tid; i < 4 * g.N; i += 256) Bt[(i >> 2) * pitch + kn + (i & 3)] = 0.0f;  // pad of the last group
       __syncthreads();
@@ -261,9 +286,16 @@ __global__ __launch_bounds__(256) void gemm_skinny_tn_kernel(GemmArgs g, int kc)
     for (int k0 = 0; k0 < g.K; k0 += kc) {
       const int kn = g.K - k0 < kc ? g.K - k0 : kc;
       __syncthreads();
-      for (int i = tid; i < kn * kSkinnyN; i += 256) {
-        const int k = i >> 4, c = i & 15;
-        Bs[i] = c < g.N ? B[(int64_t)(k0 + k) * g.ldb[s] + c] : 0.0f;
+      for (int i0 = tid; i0 < kn * kSkinnyN; i0 += 8 * 256) {  // eight elements in flight per thread
+        float t[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int i = i0 + j * 256, k = i >> 4, c = i & 15;
+          t[j] = (i < kn * kSkinnyN && c < g.N) ? B[(int64_t)(k0 + k) * g.ldb[s] + c] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (i0 + j * 256 < kn * kSkinnyN) Bs[i0 + j * 256] = t[j];
       }
       __syncthreads();
       if (m < g.M) {

@@ -94,7 +94,8 @@ struct lpc_ctx {
   bool grad_ok;           // the gradient passes are built for this problem
   bool csr;               // rows are stored in CSR
   bool mlp;               // multi-layer perceptron instance
-  int64_t mlp_rows;       // rows per pass (N*B)
+  int64_t mlp_rows;       // rows of a worker pass (N*B)
+  int64_t mlp_cap;        // rows each of the two activation sets can hold (the snapshot pass uses both as one)
   std::vector<int64_t> mlp_woff, mlp_boff, mlp_act_off;  // per layer offsets
   int64_t mlp_act_floats;
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)

@@ -177,6 +177,9 @@ void mlp_plan(lpc_ctx *c) {
   const int L = c->prob.mlp_nlayers;
   const int32_t *dims = c->mlp_dims.data();
   c->mlp_rows = (int64_t)c->cfg.N * c->cfg.B;
+  // the snapshot pass works through chunks of 2*mlp_cap rows: at least 8192, so that its products are large
+  // enough to fill the chip
+  c->mlp_cap = c->mlp_rows > 4096 ? c->mlp_rows : 4096;
   c->mlp_woff.assign(L, 0);
   c->mlp_boff.assign(L, 0);
   c->mlp_act_off.assign(L + 1, 0);
@@ -187,7 +190,7 @@ void mlp_plan(lpc_ctx *c) {
   }
   for (int l = 1; l <= L; ++l) {
     c->mlp_act_off[l] = aoff;
-    aoff += 2 * c->mlp_rows * dims[l];
+    aoff += 2 * c->mlp_cap * dims[l];
     aoff = (aoff + 63) / 64 * 64;
   }
   c->mlp_act_floats = aoff;
@@ -196,10 +199,11 @@ void mlp_plan(lpc_ctx *c) {
 // Alg. 1 step 4 for the MLP: mean gradient (and loss) over the first n_rows samples, in chunks of N*B rows.
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
                                 hipStream_t st) {
-  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_rows};
+  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_cap};
   const float alpha = (float)(1.0 / (double)n_rows);
-  for (int64_t r0 = 0; r0 < n_rows; r0 += c->mlp_rows) {
-    const int rows = (int)((n_rows - r0 < c->mlp_rows) ? n_rows - r0 : c->mlp_rows);
+  const int64_t chunk = 2 * c->mlp_cap;  // both activation sets, back to back, hold one chunk
+  for (int64_t r0 = 0; r0 < n_rows; r0 += chunk) {
+    const int rows = (int)((n_rows - r0 < chunk) ? n_rows - r0 : chunk);
     const float *in0 = c->prob.X + r0 * c->prob.ldx;
     const float *labels = c->prob.y + r0;
     hipError_t e = forward(nn, w, 0, 1, in0, c->prob.ldx, rows, st);
@@ -231,7 +235,7 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
 // (or the one shared batch), written to consecutive rows of U (row stride d_pad).
 hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, StreamKey key, uint32_t tag,
                               int32_t worker_begin, int32_t worker_end, float *U, hipStream_t st) {
-  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_rows};
+  Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_cap};
   const int nw = worker_end - worker_begin, B = c->cfg.B, rows = nw * B;
   const int in0 = nn.dims[0];
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, c->prob.X, c->prob.ldx, c->prob.y,
