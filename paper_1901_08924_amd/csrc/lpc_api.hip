@@ -54,7 +54,7 @@ lpc_status check_problem(const lpc_problem *p) {
     if (p->loss != LPC_LOSS_MLP_SOFTMAX && p->ldx < p->d) return LPC_ESHAPE;
   } else {
     if (!p->row_ptr || !p->col_idx || !p->vals) return LPC_ENULL;
-    if (!aligned(p->col_idx, 16) || !aligned(p->vals, 16) || !aligned(p->row_ptr, 4)) return LPC_ESHAPE;
+    if (!aligned(p->col_idx, 4) || !aligned(p->vals, 4) || !aligned(p->row_ptr, 4)) return LPC_ESHAPE;
     if (p->nnz < 0 || p->nnz > (int64_t)0x7FFFFFFFll) return LPC_ESHAPE;
     if (p->loss == LPC_LOSS_MLP_SOFTMAX) return LPC_EINVAL;
   }
@@ -175,7 +175,7 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->sparse_head = csr_head_columns(c->d);
     c->bitmap_words = (c->d_pad / 32 + 31) / 32;
     const double touched = (double)cfg->B * (double)p->nnz / (double)p->n;
-    c->csr_sparse = c->quant && cfg->algo == LPC_ALGO_LPC && cfg->scheme == LPC_SCHEME_A &&
+    c->csr_sparse = c->quant && cfg->algo == LPC_ALGO_LPC && cfg->scheme == LPC_SCHEME_A && cfg->N <= 64 &&
                     p->d >= 4 * (int64_t)c->sparse_head && touched * 8.0 <= (double)p->d;
     if (c->csr_sparse) {
       const size_t head_parts = (size_t)cfg->N * csr_sparse_parts(cfg->B) * c->sparse_head;
