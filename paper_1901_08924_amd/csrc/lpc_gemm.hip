@@ -21,7 +21,10 @@ namespace lpc {
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 16;
+#ifndef LPC_GEMM_BK
+#define LPC_GEMM_BK 16
+#endif
+constexpr int BM = 128, BK = LPC_GEMM_BK;
 constexpr int LDT = BM + 4;  // LDS row pitch (floats)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -31,23 +34,22 @@ __device__ __forceinline__ float guarded(const float *p, int64_t ld, int r, int 
   return (r < R && c < C) ? p[(int64_t)r * ld + c] : 0.0f;
 }
 
-// Fetch this thread's share of a 128 x 16 operand slab into 8 registers.
-//   TRANS == false: the operand is stored [mn][k] (k contiguous).  Thread t takes rows (t/4) and (t/4)+64,
-//                   columns k0 + 4*(t%4) .. +3.
-//   TRANS == true : the operand is stored [k][mn] (mn contiguous).  Thread t takes rows k0 + t/32 and
-//                   k0 + t/32 + 8, columns 4*(t%32) .. +3.
-// TILE (128 or 64) is the slab's extent along m (or n); a 64-wide slab needs one 16-byte load per thread.
+// Fetch this thread's share of a TILE x BK operand slab into registers, as TILE*BK/1024 groups of four.
+//   TRANS == false: the operand is stored [mn][k] (k contiguous).  Group h of thread t: row t/(BK/4) +
+//                   h*(1024/BK), columns k0 + 4*(t % (BK/4)) .. +3.
+//   TRANS == true : the operand is stored [k][mn] (mn contiguous).  Group h of thread t: row k0 +
+//                   t/(TILE/4) + h*(1024/TILE), columns 4*(t % (TILE/4)) .. +3.
 // FULL: the whole slab lies inside the operand and is 16-byte aligned (the launcher checks): plain vector
 // loads with no branches between them, so all of a slab's loads are in flight together.
 template <bool TRANS, int TILE, bool FULL>
 __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t ld, int mn0, int k0, int MN, int K,
-                                           bool vec_ok, int tid, float (&r)[8]) {
+                                           bool vec_ok, int tid, float (&r)[TILE * BK / 256]) {
+  constexpr int G = TILE * BK / 1024;
 #pragma unroll
-  for (int h = 0; h < TILE / 64; ++h) {
+  for (int h = 0; h < G; ++h) {
     int row, col, R, C;
-    if (!TRANS) { row = mn0 + (tid >> 2) + 64 * h; col = k0 + 4 * (tid & 3); R = MN; C = K; }
-    else if (TILE == 128) { row = k0 + (tid >> 5) + 8 * h; col = mn0 + 4 * (tid & 31); R = K; C = MN; }
-    else { row = k0 + (tid >> 4); col = mn0 + 4 * (tid & 15); R = K; C = MN; }
+    if (!TRANS) { row = mn0 + tid / (BK / 4) + h * (1024 / BK); col = k0 + 4 * (tid % (BK / 4)); R = MN; C = K; }
+    else { row = k0 + tid / (TILE / 4) + h * (1024 / TILE); col = mn0 + 4 * (tid % (TILE / 4)); R = K; C = MN; }
     if constexpr (FULL) {
       const float4 v = *reinterpret_cast<const float4 *>(p + (int64_t)row * ld + col);
       r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
@@ -63,16 +65,16 @@ __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t 
 
 // Store the registers k-major into an LDS slab T[k][mn].
 template <bool TRANS, int TILE>
-__device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float (&r)[8]) {
+__device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float (&r)[TILE * BK / 256]) {
+  constexpr int G = TILE * BK / 1024;
 #pragma unroll
-  for (int h = 0; h < TILE / 64; ++h) {
+  for (int h = 0; h < G; ++h) {
     if (!TRANS) {
-      const int mn = (tid >> 2) + 64 * h, k = 4 * (tid & 3);
+      const int mn = tid / (BK / 4) + h * (1024 / BK), k = 4 * (tid % (BK / 4));
 #pragma unroll
       for (int i = 0; i < 4; ++i) T[k + i][mn] = r[4 * h + i];
     } else {
-      const int k = TILE == 128 ? (tid >> 5) + 8 * h : (tid >> 4);
-      const int mn = TILE == 128 ? 4 * (tid & 31) : 4 * (tid & 15);
+      const int k = tid / (TILE / 4) + h * (1024 / TILE), mn = 4 * (tid % (TILE / 4));
       *reinterpret_cast<float4 *>(&T[k][mn]) = make_float4(r[4 * h], r[4 * h + 1], r[4 * h + 2], r[4 * h + 3]);
     }
   }
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 
   // Two register sets per operand: while slab t is consumed from LDS, slab t+1 waits in registers and slab t+2
   // is in flight, so a slab's loads have two slabs' worth of matrix-unit time to arrive.
-  float ra[2][8], rb[2][8];
+  float ra[2][BM * BK / 256], rb[2][TN * BK / 256];
   auto consume = [&](int cur) {
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
