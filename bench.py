@@ -116,6 +116,51 @@ def cpu_baseline(sp, cfgkw, alpc):
                       % (epochs, sample["m"], note, tc)}
 
 
+def contraction_shapes():
+    """The products of C5's layers (2048 rows per worker pass, 16 workers, snapshot chunks of 2048 rows) and a
+    4096^3 reference, each timed alone with HIP events: M, N, K, transposed operands, time, TFLOP/s."""
+    import ctypes as C
+    import torch
+    from paper_1901_08924_amd import lpc
+    fn = lpc.lib.lpc_debug_gemm
+    fn.restype = C.c_int
+    fn.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_float, C.c_void_p,
+                                                                        C.c_int, C.c_int, C.c_void_p]
+    st = torch.cuda.Stream()
+    torch.cuda.set_stream(st)
+    shapes = [("forward layer 1", 2048, 1024, 3072, 0, 0), ("forward layer 2", 2048, 1024, 1024, 0, 0),
+              ("forward layer 3", 2048, 10, 1024, 0, 0), ("data gradient layer 2", 2048, 1024, 1024, 0, 1),
+              ("data gradient layer 3", 2048, 1024, 10, 0, 1),
+              ("weight gradient layer 1, 2048 rows", 3072, 1024, 2048, 1, 0),
+              ("weight gradient layer 2, 2048 rows", 1024, 1024, 2048, 1, 0),
+              ("weight gradient layer 3, 2048 rows", 1024, 10, 2048, 1, 0),
+              ("weight gradient layer 1, one worker", 3072, 1024, 256, 1, 0),
+              ("weight gradient layer 2, one worker", 1024, 1024, 256, 1, 0),
+              ("reference", 4096, 4096, 4096, 0, 0)]
+    for name, M, N, K, tA, tB in shapes:
+        A = torch.randn((K, M) if tA else (M, K), device="cuda:0")
+        B = torch.randn((N, K) if tB else (K, N), device="cuda:0")
+        Cm = torch.zeros(M, N, device="cuda:0")
+        lda, ldb = (M if tA else K), (K if tB else N)
+
+        def run():
+            rc = fn(A.data_ptr(), B.data_ptr(), Cm.data_ptr(), M, N, K, lda, ldb, N, tA, tB, 1.0, None, 0, 0,
+                    st.cuda_stream)
+            assert rc == 0
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            run()
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        print(json.dumps({"product": name, "M": M, "N": N, "K": K, "transA": tA, "transB": tB, "us": round(us, 1),
+                          "tflops": round(2.0 * M * N * K / us * 1e-6, 1)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,7 +172,13 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten 1 GiB device-to-device copies (a kernel of known traffic: 1 GiB read, "
                          "1 GiB written) so that rocprofv3's FETCH_SIZE / WRITE_SIZE counters can be scaled")
+    ap.add_argument("--contractions", action="store_true",
+                    help="only time the MLP workload's matrix products one by one (the contraction kernel's "
+                         "unit-test entry point), one line per shape")
     args = ap.parse_args()
+    if args.contractions:
+        contraction_shapes()
+        return
     if args.copy_calibration:
         import torch
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
