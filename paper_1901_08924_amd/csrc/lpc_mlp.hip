@@ -54,6 +54,138 @@ __global__ void softmax_delta_kernel(const float *__restrict__ logits, const flo
   if (row_loss) row_loss[r] = (double)(logf(sum) + mx - z[label]);
 }
 
+// The last layer as one launch per pass: logits = a*W + b, softmax cross-entropy delta, and the delta handed
+// to the layer below, delta_prev = (a > 0) .* (delta * W').  With at most 16 classes W ([K][C]) fits LDS
+// (transposed, Wt[c][k]) and everything is a per-row computation: a wavefront takes four rows at a time, lane l
+// owns the activations k = 256*q + 4*l .. +3, the C dot products close with wavefront reductions, and the
+// activations are still in registers when delta_prev needs their signs.  blockIdx.y selects the parameter set
+// (set 1 = snapshot parameters, negated deltas).
+constexpr int kLastMaxC = 16;
+constexpr int kLastMaxK = 1024;
+constexpr int kLastRows = 16;  // rows per workgroup
+
+struct LastArgs {
+  const float *a;       // [set][rows][lda]
+  int64_t lda, a_set_stride;
+  const float *W;       // parameters of the layer, set s at W + s*w_set_stride: weights [K][C] then bias [C]
+  int64_t w_set_stride, bias_off;
+  const float *labels;
+  int rows, K, C;
+  float *delta;         // [set][rows][C]
+  int64_t d_set_stride;
+  float *delta_prev;    // [set][rows][K] or nullptr
+  int64_t dp_set_stride;
+  double *row_loss;     // set 0 only, or nullptr
+};
+
+__global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
+  extern __shared__ float Wt[];  // [C][K + 4], then bias [C]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int set = blockIdx.y;
+  const int pitch = g.K + 4;
+  const float *W = g.W + (int64_t)set * g.w_set_stride;
+  float *bias = Wt + g.C * pitch;
+  for (int i0 = tid; i0 < g.K * g.C; i0 += 20 * 256) {  // twenty elements in flight per thread
+    float t[20];
+#pragma unroll
+    for (int j = 0; j < 20; ++j) t[j] = i0 + j * 256 < g.K * g.C ? W[i0 + j * 256] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < 20; ++j) {
+      const int i = i0 + j * 256, k = i / g.C, c = i - k * g.C;
+      if (i < g.K * g.C) Wt[c * pitch + k] = t[j];
+    }
+  }
+  if (tid < g.C) bias[tid] = W[g.bias_off + tid];
+  __syncthreads();
+  const float sign = set == 0 ? 1.0f : -1.0f;
+  const int row0 = blockIdx.x * kLastRows + wave * 4;
+  const float *a = g.a + (int64_t)set * g.a_set_stride;
+  // this lane's activations of the wavefront's four rows (K <= 1024: at most four groups of four per row)
+  float4 av[4][4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int k = 256 * q + 4 * lane;
+      av[r][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (row0 + r < g.rows && k < g.K) av[r][q] = *reinterpret_cast<const float4 *>(a + (int64_t)(row0 + r) * g.lda + k);
+    }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = row0 + r;
+    float z[kLastMaxC];
+#pragma unroll
+    for (int c = 0; c < kLastMaxC; ++c) {
+      z[c] = -INFINITY;
+      if (c < g.C) {  // uniform
+        float s = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int k = 256 * q + 4 * lane;
+          if (k < g.K) {
+            const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
+            s = fmaf(av[r][q].x, w4.x, fmaf(av[r][q].y, w4.y, fmaf(av[r][q].z, w4.z, fmaf(av[r][q].w, w4.w, s))));
+          }
+        }
+        z[c] = wave_sum(s) + bias[c];
+      }
+    }
+    if (row >= g.rows) continue;  // uniform over the wavefront
+    // softmax cross-entropy, every lane redundantly (C <= 16)
+    float mx = z[0];
+#pragma unroll
+    for (int c = 1; c < kLastMaxC; ++c) mx = fmaxf(mx, z[c]);
+    float sum = 0.0f, e[kLastMaxC];
+#pragma unroll
+    for (int c = 0; c < kLastMaxC; ++c) {
+      e[c] = c < g.C ? expf(z[c] - mx) : 0.0f;
+      sum += e[c];
+    }
+    const int label = (int)g.labels[row];
+    const float inv = 1.0f / sum;
+    float dl[kLastMaxC], zl = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kLastMaxC; ++c) {
+      dl[c] = sign * (e[c] * inv - (c == label ? 1.0f : 0.0f));
+      if (c == label) zl = z[c];
+    }
+    if (lane < g.C) {
+      float mine = 0.0f;
+#pragma unroll
+      for (int c = 0; c < kLastMaxC; ++c) mine = lane == c ? dl[c] : mine;
+      g.delta[(int64_t)set * g.d_set_stride + (int64_t)row * g.C + lane] = mine;
+    }
+    if (lane == 0 && set == 0 && g.row_loss) g.row_loss[row] = (double)(logf(sum) + mx - zl);
+    if (g.delta_prev) {
+      float *dp = g.delta_prev + (int64_t)set * g.dp_set_stride + (int64_t)row * g.K;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int k = 256 * q + 4 * lane;
+        if (k >= g.K) continue;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int c = 0; c < kLastMaxC; ++c) {
+          if (c < g.C) {
+            const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
+            o.x = fmaf(dl[c], w4.x, o.x); o.y = fmaf(dl[c], w4.y, o.y);
+            o.z = fmaf(dl[c], w4.z, o.z); o.w = fmaf(dl[c], w4.w, o.w);
+          }
+        }
+        o.x = av[r][q].x > 0.0f ? o.x : 0.0f; o.y = av[r][q].y > 0.0f ? o.y : 0.0f;
+        o.z = av[r][q].z > 0.0f ? o.z : 0.0f; o.w = av[r][q].w > 0.0f ? o.w : 0.0f;
+        *reinterpret_cast<float4 *>(dp + k) = o;
+      }
+    }
+  }
+}
+
+// whether the fused last-layer launch applies: few classes, a previous layer of ReLU activations (or the
+// inputs when the net has one layer) that one wavefront can hold, 16-byte aligned rows
+bool last_layer_fused(int K, int C, int64_t lda, const float *a, int64_t a_stride) {
+  return C <= kLastMaxC && K <= kLastMaxK && K % 4 == 0 && lda % 4 == 0 && a_stride % 4 == 0 &&
+         (((uintptr_t)a) & 15u) == 0 && (int64_t)C * (K + 4) + C <= 16384;
+}
+
 __global__ void add_inplace_kernel(float *__restrict__ a, const float *__restrict__ b, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] += b[i];
@@ -125,9 +257,27 @@ struct Net {
 
 // Forward pass of `rows` rows whose inputs start at in0 (leading dimension ld0) into activation sets
 // 0..nsets-1: set s uses the parameters at W + s*wstride (one batched product per layer).
+// input rows of the last layer and whether backward_data() computes that layer itself (fused launch)
+struct LastIn {
+  const float *a;
+  int64_t lda, set_stride;
+  bool fused;
+};
+LastIn last_layer_input(const Net &nn, const float *in0, int64_t ld0) {
+  LastIn li;
+  const int l = nn.L - 1;
+  li.a = l == 0 ? in0 : nn.act(l, 0);
+  li.lda = l == 0 ? ld0 : nn.dims[l];
+  li.set_stride = l == 0 ? 0 : nn.rows_cap * nn.dims[l];
+  li.fused = last_layer_fused(nn.dims[l], nn.dims[l + 1], li.lda, li.a, li.set_stride);
+  return li;
+}
+
 hipError_t forward(const Net &nn, const float *W, int64_t wstride, int nsets, const float *in0, int64_t ld0, int rows,
                    hipStream_t st) {
+  const bool skip_last = last_layer_input(nn, in0, ld0).fused;
   for (int l = 0; l < nn.L; ++l) {
+    if (l == nn.L - 1 && skip_last) break;  // logits are formed inside the fused last-layer launch
     GemmArgs g{};
     g.A[0] = l == 0 ? in0 : nn.act(l, 0);
     g.lda[0] = l == 0 ? ld0 : nn.dims[l];
@@ -149,14 +299,31 @@ hipError_t forward(const Net &nn, const float *W, int64_t wstride, int nsets, co
 
 // Deltas of every layer from the logits down for sets 0..nsets-1; set 1 (the snapshot parameters) gets
 // negated deltas, so that the weight gradients of the two sets add up to the variance-reduced difference.
-hipError_t backward_data(const Net &nn, const float *W, int64_t wstride, int nsets, const float *labels, int rows,
-                         double *row_loss, hipStream_t st) {
+hipError_t backward_data(const Net &nn, const float *W, int64_t wstride, int nsets, const float *in0, int64_t ld0,
+                         const float *labels, int rows, double *row_loss, hipStream_t st) {
   const int classes = nn.dims[nn.L];
-  for (int set = 0; set < nsets; ++set)
-    hipLaunchKernelGGL(softmax_delta_kernel, dim3((unsigned)((rows + 127) / 128)), dim3(128), 0, st,
-                       (const float *)nn.act(nn.L, set), labels, rows, classes, set == 0 ? 1.0f : -1.0f,
-                       nn.del(nn.L, set), set == 0 ? row_loss : nullptr);
-  for (int l = nn.L - 1; l >= 1; --l) {
+  const LastIn li = last_layer_input(nn, in0, ld0);
+  int first = nn.L - 1;  // highest layer whose input delta is still to be formed by a product
+  if (li.fused) {
+    LastArgs g{};
+    const int l = nn.L - 1;
+    g.a = li.a; g.lda = li.lda; g.a_set_stride = li.set_stride;
+    g.W = W + nn.c->mlp_woff[l]; g.w_set_stride = wstride; g.bias_off = nn.c->mlp_boff[l] - nn.c->mlp_woff[l];
+    g.labels = labels; g.rows = rows; g.K = nn.dims[l]; g.C = classes;
+    g.delta = nn.del(nn.L, 0); g.d_set_stride = nn.rows_cap * classes;
+    g.delta_prev = l >= 1 ? nn.del(l, 0) : nullptr; g.dp_set_stride = nn.rows_cap * nn.dims[l];
+    g.row_loss = row_loss;
+    const size_t lds = ((size_t)classes * (g.K + 4) + classes) * sizeof(float);
+    hipLaunchKernelGGL(last_layer_kernel, dim3((unsigned)((rows + kLastRows - 1) / kLastRows), (unsigned)nsets),
+                       dim3(256), lds, st, g);
+    first = nn.L - 2;
+  } else {
+    for (int set = 0; set < nsets; ++set)
+      hipLaunchKernelGGL(softmax_delta_kernel, dim3((unsigned)((rows + 127) / 128)), dim3(128), 0, st,
+                         (const float *)nn.act(nn.L, set), labels, rows, classes, set == 0 ? 1.0f : -1.0f,
+                         nn.del(nn.L, set), set == 0 ? row_loss : nullptr);
+  }
+  for (int l = first; l >= 1; --l) {
     GemmArgs g{};
     g.A[0] = nn.del(l + 1, 0); g.lda[0] = nn.dims[l + 1]; g.strideA[0] = nn.rows_cap * nn.dims[l + 1];
     g.B[0] = W + nn.c->mlp_woff[l]; g.ldb[0] = nn.dims[l + 1]; g.transB = 1;  // W_l is [in][out]; we need W_l'
@@ -208,7 +375,7 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
     const float *labels = c->prob.y + r0;
     hipError_t e = forward(nn, w, 0, 1, in0, c->prob.ldx, rows, st);
     if (e != hipSuccess) return e;
-    e = backward_data(nn, w, 0, 1, labels, rows, f_out ? c->s.mlp_loss : nullptr, st);
+    e = backward_data(nn, w, 0, 1, in0, c->prob.ldx, labels, rows, f_out ? c->s.mlp_loss : nullptr, st);
     if (e != hipSuccess) return e;
     if (f_out)
       hipLaunchKernelGGL(sum_rows_loss_kernel, dim3(1), dim3(256), 0, st, (const double *)c->s.mlp_loss, rows,
@@ -244,7 +411,7 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const int64_t wstride = w_snap - w;
   hipError_t e = forward(nn, w, wstride, 2, c->s.mlp_xb, in0, rows, st);
   if (e != hipSuccess) return e;
-  e = backward_data(nn, w, wstride, 2, c->s.mlp_yb, rows, nullptr, st);
+  e = backward_data(nn, w, wstride, 2, c->s.mlp_xb, in0, c->s.mlp_yb, rows, nullptr, st);
   if (e != hipSuccess) return e;
   const float alpha = (float)(1.0 / (double)B);
   for (int l = nn.L - 1; l >= 0; --l) {

@@ -45,7 +45,9 @@ def test_matrix_core_contraction(M, N, K, tA, tB):
         assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
 
 
-MLPS = [((6, 5, 4, 3), 64, 2, 6), ((40, 33, 10), 200, 3, 20), ((300, 129, 70, 10), 640, 4, 32), ((17, 5), 90, 2, 9)]
+# the last three take the fused last-layer launch (hidden width a multiple of 4, at most 1024; few classes)
+MLPS = [((6, 5, 4, 3), 64, 2, 6), ((40, 33, 10), 200, 3, 20), ((300, 129, 70, 10), 640, 4, 32), ((17, 5), 90, 2, 9),
+        ((64, 256, 10), 256, 2, 16), ((32, 1024, 12), 128, 2, 8), ((64, 10), 128, 2, 8)]
 
 
 @pytest.mark.parametrize("dims,n,N,B", MLPS)
