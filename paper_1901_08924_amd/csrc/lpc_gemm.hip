@@ -399,13 +399,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_tn_kernel(GemmArgs g, int kc)
       }
       __syncthreads();
       if (m < g.M) {
-        for (int k = wave; k < kn; k += 32) {
-          // eight rows of A in flight per step
-          float a[8];
+        for (int k = wave; k < kn; k += 128) {
+          // 32 rows of A in flight per step
+          float a[32];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) a[j] = k + 4 * j < kn ? A[(int64_t)(k0 + k + 4 * j) * g.lda[s] + m] : 0.0f;
+          for (int j = 0; j < 32; ++j) a[j] = k + 4 * j < kn ? A[(int64_t)(k0 + k + 4 * j) * g.lda[s] + m] : 0.0f;
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
+          for (int j = 0; j < 32; ++j) {
             const int kk = k + 4 * j < kn ? k + 4 * j : 0;  // a[j] is zero past the end
             const float4 *b = reinterpret_cast<const float4 *>(&Bs[kk * kSkinnyN]);
             const float4 b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
