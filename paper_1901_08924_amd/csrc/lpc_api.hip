@@ -194,6 +194,14 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   }
   c->fold_slices = (c->full_grad_wgs >= 32 && c->full_grad_wgs % 16 == 0) ? 16 : 1;
   c->stat_slots = (int32_t)((c->d_pad + 63) / 64);
+  if (c->mlp) {
+    // the MLP's statistic partials come per output tile of the weight-gradient products plus one per bias
+    // vector (and per layer computed on the vector units): small layers need more slots than d_pad/64
+    int64_t need = 0;
+    for (int l = 0; l < p->mlp_nlayers; ++l)
+      need += (int64_t)(c->mlp_dims[l] / 128 + 1) * (c->mlp_dims[l + 1] / 64 + 1) + 2;
+    if (need > c->stat_slots) c->stat_slots = (int32_t)need;
+  }
   return LPC_OK;
 }
 
@@ -233,11 +241,15 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
   hipError_t e;
   const int32_t slot0 = (tag == kTagShared) ? c->cfg.N : wb;
-  if (c->csr || c->mlp) {
+  if (c->mlp) {
+    // the products' epilogues leave the statistic partials; only their fold is a launch of its own
+    ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+    return dev(launch_mlp_vr_grad(c, w, w_snap, key, tag, wb, we, U_row0, stats_mode, stats_row0, stat_slots_used, st));
+  }
+  if (c->csr) {
     {
       ProfScope ps(c, LPC_PROF_VR_ROWS, st);
-      e = c->mlp ? launch_mlp_vr_grad(c, w, w_snap, key, tag, wb, we, U_row0, st)
-                 : launch_csr_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, U_row0, st);
+      e = launch_csr_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, U_row0, st);
     }
     if (e != hipSuccess) return LPC_EDEVICE;
     if (stats_mode == kStatsNone) return LPC_OK;

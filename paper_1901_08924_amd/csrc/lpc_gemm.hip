@@ -163,6 +163,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   // 8*(v/4) + 4*(l/32) + (v%4).
   float *C = g.C + bz * g.strideC;
   const float *mask = g.relu_mask ? g.relu_mask + bz * g.strideC : nullptr;
+  // statistics of the stored values: per thread in fp32 (at most 64 terms), in fp64 across threads
+  float fmx = 0.0f, ssum = 0.0f, ssq = 0.0f, sbad = 0.0f;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -180,7 +182,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         if (mask) val = mask[off] > 0.0f ? val : 0.0f;
         if (g.accumulate) val += C[off];
         C[off] = val;
+        if (g.stat_part) {  // uniform
+          if (isfinite(val)) {
+            fmx = fmaxf(fmx, fabsf(val)); ssum += val; ssq = fmaf(val, val, ssq);
+          } else {
+            sbad += 1.0f;
+          }
+        }
       }
+    }
+  }
+  if (g.stat_part) {
+    // the tile's statistics: wavefront reductions, then the four wavefronts in order (LDS is free: the K loop
+    // ended with a barrier)
+    double *red = reinterpret_cast<double *>(&As[0][0][0]);
+    const double a_w = (double)wave_max(fmx), s_w = wave_sum((double)ssum), q_w = wave_sum((double)ssq),
+                 b_w = wave_sum((double)sbad);
+    if (lane == 0) { red[wave * 4 + 0] = a_w; red[wave * 4 + 1] = s_w; red[wave * 4 + 2] = q_w; red[wave * 4 + 3] = b_w; }
+    __syncthreads();
+    if (tid == 0) {
+      double a_t = 0.0, s_t = 0.0, q_t = 0.0, b_t = 0.0;
+      for (int k = 0; k < 4; ++k) { a_t = fmax(a_t, red[k * 4]); s_t += red[k * 4 + 1]; q_t += red[k * 4 + 2]; b_t += red[k * 4 + 3]; }
+      double *p = g.stat_part + bz * g.stat_batch_stride +
+                  ((int64_t)g.stat_slot0 + (int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
+      p[0] = a_t; p[1] = s_t; p[2] = q_t; p[3] = b_t;
     }
   }
 }
@@ -440,10 +465,24 @@ __global__ __launch_bounds__(256) void gemm_skinny_tn_kernel(GemmArgs g, int kc)
 
 }  // namespace
 
+namespace {
+bool gemm_narrow(const GemmArgs &g) {
+  const int64_t tiles128 = (int64_t)((g.N + 127) / 128) * ((g.M + BM - 1) / BM) * g.batch;
+  return tiles128 < 512 || g.N <= 64;  // fewer than two 128x128 tiles per CU: halve the tile
+}
+}  // namespace
+
+bool gemm_takes_matrix_cores(const GemmArgs &g) { return !(g.N <= kSkinnyN && !g.transB && g.M >= 64); }
+
+int gemm_tiles(const GemmArgs &g) {
+  const int tn = gemm_narrow(g) ? 64 : 128;
+  return ((g.N + tn - 1) / tn) * ((g.M + BM - 1) / BM);
+}
+
 // Validates shapes on the host (every access in the kernel is guarded by M, N, K).
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.nseg < 1 || g.nseg > 2 || g.batch < 1) return hipErrorInvalidValue;
-  if (g.N <= kSkinnyN && !g.transB && g.M >= 64) {
+  if (!gemm_takes_matrix_cores(g)) {
     if (!g.transA) {
       int kc = kSkinnyLdsFloats / g.N - 4;
       kc = kc / 4 * 4;
@@ -460,8 +499,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
     }
     return hipGetLastError();
   }
-  const int64_t tiles128 = (int64_t)((g.N + 127) / 128) * ((g.M + BM - 1) / BM) * g.batch;
-  const bool narrow = tiles128 < 512 || g.N <= 64;   // fewer than two 128x128 tiles per CU: halve the tile
+  const bool narrow = gemm_narrow(g);
   const int tn = narrow ? 64 : 128;
   const dim3 grid((unsigned)((g.N + tn - 1) / tn), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
   // whole tiles and slabs, 16-byte aligned rows: the branch-free fetch
@@ -476,7 +514,7 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
   } while (0)
   // at most one whole narrow tile per CU: eight wavefronts per tile (measured: 6-30 % faster there, no gain
   // once two four-wavefront workgroups share a CU)
-  const bool eight = full && narrow && (int64_t)grid.x * grid.y * grid.z <= 256;
+  const bool eight = full && narrow && (int64_t)grid.x * grid.y * grid.z <= 256 && !g.stat_part;
 #define LPC_GEMM_LAUNCH(TA_, TB_)                                                                   \
   do {                                                                                              \
     if (eight) hipLaunchKernelGGL((gemm_mfma8_kernel<TA_, TB_>), grid, dim3(512), 0, st, g);        \

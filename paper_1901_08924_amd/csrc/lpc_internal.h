@@ -45,6 +45,11 @@ struct GemmArgs {
   const float *relu_mask;  // same layout as C
   int accumulate;
   int nseg, batch;
+  // optional: every tile also leaves the statistics (|max|, sum, sum of squares, non-finite count) of the values
+  // it stored as partial number stat_slot0 + tile index of its batch item (matrix-core path only)
+  double *stat_part;
+  int64_t stat_batch_stride;  // doubles between the partial arrays of consecutive batch items
+  int32_t stat_slot0;
 };
 
 // ---- device scratch owned by a context (all pointers into the workspace) ----
@@ -151,11 +156,15 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 
 // MLP instance (lpc_gemm.hip, lpc_mlp.hip)
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
+bool gemm_takes_matrix_cores(const GemmArgs &g);  // false: the vector-unit path (no statistic partials)
+int gemm_tiles(const GemmArgs &g);                 // statistic partials a matrix-core launch writes per batch item
 void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
                                 hipStream_t st);
+// stats_mode != kStatsNone: the statistics of the N rows of U come out of the producing kernels' epilogues
 hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, StreamKey key, uint32_t tag,
-                              int32_t worker_begin, int32_t worker_end, float *U, hipStream_t st);
+                              int32_t worker_begin, int32_t worker_end, float *U, int stats_mode, double *stats_out,
+                              int32_t *stat_slots_used, hipStream_t st);
 
 // Reductions, statistics, quantizer, receiver, prox (lpc_quant.hip)
 // out[v][0..d_pad) = scale * sum_p part[(v*parts + p)*d + j] (zero beyond d), then statistics of each
@@ -179,6 +188,16 @@ struct AlpcStep {
 };
 hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key,
                                       uint32_t *packed, float *delta_out, const AlpcStep &al, hipStream_t st);
+// statistic partials of up to 8 column ranges [begin, begin+len) of nvec rows of U (one workgroup each), as slots
+// slot0 .. slot0+nranges-1; then, for kStatsFinal, the fold of all nslots partials per vector
+struct StatRange {
+  int64_t begin[8], len[8];
+  int32_t n;
+};
+hipError_t launch_range_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
+                              const StatRange &ranges, int32_t slot0, hipStream_t st);
+hipError_t launch_finalize_stats(const lpc_ctx *c, int32_t vec_begin, int32_t nvec, int32_t nslots, double *stats_out,
+                                 hipStream_t st);
 hipError_t launch_vector_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
                                double *stats_out, int stats_mode, int32_t *slots_used, hipStream_t st);
 hipError_t launch_prepare_qparams(const lpc_ctx *c, const double *stats, const float *delta_in, int32_t nvec,

@@ -401,7 +401,8 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
 // Alg. 1 step 6 for the MLP: u^i = grad f_{B_i}(w) - grad f_{B_i}(w_snap) for workers [worker_begin, worker_end)
 // (or the one shared batch), written to consecutive rows of U (row stride d_pad).
 hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, StreamKey key, uint32_t tag,
-                              int32_t worker_begin, int32_t worker_end, float *U, hipStream_t st) {
+                              int32_t worker_begin, int32_t worker_end, float *U, int stats_mode, double *stats_out,
+                              int32_t *stat_slots_used, hipStream_t st) {
   Net nn{c->prob.mlp_nlayers, c->mlp_dims.data(), c, c->mlp_cap};
   const int nw = worker_end - worker_begin, B = c->cfg.B, rows = nw * B;
   const int in0 = nn.dims[0];
@@ -414,6 +415,13 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   e = backward_data(nn, w, wstride, 2, c->s.mlp_xb, in0, c->s.mlp_yb, rows, nullptr, st);
   if (e != hipSuccess) return e;
   const float alpha = (float)(1.0 / (double)B);
+  // Statistics of u^i (Sec. 3.2 needs |u|_inf before anything can be quantized): the matrix-core products leave
+  // one partial per output tile from their epilogues, the few columns written by other kernels (biases, a
+  // last layer on the vector units) get a small reduction of their own; no extra pass over U.
+  const bool want_stats = stats_mode != kStatsNone;
+  const int32_t vec0 = (tag == kTagShared) ? c->cfg.N : worker_begin;
+  int32_t slot = 0;
+  StatRange ranges{};
   for (int l = nn.L - 1; l >= 0; --l) {
     const int out = nn.dims[l + 1], in = nn.dims[l];
     // bias: column sums of the two delta sets over the worker's rows
@@ -439,12 +447,40 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
         g.B[set] = nn.del(l + 1, set); g.ldb[set] = out; g.strideB[set] = (int64_t)B * out;
       }
     }
+    if (want_stats) {
+      ranges.begin[ranges.n] = c->mlp_boff[l]; ranges.len[ranges.n] = out; ++ranges.n;
+      if (gemm_takes_matrix_cores(g)) {
+        g.stat_part = c->s.stat_part + (int64_t)vec0 * c->stat_slots * 4;
+        g.stat_batch_stride = (int64_t)c->stat_slots * 4;
+        g.stat_slot0 = slot;
+        slot += gemm_tiles(g);
+      } else {
+        ranges.begin[ranges.n] = c->mlp_woff[l]; ranges.len[ranges.n] = (int64_t)in * out; ++ranges.n;
+      }
+    }
     e = launch_gemm(g, st);
     if (e != hipSuccess) return e;
+    if (want_stats && ranges.n >= 6) {  // deep nets: reduce the ranges collected so far (all written by now)
+      e = launch_range_stats(c, U, c->d_pad, vec0, nw, ranges, slot, st);
+      if (e != hipSuccess) return e;
+      slot += ranges.n;
+      ranges.n = 0;
+    }
   }
   if (c->d_pad > c->d) {
     const int64_t cnt = (c->d_pad - c->d) * nw;
     hipLaunchKernelGGL(zero_tail_kernel, dim3((unsigned)((cnt + 63) / 64)), dim3(64), 0, st, U, c->d, c->d_pad, nw);
+  }
+  if (want_stats) {
+    e = launch_range_stats(c, U, c->d_pad, vec0, nw, ranges, slot, st);
+    if (e != hipSuccess) return e;
+    slot += ranges.n;
+    if (slot > c->stat_slots) return hipErrorInvalidValue;  // cannot happen: a tile covers at least 64 coordinates
+    if (stats_mode == kStatsFinal) {
+      e = launch_finalize_stats(c, vec0, nw, slot, stats_out, st);
+      if (e != hipSuccess) return e;
+    }
+    if (stat_slots_used) *stat_slots_used = slot;
   }
   return hipGetLastError();
 }

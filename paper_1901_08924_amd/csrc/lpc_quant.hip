@@ -220,6 +220,42 @@ __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__r
   publish_stats(sk, vec_begin + vec, blockIdx.x, amax, sum, sumsq, bad);
 }
 
+// statistic partials of short column ranges of rows of U: workgroup (r, vec) reduces range r of vector vec
+__global__ __launch_bounds__(kThreads) void range_stats_kernel(const float *__restrict__ U, int64_t ld, StatRange rg,
+                                                               int32_t vec_begin, int32_t slot0, StatSinks sk) {
+  __shared__ double red[4][4];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int32_t vec = blockIdx.y;
+  const float *u = U + (int64_t)vec * ld + rg.begin[blockIdx.x];
+  const int64_t len = rg.len[blockIdx.x];
+  double sum = 0.0, sumsq = 0.0, bad = 0.0;
+  float fmx = 0.0f;
+  for (int64_t j = tid; j < len; j += 8 * kThreads) {  // eight elements in flight per thread
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = j + q * kThreads < len ? u[j + q * kThreads] : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      if (isfinite(v[q])) {
+        fmx = fmaxf(fmx, fabsf(v[q])); sum += (double)v[q]; sumsq += (double)v[q] * (double)v[q];
+      } else {
+        bad += 1.0;
+      }
+    }
+  }
+  fmx = wave_max(fmx);
+  sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
+  if (lane == 0) { red[wv][0] = (double)fmx; red[wv][1] = sum; red[wv][2] = sumsq; red[wv][3] = bad; }
+  __syncthreads();
+  if (tid == 0) {
+    double amax = 0.0;
+    sum = 0.0; sumsq = 0.0; bad = 0.0;
+    for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
+    double *p = sk.stat_part + ((int64_t)(vec_begin + vec) * sk.stat_slots + slot0 + blockIdx.x) * 4;
+    p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
+  }
+}
+
 __global__ void prepare_qparams_kernel(const double *stats, const float *delta_in, int32_t nvec, int64_t d,
                                        QuantSpec qs, QParams *qp, uint32_t *n_clipped, uint32_t *flags) {
   const int v = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1066,6 +1102,21 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
   if (stats_mode == kStatsFinal)
     hipLaunchKernelGGL(finalize_stats_kernel, dim3((unsigned)nvec), dim3(64), 0, st, sinks_of(c, stats_out),
                        spec_of(c), vec_begin, (int32_t)grid.x, c->d);
+  return hipGetLastError();
+}
+
+hipError_t launch_range_stats(const lpc_ctx *c, const float *U, int64_t ld, int32_t vec_begin, int32_t nvec,
+                              const StatRange &ranges, int32_t slot0, hipStream_t st) {
+  if (ranges.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(range_stats_kernel, dim3((unsigned)ranges.n, (unsigned)nvec), dim3(kThreads), 0, st, U, ld, ranges,
+                     vec_begin, slot0, sinks_of(c, nullptr));
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize_stats(const lpc_ctx *c, int32_t vec_begin, int32_t nvec, int32_t nslots, double *stats_out,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(finalize_stats_kernel, dim3((unsigned)nvec), dim3(64), 0, st, sinks_of(c, stats_out), spec_of(c),
+                     vec_begin, nslots, c->d);
   return hipGetLastError();
 }
 
