@@ -106,7 +106,6 @@ size_t layout(lpc_ctx *c, char *base) {
   s.stat_part = (double *)take((size_t)N1 * c->stat_slots * 4 * sizeof(double));
   s.stats = (double *)take((size_t)N1 * 4 * sizeof(double));
   s.qparams = (QParams *)take((size_t)N1 * sizeof(QParams));
-  s.counters = (uint32_t *)take((size_t)N1 * sizeof(uint32_t));
   s.flags = (uint32_t *)take(4 * sizeof(uint32_t));
   s.n_clipped = (uint32_t *)take((size_t)N1 * sizeof(uint32_t));
   s.z_snap = (float *)take((size_t)c->n * sizeof(float));
@@ -371,9 +370,9 @@ lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_c
   layout(c, (char *)workspace);
   c->workspace = workspace;
   c->workspace_bytes = workspace_bytes;
-  // arrival counters, flags and clip counts start at zero (contiguous, see layout())
-  const size_t words = ((char *)c->s.z_snap - (char *)c->s.counters) / sizeof(uint32_t);
-  if (launch_fill_u32(c->s.counters, 0u, (int64_t)words, nullptr) != hipSuccess ||
+  // flags and clip counts start at zero (contiguous, see layout())
+  const size_t words = ((char *)c->s.z_snap - (char *)c->s.flags) / sizeof(uint32_t);
+  if (launch_fill_u32(c->s.flags, 0u, (int64_t)words, nullptr) != hipSuccess ||
       hipStreamSynchronize(nullptr) != hipSuccess) {
     delete c;
     return LPC_EDEVICE;

@@ -60,7 +60,6 @@ struct Scratch {
   double *stat_part;    // [(N+1)][stat_slots][4]
   double *stats;        // [(N+1)][4]
   QParams *qparams;     // [(N+1)]
-  uint32_t *counters;   // [(N+1)] arrival counters of the "last block finishes" reductions
   uint32_t *flags;      // [4]: [0] = a non-finite value was seen
   uint32_t *n_clipped;  // [N]
   float *z_snap;        // [n]

@@ -39,7 +39,6 @@ struct StatSinks {
   double *stat_part;
   double *stats;
   QParams *qparams;
-  uint32_t *counters;
   uint32_t *flags;
   uint32_t *n_clipped;
   double *stats_out;  // caller's buffer or nullptr
@@ -442,35 +441,49 @@ struct ProxArgs {
   int64_t bitmap_words;
 };
 
-template <int B, bool PROX>
-__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *packed, int64_t W,
+// TPB threads per workgroup (one segment each): 256 for long vectors, 64 when that would leave CUs without work
+template <int B, bool PROX, int TPB>
+__global__ __launch_bounds__(TPB) void dequantize_kernel(const uint32_t *packed, int64_t W,
                                                               const float *__restrict__ delta, int32_t N, int64_t d,
                                                               int64_t d_pad, float *__restrict__ u_avg, ProxArgs pa) {
-  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
+  __shared__ __attribute__((aligned(16))) float tile[TPB * kPitch];
   const int tid = threadIdx.x;
-  const int64_t tile_base = (int64_t)blockIdx.x * kTileFloats;
+  const int64_t tile_base = (int64_t)blockIdx.x * (TPB * kSegFloats);
   const int64_t seg = tile_base / kSegFloats + tid;
+  // the proximal step's operands are requested before the messages are unpacked (one round trip, not two)
+  float4 w_pre[8], mu_pre[8];
+  if constexpr (PROX) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int64_t j = tile_base + (int64_t)(r * TPB + tid) * 4;
+      w_pre[r] = mu_pre[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j + 4 <= d) {
+        mu_pre[r] = *reinterpret_cast<const float4 *>(pa.mu + j);
+        w_pre[r] = *reinterpret_cast<const float4 *>(pa.w + j);
+      }
+    }
+  }
   if (seg * kSegFloats < d_pad) {
     float acc[32];
 #pragma unroll
     for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
-    // four messages in flight at a time; accumulation stays in worker order
+    // several messages in flight at a time (as many as the word count lets the registers hold);
+    // accumulation stays in worker order
+    constexpr int kInFlight = B <= 4 ? 16 : (B <= 8 ? 8 : 4);
     uint64_t nonzero = 0;
-    int32_t i = 0;
-    for (; i + 4 <= N; i += 4) {
-      uint32_t w0[B], w1[B], w2[B], w3[B];
-      const uint32_t *src = packed + (int64_t)i * W + seg * B;
-      load_words<B>(src, w0); load_words<B>(src + W, w1); load_words<B>(src + 2 * W, w2); load_words<B>(src + 3 * W, w3);
-      const float d0 = delta[i], d1 = delta[i + 1], d2 = delta[i + 2], d3 = delta[i + 3];
-      if (accumulate_words<B>(w0, d0, acc)) nonzero |= 1ull << (i & 63);
-      if (accumulate_words<B>(w1, d1, acc)) nonzero |= 1ull << ((i + 1) & 63);
-      if (accumulate_words<B>(w2, d2, acc)) nonzero |= 1ull << ((i + 2) & 63);
-      if (accumulate_words<B>(w3, d3, acc)) nonzero |= 1ull << ((i + 3) & 63);
-    }
-    for (; i < N; ++i) {
-      uint32_t w0[B];
-      load_words<B>(packed + (int64_t)i * W + seg * B, w0);
-      if (accumulate_words<B>(w0, delta[i], acc)) nonzero |= 1ull << (i & 63);
+    for (int32_t i0 = 0; i0 < N; i0 += kInFlight) {
+      uint32_t wds[kInFlight][B];
+#pragma unroll
+      for (int q = 0; q < kInFlight; ++q) {
+        const int32_t i = i0 + q < N ? i0 + q : N - 1;  // past the end: a repeated load, ignored below
+        load_words<B>(packed + (int64_t)i * W + seg * B, wds[q]);
+      }
+#pragma unroll
+      for (int q = 0; q < kInFlight; ++q) {
+        if (i0 + q < N) {
+          if (accumulate_words<B>(wds[q], delta[i0 + q], acc)) nonzero |= 1ull << ((i0 + q) & 63);
+        }
+      }
     }
     if constexpr (PROX) {
       if (pa.rezero) {
@@ -495,7 +508,7 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *pa
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
-    const int e = r * kThreads + tid;
+    const int e = r * TPB + tid;
     const int64_t j = tile_base + (int64_t)e * 4;
     if (j >= d) continue;
     const float4 a = *reinterpret_cast<const float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]);
@@ -503,8 +516,8 @@ __global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *pa
     if (j + 4 <= d) {
       if (u_avg) *reinterpret_cast<float4 *>(u_avg + j) = a;
       if constexpr (PROX) {
-        const float4 m = *reinterpret_cast<const float4 *>(pa.mu + j);
-        float4 w = *reinterpret_cast<const float4 *>(pa.w + j);
+        const float4 m = mu_pre[r];
+        float4 w = w_pre[r];
         w.x = prox_scalar(w.x, a.x + m.x, pa.step, pa.thr, pa.shrink);
         w.y = prox_scalar(w.y, a.y + m.y, pa.step, pa.thr, pa.shrink);
         w.z = prox_scalar(w.z, a.z + m.z, pa.step, pa.thr, pa.shrink);
@@ -1079,7 +1092,6 @@ StatSinks sinks_of(const lpc_ctx *c, double *stats_out) {
   sk.stat_part = c->s.stat_part;
   sk.stats = c->s.stats;
   sk.qparams = c->s.qparams;
-  sk.counters = c->s.counters;
   sk.flags = c->s.flags;
   sk.n_clipped = c->s.n_clipped;
   sk.stats_out = stats_out;
@@ -1095,7 +1107,7 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
                                int64_t ld_out, int32_t vec_begin, int32_t nvec, int stats_mode, double *stats_out,
                                hipStream_t st) {
   // `out` and `stats_out` point at the row of the first vector of this launch; vec_begin only selects
-  // the scratch slots (statistics, quantizer parameters, arrival counters).
+  // the scratch slots (statistics, quantizer parameters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
   hipLaunchKernelGGL(reduce_parts_kernel, grid, dim3(kThreads), 0, st, part, parts, c->d, c->d_pad, scale, out,
                      ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
@@ -1161,9 +1173,15 @@ void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *
 template <int B, bool PROX>
 void dequantize_launch(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg, ProxArgs pa,
                        hipStream_t st) {
-  const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats));
-  hipLaunchKernelGGL((dequantize_kernel<B, PROX>), grid, dim3(kThreads), 0, st, packed, c->W, delta, c->cfg.N, c->d,
-                     c->d_pad, u_avg, pa);
+  const int64_t wide = (c->d_pad + kTileFloats - 1) / kTileFloats;
+  if (wide >= 2 * c->cus) {
+    hipLaunchKernelGGL((dequantize_kernel<B, PROX, kThreads>), dim3((unsigned)wide), dim3(kThreads), 0, st, packed, c->W,
+                       delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+  } else {
+    const int64_t tile = 64 * kSegFloats;
+    hipLaunchKernelGGL((dequantize_kernel<B, PROX, 64>), dim3((unsigned)((c->d_pad + tile - 1) / tile)), dim3(64), 0, st,
+                       packed, c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+  }
 }
 
 #define LPC_DISPATCH_BITS(bits, CALL)                                                                     \
