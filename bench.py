@@ -258,6 +258,10 @@ def main():
             else:
                 ent.update({"bound": "mfma", "algorithmic_flops": amount, "achieved": rate / 1e12, "unit": "TFLOP/s",
                             "peak": MFMA_FP32_PEAK_TFLOPS, "frac": rate / 1e12 / MFMA_FP32_PEAK_TFLOPS})
+        if 1e3 * avg_ms < 20.0:
+            # the two event records around a launch cost about 2.8 us themselves (rocprofv3's kernel trace of
+            # the same command, kept under profiles/, gives the GPU-side duration)
+            ent["note"] = "HIP-event interval of a microsecond-scale launch: includes ~2.8 us of event overhead"
         kernels[k] = ent
     traffic = {} if args.small else measured_traffic(args.workload)
     for k in kernels:
