@@ -130,6 +130,7 @@ size_t layout(lpc_ctx *c, char *base) {
     s.mlp_act = (float *)take((size_t)c->mlp_act_floats * sizeof(float));
     s.mlp_del = (float *)take((size_t)c->mlp_act_floats * sizeof(float));
     s.mlp_loss = (double *)take((size_t)2 * c->mlp_cap * sizeof(double));
+    s.mlp_part = (float *)take((size_t)c->mlp_part_floats * sizeof(float));
   }
   return off;
 }

@@ -85,6 +85,7 @@ struct Scratch {
   float *mlp_act;       // layer l (1..L) at mlp_act + act_off[l]: [2][rows][dims[l]]
   float *mlp_del;       // same layout as mlp_act
   double *mlp_loss;     // [rows] per-row losses of the snapshot pass
+  float *mlp_part;      // per-block partial sums of the snapshot pass (mlp_part_floats)
 };
 
 }  // namespace lpc
@@ -102,6 +103,7 @@ struct lpc_ctx {
   int64_t mlp_cap;        // rows each of the two activation sets can hold (the snapshot pass uses both as one)
   std::vector<int64_t> mlp_woff, mlp_boff, mlp_act_off;  // per layer offsets
   int64_t mlp_act_floats;
+  int64_t mlp_part_floats;
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
   int32_t vr_parts;       // partial rows per worker written by the worker pass
   int32_t stat_slots;     // statistic partials per vector
@@ -157,6 +159,10 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
 bool gemm_takes_matrix_cores(const GemmArgs &g);  // false: the vector-unit path (no statistic partials)
 int gemm_tiles(const GemmArgs &g);                 // statistic partials a matrix-core launch writes per batch item
+// Rows per block of the MLP snapshot pass's reductions over rows (bias column sums, weight gradients formed on
+// the vector units): a chunk is cut into blocks that are summed side by side, one partial per block, and the
+// partials are folded by a second, small column sum; a lone launch over thousands of rows would occupy 1-16 CUs.
+constexpr int kSnapBlock = 256;
 void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
                                 hipStream_t st);

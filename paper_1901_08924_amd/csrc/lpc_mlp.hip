@@ -99,6 +99,7 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
   __syncthreads();
   const float sign = set == 0 ? 1.0f : -1.0f;
   const int row0 = blockIdx.x * kLastRows + wave * 4;
+  const int lc = lane & 15;
   const float *a = g.a + (int64_t)set * g.a_set_stride;
   // this lane's activations of the wavefront's four rows (K <= 1024: at most four groups of four per row)
   float4 av[4][4];
@@ -110,70 +111,78 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
       av[r][q] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (row0 + r < g.rows && k < g.K) av[r][q] = *reinterpret_cast<const float4 *>(a + (int64_t)(row0 + r) * g.lda + k);
     }
+  // logits: one read of a column of W serves the four rows; lane (16j + c) keeps z[c] of each row
+  float z[4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = row0 + r;
-    float z[kLastMaxC];
+  for (int r = 0; r < 4; ++r) z[r] = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < kLastMaxC; ++c) {
-      z[c] = -INFINITY;
-      if (c < g.C) {  // uniform
-        float s = 0.0f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int k = 256 * q + 4 * lane;
-          if (k < g.K) {
-            const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
-            s = fmaf(av[r][q].x, w4.x, fmaf(av[r][q].y, w4.y, fmaf(av[r][q].z, w4.z, fmaf(av[r][q].w, w4.w, s))));
-          }
-        }
-        z[c] = wave_sum(s) + bias[c];
-      }
-    }
-    if (row >= g.rows) continue;  // uniform over the wavefront
-    // softmax cross-entropy, every lane redundantly (C <= 16)
-    float mx = z[0];
-#pragma unroll
-    for (int c = 1; c < kLastMaxC; ++c) mx = fmaxf(mx, z[c]);
-    float sum = 0.0f, e[kLastMaxC];
-#pragma unroll
-    for (int c = 0; c < kLastMaxC; ++c) {
-      e[c] = c < g.C ? expf(z[c] - mx) : 0.0f;
-      sum += e[c];
-    }
-    const int label = (int)g.labels[row];
-    const float inv = 1.0f / sum;
-    float dl[kLastMaxC], zl = 0.0f;
-#pragma unroll
-    for (int c = 0; c < kLastMaxC; ++c) {
-      dl[c] = sign * (e[c] * inv - (c == label ? 1.0f : 0.0f));
-      if (c == label) zl = z[c];
-    }
-    if (lane < g.C) {
-      float mine = 0.0f;
-#pragma unroll
-      for (int c = 0; c < kLastMaxC; ++c) mine = lane == c ? dl[c] : mine;
-      g.delta[(int64_t)set * g.d_set_stride + (int64_t)row * g.C + lane] = mine;
-    }
-    if (lane == 0 && set == 0 && g.row_loss) g.row_loss[row] = (double)(logf(sum) + mx - zl);
-    if (g.delta_prev) {
-      float *dp = g.delta_prev + (int64_t)set * g.dp_set_stride + (int64_t)row * g.K;
+  for (int c = 0; c < kLastMaxC; ++c) {
+    if (c < g.C) {  // uniform
+      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int k = 256 * q + 4 * lane;
-        if (k >= g.K) continue;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < g.K) {
+          const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
 #pragma unroll
-        for (int c = 0; c < kLastMaxC; ++c) {
-          if (c < g.C) {
-            const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
-            o.x = fmaf(dl[c], w4.x, o.x); o.y = fmaf(dl[c], w4.y, o.y);
-            o.z = fmaf(dl[c], w4.z, o.z); o.w = fmaf(dl[c], w4.w, o.w);
+          for (int r = 0; r < 4; ++r)
+            s[r] = fmaf(av[r][q].x, w4.x, fmaf(av[r][q].y, w4.y, fmaf(av[r][q].z, w4.z, fmaf(av[r][q].w, w4.w, s[r]))));
+        }
+      }
+      const float bc = bias[c];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float t = wave_sum(s[r]) + bc;
+        z[r] = lc == c ? t : z[r];
+      }
+    }
+  }
+  // softmax cross-entropy inside each row of 16 lanes (lanes c >= C hold -inf and contribute exp = 0)
+  float dl[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = row0 + r < g.rows ? row0 + r : g.rows - 1;
+    const float mx = row16_max(z[r]);
+    const float e = lc < g.C ? expf(z[r] - mx) : 0.0f;
+    const float sum = row16_sum(e);
+    const int label = (int)g.labels[row];
+    dl[r] = sign * (e * (1.0f / sum) - (lc == label ? 1.0f : 0.0f));
+    if (row0 + r < g.rows) {
+      if (lane < g.C) g.delta[(int64_t)set * g.d_set_stride + (int64_t)row * g.C + lane] = dl[r];
+      if (set == 0 && g.row_loss) {
+        const float zl = row16_sum(lc == label ? z[r] : 0.0f);  // uniform branch: whole rows of lanes are active
+        if (lane == 0) g.row_loss[row] = (double)(logf(sum) + mx - zl);
+      }
+    }
+  }
+  if (g.delta_prev) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int k = 256 * q + 4 * lane;
+      float4 o[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int c = 0; c < kLastMaxC; ++c) {
+        if (c < g.C) {
+          float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (k < g.K) w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float dc = read_lane(dl[r], c);
+            o[r].x = fmaf(dc, w4.x, o[r].x); o[r].y = fmaf(dc, w4.y, o[r].y);
+            o[r].z = fmaf(dc, w4.z, o[r].z); o[r].w = fmaf(dc, w4.w, o[r].w);
           }
         }
-        o.x = av[r][q].x > 0.0f ? o.x : 0.0f; o.y = av[r][q].y > 0.0f ? o.y : 0.0f;
-        o.z = av[r][q].z > 0.0f ? o.z : 0.0f; o.w = av[r][q].w > 0.0f ? o.w : 0.0f;
-        *reinterpret_cast<float4 *>(dp + k) = o;
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (row0 + r >= g.rows || k >= g.K) continue;
+        float4 t = o[r];
+        t.x = av[r][q].x > 0.0f ? t.x : 0.0f; t.y = av[r][q].y > 0.0f ? t.y : 0.0f;
+        t.z = av[r][q].z > 0.0f ? t.z : 0.0f; t.w = av[r][q].w > 0.0f ? t.w : 0.0f;
+        float *dp = g.delta_prev + (int64_t)set * g.dp_set_stride + (int64_t)(row0 + r) * g.K;
+        *reinterpret_cast<float4 *>(dp + k) = t;
       }
     }
   }
@@ -361,6 +370,16 @@ void mlp_plan(lpc_ctx *c) {
     aoff = (aoff + 63) / 64 * 64;
   }
   c->mlp_act_floats = aoff;
+  // partial sums of the snapshot pass's row blocks: per block the bias column sums of the widest layer and
+  // the largest weight gradient that is formed on the vector units
+  int64_t widest = 0, skinny = 0;
+  for (int l = 0; l < L; ++l) {
+    GemmArgs g{};
+    g.M = dims[l]; g.N = dims[l + 1];
+    if (dims[l + 1] > widest) widest = dims[l + 1];
+    if (!gemm_takes_matrix_cores(g) && (int64_t)dims[l] * dims[l + 1] > skinny) skinny = (int64_t)dims[l] * dims[l + 1];
+  }
+  c->mlp_part_floats = (2 * c->mlp_cap / kSnapBlock + 1) * (widest + skinny);
 }
 
 // Alg. 1 step 4 for the MLP: mean gradient (and loss) over the first n_rows samples, in chunks of N*B rows.
@@ -381,18 +400,54 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
       hipLaunchKernelGGL(sum_rows_loss_kernel, dim3(1), dim3(256), 0, st, (const double *)c->s.mlp_loss, rows,
                          (double)alpha, r0 > 0 ? 1 : 0, f_out);
     if (!mu) continue;
+    const int nb = rows / kSnapBlock, rest = rows - nb * kSnapBlock;  // whole blocks, then a ragged remainder
     for (int l = 0; l < nn.L; ++l) {
+      const int in = nn.dims[l], out = nn.dims[l + 1];
+      const float *a = l == 0 ? in0 : nn.act(l, 0);
+      const int64_t lda = l == 0 ? c->prob.ldx : in;
+      const float *dl = nn.del(l + 1, 0);
+      int acc = r0 > 0 ? 1 : 0;
       GemmArgs g{};
-      g.A[0] = l == 0 ? in0 : nn.act(l, 0); g.lda[0] = l == 0 ? c->prob.ldx : nn.dims[l]; g.transA = 1;
-      g.B[0] = nn.del(l + 1, 0); g.ldb[0] = nn.dims[l + 1];
-      g.C = mu + c->mlp_woff[l]; g.ldc = nn.dims[l + 1];
-      g.M = nn.dims[l]; g.N = nn.dims[l + 1]; g.K = rows;
-      g.alpha = alpha; g.accumulate = r0 > 0 ? 1 : 0; g.nseg = 1; g.batch = 1;
-      e = launch_gemm(g, st);
+      g.A[0] = a; g.lda[0] = lda; g.transA = 1;
+      g.B[0] = dl; g.ldb[0] = out;
+      g.C = mu + c->mlp_woff[l]; g.ldc = out;
+      g.M = in; g.N = out; g.K = rows;
+      g.alpha = alpha; g.accumulate = acc; g.nseg = 1; g.batch = 1;
+      float *part_b = c->s.mlp_part, *part_w = c->s.mlp_part + (int64_t)nb * out;
+      const bool blocks = nb >= 2;
+      if (blocks && !gemm_takes_matrix_cores(g)) {
+        GemmArgs h = g;
+        h.K = kSnapBlock; h.batch = nb; h.alpha = 1.0f; h.accumulate = 0;
+        h.strideA[0] = (int64_t)kSnapBlock * lda; h.strideB[0] = (int64_t)kSnapBlock * out;
+        h.C = part_w; h.strideC = (int64_t)in * out;
+        e = launch_gemm(h, st);
+        if (e != hipSuccess) return e;
+        const int cols = in * out;
+        hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((cols + 63) / 64), 1u), dim3(256), 0, st,
+                           (const float *)part_w, (const float *)nullptr, nb, cols, alpha, acc,
+                           mu + c->mlp_woff[l], (int64_t)0);
+        if (rest) {
+          g.A[0] = a + (int64_t)nb * kSnapBlock * lda; g.B[0] = dl + (int64_t)nb * kSnapBlock * out;
+          g.K = rest; g.accumulate = 1;
+          e = launch_gemm(g, st);
+        }
+      } else {
+        e = launch_gemm(g, st);
+      }
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((nn.dims[l + 1] + 63) / 64), 1u), dim3(256), 0, st,
-                         (const float *)nn.del(l + 1, 0), (const float *)nullptr, rows, nn.dims[l + 1], alpha,
-                         r0 > 0 ? 1 : 0, mu + c->mlp_boff[l], (int64_t)0);
+      const float *db = dl;
+      int brows = rows;
+      if (blocks) {
+        hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), (unsigned)nb), dim3(256), 0, st, dl,
+                           (const float *)nullptr, kSnapBlock, out, 1.0f, 0, part_b, (int64_t)out);
+        hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), 1u), dim3(256), 0, st,
+                           (const float *)part_b, (const float *)nullptr, nb, out, alpha, acc, mu + c->mlp_boff[l],
+                           (int64_t)0);
+        db = dl + (int64_t)nb * kSnapBlock * out; brows = rest; acc = 1;
+      }
+      if (brows)
+        hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), 1u), dim3(256), 0, st, db,
+                           (const float *)nullptr, brows, out, alpha, acc, mu + c->mlp_boff[l], (int64_t)0);
     }
   }
   return hipGetLastError();
