@@ -198,6 +198,30 @@ lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream);
  * scratch; the snapshot state kept by lpc_epoch is not touched.  eta > 0 else LPC_EINVAL. */
 lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double *gm2_out_host, void *stream);
 
+/* lpc_epoch that also records, for every inner iteration t and worker i, the scale factor delta_t^i the
+ * worker quantized with (eq. (3); the shared max_i delta_t^i under schemes (b), (c)) and the number of
+ * clipped coordinates d_lambda of its message (Sec. 3.2; the quantity Lemma 2 and Theorem 2 are stated in):
+ * delta_trace (floats) and nclip_trace (uint32) are device arrays [m][N]; either may be NULL, both NULL is
+ * lpc_epoch.  With quantization off both rows are zero.  The traced epoch takes the unfused launches
+ * (statistics, quantizer, receiver, prox as separate kernels) for every data kind; for Alg. 1 in
+ * LPC_CLIP_LAMBDA mode on dense data its iterates equal lpc_epoch's bit for bit, elsewhere to rounding.
+ * Asynchronous. */
+lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, float *delta_trace,
+                            uint32_t *nclip_trace, void *stream);
+
+/* Selection of the clipping parameter (Sec. 6.1 picks lambda by cross-validation, once): for each of the
+ * n_clip candidates clips_host[k] (lambda in (0,1] or c > 0, in the context's clip mode) the method is run
+ * for `epochs` epochs numbered epoch0, epoch0+1, ... from the same start w0 (ALPC-SVRG: y = z = w0) with
+ * the same random streams, and P_out_host[k] receives the objective P of eq. (1) at the final snapshot;
+ * clipped_out_host[k] (may be NULL) the clipped coordinates summed over all messages of the run.  The
+ * caller picks the candidate with the smallest P.  w0: device, d floats, not modified.  w_work (and
+ * y_work, z_work for ALPC-SVRG, else NULL): device scratch, d floats each; w_work ends as the last
+ * candidate's snapshot.  The context's clip value is restored on return.  Synchronises the stream.
+ * LPC_EINVAL with quantization off or a candidate outside the mode's range. */
+lpc_status lpc_clip_sweep(lpc_ctx *ctx, const float *w0, int32_t n_clip, const float *clips_host, int32_t epochs,
+                          uint32_t epoch0, float *w_work, float *y_work, float *z_work, double *P_out_host,
+                          uint64_t *clipped_out_host, void *stream);
+
 /* Left-hand side of Theorem 2's step-size condition,
  *   8 m^2 rho^2 [ c*d*lambda^2/(2^(bits-1)-1)^2 + d_lambda*(1-lambda)^2 + 1/(N*B) ] + rho,
  * c = 1/4 for schemes (a), (b) (eq. (6)) and 3/8 for scheme (c) (eq. (7)); rho = eta*L, d_lambda =

@@ -149,6 +149,11 @@ int lpco_alpc_params(const lpco_problem *p, const lpco_config *c, uint32_t epoch
  * w_snap: in x~^s, out x~^(s+1).  y, zacc: ALPC state, in/out (d each). */
 int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc, uint32_t epoch,
                uint64_t *bits_sent /* may be NULL; communication step 2 only, Table 1 */);
+/* The same epoch, also recording per inner iteration t and worker i the scale factor delta_t^i (eq. (3);
+ * the shared one under schemes (b), (c); 0 with quantization off) and the number of clipped coordinates
+ * d_lambda of that message (Sec. 3.2): delta_trace, nclip_trace are [m][N], either may be NULL. */
+int lpco_epoch_traced(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
+                      uint32_t epoch, float *delta_trace, uint32_t *nclip_trace);
 
 /* ---- evaluators ---- */
 /* |G_eta(w)|^2, the gradient-mapping metric of Sec. 3.3 */

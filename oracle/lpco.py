@@ -78,6 +78,7 @@ def _load():
         "lpco_code_histogram": (C.c_int, [_u32p, C.c_int64, C.c_int32, _u64p]),
         "lpco_alpc_params": (C.c_int, [P, K, C.c_uint32, _f32p, _f32p, _f32p, _f32p]),
         "lpco_epoch": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _u64p]),
+        "lpco_epoch_traced": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _f32p, _u32p]),
         "lpco_bits_per_message": (C.c_uint64, [C.c_int64, C.c_int32]),
         "lpco_bits_per_iteration": (C.c_uint64, [C.c_int64, C.c_int32, C.c_int32, C.c_int32]),
         "lpco_set_threads": (None, [C.c_int32]),
@@ -333,6 +334,16 @@ def epoch(problem, config, w_snap, epoch_index, y=None, z=None):
     _chk(lib.lpco_epoch(C.byref(problem), C.byref(config), _p(w_snap, _f32p), _p(y, _f32p), _p(z, _f32p),
                         epoch_index, C.byref(bits)))
     return bits.value
+
+
+def epoch_traced(problem, config, w_snap, epoch_index, y=None, z=None):
+    """epoch() that also returns (delta_trace, nclip_trace), each [m][N]."""
+    assert w_snap.dtype == np.float32 and w_snap.flags.c_contiguous
+    dtr = np.zeros((config.m, config.N), np.float32)
+    ntr = np.zeros((config.m, config.N), np.uint32)
+    _chk(lib.lpco_epoch_traced(C.byref(problem), C.byref(config), _p(w_snap, _f32p), _p(y, _f32p), _p(z, _f32p),
+                               epoch_index, _p(dtr, _f32p), _p(ntr, _u32p)))
+    return dtr, ntr
 
 
 def bits_per_message(d, bits):

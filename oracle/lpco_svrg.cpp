@@ -24,13 +24,17 @@ double zeta_no_clip(const lpco_problem *p, const lpco_config *c) {
 
 // communication step 2 for one iteration: U (N x d_pad) -> u_avg (d)
 int exchange(const lpco_problem *p, const lpco_config *c, uint32_t epoch, uint32_t iter, const float *U,
-             const double *stats, float *u_avg, std::vector<uint32_t> &packed, std::vector<float> &delta) {
+             const double *stats, float *u_avg, std::vector<uint32_t> &packed, std::vector<float> &delta,
+             std::vector<uint32_t> &nclip) {
   const int64_t d = p->d;
-  if (c->bits >= 32) return lpco_plain_avg(d, c->N, U, u_avg);  // quantization off
+  if (c->bits >= 32) {  // quantization off: nothing is scaled or clipped
+    for (int32_t i = 0; i < c->N; ++i) { delta[(size_t)i] = 0.0f; nclip[(size_t)i] = 0u; }
+    return lpco_plain_avg(d, c->N, U, u_avg);
+  }
   int rc;
   if (c->scheme == LPCO_SCHEME_A) {
     rc = lpco_quantize_clip(d, c->N, c->bits, c->clip_mode, c->clip, c->seed, epoch, iter, U, stats, nullptr,
-                            packed.data(), delta.data(), nullptr);
+                            packed.data(), delta.data(), nclip.data());
     if (rc != LPCO_OK) return rc;
     return lpco_dequantize_avg(d, c->N, c->bits, packed.data(), delta.data(), u_avg);
   }
@@ -44,7 +48,7 @@ int exchange(const lpco_problem *p, const lpco_config *c, uint32_t epoch, uint32
   }
   std::vector<float> shared((size_t)c->N, dmax);
   rc = lpco_quantize_clip(d, c->N, c->bits, c->clip_mode, c->clip, c->seed, epoch, iter, U, stats, shared.data(),
-                          packed.data(), delta.data(), nullptr);
+                          packed.data(), delta.data(), nclip.data());
   if (rc != LPCO_OK) return rc;
   return lpco_dequantize_shared(d, c->N, c->bits, packed.data(), delta[0], c->scheme == LPCO_SCHEME_C ? 1 : 0,
                                 c->seed, epoch, iter, u_avg, nullptr);
@@ -83,8 +87,12 @@ extern "C" int lpco_alpc_params(const lpco_problem *p, const lpco_config *c, uin
   return LPCO_OK;
 }
 
-extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
-                          uint32_t epoch, uint64_t *bits_sent) {
+namespace {
+
+// One epoch; delta_trace / nclip_trace ([m][N], may be NULL) receive, per inner iteration t and worker i, the
+// scale factor delta_t^i the worker quantized with and its number of clipped coordinates d_lambda (Sec. 3.2).
+int epoch_impl(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc, uint32_t epoch,
+               uint64_t *bits_sent, float *delta_trace, uint32_t *nclip_trace) {
   if (!p || !c || !w_snap) return LPCO_ENULL;
   if (c->N <= 0 || c->B <= 0 || c->m <= 0) return LPCO_EINVAL;
   if (c->bits < 2 || (c->bits > 16 && c->bits < 32)) return LPCO_EINVAL;
@@ -95,6 +103,13 @@ extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_
   std::vector<double> stats((size_t)N * 4);
   std::vector<uint32_t> packed(quant ? (size_t)N * (size_t)lpco_words_per_msg(d, c->bits) : 1);
   std::vector<float> delta((size_t)N);
+  std::vector<uint32_t> nclip((size_t)N);
+  auto record = [&](int32_t t) {
+    for (int32_t i = 0; i < N; ++i) {
+      if (delta_trace) delta_trace[(size_t)t * (size_t)N + (size_t)i] = delta[(size_t)i];
+      if (nclip_trace) nclip_trace[(size_t)t * (size_t)N + (size_t)i] = nclip[(size_t)i];
+    }
+  };
   uint64_t bits = 0;
 
   // communication step 1: grad f at the snapshot, full precision
@@ -107,8 +122,9 @@ extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_
       rc = lpco_worker_vr_grad(p, c, w.data(), w_snap, epoch, (uint32_t)t, LPCO_TAG_BATCH, 0, N, U.data(),
                                stats.data());
       if (rc != LPCO_OK) return rc;
-      rc = exchange(p, c, epoch, (uint32_t)t, U.data(), stats.data(), u_avg.data(), packed, delta);
+      rc = exchange(p, c, epoch, (uint32_t)t, U.data(), stats.data(), u_avg.data(), packed, delta, nclip);
       if (rc != LPCO_OK) return rc;
+      record(t);
       bits += quant ? lpco_bits_per_iteration(d, c->bits, N, c->scheme) : 32ull * d * N * (N - 1);
       // v = u_avg + mu ; x <- prox_{eta h}(x - eta v)
       rc = lpco_prox_step(d, w.data(), u_avg.data(), mu.data(), c->eta, p->lambda1, p->lambda2);
@@ -137,8 +153,9 @@ extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_
     rc = lpco_worker_vr_grad(p, c, x.data(), w_snap, epoch, (uint32_t)t, LPCO_TAG_BATCH, 0, N, U.data(),
                              stats.data());
     if (rc != LPCO_OK) return rc;
-    rc = exchange(p, c, epoch, (uint32_t)t, U.data(), stats.data(), u_avg.data(), packed, delta);
+    rc = exchange(p, c, epoch, (uint32_t)t, U.data(), stats.data(), u_avg.data(), packed, delta, nclip);
     if (rc != LPCO_OK) return rc;
+    record(t);
     bits += quant ? lpco_bits_per_iteration(d, c->bits, N, c->scheme) : 32ull * d * N * (N - 1);
     // double sampling: shared batch J, full precision, never communicated
     rc = lpco_worker_vr_grad(p, c, x.data(), w_snap, epoch, (uint32_t)t, LPCO_TAG_SHARED, 0, 1, uhat.data(),
@@ -160,4 +177,16 @@ extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_
   for (int64_t j = 0; j < d; ++j) w_snap[j] = (float)(ysum[(size_t)j] / wsum);
   if (bits_sent) *bits_sent = bits;
   return LPCO_OK;
+}
+
+}  // namespace
+
+extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
+                          uint32_t epoch, uint64_t *bits_sent) {
+  return epoch_impl(p, c, w_snap, y, zacc, epoch, bits_sent, nullptr, nullptr);
+}
+
+extern "C" int lpco_epoch_traced(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
+                                 uint32_t epoch, float *delta_trace, uint32_t *nclip_trace) {
+  return epoch_impl(p, c, w_snap, y, zacc, epoch, nullptr, delta_trace, nclip_trace);
 }

@@ -117,6 +117,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.u_avg = (float *)take((size_t)c->d * sizeof(float));
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
+  s.clip_total = (unsigned long long *)take(sizeof(unsigned long long));
   s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
   s.csc_ptr = (int32_t *)take((c->csr ? (size_t)c->d + 4 : 4) * sizeof(int32_t));
   s.csc_cursor = (int32_t *)take((c->csr ? (size_t)c->d + 1 : 4) * sizeof(int32_t));
@@ -310,6 +311,26 @@ lpc_status alpc_params(const lpc_ctx *c, uint32_t epoch, AlpcParams *out) {
   do {                                          \
     if ((expr) != hipSuccess) return LPC_EDEVICE; \
   } while (0)
+
+// Evaluation runs only: row t of the traces <- this iteration's scale factors and clip counts (zeros with
+// quantization off), and the clip counts into the running total.
+lpc_status record_iteration(lpc_ctx *c, int32_t t, hipStream_t st) {
+  Scratch &s = c->s;
+  const int32_t N = c->cfg.N;
+  const size_t row = (size_t)t * (size_t)N;
+  if (!c->quant) {
+    if (c->trace_delta) LPC_TRY_HIP(launch_zero(c->trace_delta + row, N, st));
+    if (c->trace_nclip) LPC_TRY_HIP(launch_fill_u32(c->trace_nclip + row, 0u, N, st));
+    return LPC_OK;
+  }
+  if (c->trace_delta)
+    LPC_TRY_HIP(hipMemcpyAsync(c->trace_delta + row, s.delta, sizeof(float) * (size_t)N, hipMemcpyDeviceToDevice, st));
+  if (c->trace_nclip)
+    LPC_TRY_HIP(hipMemcpyAsync(c->trace_nclip + row, s.n_clipped, sizeof(uint32_t) * (size_t)N,
+                               hipMemcpyDeviceToDevice, st));
+  if (c->count_clipped) LPC_TRY_HIP(launch_accumulate_clipped(s.n_clipped, N, s.clip_total, st));
+  return LPC_OK;
+}
 
 // communication step 2 of one inner iteration followed by the update of Alg. 1
 lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st) {
@@ -509,13 +530,16 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   Scratch &s = c->s;
   hipStream_t st = as_stream(stream);
   const lpc_config &g = c->cfg;
+  // evaluation runs take the unfused launches, whose quantizer reports the clip counts
+  const bool tracing = c->trace_delta || c->trace_nclip || c->count_clipped;
   // communication step 1
   LPC_TRY(full_grad_impl(c, w_snap, s.mu, s.z_snap, nullptr, c->n_full, st));
   const float *zs = (c->n_full == c->n) ? s.z_snap : nullptr;  // margins cached only when every row was visited
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
-    const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A;
-    if (c->csr_sparse) {
+    const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A && !tracing;
+    const bool sparse = c->csr_sparse && !tracing;
+    if (sparse) {
       // the sparse passes rely on U, the bitmap and the packed words being zero where nothing was written
       LPC_TRY_HIP(launch_zero(s.U, (int64_t)g.N * c->d_pad, st));
       LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
@@ -523,7 +547,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     }
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
-      if (c->csr_sparse) {
+      if (sparse) {
         {
           ProfScope ps(c, LPC_PROF_VR_ROWS, st);
           LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, st));
@@ -545,6 +569,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
                              c->quant ? kStatsFinal : kStatsNone, st));
         LPC_TRY(exchange_and_prox(c, key, s.w, st));
+        if (tracing) LPC_TRY(record_iteration(c, t, st));
       }
     }
     LPC_TRY_HIP(launch_copy(w_snap, s.w, c->d, st));  // x~ <- x_m
@@ -557,7 +582,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   const float step_y = (float)(1.0 / (4.0 * (double)g.L));
   double weight = 1.0, wsum = 0.0;
   float *u_hat = s.U + (int64_t)g.N * c->d_pad;
-  if (!c->csr && !c->mlp && fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A) {
+  if (!c->csr && !c->mlp && fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A && !tracing) {
     // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
     // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
@@ -604,6 +629,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
         LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
       }
     }
+    if (tracing) LPC_TRY(record_iteration(c, t, st));
     // double sampling: the shared batch J, full precision
     LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagShared, 0, 1, u_hat, nullptr, kStatsNone, st));
     LPC_TRY_HIP(launch_alpc_update(c, s.w, s.u_avg, u_hat, s.mu, step_y, ap.alpha, (float)weight, t == 0, y, z,
@@ -613,6 +639,55 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   }
   LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
   return LPC_OK;
+}
+
+lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, float *delta_trace,
+                            uint32_t *nclip_trace, void *stream) {
+  if (!ctx) return LPC_ENULL;
+  if (!delta_trace && !nclip_trace) return lpc_epoch(ctx, w_snap, y, z, epoch, stream);
+  ctx->trace_delta = delta_trace;
+  ctx->trace_nclip = nclip_trace;
+  const lpc_status rc = lpc_epoch(ctx, w_snap, y, z, epoch, stream);
+  ctx->trace_delta = nullptr;
+  ctx->trace_nclip = nullptr;
+  return rc;
+}
+
+lpc_status lpc_clip_sweep(lpc_ctx *ctx, const float *w0, int32_t n_clip, const float *clips_host, int32_t epochs,
+                          uint32_t epoch0, float *w_work, float *y_work, float *z_work, double *P_out_host,
+                          uint64_t *clipped_out_host, void *stream) {
+  if (!ctx || !w0 || !clips_host || !w_work || !P_out_host) return LPC_ENULL;
+  lpc_ctx *c = ctx;
+  if (!c->quant || n_clip < 1 || epochs < 1) return LPC_EINVAL;
+  const bool alpc = c->cfg.algo != LPC_ALGO_LPC;
+  if (alpc && (!y_work || !z_work)) return LPC_ENULL;
+  for (int32_t k = 0; k < n_clip; ++k) {
+    if (!(clips_host[k] > 0.0f)) return LPC_EINVAL;
+    if (c->cfg.clip_mode == LPC_CLIP_LAMBDA && clips_host[k] > 1.0f) return LPC_EINVAL;
+  }
+  hipStream_t st = as_stream(stream);
+  const float clip_before = c->cfg.clip;
+  lpc_status rc = LPC_OK;
+  for (int32_t k = 0; k < n_clip && rc == LPC_OK; ++k) {
+    c->cfg.clip = clips_host[k];
+    c->count_clipped = clipped_out_host != nullptr;
+    rc = [&]() -> lpc_status {
+      LPC_TRY_HIP(launch_copy(w_work, w0, c->d, st));
+      if (alpc) {
+        LPC_TRY_HIP(launch_copy(y_work, w0, c->d, st));
+        LPC_TRY_HIP(launch_copy(z_work, w0, c->d, st));
+      }
+      if (clipped_out_host) LPC_TRY_HIP(launch_fill_u32(reinterpret_cast<uint32_t *>(c->s.clip_total), 0u, 2, st));
+      for (int32_t e = 0; e < epochs; ++e) LPC_TRY(lpc_epoch(c, w_work, y_work, z_work, epoch0 + (uint32_t)e, stream));
+      if (clipped_out_host)
+        LPC_TRY_HIP(hipMemcpyAsync(&clipped_out_host[k], c->s.clip_total, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+      c->count_clipped = false;
+      return lpc_objective(c, w_work, &P_out_host[k], stream);  // synchronises the stream
+    }();
+  }
+  c->count_clipped = false;
+  c->cfg.clip = clip_before;
+  return rc;
 }
 
 lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void *stream) {

@@ -43,6 +43,14 @@ __global__ __launch_bounds__(1024) void gradient_mapping_kernel(const float *__r
   }
 }
 
+// total += sum_i n_clipped[i] (one thread; N is the number of workers)
+__global__ void accumulate_clipped_kernel(const uint32_t *__restrict__ n_clipped, int32_t N,
+                                          unsigned long long *__restrict__ total) {
+  unsigned long long t = *total;
+  for (int32_t i = 0; i < N; ++i) t += n_clipped[i];
+  *total = t;
+}
+
 __global__ void zero_u64_kernel(unsigned long long *__restrict__ dst, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = 0ull;
@@ -90,6 +98,11 @@ hipError_t launch_gradient_mapping(const lpc_ctx *c, const float *w, const float
                                    hipStream_t st) {
   hipLaunchKernelGGL(gradient_mapping_kernel, dim3(1), dim3(1024), 0, st, w, grad, c->d, eta,
                      (double)c->prob.lambda1, (double)c->prob.lambda2, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st) {
+  hipLaunchKernelGGL(accumulate_clipped_kernel, dim3(1), dim3(1), 0, st, n_clipped, N, total);
   return hipGetLastError();
 }
 

@@ -71,6 +71,7 @@ struct Scratch {
   float *u_avg;         // [d]
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
+  unsigned long long *clip_total;  // [1] clipped coordinates summed over an evaluation run
   float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
   // column-major copy of the CSR entries whose column is not in the head (built by lpc_create)
   int32_t *csc_ptr;     // [d+4]: column extents (head columns are empty), the longest column, two build counters
@@ -102,6 +103,10 @@ struct lpc_ctx {
   int64_t mlp_rows;       // rows of a worker pass (N*B)
   int64_t mlp_cap;        // rows each of the two activation sets can hold (the snapshot pass uses both as one)
   std::vector<int64_t> mlp_woff, mlp_boff, mlp_act_off;  // per layer offsets
+  // set only while an evaluation entry point (traced epoch, clip sweep) runs an epoch; all null otherwise
+  float *trace_delta = nullptr;                // [m][N]
+  uint32_t *trace_nclip = nullptr;             // [m][N]
+  bool count_clipped = false;                  // add every message's clip count to s.clip_total
   int64_t mlp_act_floats;
   int64_t mlp_part_floats;
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
@@ -163,6 +168,7 @@ int gemm_tiles(const GemmArgs &g);                 // statistic partials a matri
 // the vector units): a chunk is cut into blocks that are summed side by side, one partial per block, and the
 // partials are folded by a second, small column sum; a lone launch over thousands of rows would occupy 1-16 CUs.
 constexpr int kSnapBlock = 256;
+hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st);
 void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
                                 hipStream_t st);

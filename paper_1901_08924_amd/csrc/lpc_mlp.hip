@@ -85,18 +85,6 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
   const int pitch = g.K + 4;
   const float *W = g.W + (int64_t)set * g.w_set_stride;
   float *bias = Wt + g.C * pitch;
-  for (int i0 = tid; i0 < g.K * g.C; i0 += 20 * 256) {  // twenty elements in flight per thread
-    float t[20];
-#pragma unroll
-    for (int j = 0; j < 20; ++j) t[j] = i0 + j * 256 < g.K * g.C ? W[i0 + j * 256] : 0.0f;
-#pragma unroll
-    for (int j = 0; j < 20; ++j) {
-      const int i = i0 + j * 256, k = i / g.C, c = i - k * g.C;
-      if (i < g.K * g.C) Wt[c * pitch + k] = t[j];
-    }
-  }
-  if (tid < g.C) bias[tid] = W[g.bias_off + tid];
-  __syncthreads();
   const float sign = set == 0 ? 1.0f : -1.0f;
   const int row0 = blockIdx.x * kLastRows + wave * 4;
   const int lc = lane & 15;
@@ -111,6 +99,21 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
       av[r][q] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (row0 + r < g.rows && k < g.K) av[r][q] = *reinterpret_cast<const float4 *>(a + (int64_t)(row0 + r) * g.lda + k);
     }
+  // W goes to LDS while the activations are on their way
+  const uint32_t inv_c = (uint32_t)((0x100000000ull + (uint32_t)g.C - 1) / (uint32_t)g.C);
+  for (int i0 = tid; i0 < g.K * g.C; i0 += 20 * 256) {  // twenty elements in flight per thread
+    float t[20];
+#pragma unroll
+    for (int j = 0; j < 20; ++j) t[j] = i0 + j * 256 < g.K * g.C ? W[i0 + j * 256] : 0.0f;
+#pragma unroll
+    for (int j = 0; j < 20; ++j) {
+      // i / C by a multiply: exact for i < 2^16 and C <= 16 with the rounded-up reciprocal 2^32 / C
+      const int i = i0 + j * 256, k = (int)__umulhi((uint32_t)i, inv_c), c = i - k * g.C;
+      if (i < g.K * g.C) Wt[c * pitch + k] = t[j];
+    }
+  }
+  if (tid < g.C) bias[tid] = W[g.bias_off + tid];
+  __syncthreads();
   // logits: one read of a column of W serves the four rows; lane (16j + c) keeps z[c] of each row
   float z[4];
 #pragma unroll

@@ -53,6 +53,9 @@ EXPORTS = {
     "lpc_exchange": (C.c_int, [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
+    "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, _vp]),
+    "lpc_clip_sweep": (C.c_int, [_vp, _vp, C.c_int32, C.POINTER(C.c_float), C.c_int32, C.c_uint32, _vp, _vp, _vp,
+                                 C.POINTER(C.c_double), C.POINTER(C.c_uint64), _vp]),
     "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
     "lpc_take_device_flags": (C.c_int, [_vp, _vp]),
     "lpc_gradient_mapping": (C.c_int, [_vp, _vp, C.c_float, C.POINTER(C.c_double), _vp]),
@@ -213,6 +216,28 @@ class Context:
 
     def epoch(self, w_snap, epoch, y=None, z=None, stream=None):
         _chk(lib.lpc_epoch(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _stream(stream)), "lpc_epoch")
+
+    def epoch_traced(self, w_snap, epoch, y=None, z=None, stream=None):
+        """epoch() that also returns (delta_trace float32 [m][N], nclip_trace int32 [m][N]) on the device."""
+        m = int(self.config.m)
+        dtr = torch.empty((m, self.N), dtype=torch.float32, device=self.device)
+        ntr = torch.empty((m, self.N), dtype=torch.int32, device=self.device)   # uint32 bit patterns
+        _chk(lib.lpc_epoch_traced(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _ptr(dtr), _ptr(ntr),
+                                  _stream(stream)), "lpc_epoch_traced")
+        return dtr, ntr
+
+    def clip_sweep(self, w0, clips, epochs, epoch0=0, stream=None):
+        """Objective and total clipped coordinates after `epochs` epochs from w0 for each candidate clip value."""
+        k = len(clips)
+        arr = (C.c_float * k)(*[float(v) for v in clips])
+        P = (C.c_double * k)()
+        clipped = (C.c_uint64 * k)()
+        work = [torch.empty_like(w0) for _ in range(3)]
+        alpc = int(self.config.algo) != 0
+        _chk(lib.lpc_clip_sweep(self._h, _ptr(w0), k, arr, epochs, epoch0, _ptr(work[0]),
+                                _ptr(work[1]) if alpc else None, _ptr(work[2]) if alpc else None, P, clipped,
+                                _stream(stream)), "lpc_clip_sweep")
+        return list(P), [int(v) for v in clipped], work[0]
 
     def objective(self, w, stream=None):
         out = C.c_double()

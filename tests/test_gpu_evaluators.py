@@ -73,3 +73,113 @@ def test_code_histogram_bit_exact_and_huffman_size(d, bits, clip):
     # a second call overwrites the counts rather than adding to them
     again = ctx.code_histogram(packed[1], counts=torch.full((1 << bits,), 7, dtype=torch.int64, device="cuda"))
     assert np.array_equal(again.cpu().numpy().astype(np.uint64), ref)
+
+
+# ---------------------------------------------------------------- traces of delta_t^i and d_lambda, clip selection
+
+def _oracle_traced_run(sp, epochs, **over):
+    from _common import oracle_config
+    p, _keep = oracle_problem(sp)
+    cfg = oracle_config(sp, **over)
+    alpc = cfg.algo != lpco.ALGO_LPC
+    w = sp.w0.copy()
+    y, z = (sp.w0.copy(), sp.w0.copy()) if alpc else (None, None)
+    rows = [lpco.epoch_traced(p, cfg, w, s, y, z) for s in range(epochs)]
+    return p, w, rows
+
+
+@pytest.mark.parametrize("name,over,cfg_over", [
+    ("c2", dict(n=2048, d=512, N=4, B=16), dict(m=8, bits=4, clip_mode=0, clip=0.8)),
+    ("c2", dict(n=1024, d=20_000, N=3, B=16), dict(m=4, bits=3, clip_mode=0, clip=0.6)),     # unfused by size
+    ("c2", dict(n=2048, d=512, N=4, B=16), dict(m=6, bits=3, clip_mode=0, clip=0.7, scheme=1)),
+    ("c4", dict(n=2048, d=256, N=4, B=16), dict(m=6, bits=3, clip_mode=0, clip=0.9, algo=1, tau2=0.5)),
+])
+def test_traced_epoch_matches_plain_epoch_and_the_oracle_trace(name, over, cfg_over):
+    import torch
+    sp = lpc_synth.make(name, **over)
+    alpc = cfg_over.get("algo", 0) != 0
+    _p, w_o, rows_o = _oracle_traced_run(sp, 2, **cfg_over)
+    ctx = gpu_context(sp, **cfg_over)
+    w_a, w_b = to_dev(sp.w0), to_dev(sp.w0)
+    st_a = (to_dev(sp.w0), to_dev(sp.w0)) if alpc else (None, None)
+    st_b = (to_dev(sp.w0), to_dev(sp.w0)) if alpc else (None, None)
+    for s in range(2):
+        ctx.epoch(w_a, s, *st_a)
+        dtr, ntr = ctx.epoch_traced(w_b, s, *st_b)
+        if alpc:
+            assert torch.allclose(w_a, w_b, rtol=1e-5, atol=1e-7)
+        else:
+            assert torch.equal(w_a, w_b)                 # Alg. 1, lambda mode, dense data: the same iterates bit for bit
+        dtr, ntr = dtr.cpu().numpy(), ntr.cpu().numpy().view(np.uint32)
+        d_o, n_o = rows_o[s]
+        if not alpc:
+            assert np.all(dtr[0] == 0.0) and np.all(ntr[0] == 0)      # x_0 = x~: the first message is zero
+        assert np.allclose(dtr, d_o, rtol=1e-3, atol=0.0)
+        # a coordinate within float rounding of the clip threshold may be counted on one side only
+        assert np.abs(ntr.astype(np.int64) - n_o.astype(np.int64)).max() <= 1
+        if cfg_over.get("scheme", 0) != 0:
+            assert np.all(dtr == dtr[:, :1])
+    assert ctx.take_device_flags() == 0
+    ctx.close()
+
+
+def test_traced_epoch_on_csr_data_and_with_quantization_off():
+    sp = lpc_synth.make("c3", n=8192, d=40_000, nnz_mean=12, N=4, B=32)
+    over = dict(m=5, bits=2, clip_mode=0, clip=0.9)
+    p, w_o, rows_o = _oracle_traced_run(sp, 1, **over)
+    ctx = gpu_context(sp, **over)
+    w = to_dev(sp.w0)
+    dtr, ntr = ctx.epoch_traced(w, 0)
+    d_o, n_o = rows_o[0]
+    assert np.allclose(dtr.cpu().numpy(), d_o, rtol=1e-3)
+    assert np.abs(ntr.cpu().numpy().view(np.uint32).astype(np.int64) - n_o.astype(np.int64)).max() <= 1
+    P_o, P_g = lpco.objective(p, w_o), ctx.objective(w)
+    assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    ctx.close()
+    ctx = gpu_context(sp, m=3, bits=32)
+    dtr, ntr = ctx.epoch_traced(to_dev(sp.w0), 0)
+    assert float(dtr.abs().max()) == 0.0 and int(ntr.abs().max()) == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,over,cfg_over,clips", [
+    ("c2", dict(n=2048, d=512, N=4, B=16), dict(m=8, bits=3, clip_mode=0, clip=1.0), [1.0, 0.8, 0.5, 0.2]),
+    ("c4", dict(n=2048, d=256, N=4, B=16), dict(m=8, bits=3, clip_mode=1, clip=2.0, tau2=0.5), [1.5, 2.0, 3.0]),
+])
+def test_clip_sweep_matches_one_oracle_run_per_candidate(name, over, cfg_over, clips):
+    import torch
+    sp = lpc_synth.make(name, **over)
+    ctx = gpu_context(sp, **cfg_over)
+    w0 = to_dev(sp.w0)
+    P, clipped, _w = ctx.clip_sweep(w0, clips, epochs=3, epoch0=0)
+    assert torch.equal(w0, to_dev(sp.w0))                 # the start is not modified
+    for k, clip in enumerate(clips):
+        p, w_o, rows = _oracle_traced_run(sp, 3, **dict(cfg_over, clip=clip))
+        P_o = lpco.objective(p, w_o)
+        assert abs(P[k] - P_o) <= 1e-4 * abs(P_o), (clip, P[k], P_o)
+        total_o = int(sum(int(n.sum()) for _d, n in rows))
+        assert abs(clipped[k] - total_o) <= max(3, 0.005 * total_o), (clip, clipped[k], total_o)
+        if cfg_over["clip_mode"] == 0 and clip == 1.0:
+            assert clipped[k] == 0                        # Sec. 4.1: lambda = 1 never clips
+    # the context's own clip value is back in force
+    fresh = gpu_context(sp, **cfg_over)
+    a, b = to_dev(sp.w0), to_dev(sp.w0)
+    st = [(to_dev(sp.w0), to_dev(sp.w0)) if sp.algo != 0 else (None, None) for _ in range(2)]
+    ctx.epoch(a, 0, *st[0]); fresh.epoch(b, 0, *st[1])
+    assert torch.equal(a, b)
+    ctx.close(); fresh.close()
+
+
+def test_clip_sweep_rejects_bad_candidates():
+    from paper_1901_08924_amd import lpc
+    sp = lpc_synth.make("c2", n=1024, d=128, N=2, B=16)
+    ctx = gpu_context(sp, bits=4, clip_mode=0, clip=1.0)
+    with pytest.raises(Exception):
+        ctx.clip_sweep(to_dev(sp.w0), [0.5, 1.5], epochs=1)
+    with pytest.raises(Exception):
+        ctx.clip_sweep(to_dev(sp.w0), [0.0], epochs=1)
+    ctx.close()
+    ctx = gpu_context(sp, bits=32)
+    with pytest.raises(Exception):
+        ctx.clip_sweep(to_dev(sp.w0), [0.5], epochs=1)
+    ctx.close()

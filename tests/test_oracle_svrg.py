@@ -266,3 +266,72 @@ def test_double_sampling_gradient_is_unbiased():
     mean = acc / T
     se = np.sqrt(np.maximum(acc2 / T - mean ** 2, 1e-12) / T)
     assert np.all(np.abs(mean - target) <= 4.5 * se)
+
+
+# ---------------------------------------------------------------- traces of delta and d_lambda (Sec. 3.2)
+
+def test_traced_epoch_takes_the_same_steps_and_starts_with_a_zero_message():
+    sp = lpc_synth.make("c2", n=512, d=96, N=4, B=8)
+    p, _k = _problem_from(sp)
+    cfg = _config_from(sp, m=6, bits=3, clip_mode=lpco.CLIP_LAMBDA, clip=0.7)
+    w_a, w_b = sp.w0.copy(), sp.w0.copy()
+    lpco.epoch(p, cfg, w_a, 0)
+    dtr, ntr = lpco.epoch_traced(p, cfg, w_b, 0)
+    assert np.array_equal(w_a, w_b)
+    assert dtr.shape == (6, 4) and ntr.shape == (6, 4)
+    # x_0 = x~: every worker's first message is the zero vector, nothing to scale or clip
+    assert np.all(dtr[0] == 0.0) and np.all(ntr[0] == 0)
+    assert np.all(dtr[1:] > 0.0)
+    # lambda < 1 cuts at least the largest coordinate of every later message
+    assert np.all(ntr[1:] >= 1)
+
+
+def test_trace_rows_are_eq3_and_the_clip_count_written_out_by_hand():
+    # iteration t = 1 recomputed in float64 numpy: x_1 = prox(x~ - eta*mu) (the first message is zero),
+    # u^i = grad f_{B_i}(x_1) - grad f_{B_i}(x~), delta_i = lambda*|u^i|_inf/(2^(b-1)-1), d_lambda = #{u_j outside dom(delta_i, b)}
+    sp = lpc_synth.make("c2", n=256, d=48, N=3, B=8)
+    p, _k = _problem_from(sp)
+    lam, b = 0.6, 4
+    cfg = _config_from(sp, m=2, bits=b, clip_mode=lpco.CLIP_LAMBDA, clip=lam)
+    w0 = (0.2 * np.random.default_rng(5).standard_normal(sp.d)).astype(np.float32)
+    w = w0.copy()
+    dtr, ntr = lpco.epoch_traced(p, cfg, w, 7)
+    X, y = sp.X.astype(np.float64), sp.y.astype(np.float64)
+    snap = w0.astype(np.float64)
+    mu = X.T @ _slope(sp.loss, X @ snap, y) / sp.n
+    step = float(sp.eta)
+    x1 = _soft(snap - step * mu, step * sp.lambda1) / (1 + step * sp.lambda2)
+    x1 = x1.astype(np.float32).astype(np.float64)          # the iterate is kept in float
+    for i in range(3):
+        idx = lpco.sample_batch(sp.seed, 7, 1, lpco.TAG_BATCH, i, 8, sp.n)
+        Xb, yb = X[idx], y[idx]
+        u = Xb.T @ (_slope(sp.loss, Xb @ x1, yb) - _slope(sp.loss, Xb @ snap, yb)) / 8
+        amax = np.abs(u).max()
+        assert dtr[1, i] == pytest.approx(lam * amax / (2 ** (b - 1) - 1), rel=2e-5)
+        # coordinates within 1e-4 of the threshold could go either way in float: none here, or skip the count
+        # outside dom(delta, b) = [-2^(b-1)*delta, (2^(b-1)-1)*delta]: the codebook has one more negative point
+        hi, lo = lam * amax, -(2 ** (b - 1)) * lam * amax / (2 ** (b - 1) - 1)
+        near = (np.abs(u - hi) < 1e-4 * amax) | (np.abs(u - lo) < 1e-4 * amax)
+        if not near.any():
+            assert ntr[1, i] == int((u > hi).sum() + (u < lo).sum())
+
+
+def test_no_clipping_at_lambda_one_and_shared_delta_under_scheme_b():
+    sp = lpc_synth.make("c2", n=512, d=64, N=4, B=8)
+    p, _k = _problem_from(sp)
+    w = sp.w0.copy()
+    dtr, ntr = lpco.epoch_traced(p, _config_from(sp, m=5, bits=3, clip_mode=lpco.CLIP_LAMBDA, clip=1.0), w, 0)
+    assert np.all(ntr == 0)                                  # Sec. 4.1: lambda = 1 is LP-SVRG, d_lambda = 0
+    w = sp.w0.copy()
+    dtr_b, _ = lpco.epoch_traced(p, _config_from(sp, m=5, bits=3, clip_mode=lpco.CLIP_LAMBDA, clip=1.0,
+                                                 scheme=lpco.SCHEME_B), w, 0)
+    assert np.all(dtr_b == dtr_b[:, :1])                     # one scale factor per iteration: max_i delta_i
+    assert np.all(dtr_b[1] == dtr[1].max())                  # iteration 1 starts from the same iterate
+
+
+def test_trace_is_zero_with_quantization_off():
+    sp = lpc_synth.make("c1", n=256, d=20, N=2, B=8)
+    p, _k = _problem_from(sp)
+    w = sp.w0.copy()
+    dtr, ntr = lpco.epoch_traced(p, _config_from(sp, m=3, bits=32), w, 0)
+    assert np.all(dtr == 0.0) and np.all(ntr == 0)
