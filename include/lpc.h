@@ -201,13 +201,17 @@ lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double 
 /* lpc_epoch that also records, for every inner iteration t and worker i, the scale factor delta_t^i the
  * worker quantized with (eq. (3); the shared max_i delta_t^i under schemes (b), (c)) and the number of
  * clipped coordinates d_lambda of its message (Sec. 3.2; the quantity Lemma 2 and Theorem 2 are stated in):
- * delta_trace (floats) and nclip_trace (uint32) are device arrays [m][N]; either may be NULL, both NULL is
- * lpc_epoch.  With quantization off both rows are zero.  The traced epoch takes the unfused launches
+ * delta_trace (floats) and nclip_trace (uint32) are device arrays [m][N], zero with quantization off.
+ * coded_bits_host is a HOST array [m][N] that receives the size in bits of each message's d codes after
+ * entropy coding (Sec. 6.1: the optimal prefix code of that message's own histogram; 32*d with
+ * quantization off; add 32 bits for delta and Table 1's fan-out for a total as in Sec. 6.1's table of
+ * communication costs); asking for it synchronises the stream once per message.  Each of the three may be
+ * NULL; all NULL is lpc_epoch.  The traced epoch takes the unfused launches
  * (statistics, quantizer, receiver, prox as separate kernels) for every data kind; for Alg. 1 in
  * LPC_CLIP_LAMBDA mode on dense data its iterates equal lpc_epoch's bit for bit, elsewhere to rounding.
- * Asynchronous. */
+ * Asynchronous unless coded_bits_host is given. */
 lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, float *delta_trace,
-                            uint32_t *nclip_trace, void *stream);
+                            uint32_t *nclip_trace, uint64_t *coded_bits_host, void *stream);
 
 /* Selection of the clipping parameter (Sec. 6.1 picks lambda by cross-validation, once): for each of the
  * n_clip candidates clips_host[k] (lambda in (0,1] or c > 0, in the context's clip mode) the method is run
@@ -240,6 +244,20 @@ lpc_status lpc_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_la
 lpc_status lpc_code_histogram(lpc_ctx *ctx, const uint32_t *packed, uint64_t *counts, void *stream);
 lpc_status lpc_huffman_bits(const uint64_t *counts_host, int32_t nsym, int32_t *lens_out_host,
                             uint64_t *bits_out_host);
+
+/* The entropy-coded message itself.  The paper names the code (Huffman), not a format; this one is fixed here:
+ * the CANONICAL prefix code of the given lengths -- symbols (bin index k = code + 2^(bits-1)) ordered by
+ * (length, k), the first codeword all zeros, each next one the previous plus one, shifted left where the
+ * length grows -- with the codewords of coordinates 0..d-1 of ONE packed message (device, W words) written
+ * one after the other, most significant bit first; stream bit p is bit p%32 of out_words[p/32] (device),
+ * unused high bits of the last word are zero.  lens_host: 2^bits lengths in [0, 32] as returned by
+ * lpc_huffman_bits (0 = symbol without codeword).  *total_bits_out_host receives the stream length.
+ * LPC_EINVAL: quantization off, lengths that are no prefix code, or a coordinate whose symbol has length
+ * 0.  LPC_ESHAPE: the stream needs more than capacity_words words (total_bits_out_host is still set, so
+ * capacity_words = 0 asks for the size only).  Uses the context's scratch; synchronises the stream once,
+ * the emitting launches are left in flight. */
+lpc_status lpc_huffman_encode(lpc_ctx *ctx, const uint32_t *packed, const int32_t *lens_host, uint32_t *out_words,
+                              int64_t capacity_words, uint64_t *total_bits_out_host, void *stream);
 
 /* ---- measurement aid (benchmarks; no passage of the paper) ------------------------------
  * While enabled, every launch of the kernel classes below made by this context is bracketed by

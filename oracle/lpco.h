@@ -151,9 +151,10 @@ int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float
                uint64_t *bits_sent /* may be NULL; communication step 2 only, Table 1 */);
 /* The same epoch, also recording per inner iteration t and worker i the scale factor delta_t^i (eq. (3);
  * the shared one under schemes (b), (c); 0 with quantization off) and the number of clipped coordinates
- * d_lambda of that message (Sec. 3.2): delta_trace, nclip_trace are [m][N], either may be NULL. */
+ * d_lambda of that message (Sec. 3.2), and the size in bits of its d codes after entropy coding (Sec. 6.1;
+ * 32*d with quantization off): delta_trace, nclip_trace, coded_trace are [m][N], each may be NULL. */
 int lpco_epoch_traced(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
-                      uint32_t epoch, float *delta_trace, uint32_t *nclip_trace);
+                      uint32_t epoch, float *delta_trace, uint32_t *nclip_trace, uint64_t *coded_trace);
 
 /* ---- evaluators ---- */
 /* |G_eta(w)|^2, the gradient-mapping metric of Sec. 3.3 */
@@ -165,6 +166,13 @@ double lpco_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambd
  * of the 2^b code values; returns the encoded size in bits */
 uint64_t lpco_huffman_bits(const uint64_t *counts, int32_t nsym, int32_t *lens_out);
 int lpco_code_histogram(const uint32_t *words, int64_t d, int32_t bits, uint64_t *counts);
+/* The entropy-coded stream of one packed message under the canonical prefix code of the given lengths
+ * (symbols ordered by (length, bin index); codewords most significant bit first; stream bit p in word p/32
+ * at bit p%32), and its inverse. */
+int lpco_huffman_encode(const uint32_t *words, int64_t d, int32_t bits, const int32_t *lens, uint32_t *out_words,
+                        int64_t capacity_words, uint64_t *total_bits_out);
+int lpco_huffman_decode(const uint32_t *stream, uint64_t total_bits, int64_t d, int32_t bits, const int32_t *lens,
+                        int32_t *codes_out);
 
 /* ---- message accounting (Table 1) ---- */
 uint64_t lpco_bits_per_message(int64_t d, int32_t bits);

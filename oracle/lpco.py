@@ -76,9 +76,11 @@ def _load():
                                            C.c_int32, C.c_double, C.c_int32]),
         "lpco_huffman_bits": (C.c_uint64, [_u64p, C.c_int32, _i32p]),
         "lpco_code_histogram": (C.c_int, [_u32p, C.c_int64, C.c_int32, _u64p]),
+        "lpco_huffman_encode": (C.c_int, [_u32p, C.c_int64, C.c_int32, _i32p, _u32p, C.c_int64, _u64p]),
+        "lpco_huffman_decode": (C.c_int, [_u32p, C.c_uint64, C.c_int64, C.c_int32, _i32p, _i32p]),
         "lpco_alpc_params": (C.c_int, [P, K, C.c_uint32, _f32p, _f32p, _f32p, _f32p]),
         "lpco_epoch": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _u64p]),
-        "lpco_epoch_traced": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _f32p, _u32p]),
+        "lpco_epoch_traced": (C.c_int, [P, K, _f32p, _f32p, _f32p, C.c_uint32, _f32p, _u32p, _u64p]),
         "lpco_bits_per_message": (C.c_uint64, [C.c_int64, C.c_int32]),
         "lpco_bits_per_iteration": (C.c_uint64, [C.c_int64, C.c_int32, C.c_int32, C.c_int32]),
         "lpco_set_threads": (None, [C.c_int32]),
@@ -320,6 +322,27 @@ def code_histogram(words, d, bits):
     return counts
 
 
+def huffman_encode(words, d, bits, lens, capacity_words=None):
+    """(stream words, total bits) of one packed message under the canonical code of `lens`."""
+    words = np.ascontiguousarray(words, np.uint32)
+    lens = np.ascontiguousarray(lens, np.int32)
+    cap = int(capacity_words) if capacity_words is not None else (int(d) * max(int(lens.max()), 1) + 31) // 32
+    out = np.zeros(max(cap, 1), np.uint32)
+    total = C.c_uint64()
+    _chk(lib.lpco_huffman_encode(_p(words, _u32p), d, bits, _p(lens, _i32p), _p(out, _u32p), cap, C.byref(total)))
+    return out[:(total.value + 31) // 32].copy(), total.value
+
+
+def huffman_decode(stream, total_bits, d, bits, lens):
+    stream = np.ascontiguousarray(stream, np.uint32)
+    if stream.size == 0:
+        stream = np.zeros(1, np.uint32)
+    lens = np.ascontiguousarray(lens, np.int32)
+    codes = np.zeros(d, np.int32)
+    _chk(lib.lpco_huffman_decode(_p(stream, _u32p), total_bits, d, bits, _p(lens, _i32p), _p(codes, _i32p)))
+    return codes
+
+
 def alpc_params(problem, config, epoch):
     t1, t2, a, th = C.c_float(), C.c_float(), C.c_float(), C.c_float()
     _chk(lib.lpco_alpc_params(C.byref(problem), C.byref(config), epoch, C.byref(t1), C.byref(t2), C.byref(a),
@@ -336,14 +359,16 @@ def epoch(problem, config, w_snap, epoch_index, y=None, z=None):
     return bits.value
 
 
-def epoch_traced(problem, config, w_snap, epoch_index, y=None, z=None):
-    """epoch() that also returns (delta_trace, nclip_trace), each [m][N]."""
+def epoch_traced(problem, config, w_snap, epoch_index, y=None, z=None, coded=False):
+    """epoch() that also returns (delta_trace, nclip_trace), each [m][N]; with coded=True also the entropy-coded
+    size of every message."""
     assert w_snap.dtype == np.float32 and w_snap.flags.c_contiguous
     dtr = np.zeros((config.m, config.N), np.float32)
     ntr = np.zeros((config.m, config.N), np.uint32)
+    ctr = np.zeros((config.m, config.N), np.uint64) if coded else None
     _chk(lib.lpco_epoch_traced(C.byref(problem), C.byref(config), _p(w_snap, _f32p), _p(y, _f32p), _p(z, _f32p),
-                               epoch_index, _p(dtr, _f32p), _p(ntr, _u32p)))
-    return dtr, ntr
+                               epoch_index, _p(dtr, _f32p), _p(ntr, _u32p), _p(ctr, _u64p)))
+    return (dtr, ntr, ctr) if coded else (dtr, ntr)
 
 
 def bits_per_message(d, bits):

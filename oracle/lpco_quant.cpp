@@ -330,3 +330,88 @@ extern "C" int lpco_code_histogram(const uint32_t *words, int64_t d, int32_t bit
   for (int64_t j = 0; j < d; ++j) counts[codes[(size_t)j] + (1 << (bits - 1))] += 1;
   return LPCO_OK;
 }
+
+// ---- the entropy-coded bit stream itself ----
+// The paper names Huffman coding and no format.  Reading taken: the prefix code is the CANONICAL one for
+// the given code lengths -- symbols (bin index k = code + 2^(b-1)) ordered by (length, k), the first gets
+// the all-zero codeword, each next one the previous codeword plus one, shifted left by the growth in
+// length -- and the codewords of coordinates 0, 1, ..., d-1 follow one another most significant bit first;
+// stream bit p lives in word p/32 at bit p%32 (the bit order of the packed messages).
+namespace {
+
+// codeword of every symbol for the given lengths, or false if the lengths do not form a prefix code
+bool canonical_codes(const int32_t *lens, int32_t nsym, std::vector<uint64_t> &code) {
+  code.assign((size_t)nsym, 0);
+  int32_t maxlen = 0;
+  for (int32_t k = 0; k < nsym; ++k) {
+    if (lens[k] < 0 || lens[k] > 57) return false;
+    if (lens[k] > maxlen) maxlen = lens[k];
+  }
+  uint64_t next = 0;
+  int32_t prev_len = 0;
+  for (int32_t len = 1; len <= maxlen; ++len) {
+    for (int32_t k = 0; k < nsym; ++k) {
+      if (lens[k] != len) continue;
+      next <<= (len - prev_len);
+      prev_len = len;
+      if (next >> len) return false;  // more codewords of this length than the shorter ones leave room for
+      code[(size_t)k] = next;
+      next += 1;
+    }
+  }
+  return true;
+}
+
+}  // namespace
+
+// Encodes the first d coordinates of one packed message.  out_words (capacity_words words, zero-filled
+// here) receives the stream, *total_bits_out its length.  LPCO_EINVAL if the lengths are no prefix code,
+// a coordinate's symbol has length 0, or the stream does not fit.
+extern "C" int lpco_huffman_encode(const uint32_t *words, int64_t d, int32_t bits, const int32_t *lens,
+                                   uint32_t *out_words, int64_t capacity_words, uint64_t *total_bits_out) {
+  if (!words || !lens || !out_words || !total_bits_out) return LPCO_ENULL;
+  if (!bits_ok(bits) || d < 0 || capacity_words < 0) return LPCO_EINVAL;
+  const int32_t nsym = 1 << bits;
+  std::vector<uint64_t> code;
+  if (!canonical_codes(lens, nsym, code)) return LPCO_EINVAL;
+  std::vector<int32_t> codes((size_t)d);
+  lpco_unpack(words, d, bits, codes.data());
+  for (int64_t w = 0; w < capacity_words; ++w) out_words[w] = 0u;
+  uint64_t pos = 0;
+  for (int64_t j = 0; j < d; ++j) {
+    const int32_t k = codes[(size_t)j] + (nsym >> 1);
+    const int32_t len = lens[k];
+    if (len == 0) return LPCO_EINVAL;
+    for (int32_t i = len - 1; i >= 0; --i) {  // most significant bit of the codeword first
+      if ((int64_t)(pos >> 5) >= capacity_words) return LPCO_EINVAL;
+      if ((code[(size_t)k] >> i) & 1u) out_words[pos >> 5] |= 1u << (pos & 31u);
+      ++pos;
+    }
+  }
+  *total_bits_out = pos;
+  return LPCO_OK;
+}
+
+// Decodes d coordinates from such a stream, reading bit by bit until the bits read so far are a codeword.
+extern "C" int lpco_huffman_decode(const uint32_t *stream, uint64_t total_bits, int64_t d, int32_t bits,
+                                   const int32_t *lens, int32_t *codes_out) {
+  if (!stream || !lens || !codes_out) return LPCO_ENULL;
+  if (!bits_ok(bits) || d < 0) return LPCO_EINVAL;
+  const int32_t nsym = 1 << bits;
+  std::vector<uint64_t> code;
+  if (!canonical_codes(lens, nsym, code)) return LPCO_EINVAL;
+  uint64_t pos = 0;
+  for (int64_t j = 0; j < d; ++j) {
+    uint64_t acc = 0;
+    int32_t len = 0, found = -1;
+    while (found < 0) {
+      if (pos >= total_bits || len >= 57) return LPCO_EINVAL;
+      acc = (acc << 1) | ((stream[pos >> 5] >> (pos & 31u)) & 1u);
+      ++pos; ++len;
+      for (int32_t k = 0; k < nsym; ++k)
+        if (lens[k] == len && code[(size_t)k] == acc) { found = k; break; }
+    }
+    codes_out[j] = found - (nsym >> 1);
+  }
+  return pos == total_bits ? LPCO_OK : LPCO_EINVAL;
+}

@@ -89,10 +89,12 @@ extern "C" int lpco_alpc_params(const lpco_problem *p, const lpco_config *c, uin
 
 namespace {
 
-// One epoch; delta_trace / nclip_trace ([m][N], may be NULL) receive, per inner iteration t and worker i, the
-// scale factor delta_t^i the worker quantized with and its number of clipped coordinates d_lambda (Sec. 3.2).
+// One epoch; delta_trace / nclip_trace / coded_trace ([m][N], may be NULL) receive, per inner iteration t and
+// worker i, the scale factor delta_t^i the worker quantized with, its number of clipped coordinates d_lambda
+// (Sec. 3.2) and the size in bits of the message's d codes after entropy coding (Sec. 6.1; 32*d with
+// quantization off).
 int epoch_impl(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc, uint32_t epoch,
-               uint64_t *bits_sent, float *delta_trace, uint32_t *nclip_trace) {
+               uint64_t *bits_sent, float *delta_trace, uint32_t *nclip_trace, uint64_t *coded_trace) {
   if (!p || !c || !w_snap) return LPCO_ENULL;
   if (c->N <= 0 || c->B <= 0 || c->m <= 0) return LPCO_EINVAL;
   if (c->bits < 2 || (c->bits > 16 && c->bits < 32)) return LPCO_EINVAL;
@@ -108,6 +110,16 @@ int epoch_impl(const lpco_problem *p, const lpco_config *c, float *w_snap, float
     for (int32_t i = 0; i < N; ++i) {
       if (delta_trace) delta_trace[(size_t)t * (size_t)N + (size_t)i] = delta[(size_t)i];
       if (nclip_trace) nclip_trace[(size_t)t * (size_t)N + (size_t)i] = nclip[(size_t)i];
+      if (coded_trace) {
+        uint64_t size = 32ull * (uint64_t)d;
+        if (quant) {
+          std::vector<uint64_t> counts((size_t)1 << c->bits);
+          lpco_code_histogram(packed.data() + (size_t)i * (size_t)lpco_words_per_msg(d, c->bits), d, c->bits,
+                              counts.data());
+          size = lpco_huffman_bits(counts.data(), 1 << c->bits, nullptr);
+        }
+        coded_trace[(size_t)t * (size_t)N + (size_t)i] = size;
+      }
     }
   };
   uint64_t bits = 0;
@@ -183,10 +195,10 @@ int epoch_impl(const lpco_problem *p, const lpco_config *c, float *w_snap, float
 
 extern "C" int lpco_epoch(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
                           uint32_t epoch, uint64_t *bits_sent) {
-  return epoch_impl(p, c, w_snap, y, zacc, epoch, bits_sent, nullptr, nullptr);
+  return epoch_impl(p, c, w_snap, y, zacc, epoch, bits_sent, nullptr, nullptr, nullptr);
 }
 
 extern "C" int lpco_epoch_traced(const lpco_problem *p, const lpco_config *c, float *w_snap, float *y, float *zacc,
-                                 uint32_t epoch, float *delta_trace, uint32_t *nclip_trace) {
-  return epoch_impl(p, c, w_snap, y, zacc, epoch, nullptr, delta_trace, nclip_trace);
+                                 uint32_t epoch, float *delta_trace, uint32_t *nclip_trace, uint64_t *coded_trace) {
+  return epoch_impl(p, c, w_snap, y, zacc, epoch, nullptr, delta_trace, nclip_trace, coded_trace);
 }

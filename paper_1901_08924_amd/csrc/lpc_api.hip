@@ -118,6 +118,13 @@ size_t layout(lpc_ctx *c, char *base) {
   s.ysum = (float *)take((size_t)c->d * sizeof(float));
   s.f_scalar = (double *)take(sizeof(double));
   s.clip_total = (unsigned long long *)take(sizeof(unsigned long long));
+  {
+    const size_t syms = c->quant ? (size_t)1 << c->cfg.bits : 1, segs = (size_t)(c->d_pad / 32);
+    s.huff_table = (HuffEntry *)take(syms * sizeof(HuffEntry));
+    s.huff_seg_bits = (uint32_t *)take((c->quant ? segs : 1) * sizeof(uint32_t));
+    s.huff_off = (unsigned long long *)take((c->quant ? segs : 1) * sizeof(unsigned long long));
+    s.huff_meta = (unsigned long long *)take(2 * sizeof(unsigned long long));
+  }
   s.csr_tail = (float *)take((c->csr ? (size_t)c->d_pad : 4) * sizeof(float));
   s.csc_ptr = (int32_t *)take((c->csr ? (size_t)c->d + 4 : 4) * sizeof(int32_t));
   s.csc_cursor = (int32_t *)take((c->csr ? (size_t)c->d + 1 : 4) * sizeof(int32_t));
@@ -321,7 +328,22 @@ lpc_status record_iteration(lpc_ctx *c, int32_t t, hipStream_t st) {
   if (!c->quant) {
     if (c->trace_delta) LPC_TRY_HIP(launch_zero(c->trace_delta + row, N, st));
     if (c->trace_nclip) LPC_TRY_HIP(launch_fill_u32(c->trace_nclip + row, 0u, N, st));
+    if (c->trace_coded_host)
+      for (int32_t i = 0; i < N; ++i) c->trace_coded_host[row + (size_t)i] = 32ull * (uint64_t)c->d;
     return LPC_OK;
+  }
+  if (c->trace_coded_host) {
+    // histogram of each message on the device, code lengths on the host (the table's scratch holds the counts)
+    const int32_t nsym = 1 << c->cfg.bits;
+    uint64_t *counts_dev = reinterpret_cast<uint64_t *>(s.huff_table);
+    std::vector<uint64_t> counts((size_t)nsym);
+    for (int32_t i = 0; i < N; ++i) {
+      LPC_TRY_HIP(launch_code_histogram(s.packed + (int64_t)i * c->W, c->d, c->cfg.bits, counts_dev, st));
+      LPC_TRY_HIP(hipMemcpyAsync(counts.data(), counts_dev, sizeof(uint64_t) * (size_t)nsym, hipMemcpyDeviceToHost,
+                                 st));
+      LPC_TRY_HIP(hipStreamSynchronize(st));
+      c->trace_coded_host[row + (size_t)i] = huffman_code_lengths(counts.data(), nsym, nullptr);
+    }
   }
   if (c->trace_delta)
     LPC_TRY_HIP(hipMemcpyAsync(c->trace_delta + row, s.delta, sizeof(float) * (size_t)N, hipMemcpyDeviceToDevice, st));
@@ -531,7 +553,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   hipStream_t st = as_stream(stream);
   const lpc_config &g = c->cfg;
   // evaluation runs take the unfused launches, whose quantizer reports the clip counts
-  const bool tracing = c->trace_delta || c->trace_nclip || c->count_clipped;
+  const bool tracing = c->trace_delta || c->trace_nclip || c->count_clipped || c->trace_coded_host;
   // communication step 1
   LPC_TRY(full_grad_impl(c, w_snap, s.mu, s.z_snap, nullptr, c->n_full, st));
   const float *zs = (c->n_full == c->n) ? s.z_snap : nullptr;  // margins cached only when every row was visited
@@ -642,14 +664,16 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
 }
 
 lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, float *delta_trace,
-                            uint32_t *nclip_trace, void *stream) {
+                            uint32_t *nclip_trace, uint64_t *coded_bits_host, void *stream) {
   if (!ctx) return LPC_ENULL;
-  if (!delta_trace && !nclip_trace) return lpc_epoch(ctx, w_snap, y, z, epoch, stream);
+  if (!delta_trace && !nclip_trace && !coded_bits_host) return lpc_epoch(ctx, w_snap, y, z, epoch, stream);
   ctx->trace_delta = delta_trace;
   ctx->trace_nclip = nclip_trace;
+  ctx->trace_coded_host = coded_bits_host;
   const lpc_status rc = lpc_epoch(ctx, w_snap, y, z, epoch, stream);
   ctx->trace_delta = nullptr;
   ctx->trace_nclip = nullptr;
+  ctx->trace_coded_host = nullptr;
   return rc;
 }
 
@@ -730,6 +754,29 @@ lpc_status lpc_code_histogram(lpc_ctx *ctx, const uint32_t *packed, uint64_t *co
   if (!ctx || !packed || !counts) return LPC_ENULL;
   if (!ctx->quant) return LPC_EINVAL;
   LPC_TRY_HIP(launch_code_histogram(packed, ctx->d, ctx->cfg.bits, counts, as_stream(stream)));
+  return LPC_OK;
+}
+
+lpc_status lpc_huffman_encode(lpc_ctx *ctx, const uint32_t *packed, const int32_t *lens_host, uint32_t *out_words,
+                              int64_t capacity_words, uint64_t *total_bits_out_host, void *stream) {
+  if (!ctx || !packed || !lens_host || !total_bits_out_host) return LPC_ENULL;
+  if (!ctx->quant || capacity_words < 0 || (capacity_words > 0 && !out_words)) return LPC_EINVAL;
+  hipStream_t st = as_stream(stream);
+  const int32_t nsym = 1 << ctx->cfg.bits;
+  std::vector<HuffEntry> table((size_t)nsym);
+  if (huffman_canonical_table(lens_host, nsym, table.data()) != 0) return LPC_EINVAL;
+  LPC_TRY_HIP(hipMemcpyAsync(ctx->s.huff_table, table.data(), sizeof(HuffEntry) * (size_t)nsym, hipMemcpyHostToDevice,
+                             st));
+  LPC_TRY_HIP(launch_huffman_measure(ctx, packed, st));
+  unsigned long long meta[2] = {0, 0};
+  LPC_TRY_HIP(hipMemcpyAsync(meta, ctx->s.huff_meta, sizeof(meta), hipMemcpyDeviceToHost, st));
+  LPC_TRY_HIP(hipStreamSynchronize(st));  // also: the table has left the host vector
+  if (meta[1]) return LPC_EINVAL;         // a coordinate whose symbol has no codeword
+  *total_bits_out_host = meta[0];
+  const int64_t need = (int64_t)((meta[0] + 31) / 32);
+  if (need > capacity_words) return LPC_ESHAPE;
+  if (need == 0) return LPC_OK;
+  LPC_TRY_HIP(launch_huffman_emit(ctx, packed, out_words, need, st));
   return LPC_OK;
 }
 

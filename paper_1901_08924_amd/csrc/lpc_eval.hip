@@ -1,7 +1,8 @@
 // Evaluators beside the hot path (gfx950): the gradient-mapping metric of
 // Sec. 3.3, the histogram of a packed message's codes and the optimal
 // prefix-code size it implies (entropy coding of the messages, Sec. 6.1), and
-// the left-hand side of Theorem 2's step-size conditions (eq. (6), (7)).
+// the left-hand side of Theorem 2's step-size conditions (eq. (6), (7)), and the emission of the entropy-coded
+// bit stream (canonical prefix code, codewords most significant bit first).
 // None of these runs inside an epoch; they are written for clarity, with fp64
 // accumulation in a fixed order.
 #include <hip/hip_runtime.h>
@@ -98,6 +99,145 @@ hipError_t launch_gradient_mapping(const lpc_ctx *c, const float *w, const float
                                    hipStream_t st) {
   hipLaunchKernelGGL(gradient_mapping_kernel, dim3(1), dim3(1024), 0, st, w, grad, c->d, eta,
                      (double)c->prob.lambda1, (double)c->prob.lambda2, out);
+  return hipGetLastError();
+}
+
+// Canonical prefix code: symbols ordered by (length, index); the first codeword is all zeros, each next one
+// is the previous plus one, shifted left when the length grows.  The table keeps every codeword bit-reversed
+// so that appending it to a little-endian bit stream puts its most significant bit first.
+int huffman_canonical_table(const int32_t *lens, int32_t nsym, HuffEntry *table) {
+  int32_t longest = 0;
+  for (int32_t k = 0; k < nsym; ++k) {
+    if (lens[k] < 0 || lens[k] > 32) return -1;
+    longest = lens[k] > longest ? lens[k] : longest;
+    table[k] = HuffEntry{0u, 0u};
+  }
+  uint64_t word = 0;   // next free codeword of the current length
+  int32_t cur = 0;
+  for (int32_t len = 1; len <= longest; ++len)
+    for (int32_t k = 0; k < nsym; ++k) {
+      if (lens[k] != len) continue;
+      word <<= (len - cur);
+      cur = len;
+      if (word >= (1ull << len)) return -1;  // Kraft's inequality violated
+      uint32_t rev = 0;
+      for (int32_t i = 0; i < len; ++i) rev |= (uint32_t)((word >> i) & 1ull) << (len - 1 - i);
+      table[k] = HuffEntry{rev, (uint32_t)len};
+      ++word;
+    }
+  return 0;
+}
+
+namespace {
+
+// symbol (bin index) of coordinate j of a 32-coordinate segment
+__device__ __forceinline__ uint32_t segment_symbol(const uint32_t *seg, int j, int b, uint32_t mask, uint32_t bias) {
+  const int off = j * b, wi = off >> 5, sh = off & 31;
+  uint32_t f = seg[wi] >> sh;
+  if (sh + b > 32) f |= seg[wi + 1] << (32 - sh);
+  return ((f & mask) + bias) & mask;
+}
+
+// seg_bits[s] = encoded size of segment s; meta[1] != 0 if some coordinate's symbol has no codeword
+__global__ __launch_bounds__(256) void huffman_measure_kernel(const uint32_t *__restrict__ words, int64_t d, int32_t b,
+                                                              const HuffEntry *__restrict__ table,
+                                                              uint32_t *__restrict__ seg_bits,
+                                                              unsigned long long *__restrict__ meta) {
+  const int64_t segs = (d + 31) / 32;
+  const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (s >= segs) return;
+  const uint32_t mask = (1u << b) - 1u, bias = 1u << (b - 1);
+  const int64_t left = d - s * 32;
+  const int cnt = left < 32 ? (int)left : 32;
+  uint32_t total = 0;
+  bool bad = false;
+  for (int j = 0; j < cnt; ++j) {
+    const uint32_t len = table[segment_symbol(words + s * b, j, b, mask, bias)].len;
+    bad = bad || len == 0;
+    total += len;
+  }
+  seg_bits[s] = total;
+  if (bad) atomicOr(&meta[1], 1ull);
+}
+
+// off[s] = sum of seg_bits[0..s), meta[0] = the total; one workgroup, each thread a contiguous share
+__global__ __launch_bounds__(1024) void huffman_scan_kernel(const uint32_t *__restrict__ seg_bits, int64_t segs,
+                                                            unsigned long long *__restrict__ off,
+                                                            unsigned long long *__restrict__ meta) {
+  __shared__ unsigned long long share[1024];
+  const int tid = threadIdx.x;
+  const int64_t per = (segs + 1023) / 1024;
+  const int64_t lo = tid * per, hi = lo + per < segs ? lo + per : segs;
+  unsigned long long mine = 0;
+  for (int64_t s = lo; s < hi; ++s) mine += seg_bits[s];
+  share[tid] = mine;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long run = 0;
+    for (int k = 0; k < 1024; ++k) {
+      const unsigned long long t = share[k];
+      share[k] = run;
+      run += t;
+    }
+    meta[0] = run;
+  }
+  __syncthreads();
+  unsigned long long pos = share[tid];
+  for (int64_t s = lo; s < hi; ++s) {
+    off[s] = pos;
+    pos += seg_bits[s];
+  }
+}
+
+// A thread appends the codewords of its segment from stream position off[s] on.  Words shared with the
+// neighbouring segments are merged with atomic ORs (the stream was zero-filled).
+__global__ __launch_bounds__(256) void huffman_emit_kernel(const uint32_t *__restrict__ words, int64_t d, int32_t b,
+                                                           const HuffEntry *__restrict__ table,
+                                                           const unsigned long long *__restrict__ off,
+                                                           uint32_t *__restrict__ out) {
+  const int64_t segs = (d + 31) / 32;
+  const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (s >= segs) return;
+  const uint32_t mask = (1u << b) - 1u, bias = 1u << (b - 1);
+  const int64_t left = d - s * 32;
+  const int cnt = left < 32 ? (int)left : 32;
+  const unsigned long long pos = off[s];
+  int64_t wi = (int64_t)(pos >> 5);
+  uint32_t filled = (uint32_t)(pos & 31ull);   // bits of out[wi] that belong to earlier segments
+  unsigned long long acc = 0;
+  for (int j = 0; j < cnt; ++j) {
+    const HuffEntry e = table[segment_symbol(words + s * b, j, b, mask, bias)];
+    acc |= (unsigned long long)e.rev << filled;   // filled <= 31, e.len <= 32
+    filled += e.len;
+    if (filled >= 32) {
+      if ((uint32_t)acc) atomicOr(&out[wi], (uint32_t)acc);
+      acc >>= 32;
+      filled -= 32;
+      ++wi;
+    }
+  }
+  if ((uint32_t)acc) atomicOr(&out[wi], (uint32_t)acc);
+}
+
+}  // namespace
+
+hipError_t launch_huffman_measure(const lpc_ctx *c, const uint32_t *words, hipStream_t st) {
+  const int64_t segs = c->d_pad / 32;
+  hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(64), 0, st, c->s.huff_meta, (int64_t)2);
+  hipLaunchKernelGGL(huffman_measure_kernel, dim3((unsigned)((segs + 255) / 256)), dim3(256), 0, st, words, c->d,
+                     c->cfg.bits, (const HuffEntry *)c->s.huff_table, c->s.huff_seg_bits, c->s.huff_meta);
+  hipLaunchKernelGGL(huffman_scan_kernel, dim3(1), dim3(1024), 0, st, (const uint32_t *)c->s.huff_seg_bits, segs,
+                     c->s.huff_off, c->s.huff_meta);
+  return hipGetLastError();
+}
+
+hipError_t launch_huffman_emit(const lpc_ctx *c, const uint32_t *words, uint32_t *out, int64_t out_words,
+                               hipStream_t st) {
+  const int64_t segs = c->d_pad / 32;
+  hipError_t e = launch_fill_u32(out, 0u, out_words, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(huffman_emit_kernel, dim3((unsigned)((segs + 255) / 256)), dim3(256), 0, st, words, c->d,
+                     c->cfg.bits, (const HuffEntry *)c->s.huff_table, (const unsigned long long *)c->s.huff_off, out);
   return hipGetLastError();
 }
 

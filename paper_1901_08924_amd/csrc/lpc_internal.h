@@ -52,6 +52,12 @@ struct GemmArgs {
   int32_t stat_slot0;
 };
 
+// One symbol of the entropy coder: the codeword with its bits reversed (the first stream bit at bit 0) and
+// its length; length 0 = the symbol has no codeword.
+struct HuffEntry {
+  uint32_t rev, len;
+};
+
 // ---- device scratch owned by a context (all pointers into the workspace) ----
 struct Scratch {
   float *part;          // partial gradient rows
@@ -72,6 +78,10 @@ struct Scratch {
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
   unsigned long long *clip_total;  // [1] clipped coordinates summed over an evaluation run
+  HuffEntry *huff_table;           // [2^bits] codeword table of the entropy coder
+  uint32_t *huff_seg_bits;         // [d_pad/32] encoded bits per 32-coordinate segment
+  unsigned long long *huff_off;    // [d_pad/32] stream position of each segment
+  unsigned long long *huff_meta;   // [2] total bits, bad-symbol flag
   float *csr_tail;      // [d_pad] CSR snapshot pass: accumulator of the non-privatised columns
   // column-major copy of the CSR entries whose column is not in the head (built by lpc_create)
   int32_t *csc_ptr;     // [d+4]: column extents (head columns are empty), the longest column, two build counters
@@ -107,6 +117,7 @@ struct lpc_ctx {
   float *trace_delta = nullptr;                // [m][N]
   uint32_t *trace_nclip = nullptr;             // [m][N]
   bool count_clipped = false;                  // add every message's clip count to s.clip_total
+  uint64_t *trace_coded_host = nullptr;        // [m][N], HOST: entropy-coded size of every message
   int64_t mlp_act_floats;
   int64_t mlp_part_floats;
   int32_t full_grad_wgs;  // workgroups of the snapshot pass (= partial rows it writes)
@@ -168,6 +179,12 @@ int gemm_tiles(const GemmArgs &g);                 // statistic partials a matri
 // the vector units): a chunk is cut into blocks that are summed side by side, one partial per block, and the
 // partials are folded by a second, small column sum; a lone launch over thousands of rows would occupy 1-16 CUs.
 constexpr int kSnapBlock = 256;
+// 0 if lens[0..nsym) (each in [0, 32]) are the lengths of a prefix code, and then table[k] holds symbol k's
+// canonical codeword; -1 otherwise.
+int huffman_canonical_table(const int32_t *lens, int32_t nsym, HuffEntry *table);
+hipError_t launch_huffman_measure(const lpc_ctx *c, const uint32_t *words, hipStream_t st);
+hipError_t launch_huffman_emit(const lpc_ctx *c, const uint32_t *words, uint32_t *out, int64_t out_words,
+                               hipStream_t st);
 hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st);
 void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,

@@ -53,7 +53,7 @@ EXPORTS = {
     "lpc_exchange": (C.c_int, [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
-    "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, _vp]),
+    "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, C.POINTER(C.c_uint64), _vp]),
     "lpc_clip_sweep": (C.c_int, [_vp, _vp, C.c_int32, C.POINTER(C.c_float), C.c_int32, C.c_uint32, _vp, _vp, _vp,
                                  C.POINTER(C.c_double), C.POINTER(C.c_uint64), _vp]),
     "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
@@ -63,6 +63,7 @@ EXPORTS = {
                                    C.c_double, C.c_int32, C.POINTER(C.c_double)]),
     "lpc_code_histogram": (C.c_int, [_vp, _vp, _vp, _vp]),
     "lpc_huffman_bits": (C.c_int, [_vp, C.c_int32, _vp, C.POINTER(C.c_uint64)]),
+    "lpc_huffman_encode": (C.c_int, [_vp, _vp, _vp, _vp, C.c_int64, C.POINTER(C.c_uint64), _vp]),
     "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
     "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), _vp]),
 }
@@ -217,13 +218,17 @@ class Context:
     def epoch(self, w_snap, epoch, y=None, z=None, stream=None):
         _chk(lib.lpc_epoch(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _stream(stream)), "lpc_epoch")
 
-    def epoch_traced(self, w_snap, epoch, y=None, z=None, stream=None):
-        """epoch() that also returns (delta_trace float32 [m][N], nclip_trace int32 [m][N]) on the device."""
+    def epoch_traced(self, w_snap, epoch, y=None, z=None, stream=None, coded=False):
+        """epoch() that also returns (delta_trace float32 [m][N], nclip_trace int32 [m][N]) on the device and,
+        with coded=True, the entropy-coded size of every message as a nested host list [m][N]."""
         m = int(self.config.m)
         dtr = torch.empty((m, self.N), dtype=torch.float32, device=self.device)
         ntr = torch.empty((m, self.N), dtype=torch.int32, device=self.device)   # uint32 bit patterns
-        _chk(lib.lpc_epoch_traced(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _ptr(dtr), _ptr(ntr),
+        sizes = (C.c_uint64 * (m * self.N))() if coded else None
+        _chk(lib.lpc_epoch_traced(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, _ptr(dtr), _ptr(ntr), sizes,
                                   _stream(stream)), "lpc_epoch_traced")
+        if coded:
+            return dtr, ntr, [[int(sizes[t * self.N + i]) for i in range(self.N)] for t in range(m)]
         return dtr, ntr
 
     def clip_sweep(self, w0, clips, epochs, epoch0=0, stream=None):
@@ -248,6 +253,21 @@ class Context:
         out = C.c_double()
         _chk(lib.lpc_gradient_mapping(self._h, _ptr(w), eta, C.byref(out), _stream(stream)), "lpc_gradient_mapping")
         return out.value
+
+    def huffman_encode(self, packed, lens, capacity_words=None, stream=None):
+        """One packed message (device) -> (stream words on the device, total bits) under the canonical code of
+        `lens` (host sequence of 2^bits lengths)."""
+        lens_arr = (C.c_int32 * len(lens))(*[int(v) for v in lens])
+        total = C.c_uint64()
+        if capacity_words is None:     # ask for the size first
+            code = lib.lpc_huffman_encode(self._h, _ptr(packed), lens_arr, None, 0, C.byref(total), _stream(stream))
+            if code not in (OK, ESHAPE):
+                raise LpcError(code, "lpc_huffman_encode")
+            capacity_words = (total.value + 31) // 32
+        out = torch.empty(max(int(capacity_words), 1), dtype=torch.int32, device=self.device)
+        _chk(lib.lpc_huffman_encode(self._h, _ptr(packed), lens_arr, _ptr(out), int(capacity_words), C.byref(total),
+                                    _stream(stream)), "lpc_huffman_encode")
+        return out[:(total.value + 31) // 32], int(total.value)
 
     def code_histogram(self, packed, counts=None, stream=None):
         """packed: one message (W uint32 words on the device) -> 2^bits int64 counts on the device."""

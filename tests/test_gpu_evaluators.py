@@ -1,5 +1,6 @@
-"""GPU parity for the evaluators: gradient mapping (Sec. 3.3) and the code histogram behind the
-entropy-coded message size (Sec. 6.1).  Histograms are integer work: bit-exact."""
+"""GPU parity for the evaluators: gradient mapping (Sec. 3.3), traces of the scale factor and clip count, the
+clip-value sweep, and the entropy coding of a message (Sec. 6.1): histogram, size and the stream itself.
+Integer work (histograms, streams) is bit-exact."""
 import numpy as np
 import pytest
 
@@ -123,6 +124,30 @@ def test_traced_epoch_matches_plain_epoch_and_the_oracle_trace(name, over, cfg_o
     ctx.close()
 
 
+def test_traced_epoch_reports_entropy_coded_message_sizes():
+    sp = lpc_synth.make("c2", n=2048, d=1000, N=4, B=16)
+    over = dict(m=6, bits=4, clip_mode=0, clip=0.8)
+    from _common import oracle_config
+    p, _keep = oracle_problem(sp)
+    w_o = sp.w0.copy()
+    _d, _n, coded_o = lpco.epoch_traced(p, oracle_config(sp, **over), w_o, 0, coded=True)
+    ctx = gpu_context(sp, **over)
+    w_plain, w = to_dev(sp.w0), to_dev(sp.w0)
+    ctx.epoch(w_plain, 0)
+    _dtr, _ntr, coded = ctx.epoch_traced(w, 0, coded=True)
+    import torch
+    assert torch.equal(w, w_plain)
+    coded = np.array(coded, np.int64)
+    assert np.all(coded[0] == sp.d)                       # zero message: one symbol, one bit per coordinate
+    # later messages differ from the oracle's in the few codes that float rounding of u can flip
+    assert np.all(np.abs(coded - coded_o.astype(np.int64)) <= 0.005 * coded_o.astype(np.int64) + 2)
+    ctx.close()
+    ctx = gpu_context(sp, m=2, bits=32)
+    _dtr, _ntr, coded = ctx.epoch_traced(to_dev(sp.w0), 0, coded=True)
+    assert np.all(np.array(coded) == 32 * sp.d)
+    ctx.close()
+
+
 def test_traced_epoch_on_csr_data_and_with_quantization_off():
     sp = lpc_synth.make("c3", n=8192, d=40_000, nnz_mean=12, N=4, B=32)
     over = dict(m=5, bits=2, clip_mode=0, clip=0.9)
@@ -182,4 +207,71 @@ def test_clip_sweep_rejects_bad_candidates():
     ctx = gpu_context(sp, bits=32)
     with pytest.raises(Exception):
         ctx.clip_sweep(to_dev(sp.w0), [0.5], epochs=1)
+    ctx.close()
+
+
+# ---------------------------------------------------------------- the entropy-coded stream (bit-exact)
+
+def _quantized_message(d, bits, clip, seed):
+    """One worker's packed message on both sides (the quantizer itself is covered elsewhere)."""
+    import torch
+    sp = lpc_synth.make("c1", n=64, d=d, N=1, B=1, bits=bits, seed=seed)
+    ctx = gpu_context(sp, bits=bits, clip_mode=lpco.CLIP_LAMBDA, clip=clip, m=1)
+    U = lpc_synth.gaussian_u(1, d, seed=seed + d)
+    po, _do, _co, _rc = lpco.quantize_clip(U, d, bits, lpco.CLIP_LAMBDA, clip, seed=seed, epoch=0, iter_=3)
+    packed = torch.empty(1, ctx.W, dtype=torch.int32, device="cuda")
+    delta = torch.empty(1, dtype=torch.float32, device="cuda")
+    stats = torch.zeros(1, 4, dtype=torch.float64, device="cuda")
+    dU = to_dev(U)
+    ctx.vector_stats(dU, 1, stats)
+    ctx.quantize_clip(dU, stats, None, 0, 3, packed, delta, None)
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), po)
+    return ctx, packed[0], po[0]
+
+
+@pytest.mark.parametrize("d,bits,clip", [(1, 2, 1.0), (31, 3, 1.0), (32, 4, 0.5), (1000, 2, 1.0), (4097, 4, 0.6),
+                                          (70_001, 8, 1.0), (300_000, 3, 0.3), (20_000, 12, 1.0)])
+def test_entropy_coded_stream_bit_exact_and_decodable(d, bits, clip):
+    from paper_1901_08924_amd import lpc
+    ctx, packed, po = _quantized_message(d, bits, clip, seed=5)
+    ref_counts = lpco.code_histogram(po, d, bits)
+    ref_bits, ref_lens = lpco.huffman_bits(ref_counts)
+    # (1) the same lengths on both sides: the streams agree word for word
+    ref_stream, ref_total = lpco.huffman_encode(po, d, bits, ref_lens)
+    got, total = ctx.huffman_encode(packed, ref_lens)
+    assert total == ref_total == ref_bits
+    assert np.array_equal(got.cpu().numpy().view(np.uint32), ref_stream)
+    # (2) the library's own chain, histogram -> lengths -> stream: optimal size, and the oracle's decoder
+    #     recovers every code from it
+    counts = ctx.code_histogram(packed).cpu().numpy().astype(np.uint64)
+    own_bits, own_lens = lpc.huffman_bits(counts)
+    got2, total2 = ctx.huffman_encode(packed, own_lens)
+    assert total2 == own_bits == ref_bits
+    codes = lpco.unpack(po, d, bits)
+    assert np.array_equal(lpco.huffman_decode(got2.cpu().numpy().view(np.uint32), total2, d, bits,
+                                              np.array(own_lens, np.int32)), codes)
+    ctx.close()
+
+
+def test_entropy_coder_errors_and_size_query():
+    import ctypes as C
+    from paper_1901_08924_amd import lpc
+    ctx, packed, po = _quantized_message(500, 2, 1.0, seed=9)
+    counts = lpco.code_histogram(po, 500, 2)
+    _bits, lens = lpco.huffman_bits(counts)
+    total = C.c_uint64()
+    arr = (C.c_int32 * 4)(*[int(v) for v in lens])
+    # capacity 0: size only
+    rc = lpc.lib.lpc_huffman_encode(ctx._h, packed.data_ptr(), arr, None, 0, C.byref(total), None)
+    assert rc == lpc.ESHAPE and total.value == _bits
+    bad = (C.c_int32 * 4)(1, 1, 1, 1)                       # Kraft sum 2: no prefix code
+    assert lpc.lib.lpc_huffman_encode(ctx._h, packed.data_ptr(), bad, None, 0, C.byref(total), None) == lpc.EINVAL
+    too_long = (C.c_int32 * 4)(33, 1, 2, 3)
+    assert lpc.lib.lpc_huffman_encode(ctx._h, packed.data_ptr(), too_long, None, 0, C.byref(total), None) == lpc.EINVAL
+    used = np.flatnonzero(counts)
+    if used.size >= 2:
+        drop = [int(v) for v in lens]
+        drop[int(used[0])] = 0                                # a symbol that occurs gets no codeword
+        miss = (C.c_int32 * 4)(*drop)
+        assert lpc.lib.lpc_huffman_encode(ctx._h, packed.data_ptr(), miss, None, 0, C.byref(total), None) == lpc.EINVAL
     ctx.close()

@@ -112,3 +112,59 @@ def test_code_histogram_and_entropy_coded_message_size():
     assert counts.sum() == d and np.array_equal(counts, np.bincount(codes + 8, minlength=16))
     hb, _ = lpco.huffman_bits(counts)
     assert hb < bits * d and hb >= d
+
+
+# ---------------------------------------------------------------- the entropy-coded stream itself
+
+def _bitstring(stream, total):
+    return "".join(str((int(stream[p >> 5]) >> (p & 31)) & 1) for p in range(total))
+
+
+def test_stream_of_a_small_message_written_out_by_hand():
+    # b = 2: bins 0..3 are the codes -2, -1, 0, 1.  Lengths (3, 2, 1, 3): ordered by (length, bin) the canonical
+    # codewords are bin 2 -> "0", bin 1 -> "10", bin 0 -> "110", bin 3 -> "111".
+    lens = np.array([3, 2, 1, 3], np.int32)
+    codes = np.array([0, 0, -1, 1, 0, -2, -1, 0], np.int32)
+    words = lpco.pack(codes, 2)
+    stream, total = lpco.huffman_encode(words, len(codes), 2, lens)
+    assert _bitstring(stream, total) == "0" + "0" + "10" + "111" + "0" + "110" + "10" + "0"
+    assert total == 14 and stream.size == 1
+    # the stream's first bit is bit 0 of word 0: "00101110110100" read from the low end
+    assert int(stream[0]) == int("00101110110100"[::-1], 2)
+    assert np.array_equal(lpco.huffman_decode(stream, total, len(codes), 2, lens), codes)
+
+
+@pytest.mark.parametrize("bits,d,scale", [(2, 1000, 0.5), (4, 4097, 1.0), (8, 3000, 3.0), (3, 31, 0.1)])
+def test_stream_round_trip_and_size(bits, d, scale):
+    rng = np.random.default_rng(bits * 100 + d)
+    half = 1 << (bits - 1)
+    codes = np.clip(np.rint(scale * rng.standard_normal(d)), -half, half - 1).astype(np.int32)
+    words = lpco.pack(codes, bits)
+    counts = lpco.code_histogram(words, d, bits)
+    size, lens = lpco.huffman_bits(counts)
+    stream, total = lpco.huffman_encode(words, d, bits, lens)
+    assert total == size == int((counts * lens.astype(np.uint64)).sum())
+    assert stream.size == (total + 31) // 32
+    assert np.array_equal(lpco.huffman_decode(stream, total, d, bits, lens), codes)
+    # no codeword is a prefix of another (checked on the bit strings themselves)
+    used = np.flatnonzero(lens)
+    book = {}
+    for k in used:
+        one = lpco.pack(np.array([k - half], np.int32), bits)
+        s, t = lpco.huffman_encode(one, 1, bits, lens)
+        book[int(k)] = _bitstring(s, t)
+        assert t == lens[k]
+    words_sorted = sorted(book.values())
+    for a, b in zip(words_sorted, words_sorted[1:]):
+        assert not b.startswith(a)
+
+
+def test_stream_rejects_lengths_that_are_no_prefix_code_and_unused_symbols():
+    codes = np.array([0, 1, -1, 0], np.int32)
+    words = lpco.pack(codes, 2)
+    with pytest.raises(Exception):
+        lpco.huffman_encode(words, 4, 2, np.array([1, 1, 1, 0], np.int32), capacity_words=4)   # Kraft sum 3/2
+    with pytest.raises(Exception):
+        lpco.huffman_encode(words, 4, 2, np.array([0, 1, 2, 0], np.int32), capacity_words=4)   # code 1 has no codeword
+    with pytest.raises(Exception):
+        lpco.huffman_encode(words, 4, 2, np.array([0, 2, 1, 2], np.int32), capacity_words=0)   # does not fit

@@ -335,3 +335,30 @@ def test_trace_is_zero_with_quantization_off():
     w = sp.w0.copy()
     dtr, ntr = lpco.epoch_traced(p, _config_from(sp, m=3, bits=32), w, 0)
     assert np.all(dtr == 0.0) and np.all(ntr == 0)
+
+
+def test_entropy_coded_sizes_in_the_trace():
+    sp = lpc_synth.make("c2", n=512, d=200, N=3, B=8)
+    p, _k = _problem_from(sp)
+    w = sp.w0.copy()
+    cfg = _config_from(sp, m=5, bits=4, clip_mode=lpco.CLIP_LAMBDA, clip=1.0)
+    _d, _n, coded = lpco.epoch_traced(p, cfg, w, 0, coded=True)
+    # the zero message of t = 0 uses one symbol: a lone symbol costs one bit per coordinate
+    assert np.all(coded[0] == sp.d)
+    # any prefix code spends at least one bit per coordinate and an optimal one no more than the fixed b bits
+    assert np.all(coded[1:] >= sp.d) and np.all(coded[1:] <= 4 * sp.d)
+    # the rows are the sizes lpco.huffman_bits gives for the messages an identical epoch produces step by step
+    w2 = sp.w0.copy()
+    mu, _, _ = lpco.full_grad(p, w2)
+    x = w2.copy()
+    for t in range(2):
+        U, stats = lpco.worker_vr_grad(p, cfg, x, w2, 0, t)
+        packed, delta, _c, _r = lpco.quantize_clip(U, sp.d, 4, lpco.CLIP_LAMBDA, 1.0, seed=sp.seed, epoch=0, iter_=t,
+                                                   stats=stats)
+        for i in range(3):
+            size, _lens = lpco.huffman_bits(lpco.code_histogram(packed[i], sp.d, 4))
+            assert coded[t, i] == size
+        x = lpco.prox_step(x, lpco.dequantize_avg(packed, delta, sp.d, 4), mu, sp.eta, sp.lambda1, sp.lambda2)
+    w3 = sp.w0.copy()
+    _d, _n, coded32 = lpco.epoch_traced(p, _config_from(sp, m=2, bits=32), w3, 0, coded=True)
+    assert np.all(coded32 == 32 * sp.d)
