@@ -80,6 +80,63 @@ __device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float
   }
 }
 
+// Epilogue of one output tile: C (+)= alpha*acc (+ bias, ReLU, ReLU mask), and the statistics of the stored
+// values (per thread in fp32 -- at most 64 terms --, in fp64 across threads).
+// Accumulator layout of the 32x32 MFMA: lane l holds column (l % 32); register v holds row
+// 8*(v/4) + 4*(l/32) + (v%4).
+template <int TN>
+__device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&acc)[2][TN / 64], int m0, int n0,
+                                           int64_t bz, int lane, int wm, int wn, float &fmx, float &ssum, float &ssq,
+                                           float &sbad) {
+  constexpr int NJ = TN / 64;
+  float *C = g.C + bz * g.strideC;
+  const float *mask = g.relu_mask ? g.relu_mask + bz * g.strideC : nullptr;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int col = n0 + wn + 32 * j + (lane & 31);
+      if (col >= g.N) continue;
+      const float bias = g.bias ? g.bias[bz * g.strideBias + col] : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        const int64_t off = (int64_t)row * g.ldc + col;
+        float val = g.alpha * acc[i][j][v] + bias;
+        if (g.relu) val = val > 0.0f ? val : 0.0f;
+        if (mask) val = mask[off] > 0.0f ? val : 0.0f;
+        if (g.accumulate) val += C[off];
+        C[off] = val;
+        if (g.stat_part) {  // uniform
+          if (isfinite(val)) {
+            fmx = fmaxf(fmx, fabsf(val)); ssum += val; ssq = fmaf(val, val, ssq);
+          } else {
+            sbad += 1.0f;
+          }
+        }
+      }
+    }
+  }
+}
+
+// The tile's statistics: wavefront reductions, then the wavefronts in order through `red` (LDS, 4 doubles per
+// wavefront, not in use by anyone else); slot `tile` of batch item bz receives them.  Contains a barrier.
+__device__ __forceinline__ void tile_statistics(const GemmArgs &g, double *red, int tid, int64_t bz, int64_t tile,
+                                                float fmx, float ssum, float ssq, float sbad) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const double a_w = (double)wave_max(fmx), s_w = wave_sum((double)ssum), q_w = wave_sum((double)ssq),
+               b_w = wave_sum((double)sbad);
+  if (lane == 0) { red[wave * 4 + 0] = a_w; red[wave * 4 + 1] = s_w; red[wave * 4 + 2] = q_w; red[wave * 4 + 3] = b_w; }
+  __syncthreads();
+  if (tid == 0) {
+    double a_t = 0.0, s_t = 0.0, q_t = 0.0, b_t = 0.0;
+    for (int k = 0; k < 4; ++k) { a_t = fmax(a_t, red[k * 4]); s_t += red[k * 4 + 1]; q_t += red[k * 4 + 2]; b_t += red[k * 4 + 3]; }
+    double *p = g.stat_part + bz * g.stat_batch_stride + ((int64_t)g.stat_slot0 + tile) * 4;
+    p[0] = a_t; p[1] = s_t; p[2] = q_t; p[3] = b_t;
+  }
+}
+
 // TN = 128: 128x128 tile, each wavefront 64x64 (2x2 MFMA tiles).  TN = 64: 128x64 tile, each wavefront
 // 64x32 (2x1) -- twice as many workgroups for outputs too small to fill the chip with 128x128 tiles.
 template <bool TA, bool TB, int TN, bool FULL>
@@ -159,55 +216,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #undef LPC_GEMM_STEP
   }
 
-  // Accumulator layout of the 32x32 MFMA: lane l holds column (l % 32); register v holds row
-  // 8*(v/4) + 4*(l/32) + (v%4).
-  float *C = g.C + bz * g.strideC;
-  const float *mask = g.relu_mask ? g.relu_mask + bz * g.strideC : nullptr;
-  // statistics of the stored values: per thread in fp32 (at most 64 terms), in fp64 across threads
   float fmx = 0.0f, ssum = 0.0f, ssq = 0.0f, sbad = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int col = n0 + wn + 32 * j + (lane & 31);
-      if (col >= g.N) continue;
-      const float bias = g.bias ? g.bias[bz * g.strideBias + col] : 0.0f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row >= g.M) continue;
-        const int64_t off = (int64_t)row * g.ldc + col;
-        float val = g.alpha * acc[i][j][v] + bias;
-        if (g.relu) val = val > 0.0f ? val : 0.0f;
-        if (mask) val = mask[off] > 0.0f ? val : 0.0f;
-        if (g.accumulate) val += C[off];
-        C[off] = val;
-        if (g.stat_part) {  // uniform
-          if (isfinite(val)) {
-            fmx = fmaxf(fmx, fabsf(val)); ssum += val; ssq = fmaf(val, val, ssq);
-          } else {
-            sbad += 1.0f;
-          }
-        }
-      }
-    }
-  }
-  if (g.stat_part) {
-    // the tile's statistics: wavefront reductions, then the four wavefronts in order (LDS is free: the K loop
-    // ended with a barrier)
-    double *red = reinterpret_cast<double *>(&As[0][0][0]);
-    const double a_w = (double)wave_max(fmx), s_w = wave_sum((double)ssum), q_w = wave_sum((double)ssq),
-                 b_w = wave_sum((double)sbad);
-    if (lane == 0) { red[wave * 4 + 0] = a_w; red[wave * 4 + 1] = s_w; red[wave * 4 + 2] = q_w; red[wave * 4 + 3] = b_w; }
-    __syncthreads();
-    if (tid == 0) {
-      double a_t = 0.0, s_t = 0.0, q_t = 0.0, b_t = 0.0;
-      for (int k = 0; k < 4; ++k) { a_t = fmax(a_t, red[k * 4]); s_t += red[k * 4 + 1]; q_t += red[k * 4 + 2]; b_t += red[k * 4 + 3]; }
-      double *p = g.stat_part + bz * g.stat_batch_stride +
-                  ((int64_t)g.stat_slot0 + (int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4;
-      p[0] = a_t; p[1] = s_t; p[2] = q_t; p[3] = b_t;
-    }
-  }
+  store_tile<TN>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  // LDS is free for the statistics: the K loop ended with a barrier
+  if (g.stat_part)
+    tile_statistics(g, reinterpret_cast<double *>(&As[0][0][0]), tid, bz,
+                    (int64_t)blockIdx.y * gridDim.x + blockIdx.x, fmx, ssum, ssq, sbad);
 }
 
 // Whole 128x64 tiles with EIGHT wavefronts (one 32x32 matrix-core tile each) instead of four: for products

@@ -4,7 +4,8 @@
 // parameter vector (one scale factor per worker, Sec. 3.2 last paragraph).
 //
 // Parameter vector: layer by layer, weight matrix [in][out] row-major, then the
-// bias [out].  All contractions run on the matrix cores (lpc_gemm.hip):
+// bias [out].  The contractions run on the matrix cores (lpc_gemm.hip), except a last layer of at most 16
+// classes, which is a per-row kernel on the vector units (below):
 //   forward        H_l = relu(H_{l-1} W_l + b_l)                (rows x in) (in x out)
 //   data gradient  D_{l-1} = (D_l W_l') masked by H_{l-1} > 0   (rows x out) (out x in)
 //   weight grad    G_l = H_{l-1}' D_l                           (in x rows) (rows x out)
@@ -57,7 +58,8 @@ __global__ void softmax_delta_kernel(const float *__restrict__ logits, const flo
 // The last layer as one launch per pass: logits = a*W + b, softmax cross-entropy delta, and the delta handed
 // to the layer below, delta_prev = (a > 0) .* (delta * W').  With at most 16 classes W ([K][C]) fits LDS
 // (transposed, Wt[c][k]) and everything is a per-row computation: a wavefront takes four rows at a time, lane l
-// owns the activations k = 256*q + 4*l .. +3, the C dot products close with wavefront reductions, and the
+// owns the activations k = 256*q + 4*l .. +3, one read of a column of W serves the four rows, the C dot products
+// close with wavefront reductions, the softmax runs inside a row of 16 lanes (lane c holds class c), and the
 // activations are still in registers when delta_prev needs their signs.  blockIdx.y selects the parameter set
 // (set 1 = snapshot parameters, negated deltas).
 constexpr int kLastMaxC = 16;
