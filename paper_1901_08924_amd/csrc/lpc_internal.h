@@ -179,6 +179,7 @@ int gemm_tiles(const GemmArgs &g);                 // statistic partials a matri
 // the vector units): a chunk is cut into blocks that are summed side by side, one partial per block, and the
 // partials are folded by a second, small column sum; a lone launch over thousands of rows would occupy 1-16 CUs.
 constexpr int kSnapBlock = 256;
+constexpr int kSnapWide = 2048;  // rows per block of its weight-gradient products on the matrix cores
 // 0 if lens[0..nsym) (each in [0, 32]) are the lengths of a prefix code, and then table[k] holds symbol k's
 // canonical codeword; -1 otherwise.
 int huffman_canonical_table(const int32_t *lens, int32_t nsym, HuffEntry *table);

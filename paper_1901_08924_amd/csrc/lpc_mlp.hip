@@ -239,6 +239,29 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ D
   }
 }
 
+// out[j] (+)= alpha * (P[0][j] + P[1][j] + ... + P[nb-1][j]) for j < count, the partial vectors `stride` floats
+// apart; summed in block order.  count and the pointers are multiples of four floats / 16 bytes.
+__global__ __launch_bounds__(256) void fold_blocks_kernel(const float *__restrict__ P, int nb, int64_t stride,
+                                                          int64_t count, float alpha, int accumulate,
+                                                          float *__restrict__ out) {
+  const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (4 * q >= count) return;
+  float4 acc = *reinterpret_cast<const float4 *>(P + 4 * q);
+  for (int b0 = 1; b0 < nb; b0 += 4) {  // up to four partial vectors in flight
+    float4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      v[j] = b0 + j < nb ? *reinterpret_cast<const float4 *>(P + (int64_t)(b0 + j) * stride + 4 * q)
+                         : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { acc.x += v[j].x; acc.y += v[j].y; acc.z += v[j].z; acc.w += v[j].w; }
+  }
+  float4 *o = reinterpret_cast<float4 *>(out + 4 * q);
+  float4 r = make_float4(alpha * acc.x, alpha * acc.y, alpha * acc.z, alpha * acc.w);
+  if (accumulate) { const float4 t = *o; r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w; }
+  *o = r;
+}
+
 __global__ void sum_rows_loss_kernel(const double *__restrict__ row_loss, int rows, double scale, int accumulate,
                                      double *__restrict__ f_out) {
   __shared__ double red[4];
@@ -420,7 +443,24 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
       g.alpha = alpha; g.accumulate = acc; g.nseg = 1; g.batch = 1;
       float *part_b = c->s.mlp_part, *part_w = c->s.mlp_part + (int64_t)nb * out;
       const bool blocks = nb >= 2;
-      if (blocks && !gemm_takes_matrix_cores(g)) {
+      // A product on the matrix cores over thousands of rows has few output tiles (in*out/128^2): cut the rows
+      // into kSnapWide-row blocks whose products run side by side into the rows of U (free during this pass)
+      // and are folded afterwards, so that every CU has tiles to work on.
+      const int nw = rows / kSnapWide;
+      const int64_t cnt = (int64_t)in * out;
+      const bool wide = gemm_takes_matrix_cores(g) && nw >= 2 && rows % kSnapWide == 0 && nw <= c->cfg.N + 1 &&
+                        cnt / (128 * 128) < 2 * c->cus && cnt % 4 == 0 && c->mlp_woff[l] % 4 == 0;
+      if (wide) {
+        GemmArgs h = g;
+        h.K = kSnapWide; h.batch = nw; h.alpha = 1.0f; h.accumulate = 0;
+        h.strideA[0] = (int64_t)kSnapWide * lda; h.strideB[0] = (int64_t)kSnapWide * out;
+        h.C = c->s.U + c->mlp_woff[l]; h.strideC = c->d_pad;
+        e = launch_gemm(h, st);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(fold_blocks_kernel, dim3((unsigned)((cnt / 4 + 255) / 256)), dim3(256), 0, st,
+                           (const float *)(c->s.U + c->mlp_woff[l]), nw, c->d_pad, cnt, alpha, acc,
+                           mu + c->mlp_woff[l]);
+      } else if (blocks && !gemm_takes_matrix_cores(g)) {
         GemmArgs h = g;
         h.K = kSnapBlock; h.batch = nb; h.alpha = 1.0f; h.accumulate = 0;
         h.strideA[0] = (int64_t)kSnapBlock * lda; h.strideB[0] = (int64_t)kSnapBlock * out;
