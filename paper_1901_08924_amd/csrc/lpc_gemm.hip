@@ -4,8 +4,11 @@
 //
 // The only dense contractions of the hot path are the MLP's layer products, so
 // this is where MFMA is used: v_mfma_f32_32x32x2_f32, fp32 in, fp32 accumulate.
-// A workgroup of 4 wavefronts owns a 128x128 tile of C; each wavefront owns a
-// 64x64 quadrant = 2x2 MFMA tiles (64 accumulator registers).  The K loop runs
+// A workgroup of 4 wavefronts owns a 128x64 tile of C; each wavefront owns a
+// 64x32 part = 2x1 MFMA tiles (32 accumulator registers).  (128x128 tiles, 64
+// accumulator registers per lane, were measured no faster on any product here,
+// 4096^3 included: their 164 registers allow three workgroups per CU, not four.)
+// The K loop runs
 // in slabs of 16: the next slab is fetched from global memory into registers
 // while the current one is consumed from LDS (stored k-major so that the 32
 // lanes of an MFMA operand read consecutive words).  Operands may be given
@@ -24,7 +27,7 @@ namespace {
 #ifndef LPC_GEMM_BK
 #define LPC_GEMM_BK 16
 #endif
-constexpr int BM = 128, BK = LPC_GEMM_BK;
+constexpr int BM = 128, BN = 64, BK = LPC_GEMM_BK;
 constexpr int LDT = BM + 4;  // LDS row pitch (floats)
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -137,8 +140,7 @@ __device__ __forceinline__ void tile_statistics(const GemmArgs &g, double *red, 
   }
 }
 
-// TN = 128: 128x128 tile, each wavefront 64x64 (2x2 MFMA tiles).  TN = 64: 128x64 tile, each wavefront
-// 64x32 (2x1) -- twice as many workgroups for outputs too small to fill the chip with 128x128 tiles.
+// TN = 64: 128x64 tile, each wavefront 64x32 (2x1 MFMA tiles); the code is also valid for TN = 128 (2x2).
 template <bool TA, bool TB, int TN, bool FULL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int NJ = TN / 64;
@@ -479,18 +481,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_tn_kernel(GemmArgs g, int kc)
 
 }  // namespace
 
-namespace {
-bool gemm_narrow(const GemmArgs &g) {
-  const int64_t tiles128 = (int64_t)((g.N + 127) / 128) * ((g.M + BM - 1) / BM) * g.batch;
-  return tiles128 < 512 || g.N <= 64;  // fewer than two 128x128 tiles per CU: halve the tile
-}
-}  // namespace
-
 bool gemm_takes_matrix_cores(const GemmArgs &g) { return !(g.N <= kSkinnyN && !g.transB && g.M >= 64); }
 
 int gemm_tiles(const GemmArgs &g) {
-  const int tn = gemm_narrow(g) ? 64 : 128;
-  return ((g.N + tn - 1) / tn) * ((g.M + BM - 1) / BM);
+  return ((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
 }
 
 // Validates shapes on the host (every access in the kernel is guarded by M, N, K).
@@ -513,22 +507,18 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
     }
     return hipGetLastError();
   }
-  const bool narrow = gemm_narrow(g);
-  const int tn = narrow ? 64 : 128;
+  constexpr int tn = BN;
   const dim3 grid((unsigned)((g.N + tn - 1) / tn), (unsigned)((g.M + BM - 1) / BM), (unsigned)g.batch);
   // whole tiles and slabs, 16-byte aligned rows: the branch-free fetch
   bool full = g.M % BM == 0 && g.N % tn == 0 && g.K % BK == 0;
   for (int s = 0; s < g.nseg; ++s)
     full = full && g.lda[s] % 4 == 0 && g.ldb[s] % 4 == 0 && ((uintptr_t)g.A[s] & 15u) == 0 &&
            ((uintptr_t)g.B[s] & 15u) == 0 && g.strideA[s] % 4 == 0 && g.strideB[s] % 4 == 0;
-#define LPC_GEMM_LAUNCH2(TA_, TB_, FULL_)                                                                  \
-  do {                                                                                                     \
-    if (narrow) hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 64, FULL_>), grid, dim3(256), 0, st, g);     \
-    else hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, 128, FULL_>), grid, dim3(256), 0, st, g);           \
-  } while (0)
-  // at most one whole narrow tile per CU: eight wavefronts per tile (measured: 6-30 % faster there, no gain
+#define LPC_GEMM_LAUNCH2(TA_, TB_, FULL_) \
+  hipLaunchKernelGGL((gemm_mfma_kernel<TA_, TB_, BN, FULL_>), grid, dim3(256), 0, st, g)
+  // at most one whole tile per CU: eight wavefronts per tile (measured: 6-30 % faster there, no gain
   // once two four-wavefront workgroups share a CU)
-  const bool eight = full && narrow && (int64_t)grid.x * grid.y * grid.z <= 256 && !g.stat_part;
+  const bool eight = full && (int64_t)grid.x * grid.y * grid.z <= 256 && !g.stat_part;
 #define LPC_GEMM_LAUNCH(TA_, TB_)                                                                   \
   do {                                                                                              \
     if (eight) hipLaunchKernelGGL((gemm_mfma8_kernel<TA_, TB_>), grid, dim3(512), 0, st, g);        \
