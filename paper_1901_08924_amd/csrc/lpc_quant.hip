@@ -269,47 +269,60 @@ __global__ void prepare_qparams_kernel(const double *stats, const float *delta_i
   n_clipped[v] = 0u;
 }
 
-// Quantize the 32 coordinates of segment `seg` of one worker's vector (Sec. 3.2 rules (1), (2) with the
-// scale of eq. (3)) and store its B packed words at dst.  load4(k) returns coordinates 4k..4k+3.  Returns
-// the number of coordinates outside dom(delta, b).  All arithmetic is fp32 without contraction:
+// Sec. 3.2 rules (1), (2) with the scale of eq. (3) for four consecutive coordinates 4*block .. 4*block+3 of
+// one worker's vector (they share one Philox block): code[t] receives the integer codes; returns the number
+// of coordinates outside dom(delta, b).  All arithmetic is fp32 without contraction:
 //   s = u*(1/delta), clamp to [-2^(b-1), 2^(b-1)-1], lo = floor(s), frac = s - lo (exact),
-//   U = (word >> 8)*2^-24 from the Philox block of the coordinate's group of four, code = lo + (U < frac).
+//   U = (word >> 8)*2^-24, code = lo + (U < frac).
+template <int B>
+__device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams &q, const StreamKey &key,
+                                                  uint32_t worker, uint32_t block, int32_t (&code)[4]) {
+  const float hi = (float)((1 << (B - 1)) - 1);
+  const float lo = -(float)(1 << (B - 1));
+  const bool count = q.delta > 0.0f;
+  uint32_t clipped = 0;
+  const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
+  float base[4], frac[4];
+  bool any = false;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    float s = vals[t] * q.rdelta;        // position on the grid
+    s = fminf(fmaxf(s, lo), hi);         // rule (2): project onto the hull
+    base[t] = floorf(s);
+    frac[t] = s - base[t];               // exact
+    any = any || (frac[t] != 0.0f);
+    if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
+  }
+  uint32_t rnd[4] = {0u, 0u, 0u, 0u};
+  if (any) {  // on-grid values (zeros in particular) need no random draw
+    const Philox4 blk = stream_block(key, kTagQuant, worker, block);
+    rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
+    code[t] = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
+  }
+  return clipped;
+}
+
+// Quantize the 32 coordinates of segment `seg` of one worker's vector and store its B packed words at dst.
+// load4(k) returns coordinates 4k..4k+3.  Returns the number of coordinates outside dom(delta, b).
 template <int B, class Load4>
 __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams &q, const StreamKey &key,
                                                      uint32_t worker, int64_t seg, uint32_t *__restrict__ dst) {
-  const float hi = (float)((1 << (B - 1)) - 1);
-  const float lo = -(float)(1 << (B - 1));
   constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
-  const bool count = q.delta > 0.0f;
   uint32_t clipped = 0;
   uint32_t words[B];
   uint64_t bitbuf = 0;
   int nb = 0, wi = 0;
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
-    const float4 v4 = load4(k);
-    const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
-    float base[4], frac[4];
-    bool any = false;
+    int32_t code[4];
+    clipped += quantize_four<B>(load4(k), q, key, worker, (uint32_t)(seg * 8 + k), code);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      float s = vals[t] * q.rdelta;        // position on the grid
-      s = fminf(fmaxf(s, lo), hi);         // rule (2): project onto the hull
-      base[t] = floorf(s);
-      frac[t] = s - base[t];               // exact
-      any = any || (frac[t] != 0.0f);
-      if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
-    }
-    uint32_t rnd[4] = {0u, 0u, 0u, 0u};
-    if (any) {  // on-grid values (zeros in particular) need no random draw
-      const Philox4 blk = stream_block(key, kTagQuant, worker, (uint32_t)(seg * 8 + k));
-      rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
-    }
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
-      const int32_t code = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
-      bitbuf |= (uint64_t)((uint32_t)code & mask) << nb;
+      bitbuf |= (uint64_t)((uint32_t)code[t] & mask) << nb;
       nb += B;
       if (nb >= 32) {
         words[wi++] = (uint32_t)bitbuf;
@@ -330,6 +343,24 @@ __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams 
     for (int i = 0; i < B; ++i) dst[i] = words[i];
   }
   return clipped;
+}
+
+// Word w (of B) of a segment's message from its 32 codes: stream bits [32w, 32w+32), code c at bits [cB, cB+B).
+template <int B>
+__device__ __forceinline__ uint32_t assemble_word(const int32_t *__restrict__ codes, int w) {
+  constexpr uint32_t mask = (1u << B) - 1u;
+  const int bit0 = 32 * w, c0 = bit0 / B;
+  uint32_t word = 0u;
+#pragma unroll
+  for (int t = 0; t < 32 / B + 2; ++t) {
+    const int c = c0 + t;
+    if (c < 32 && c * B < bit0 + 32) {
+      const uint32_t field = (uint32_t)codes[c] & mask;
+      const int sh = c * B - bit0;
+      word |= sh >= 0 ? (field << sh) : (field >> (-sh));
+    }
+  }
+  return word;
 }
 
 // ---------------------------------------------------------------------------
@@ -559,14 +590,15 @@ __device__ __forceinline__ bool segment_marked(const uint32_t *bm, int64_t seg) 
 constexpr int kWaveWords = 32;
 constexpr int kWaveSegs = kWaveWords * 32;
 
+template <int WORDS = kWaveWords>
 __device__ __forceinline__ int32_t compact_marked(const uint32_t *__restrict__ bm, int64_t bitmap_words,
                                                   int64_t first_word, int64_t stride, int64_t total_segs, int lane,
                                                   int32_t *__restrict__ list) {
   const int64_t wi = first_word + lane * stride;
-  const uint32_t word = (lane < kWaveWords && wi < bitmap_words) ? bm[wi] : 0u;
+  const uint32_t word = (lane < WORDS && wi < bitmap_words) ? bm[wi] : 0u;
   int32_t n = 0;
 #pragma unroll 4
-  for (int c = 0; c < kWaveWords / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
+  for (int c = 0; c < WORDS / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
     const int k = 2 * c + (lane >> 5);
     const uint32_t w = __shfl(word, k, 64);
     const int64_t seg = (first_word + k * stride) * 32 + (lane & 31);
@@ -641,37 +673,56 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
 }
 
 // eq. (3) + quantize + pack over the visited segments; a marked tail segment of U is set back to zero for the
-// next iteration.  Every workgroup folds its worker's statistic partials itself (the fixed order of
-// fold_stat_slots, so all of them derive the same scale); workgroup 0 of a worker records the results.
-// Workgroup 0 of a worker takes the head (one dense tile, transposed through LDS like the dense quantizer);
-// in the others every wavefront visits the marked ones of its kWaveSegs tail segments.
+// next iteration.  The launch is bound by latency, not throughput, so the work is spread thin: EIGHT lanes
+// share a segment (four coordinates = one Philox block each), the 32 codes of a segment meet in LDS and the
+// B words are assembled from there.  Workgroups [0, head/1024) of a worker take 32 head segments each; in
+// the others every wavefront visits the marked ones of its kQuantSegs tail segments, up to 32 at a time.
+// Every workgroup folds its worker's statistic partials itself (the fixed order of fold_stat_slots, so all of
+// them derive the same scale); workgroup 0 of a worker records the results.
+constexpr int kQuantWords = 8;                  // bitmap words per wavefront
+constexpr int kQuantSegs = kQuantWords * 32;
+
 template <int B>
 __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a, StatSinks sk, QuantSpec qs,
                                                                    int32_t nslots, int64_t d, StreamKey key,
                                                                    uint32_t *__restrict__ packed,
                                                                    float *__restrict__ delta_out) {
-  // the head workgroup uses the whole tile; a tail wavefront uses its quarter (64 segments) and its list
-  __shared__ __attribute__((aligned(16))) float tile[kThreads * kPitch];
-  __shared__ int32_t lists[4][kWaveSegs];
+  __shared__ int32_t codes[4][32][32];  // per wavefront: 32 segments x 32 codes
+  __shared__ int32_t lists[4][kQuantSegs];
   __shared__ QParams q_sh;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int sub = lane >> 3, part = lane & 7;  // this lane moves coordinates 4*part..+3 of segment slot `sub` (+8q)
   const uint32_t worker = blockIdx.y;
-  const bool head = blockIdx.x == 0;
+  const int32_t head_wgs = a.head / (32 * kSegFloats);
+  const bool head = (int32_t)blockIdx.x < head_wgs;
   float *urow = a.U + (int64_t)worker * a.d_pad;
+  uint32_t *out = packed + (int64_t)worker * a.W;
   int32_t *list = lists[wv];
   int32_t n = 0;
-  if (head) {
+  float4 v[4];
+  // a batch = up to 32 listed segments of this wavefront: slot 8q + sub for q < 4; the tail's are zeroed as read
+  auto load_batch = [&](int32_t i0) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int e = r * kThreads + tid;
-      *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) =
-          *reinterpret_cast<const float4 *>(urow + (int64_t)e * 4);
+    for (int q = 0; q < 4; ++q) {
+      const int32_t i = i0 + 8 * q + sub;
+      v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < n) {
+        float *u = urow + (int64_t)list[i] * kSegFloats + part * 4;
+        v[q] = *reinterpret_cast<const float4 *>(u);
+        *reinterpret_cast<float4 *>(u) = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
+  };
+  const int64_t head_seg = (int64_t)blockIdx.x * 32 + wv * 8 + sub;  // head: one segment per eight lanes
+  if (head) {
+    v[0] = *reinterpret_cast<const float4 *>(urow + head_seg * kSegFloats + part * 4);
   } else {
-    const int64_t stride = (int64_t)(gridDim.x - 1) * 4;  // tail wavefronts of this worker
-    const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - 1) * 4 + wv;
-    n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
-                       a.d_pad / kSegFloats, lane, list);
+    const int64_t stride = (int64_t)(gridDim.x - head_wgs) * 4;  // tail wavefronts of this worker
+    const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - head_wgs) * 4 + wv;
+    n = compact_marked<kQuantWords>(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
+                                    a.d_pad / kSegFloats, lane, list);
+    __builtin_amdgcn_wave_barrier();
+    load_batch(0);  // on its way while the statistics are folded
   }
   if (tid < 64) {
     double amax, sum, sumsq, bad;
@@ -692,28 +743,29 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
   const QParams q = q_sh;
   uint32_t clipped = 0;
   if (head) {
-    const float *mine = &tile[tid * kPitch];
-    clipped = quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key, worker,
-                                  (int64_t)tid, packed + (int64_t)worker * a.W + (int64_t)tid * B);
+    int32_t code[4];
+    clipped = quantize_four<B>(v[0], q, key, worker, (uint32_t)(head_seg * 8 + part), code);
+    *reinterpret_cast<int4 *>(&codes[wv][sub][4 * part]) = make_int4(code[0], code[1], code[2], code[3]);
+    __builtin_amdgcn_wave_barrier();
+    const int64_t seg0 = (int64_t)blockIdx.x * 32 + wv * 8;  // the wavefront's eight segments are consecutive
+    for (int t = lane; t < 8 * B; t += 64) out[seg0 * B + t] = assemble_word<B>(codes[wv][t / B], t % B);
   } else {
-    float *wtile = tile + wv * 64 * kPitch;
-    for (int32_t i0 = 0; i0 < n; i0 += 64) {
-      // 64 segments per step: eight lanes move one segment in and, zeroed, back out
+    for (int32_t i0 = 0; i0 < n; i0 += 32) {
+      if (i0 > 0) load_batch(i0);
 #pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int32_t local = r * 8 + (lane >> 3);
-        if (i0 + local < n) {
-          float *u = urow + (int64_t)list[i0 + local] * kSegFloats + (lane & 7) * 4;
-          *reinterpret_cast<float4 *>(&wtile[local * kPitch + (lane & 7) * 4]) = *reinterpret_cast<const float4 *>(u);
-          *reinterpret_cast<float4 *>(u) = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int qi = 0; qi < 4; ++qi) {
+        const int32_t i = i0 + 8 * qi + sub;
+        if (i < n) {
+          int32_t code[4];
+          clipped += quantize_four<B>(v[qi], q, key, worker, (uint32_t)list[i] * 8u + (uint32_t)part, code);
+          *reinterpret_cast<int4 *>(&codes[wv][8 * qi + sub][4 * part]) = make_int4(code[0], code[1], code[2], code[3]);
         }
       }
       __builtin_amdgcn_wave_barrier();
-      if (i0 + lane < n) {
-        const int64_t seg = list[i0 + lane];
-        const float *mine = &wtile[lane * kPitch];
-        clipped += quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key,
-                                       worker, seg, packed + (int64_t)worker * a.W + seg * B);
+      const int32_t cnt = n - i0 < 32 ? n - i0 : 32;
+      for (int t = lane; t < cnt * B; t += 64) {
+        const int sl = t / B, w = t % B;
+        out[(int64_t)list[i0 + sl] * B + w] = assemble_word<B>(codes[wv][sl], w);
       }
       __builtin_amdgcn_wave_barrier();
     }
@@ -1255,7 +1307,10 @@ hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st) {
 }
 
 hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st) {
-  const dim3 grid((unsigned)(1 + sparse_tail_wgs(c)), (unsigned)c->cfg.N);
+  // 32 head segments per workgroup; kQuantSegs tail segments per wavefront, four wavefronts per workgroup
+  const int64_t tail_words = c->bitmap_words - c->sparse_head / (kSegFloats * 32);
+  const int64_t tail_wgs = (tail_words + 4 * kQuantWords - 1) / (4 * kQuantWords);
+  const dim3 grid((unsigned)(c->sparse_head / (32 * kSegFloats) + (tail_wgs > 0 ? tail_wgs : 1)), (unsigned)c->cfg.N);
   const int32_t slots = sparse_stat_slots(c);
 #define CALL(BITS)                                                                                             \
   hipLaunchKernelGGL(sparse_quantize_kernel<BITS>, grid, dim3(kThreads), 0, st, sparse_args_of(c), sinks_of(c, nullptr), \
