@@ -587,18 +587,17 @@ __device__ __forceinline__ bool segment_marked(const uint32_t *bm, int64_t seg) 
 // returns their number.
 // A segment is one 128-byte line: it is always moved by eight adjacent lanes with 16 bytes each (one request
 // per line); a lane that walks a line of its own costs a request per 16 bytes.
-constexpr int kWaveWords = 32;
+constexpr int kWaveWords = 8;
 constexpr int kWaveSegs = kWaveWords * 32;
 
-template <int WORDS = kWaveWords>
 __device__ __forceinline__ int32_t compact_marked(const uint32_t *__restrict__ bm, int64_t bitmap_words,
                                                   int64_t first_word, int64_t stride, int64_t total_segs, int lane,
                                                   int32_t *__restrict__ list) {
   const int64_t wi = first_word + lane * stride;
-  const uint32_t word = (lane < WORDS && wi < bitmap_words) ? bm[wi] : 0u;
+  const uint32_t word = (lane < kWaveWords && wi < bitmap_words) ? bm[wi] : 0u;
   int32_t n = 0;
 #pragma unroll 4
-  for (int c = 0; c < WORDS / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
+  for (int c = 0; c < kWaveWords / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
     const int k = 2 * c + (lane >> 5);
     const uint32_t w = __shfl(word, k, 64);
     const int64_t seg = (first_word + k * stride) * 32 + (lane & 31);
@@ -676,19 +675,16 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
 // next iteration.  The launch is bound by latency, not throughput, so the work is spread thin: EIGHT lanes
 // share a segment (four coordinates = one Philox block each), the 32 codes of a segment meet in LDS and the
 // B words are assembled from there.  Workgroups [0, head/1024) of a worker take 32 head segments each; in
-// the others every wavefront visits the marked ones of its kQuantSegs tail segments, up to 32 at a time.
+// the others every wavefront visits the marked ones of its kWaveSegs tail segments, up to 32 at a time.
 // Every workgroup folds its worker's statistic partials itself (the fixed order of fold_stat_slots, so all of
 // them derive the same scale); workgroup 0 of a worker records the results.
-constexpr int kQuantWords = 8;                  // bitmap words per wavefront
-constexpr int kQuantSegs = kQuantWords * 32;
-
 template <int B>
 __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a, StatSinks sk, QuantSpec qs,
                                                                    int32_t nslots, int64_t d, StreamKey key,
                                                                    uint32_t *__restrict__ packed,
                                                                    float *__restrict__ delta_out) {
   __shared__ int32_t codes[4][32][32];  // per wavefront: 32 segments x 32 codes
-  __shared__ int32_t lists[4][kQuantSegs];
+  __shared__ int32_t lists[4][kWaveSegs];
   __shared__ QParams q_sh;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int sub = lane >> 3, part = lane & 7;  // this lane moves coordinates 4*part..+3 of segment slot `sub` (+8q)
@@ -719,7 +715,7 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
   } else {
     const int64_t stride = (int64_t)(gridDim.x - head_wgs) * 4;  // tail wavefronts of this worker
     const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - head_wgs) * 4 + wv;
-    n = compact_marked<kQuantWords>(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
+    n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
                                     a.d_pad / kSegFloats, lane, list);
     __builtin_amdgcn_wave_barrier();
     load_batch(0);  // on its way while the statistics are folded
@@ -1307,10 +1303,8 @@ hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st) {
 }
 
 hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st) {
-  // 32 head segments per workgroup; kQuantSegs tail segments per wavefront, four wavefronts per workgroup
-  const int64_t tail_words = c->bitmap_words - c->sparse_head / (kSegFloats * 32);
-  const int64_t tail_wgs = (tail_words + 4 * kQuantWords - 1) / (4 * kQuantWords);
-  const dim3 grid((unsigned)(c->sparse_head / (32 * kSegFloats) + (tail_wgs > 0 ? tail_wgs : 1)), (unsigned)c->cfg.N);
+  // 32 head segments per workgroup, then the tail workgroups
+  const dim3 grid((unsigned)(c->sparse_head / (32 * kSegFloats) + sparse_tail_wgs(c)), (unsigned)c->cfg.N);
   const int32_t slots = sparse_stat_slots(c);
 #define CALL(BITS)                                                                                             \
   hipLaunchKernelGGL(sparse_quantize_kernel<BITS>, grid, dim3(kThreads), 0, st, sparse_args_of(c), sinks_of(c, nullptr), \
