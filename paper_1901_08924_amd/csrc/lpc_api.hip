@@ -131,6 +131,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.csc_rows = (int32_t *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(int32_t));
   s.csc_vals = (float *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(float));
   s.csc_coef = (float *)take((c->csr ? (size_t)c->n : 4) * sizeof(float));
+  s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * c->cfg.N * c->cfg.B : 1) * sizeof(RowPlan));
   s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
@@ -566,13 +567,15 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       LPC_TRY_HIP(launch_zero(s.U, (int64_t)g.N * c->d_pad, st));
       LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
       LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
+      // the epoch's draws with each row's extent, label and snapshot margin, looked up once
+      LPC_TRY_HIP(launch_csr_plan(c, zs, key_of(c, epoch, 0), st));
     }
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       if (sparse) {
         {
           ProfScope ps(c, LPC_PROF_VR_ROWS, st);
-          LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, st));
+          LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, s.csr_plan + (int64_t)t * g.N * g.B, st));
         }
         {
           ProfScope ps(c, LPC_PROF_VR_FOLD, st);

@@ -59,6 +59,7 @@ struct CsrArgs {
   uint32_t *touched;  // sparse worker pass: [N][bitmap_words], one bit per 32-coordinate segment
   int64_t bitmap_words;
   int32_t parts, rows_per_part;  // sparse worker pass: workgroups per worker, sampled rows per workgroup
+  const RowPlan *plan;           // sparse worker pass: [N][B] rows of this iteration, looked up ahead
   int64_t n, d, d_pad, n_rows, nnz;
   int32_t head;       // columns [0, head) are privatised in LDS (snapshot pass)
   int32_t loss, want_loss, want_grad;
@@ -411,19 +412,22 @@ template <bool CACHED>
 __global__ __launch_bounds__(kSparseThreads) void csr_vr_sparse_kernel(CsrArgs a) {
   extern __shared__ float head_acc[];
   const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
-  for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
-  __syncthreads();
   const int32_t wrel = blockIdx.x / a.parts, part = blockIdx.x % a.parts;
-  const uint32_t worker = (uint32_t)(a.worker_begin + wrel);
   const int32_t pos0 = part * a.rows_per_part;
   const int32_t pos1 = pos0 + a.rows_per_part < a.B ? pos0 + a.rows_per_part : a.B;
+  // the draws and each row's extent, label and snapshot margin were looked up ahead of the inner loop; the
+  // group's first row is requested while the accumulators are cleared
+  const RowPlan *plan = a.plan + (int64_t)wrel * a.B;
+  RowPlan p{0, 0, 0.0f, 0.0f};
+  if (pos0 + grp < pos1) p = plan[pos0 + grp];
+  for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
+  __syncthreads();
   float *u = a.U + (int64_t)wrel * a.d_pad;
   uint32_t *bm = a.touched + (int64_t)wrel * a.bitmap_words;
   for (int32_t pos = pos0 + grp; pos < pos1; pos += kSparseGroups) {
-    const int64_t r = sample_row(a.key, a.tag, worker, (uint32_t)pos, a.n);
-    const int32_t lo = a.row_ptr[r], hi = a.row_ptr[r + 1];
-    const float yr = a.y[r];
-    const float zc = CACHED ? a.z_snap[r] : 0.0f;
+    if (pos != pos0 + grp) p = plan[pos];
+    const int32_t lo = p.lo, hi = p.hi;
+    const float yr = p.y, zc = p.z;
     // 64 entries of the row per step, all loads of a step in flight together (most rows need one step)
     float s = 0.0f, s2 = 0.0f;
     int32_t c[4];
@@ -471,6 +475,25 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_sparse_kernel(CsrArgs a
   __syncthreads();
   float *dst = a.part + (int64_t)blockIdx.x * a.head;
   for (int32_t j = tid; j < a.head; j += kSparseThreads) dst[j] = head_acc[j];
+}
+
+// plan[(t*N + i)*B + pos] for every inner iteration t < m of an epoch: the draws do not depend on the iterates,
+// so the random stream, row_ptr, y and the cached margins are read once here instead of at the head of every
+// iteration's dependency chain.
+__global__ void csr_plan_kernel(CsrArgs a, int32_t m, int32_t N, RowPlan *__restrict__ plan) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_iter = (int64_t)N * a.B;
+  if (idx >= (int64_t)m * per_iter) return;
+  StreamKey key = a.key;
+  key.iter = (uint32_t)(idx / per_iter);
+  const int64_t rem = idx % per_iter;
+  const uint32_t worker = (uint32_t)(rem / a.B), pos = (uint32_t)(rem % a.B);
+  const int64_t r = sample_row(key, a.tag, worker, pos, a.n);
+  RowPlan p;
+  p.lo = a.row_ptr[r]; p.hi = a.row_ptr[r + 1];
+  p.y = a.y[r];
+  p.z = a.z_snap ? a.z_snap[r] : 0.0f;
+  plan[idx] = p;
 }
 
 __global__ void zero_kernel(float4 *__restrict__ dst, int64_t n4) {
@@ -617,9 +640,20 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 // Sparse worker pass (all N workers).  s.U rows and the bitmap must be zero outside what this call adds.
 int csr_sparse_parts(int32_t B) { return (B + kSparseGroups - 1) / kSparseGroups; }
 
-hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
-                                StreamKey key, hipStream_t st) {
+hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, hipStream_t st) {
   CsrArgs a{};
+  a.row_ptr = c->prob.row_ptr; a.y = c->prob.y; a.z_snap = z_snap;
+  a.n = c->n; a.B = c->cfg.B; a.key = key0; a.tag = kTagBatch;
+  const int64_t total = (int64_t)c->cfg.m * c->cfg.N * c->cfg.B;
+  hipLaunchKernelGGL(csr_plan_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, c->cfg.m, c->cfg.N,
+                     c->s.csr_plan);
+  return hipGetLastError();
+}
+
+hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
+                                StreamKey key, const RowPlan *plan, hipStream_t st) {
+  CsrArgs a{};
+  a.plan = plan;
   a.row_ptr = c->prob.row_ptr; a.col_idx = c->prob.col_idx; a.vals = c->prob.vals; a.y = c->prob.y;
   a.w = w; a.w_snap = w_snap; a.z_snap = z_snap; a.U = c->s.U; a.part = c->s.part;
   a.touched = c->s.touched; a.bitmap_words = c->bitmap_words;

@@ -52,6 +52,13 @@ struct GemmArgs {
   int32_t stat_slot0;
 };
 
+// One sampled row of a CSR epoch, looked up ahead of the inner loop: its extent in col_idx/vals, its label and
+// its cached snapshot margin.
+struct RowPlan {
+  int32_t lo, hi;
+  float y, z;
+};
+
 // One symbol of the entropy coder: the codeword with its bits reversed (the first stream bit at bit 0) and
 // its length; length 0 = the symbol has no codeword.
 struct HuffEntry {
@@ -77,6 +84,7 @@ struct Scratch {
   float *u_avg;         // [d]
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
+  RowPlan *csr_plan;               // sparse CSR epoch: [m][N][B] sampled rows of the epoch
   unsigned long long *clip_total;  // [1] clipped coordinates summed over an evaluation run
   HuffEntry *huff_table;           // [2^bits] codeword table of the entropy coder
   uint32_t *huff_seg_bits;         // [d_pad/32] encoded bits per 32-coordinate segment
@@ -162,8 +170,9 @@ hipError_t build_csc_tail(lpc_ctx *c, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
 int csr_sparse_parts(int32_t B);
+hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, hipStream_t st);
 hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
-                                StreamKey key, hipStream_t st);
+                                StreamKey key, const RowPlan *plan, hipStream_t st);
 hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st);
 hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st);
 hipError_t launch_sparse_receive_prox(const lpc_ctx *c, const float *mu, float step, float *w, hipStream_t st);
