@@ -11,8 +11,8 @@ resident in HBM before the timed region.
 Prints ONE JSON line.  `value` = inner iterations per second over whole steps (the snapshot pass
 included).  After the timed region the same steps are run once more with the library's event
 profiling on (HIP events on the launch stream around each kernel class); `kernels` lists every
-class with its algorithmic bytes (or flops) per launch, `roofline` is the class with the largest
-share of the step.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+class with its algorithmic bytes (or flops) per launch, `roofline` is the class that carries most of
+the step's algorithmic work (launches per step x work per launch, weighed by its own peak).  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -268,7 +268,15 @@ def main():
         if k in traffic:
             kernels[k]["traffic_bytes"] = traffic[k]
     rated = [k for k in kernels if "frac" in kernels[k]]
-    dom = max(rated, key=lambda k: kernels[k]["share_of_step"])
+    # the dominant class: the one that carries most of the step's algorithmic work, measured as the time it
+    # would take at its own roofline (launches per step x bytes or flops per launch / peak); time shares of
+    # microsecond-scale launches are within each other's measurement noise and would make the choice flip
+    def roofline_seconds(k):
+        e = kernels[k]
+        amount = e.get("algorithmic_bytes", e.get("algorithmic_flops", 0.0))
+        peak = e["peak"] * (1e9 if e["unit"] == "GB/s" else 1e12)
+        return e["launches_per_step"] * amount / peak
+    dom = max(rated, key=roofline_seconds)
     kd = kernels[dom]
     roofline = {"kernel": kd["name"], "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
                 "unit": kd["unit"], "frac": kd["frac"], "traffic": kd.get("traffic_bytes"), "us_per_launch": kd["avg_us"],

@@ -132,6 +132,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.csc_vals = (float *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(float));
   s.csc_coef = (float *)take((c->csr ? (size_t)c->n : 4) * sizeof(float));
   s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * c->cfg.N * c->cfg.B : 1) * sizeof(RowPlan));
+  s.warm_sink = (float *)take(sizeof(float));
   s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));

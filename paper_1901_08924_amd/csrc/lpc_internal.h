@@ -85,6 +85,7 @@ struct Scratch {
   float *ysum;          // [d]   running weighted sum of y (Alg. 2 step 15 / Alg. 3 step 5)
   double *f_scalar;     // [1]
   RowPlan *csr_plan;               // sparse CSR epoch: [m][N][B] sampled rows of the epoch
+  float *warm_sink;                // [1] never written in practice: keeps the cache-warming loads alive
   unsigned long long *clip_total;  // [1] clipped coordinates summed over an evaluation run
   HuffEntry *huff_table;           // [2^bits] codeword table of the entropy coder
   uint32_t *huff_seg_bits;         // [d_pad/32] encoded bits per 32-coordinate segment
