@@ -1361,7 +1361,7 @@ hipError_t launch_sparse_receive_prox(const lpc_ctx *c, const float *mu, float s
 
 namespace {
 // Fills the warming fields and returns the number of extra workgroups (0 when there is nothing to warm: no
-// next iteration in this epoch, other data kinds, or more rows than can arrive while the exchange runs).  `shared`: the
+// next iteration in this epoch, other data kinds).  `shared`: the
 // next worker pass also reads the shared batch J as worker index N.
 int warm_setup(const lpc_ctx *c, StreamKey key, bool shared, FusedArgs *a) {
   a->warm_groups = 0;
@@ -1369,16 +1369,19 @@ int warm_setup(const lpc_ctx *c, StreamKey key, bool shared, FusedArgs *a) {
   const int32_t workers = c->cfg.N + (shared ? 1 : 0);
   const int32_t parts = c->vr_parts, B = c->cfg.B;
   const int32_t rows_per_part = (B + parts - 1) / parts;
-  // measured: 8.5 MB arrive within the exchange's own 6 us; with 36 MB the requests outlast it and the launch
-  // grows by what the next worker pass saves
-  if ((int64_t)workers * B * c->d * 4 > (16 << 20)) return 0;
+  // measured: 8.5 MB arrive within the exchange's own 6 us; with 16 MB or more the requests outlast it and the
+  // launch grows by what the next worker pass saves.  Larger batches are warmed in part (their first workgroups).
+  const int64_t cap = 9 << 20;
+  const int64_t bytes_per_group = (int64_t)rows_per_part * c->d * 4;
+  const int64_t groups_cap = cap / bytes_per_group;
+  if (groups_cap < 1) return 0;
   a->warm_X = c->prob.X; a->warm_ldx = c->prob.ldx; a->warm_y = c->prob.y;
   a->warm_z = (c->n_full == c->n) ? c->s.z_snap : nullptr;
   a->warm_n = c->n;
   a->warm_key = key;
   a->warm_key.iter = key.iter + 1;
   a->warm_shared = shared ? c->cfg.N : -1;
-  a->warm_groups = workers * parts; a->warm_parts = parts; a->warm_rows_per_part = rows_per_part; a->warm_B = B;
+  a->warm_groups = (int32_t)(groups_cap < (int64_t)workers * parts ? groups_cap : (int64_t)workers * parts); a->warm_parts = parts; a->warm_rows_per_part = rows_per_part; a->warm_B = B;
   a->warm_sink = c->s.warm_sink;
   return a->warm_groups;
 }
