@@ -69,13 +69,32 @@ def test_mlp_full_gradient(dims, n, N, B):
 
 def test_mlp_full_gradient_partial_snapshot():
     import torch
-    sp = lpc_synth.make("c5", n=500, dims=(40, 33, 10), N=3, B=20, n_full=150)     # 2.5 chunks of 60 rows
+    sp = lpc_synth.make("c5", n=500, dims=(40, 33, 10), N=3, B=20, n_full=150)     # the first 150 rows only
     ctx = gpu_context(sp)
     p, _k = oracle_problem(sp)
     mu = torch.zeros(sp.d, device="cuda")
     ctx.full_grad(to_dev(sp.w0), mu, None, None)
     mu_o, _, _ = lpco.full_grad(p, sp.w0, n_rows=150)
     assert np.abs(mu.cpu().numpy() - mu_o).max() <= 1e-5 * np.abs(mu_o).max()
+    ctx.close()
+
+
+@pytest.mark.parametrize("n", [10240, 9000])
+def test_mlp_full_gradient_over_several_chunks_and_row_blocks(n):
+    # the snapshot pass takes 8192 rows at a time; inside a chunk the weight-gradient product of the first
+    # layer runs as 2048-row blocks side by side, the bias sums and the 10-column layer as 256-row blocks;
+    # n = 9000 leaves a ragged second chunk (three whole 256-row blocks and 40 rows)
+    import torch
+    sp = lpc_synth.make("c5", n=n, dims=(64, 128, 10), N=3, B=16, n_full=n)
+    ctx = gpu_context(sp)
+    p, _k = oracle_problem(sp)
+    w = (sp.w0 + 0.05 * np.random.default_rng(2).standard_normal(sp.d)).astype(np.float32)
+    mu = torch.full((sp.d,), -7.0, device="cuda")
+    f = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ctx.full_grad(to_dev(w), mu, None, f)
+    mu_o, _, f_o = lpco.full_grad(p, w)
+    assert np.abs(mu.cpu().numpy() - mu_o).max() <= 1e-5 * np.abs(mu_o).max()
+    assert abs(f.item() - f_o) <= 1e-5 * abs(f_o)
     ctx.close()
 
 
