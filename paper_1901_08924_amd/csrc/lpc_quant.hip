@@ -8,12 +8,15 @@
 // Data layout.  A worker's vector u (d_pad floats) is cut into segments of 32
 // consecutive coordinates; segment s becomes `bits` consecutive 32-bit words of
 // the message (coordinate j occupies bits [j*bits, (j+1)*bits) of a
-// little-endian bit stream, so a segment never straddles its words).  One
-// thread owns one segment: it needs 8 Philox blocks and emits whole words, so
-// no cross-lane traffic is needed for packing.  HBM accesses stay coalesced by
-// staging a tile of 256 segments through LDS with a row pitch of 36 floats
-// (pitch mod 32 banks = 4, so eight consecutive lanes reading 16 bytes each hit
-// disjoint banks).
+// little-endian bit stream, so a segment never straddles its words).  In the
+// throughput-bound dense quantizer one thread owns one segment: it needs 8
+// Philox blocks and emits whole words, so no cross-lane traffic is needed for
+// packing; HBM accesses stay coalesced by staging a tile of 256 segments
+// through LDS with a row pitch of 36 floats (pitch mod 32 banks = 4, so eight
+// consecutive lanes reading 16 bytes each hit disjoint banks).  In the
+// latency-bound launches (small-d fused exchange, sparse quantizer) a lane
+// takes four coordinates = one Philox block, the codes meet in LDS and the
+// words are assembled from there.
 #include <hip/hip_runtime.h>
 
 #include "lpc_device.h"
