@@ -419,7 +419,7 @@ lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_c
   // flags and clip counts start at zero (contiguous, see layout())
   const size_t words = ((char *)c->s.z_snap - (char *)c->s.flags) / sizeof(uint32_t);
   if (launch_fill_u32(c->s.flags, 0u, (int64_t)words, nullptr) != hipSuccess ||
-      hipStreamSynchronize(nullptr) != hipSuccess) {
+      (c->mlp && launch_mlp_clear_padding(c, nullptr) != hipSuccess) || hipStreamSynchronize(nullptr) != hipSuccess) {
     delete c;
     return LPC_EDEVICE;
   }

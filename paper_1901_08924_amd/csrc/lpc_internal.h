@@ -197,7 +197,8 @@ hipError_t launch_huffman_measure(const lpc_ctx *c, const uint32_t *words, hipSt
 hipError_t launch_huffman_emit(const lpc_ctx *c, const uint32_t *words, uint32_t *out, int64_t out_words,
                                hipStream_t st);
 hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st);
-void mlp_plan(lpc_ctx *c);  // fills the offsets and sizes above
+void mlp_plan(lpc_ctx *c);
+hipError_t launch_mlp_clear_padding(const lpc_ctx *c, hipStream_t st);  // padding of the context's own U rows  // fills the offsets and sizes above
 hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, double *f_out, int64_t n_rows,
                                 hipStream_t st);
 // stats_mode != kStatsNone: the statistics of the N rows of U come out of the producing kernels' epilogues

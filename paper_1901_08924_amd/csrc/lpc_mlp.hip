@@ -200,23 +200,19 @@ bool last_layer_fused(int K, int C, int64_t lda, const float *a, int64_t a_strid
          (((uintptr_t)a) & 15u) == 0 && (int64_t)C * (K + 4) + C <= 16384;
 }
 
-__global__ void add_inplace_kernel(float *__restrict__ a, const float *__restrict__ b, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) a[i] += b[i];
-}
-
 // out[b][c] (+)= alpha * sum over the K rows of batch item b of (D0[row][c] + D1[row][c]).
 // 64 columns per workgroup; the 4 waves take interleaved rows and are combined in wave order.
-__global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ D0, const float *__restrict__ D1, int K,
+// sum_back: D0[row][c] also receives D0[row][c] + D1[row][c] (every element is read by exactly one thread).
+__global__ __launch_bounds__(256) void colsum_kernel(float *__restrict__ D0, const float *__restrict__ D1, int K,
                                                      int cols, float alpha, int accumulate, float *__restrict__ out,
-                                                     int64_t out_stride) {
+                                                     int64_t out_stride, int sum_back) {
   __shared__ float red[4][64];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
   const int b = blockIdx.y;
   float s = 0.0f;
   if (c < cols) {
-    const float *p0 = D0 + (int64_t)b * K * cols + c;
+    float *p0 = D0 + (int64_t)b * K * cols + c;
     const float *p1 = D1 ? D1 + (int64_t)b * K * cols + c : nullptr;
     for (int k = wv; k < K; k += 32) {  // eight rows of each set in flight per step
       float v0[8], v1[8];
@@ -227,7 +223,11 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *__restrict__ D
         v1[j] = (ok && p1) ? p1[(int64_t)(k + 4 * j) * cols] : 0.0f;
       }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) s += v0[j] + v1[j];
+      for (int j = 0; j < 8; ++j) {
+        const float t = v0[j] + v1[j];
+        s += t;
+        if (sum_back && k + 4 * j < K) p0[(int64_t)(k + 4 * j) * cols] = t;
+      }
     }
   }
   red[wv][lane] = s;
@@ -377,6 +377,14 @@ hipError_t backward_data(const Net &nn, const float *W, int64_t wstride, int nse
 
 }  // namespace
 
+hipError_t launch_mlp_clear_padding(const lpc_ctx *c, hipStream_t st) {
+  if (c->d_pad == c->d) return hipSuccess;
+  const int nvec = c->cfg.N + 1;
+  const int64_t cnt = (c->d_pad - c->d) * nvec;
+  hipLaunchKernelGGL(zero_tail_kernel, dim3((unsigned)((cnt + 63) / 64)), dim3(64), 0, st, c->s.U, c->d, c->d_pad, nvec);
+  return hipGetLastError();
+}
+
 void mlp_plan(lpc_ctx *c) {
   const int L = c->prob.mlp_nlayers;
   const int32_t *dims = c->mlp_dims.data();
@@ -433,7 +441,7 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
       const int in = nn.dims[l], out = nn.dims[l + 1];
       const float *a = l == 0 ? in0 : nn.act(l, 0);
       const int64_t lda = l == 0 ? c->prob.ldx : in;
-      const float *dl = nn.del(l + 1, 0);
+      float *dl = nn.del(l + 1, 0);
       int acc = r0 > 0 ? 1 : 0;
       GemmArgs g{};
       g.A[0] = a; g.lda[0] = lda; g.transA = 1;
@@ -469,8 +477,7 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
         if (e != hipSuccess) return e;
         const int cols = in * out;
         hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((cols + 63) / 64), 1u), dim3(256), 0, st,
-                           (const float *)part_w, (const float *)nullptr, nb, cols, alpha, acc,
-                           mu + c->mlp_woff[l], (int64_t)0);
+                           part_w, (const float *)nullptr, nb, cols, alpha, acc, mu + c->mlp_woff[l], (int64_t)0, 0);
         if (rest) {
           g.A[0] = a + (int64_t)nb * kSnapBlock * lda; g.B[0] = dl + (int64_t)nb * kSnapBlock * out;
           g.K = rest; g.accumulate = 1;
@@ -480,19 +487,18 @@ hipError_t launch_mlp_full_grad(const lpc_ctx *c, const float *w, float *mu, dou
         e = launch_gemm(g, st);
       }
       if (e != hipSuccess) return e;
-      const float *db = dl;
+      float *db = dl;
       int brows = rows;
       if (blocks) {
         hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), (unsigned)nb), dim3(256), 0, st, dl,
-                           (const float *)nullptr, kSnapBlock, out, 1.0f, 0, part_b, (int64_t)out);
+                           (const float *)nullptr, kSnapBlock, out, 1.0f, 0, part_b, (int64_t)out, 0);
         hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), 1u), dim3(256), 0, st,
-                           (const float *)part_b, (const float *)nullptr, nb, out, alpha, acc, mu + c->mlp_boff[l],
-                           (int64_t)0);
+                           part_b, (const float *)nullptr, nb, out, alpha, acc, mu + c->mlp_boff[l], (int64_t)0, 0);
         db = dl + (int64_t)nb * kSnapBlock * out; brows = rest; acc = 1;
       }
       if (brows)
         hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), 1u), dim3(256), 0, st, db,
-                           (const float *)nullptr, brows, out, alpha, acc, mu + c->mlp_boff[l], (int64_t)0);
+                           (const float *)nullptr, brows, out, alpha, acc, mu + c->mlp_boff[l], (int64_t)0, 0);
     }
   }
   return hipGetLastError();
@@ -524,19 +530,17 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   StatRange ranges{};
   for (int l = nn.L - 1; l >= 0; --l) {
     const int out = nn.dims[l + 1], in = nn.dims[l];
-    // bias: column sums of the two delta sets over the worker's rows
+    // bias: column sums of the two delta sets over the worker's rows; for the first layer, whose input rows are
+    // the same for both sets, the pass also leaves the sum of the two deltas in set 0 (one contraction below)
     hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), (unsigned)nw), dim3(256), 0, st,
-                       (const float *)nn.del(l + 1, 0), (const float *)nn.del(l + 1, 1), B, out, alpha, 0,
-                       U + c->mlp_boff[l], c->d_pad);
+                       nn.del(l + 1, 0), (const float *)nn.del(l + 1, 1), B, out, alpha, 0, U + c->mlp_boff[l],
+                       c->d_pad, l == 0 ? 1 : 0);
     GemmArgs g{};
     g.transA = 1;
     g.C = U + c->mlp_woff[l]; g.ldc = out; g.strideC = c->d_pad;
     g.M = in; g.N = out; g.K = B; g.alpha = alpha; g.batch = nw;
     if (l == 0) {
-      // same input rows for both sets: add the deltas first, contract once
-      const int64_t cnt = (int64_t)rows * out;
-      hipLaunchKernelGGL(add_inplace_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st, nn.del(1, 0),
-                         (const float *)nn.del(1, 1), cnt);
+      // same input rows for both sets: the deltas were added by the bias pass above, contract once
       g.nseg = 1;
       g.A[0] = c->s.mlp_xb; g.lda[0] = in; g.strideA[0] = (int64_t)B * in;
       g.B[0] = nn.del(1, 0); g.ldb[0] = out; g.strideB[0] = (int64_t)B * out;
@@ -567,7 +571,9 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
       ranges.n = 0;
     }
   }
-  if (c->d_pad > c->d) {
+  // the padding of the context's own U was cleared when the context was made and nothing writes it
+  const bool own_u = U >= c->s.U && U < c->s.U + (int64_t)(c->cfg.N + 1) * c->d_pad;
+  if (c->d_pad > c->d && !own_u) {
     const int64_t cnt = (c->d_pad - c->d) * nw;
     hipLaunchKernelGGL(zero_tail_kernel, dim3((unsigned)((cnt + 63) / 64)), dim3(64), 0, st, U, c->d, c->d_pad, nw);
   }
