@@ -1145,15 +1145,23 @@ __global__ __launch_bounds__(kThreads) void sum_loss_kernel(const double *__rest
   if (tid == 0) *f_out = (((red[0] + red[1]) + red[2]) + red[3]) * scale;
 }
 
-// acc += lambda1*|w|_1 + (lambda2/2)*|w|^2 (one workgroup)
+// partial[g] = lambda1*|w|_1 + (lambda2/2)*|w|^2 over workgroup g's share of w (coordinates g*1024 + tid, then in
+// steps of 1024*gridDim.x; eight loads in flight per thread); fixed order, fp64
 __global__ __launch_bounds__(1024) void objective_reg_kernel(const float *__restrict__ w, int64_t d, double l1,
-                                                             double l2, double *__restrict__ acc) {
+                                                             double l2, double *__restrict__ partial) {
   __shared__ double red[16];
   const int tid = threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * 1024;
   double a = 0.0;
-  for (int64_t j = tid; j < d; j += 1024) {
-    const double v = (double)w[j];
-    a += l1 * fabs(v) + 0.5 * l2 * v * v;
+  for (int64_t j = (int64_t)blockIdx.x * 1024 + tid; j < d; j += 8 * stride) {
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = j + q * stride < d ? w[j + q * stride] : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const double x = (double)v[q];
+      a += l1 * fabs(x) + 0.5 * l2 * x * x;
+    }
   }
   a = wave_sum(a);
   if ((tid & 63) == 0) red[tid >> 6] = a;
@@ -1161,8 +1169,16 @@ __global__ __launch_bounds__(1024) void objective_reg_kernel(const float *__rest
   if (tid == 0) {
     double t = 0.0;
     for (int k = 0; k < 16; ++k) t += red[k];
-    *acc += t;
+    partial[blockIdx.x] = t;
   }
+}
+
+// acc += partial[0] + partial[1] + ... in order
+__global__ void objective_reg_fold_kernel(const double *__restrict__ partial, int32_t n, double *__restrict__ acc) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  double t = 0.0;
+  for (int32_t k = 0; k < n; ++k) t += partial[k];
+  *acc += t;
 }
 
 QuantSpec spec_of(const lpc_ctx *c) {
@@ -1528,8 +1544,15 @@ hipError_t launch_scale_to(const lpc_ctx *c, const float *src, float scale, floa
 }
 
 hipError_t launch_objective_reg(const lpc_ctx *c, const float *w, double *acc, hipStream_t st) {
-  hipLaunchKernelGGL(objective_reg_kernel, dim3(1), dim3(1024), 0, st, w, c->d, (double)c->prob.lambda1,
-                     (double)c->prob.lambda2, acc);
+  // one workgroup per 8192 coordinates, at most as many as the statistic scratch (free outside an epoch) holds
+  int64_t groups = (c->d + 8191) / 8192;
+  const int64_t room = (int64_t)(c->cfg.N + 1) * c->stat_slots * 4;
+  if (groups > room) groups = room;
+  if (groups > 256) groups = 256;
+  hipLaunchKernelGGL(objective_reg_kernel, dim3((unsigned)groups), dim3(1024), 0, st, w, c->d,
+                     (double)c->prob.lambda1, (double)c->prob.lambda2, c->s.stat_part);
+  hipLaunchKernelGGL(objective_reg_fold_kernel, dim3(1), dim3(64), 0, st, (const double *)c->s.stat_part,
+                     (int32_t)groups, acc);
   return hipGetLastError();
 }
 
