@@ -1173,12 +1173,16 @@ __global__ __launch_bounds__(1024) void objective_reg_kernel(const float *__rest
   }
 }
 
-// acc += partial[0] + partial[1] + ... in order
-__global__ void objective_reg_fold_kernel(const double *__restrict__ partial, int32_t n, double *__restrict__ acc) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
-  double t = 0.0;
-  for (int32_t k = 0; k < n; ++k) t += partial[k];
-  *acc += t;
+// acc += the n <= 256 partials: lane l takes partial[l], [l+64], [l+128], [l+192], then the wavefront sum (one
+// wavefront; a fixed order)
+__global__ __launch_bounds__(64) void objective_reg_fold_kernel(const double *__restrict__ partial, int32_t n,
+                                                               double *__restrict__ acc) {
+  const int lane = threadIdx.x;
+  double v[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) v[q] = lane + 64 * q < n ? partial[lane + 64 * q] : 0.0;
+  const double t = wave_sum((v[0] + v[1]) + (v[2] + v[3]));
+  if (lane == 0) *acc += t;
 }
 
 QuantSpec spec_of(const lpc_ctx *c) {
