@@ -860,10 +860,17 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
     if (i < a.N && tile0 + 4 * (tid & 31) < a.d_pad)
       v_all[q] = *reinterpret_cast<const float4 *>(a.U + (int64_t)i * a.d_pad + tile0 + 4 * (tid & 31));
   }
-  float w_old = 0.0f, mu_j = 0.0f;
-  if (a.do_prox && tid < kFusedCoords && tile0 + tid < a.d) {
-    w_old = a.w[tile0 + tid];
-    mu_j = a.mu[tile0 + tid];
+  float w_old = 0.0f, mu_j = 0.0f, x_j = 0.0f, z_j = 0.0f, uhat_j = 0.0f, ysum_j = 0.0f, snap_j = 0.0f;
+  if (tid < kFusedCoords && tile0 + tid < a.d) {
+    const int64_t j = tile0 + tid;
+    if (a.do_prox) {
+      w_old = a.w[j];
+      mu_j = a.mu[j];
+    }
+    if (a.do_alpc) {
+      mu_j = a.mu[j]; x_j = a.x[j]; z_j = a.z[j]; uhat_j = a.u_hat[j]; snap_j = a.w_snap[j];
+      ysum_j = a.first ? 0.0f : a.ysum[j];
+    }
   }
   // wavefront wv folds the statistics of vectors wv, wv+4, ...; four vectors at a time so that their partials
   // are requested together (the lane-wise sums and the butterflies keep fold_stat_slots' order)
@@ -975,13 +982,12 @@ __global__ __launch_bounds__(kThreads) void fused_exchange_kernel(FusedArgs a) {
       if (a.u_avg_out) a.u_avg_out[j] = avg;
       if (a.do_prox) a.w[j] = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
       if (a.do_alpc) {
-        const float m = a.mu[j];
-        const float yn = prox_scalar(a.x[j], avg + m, a.step_y, a.thr_y, a.shrink_y);   // low-precision gradient
-        const float zn = prox_scalar(a.z[j], a.u_hat[j] + m, a.alpha, a.thr_z, a.shrink_z);  // full precision
+        const float yn = prox_scalar(x_j, avg + mu_j, a.step_y, a.thr_y, a.shrink_y);   // low-precision gradient
+        const float zn = prox_scalar(z_j, uhat_j + mu_j, a.alpha, a.thr_z, a.shrink_z);  // full precision
         a.y[j] = yn;
         a.z[j] = zn;
-        a.ysum[j] = a.first ? a.weight * yn : a.ysum[j] + a.weight * yn;
-        a.x_next[j] = (a.t1 * zn + a.t2 * a.w_snap[j]) + a.t3 * yn;
+        a.ysum[j] = a.first ? a.weight * yn : ysum_j + a.weight * yn;
+        a.x_next[j] = (a.t1 * zn + a.t2 * snap_j) + a.t3 * yn;
       }
     }
   }
