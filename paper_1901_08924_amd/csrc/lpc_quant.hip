@@ -635,9 +635,15 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
     const int64_t j = ((int64_t)blockIdx.x * kThreads + tid) * 4;
     const float *src = a.head_part + (int64_t)worker * a.parts * a.head + j;
     float4 v = *reinterpret_cast<const float4 *>(src);
-    for (int32_t p = 1; p < a.parts; ++p) {
-      const float4 t = *reinterpret_cast<const float4 *>(src + (int64_t)p * a.head);
-      v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    for (int32_t p0 = 1; p0 < a.parts; p0 += 4) {  // four partial rows in flight, added in order
+      float4 t[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        t[q] = p0 + q < a.parts ? *reinterpret_cast<const float4 *>(src + (int64_t)(p0 + q) * a.head)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (p0 + q < a.parts) { v.x += t[q].x; v.y += t[q].y; v.z += t[q].z; v.w += t[q].w; }
     }
     *reinterpret_cast<float4 *>(urow + j) = v;
     take(v.x); take(v.y); take(v.z); take(v.w);
