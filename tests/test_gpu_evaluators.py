@@ -275,3 +275,28 @@ def test_entropy_coder_errors_and_size_query():
         miss = (C.c_int32 * 4)(*drop)
         assert lpc.lib.lpc_huffman_encode(ctx._h, packed.data_ptr(), miss, None, 0, C.byref(total), None) == lpc.EINVAL
     ctx.close()
+
+
+def test_traced_epoch_on_the_mlp_instance():
+    import torch
+    from _common import oracle_config
+    sp = lpc_synth.make("c5", n=256, dims=(24, 32, 10), N=3, B=16, n_full=256)
+    over = dict(m=4, bits=4, clip_mode=0, clip=0.8)
+    p, _keep = oracle_problem(sp)
+    w_o = sp.w0.copy()
+    d_o, n_o = lpco.epoch_traced(p, oracle_config(sp, **over), w_o, 0)
+    ctx = gpu_context(sp, **over)
+    w_a, w_b = to_dev(sp.w0), to_dev(sp.w0)
+    ctx.epoch(w_a, 0)
+    dtr, ntr = ctx.epoch_traced(w_b, 0)
+    assert torch.equal(w_a, w_b)                      # the MLP's epoch takes the same launches either way
+    dtr = dtr.cpu().numpy()
+    # x_0 = x~: the oracle's first message is exactly zero; here the difference of the two weight gradients is one
+    # contraction over stacked rows (+ rows of x, - rows of x~), which cancels only to fp32 rounding
+    assert np.all(dtr[0] <= 1e-5 * dtr[1:].min())
+    assert np.allclose(dtr[1:], d_o[1:], rtol=1e-3)
+    diff = ntr.cpu().numpy().view(np.uint32).astype(np.int64) - n_o.astype(np.int64)
+    assert np.abs(diff[1:]).max() <= 2
+    P_o, P_g = lpco.objective(p, w_o), ctx.objective(w_b)
+    assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    ctx.close()
