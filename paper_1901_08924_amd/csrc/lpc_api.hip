@@ -357,7 +357,8 @@ lpc_status record_iteration(lpc_ctx *c, int32_t t, hipStream_t st) {
 }
 
 // communication step 2 of one inner iteration followed by the update of Alg. 1
-lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st) {
+// (want_clip_counts: an evaluation run records them; the quantizer is quicker without)
+lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, bool want_clip_counts, hipStream_t st) {
   Scratch &s = c->s;
   ProfScope ps(c, LPC_PROF_EXCHANGE, st);
   if (c->quant && c->cfg.scheme != LPC_SCHEME_A) {
@@ -367,7 +368,7 @@ lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, hipStream_t st
     LPC_TRY_HIP(launch_dequantize_shared(c, s.packed, s.delta, c->cfg.scheme == LPC_SCHEME_C, key, s.u_avg, st));
     LPC_TRY_HIP(launch_prox(c, w, s.u_avg, s.mu, c->cfg.eta, st));
   } else if (c->quant) {
-    LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, s.n_clipped, st));
+    LPC_TRY_HIP(launch_quantize(c, s.U, key, s.packed, s.delta, want_clip_counts ? s.n_clipped : nullptr, st));
     LPC_TRY_HIP(launch_dequantize_prox(c, s.packed, s.delta, s.mu, c->cfg.eta, w, nullptr, st));
   } else {
     LPC_TRY_HIP(launch_plain_avg(c, s.U, s.u_avg, st));
@@ -594,7 +595,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       } else {
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
                              c->quant ? kStatsFinal : kStatsNone, st));
-        LPC_TRY(exchange_and_prox(c, key, s.w, st));
+        LPC_TRY(exchange_and_prox(c, key, s.w, tracing, st));
         if (tracing) LPC_TRY(record_iteration(c, t, st));
       }
     }

@@ -277,12 +277,13 @@ __global__ void prepare_qparams_kernel(const double *stats, const float *delta_i
 // of coordinates outside dom(delta, b).  All arithmetic is fp32 without contraction:
 //   s = u*(1/delta), clamp to [-2^(b-1), 2^(b-1)-1], lo = floor(s), frac = s - lo (exact),
 //   U = (word >> 8)*2^-24, code = lo + (U < frac).
-template <int B>
+// COUNT = false leaves the clip count out (it returns 0): the count is wanted by evaluation runs only.
+template <int B, bool COUNT = true>
 __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams &q, const StreamKey &key,
                                                   uint32_t worker, uint32_t block, int32_t (&code)[4]) {
   const float hi = (float)((1 << (B - 1)) - 1);
   const float lo = -(float)(1 << (B - 1));
-  const bool count = q.delta > 0.0f;
+  const bool count = COUNT && q.delta > 0.0f;
   uint32_t clipped = 0;
   const float vals[4] = {v4.x, v4.y, v4.z, v4.w};
   float base[4], frac[4];
@@ -311,7 +312,7 @@ __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams
 
 // Quantize the 32 coordinates of segment `seg` of one worker's vector and store its B packed words at dst.
 // load4(k) returns coordinates 4k..4k+3.  Returns the number of coordinates outside dom(delta, b).
-template <int B, class Load4>
+template <int B, bool COUNT, class Load4>
 __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams &q, const StreamKey &key,
                                                      uint32_t worker, int64_t seg, uint32_t *__restrict__ dst) {
   constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
@@ -322,7 +323,7 @@ __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams 
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
     int32_t code[4];
-    clipped += quantize_four<B>(load4(k), q, key, worker, (uint32_t)(seg * 8 + k), code);
+    clipped += quantize_four<B, COUNT>(load4(k), q, key, worker, (uint32_t)(seg * 8 + k), code);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       bitbuf |= (uint64_t)((uint32_t)code[t] & mask) << nb;
@@ -368,7 +369,7 @@ __device__ __forceinline__ uint32_t assemble_word(const int32_t *__restrict__ co
 
 // ---------------------------------------------------------------------------
 // Quantize + pack.  grid = (tiles of 8192 coordinates, N workers).
-template <int B>
+template <int B, bool COUNT>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad,
                                                             const QParams *__restrict__ qp, StreamKey key,
                                                             uint32_t *__restrict__ packed, int64_t W,
@@ -403,10 +404,10 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
   uint32_t clipped = 0;
   if (active) {
     const float *mine = &tile[tid * kPitch];
-    clipped = quantize_segment<B>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key, worker,
-                                  seg, packed + (int64_t)worker * W + seg * B);
+    clipped = quantize_segment<B, COUNT>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key,
+                                         worker, seg, packed + (int64_t)worker * W + seg * B);
   }
-  if (n_clipped) {
+  if (COUNT) {
     clipped = wave_sum(clipped);
     if ((tid & 63) == 0 && clipped) atomicAdd(&n_clipped[worker], clipped);
   }
@@ -676,7 +677,6 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
     for (int k = 0; k < 4; ++k) { amax = fmax(amax, red[k][0]); sum += red[k][1]; sumsq += red[k][2]; bad += red[k][3]; }
     double *p = sk.stat_part + ((int64_t)worker * sk.stat_slots + blockIdx.x) * 4;
     p[0] = amax; p[1] = sum; p[2] = sumsq; p[3] = bad;
-    if (blockIdx.x == 0) sk.n_clipped[worker] = 0u;  // the quantizer pass adds to it
   }
 }
 
@@ -746,10 +746,9 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
   }
   __syncthreads();
   const QParams q = q_sh;
-  uint32_t clipped = 0;
   if (head) {
     int32_t code[4];
-    clipped = quantize_four<B>(v[0], q, key, worker, (uint32_t)(head_seg * 8 + part), code);
+    quantize_four<B, false>(v[0], q, key, worker, (uint32_t)(head_seg * 8 + part), code);
     *reinterpret_cast<int4 *>(&codes[wv][sub][4 * part]) = make_int4(code[0], code[1], code[2], code[3]);
     __builtin_amdgcn_wave_barrier();
     const int64_t seg0 = (int64_t)blockIdx.x * 32 + wv * 8;  // the wavefront's eight segments are consecutive
@@ -762,7 +761,7 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
         const int32_t i = i0 + 8 * qi + sub;
         if (i < n) {
           int32_t code[4];
-          clipped += quantize_four<B>(v[qi], q, key, worker, (uint32_t)list[i] * 8u + (uint32_t)part, code);
+          quantize_four<B, false>(v[qi], q, key, worker, (uint32_t)list[i] * 8u + (uint32_t)part, code);
           *reinterpret_cast<int4 *>(&codes[wv][8 * qi + sub][4 * part]) = make_int4(code[0], code[1], code[2], code[3]);
         }
       }
@@ -775,8 +774,6 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
       __builtin_amdgcn_wave_barrier();
     }
   }
-  clipped = wave_sum(clipped);
-  if (lane == 0 && clipped) atomicAdd(&sk.n_clipped[worker], clipped);
 }
 
 // ---------------------------------------------------------------------------
@@ -1285,8 +1282,12 @@ template <int B>
 void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
                      uint32_t *n_clipped, hipStream_t st) {
   const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats), (unsigned)c->cfg.N);
-  hipLaunchKernelGGL(quantize_kernel<B>, grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key, packed,
-                     c->W, delta_out, n_clipped);
+  if (n_clipped)
+    hipLaunchKernelGGL((quantize_kernel<B, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key,
+                       packed, c->W, delta_out, n_clipped);
+  else
+    hipLaunchKernelGGL((quantize_kernel<B, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key,
+                       packed, c->W, delta_out, n_clipped);
 }
 
 template <int B, bool PROX>
