@@ -278,7 +278,10 @@ __global__ void prepare_qparams_kernel(const double *stats, const float *delta_i
 //   s = u*(1/delta), clamp to [-2^(b-1), 2^(b-1)-1], lo = floor(s), frac = s - lo (exact),
 //   U = (word >> 8)*2^-24, code = lo + (U < frac).
 // COUNT = false leaves the clip count out (it returns 0): the count is wanted by evaluation runs only.
-template <int B, bool COUNT = true>
+// SKIP: on-grid groups (zeros in particular) draw no random numbers -- worth a branch where vectors are mostly
+// zero (sparse data), a loss where they are dense (the branches keep the compiler from interleaving the eight
+// generator chains of a segment).
+template <int B, bool COUNT = true, bool SKIP = true>
 __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams &q, const StreamKey &key,
                                                   uint32_t worker, uint32_t block, int32_t (&code)[4]) {
   const float hi = (float)((1 << (B - 1)) - 1);
@@ -298,7 +301,7 @@ __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams
     if (count && (vals[t] > q.thresh || vals[t] < q.neg_edge)) ++clipped;
   }
   uint32_t rnd[4] = {0u, 0u, 0u, 0u};
-  if (any) {  // on-grid values (zeros in particular) need no random draw
+  if (!SKIP || any) {  // an on-grid value keeps its code whatever the draw
     const Philox4 blk = stream_block(key, kTagQuant, worker, block);
     rnd[0] = blk.x; rnd[1] = blk.y; rnd[2] = blk.z; rnd[3] = blk.w;
   }
@@ -312,7 +315,7 @@ __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams
 
 // Quantize the 32 coordinates of segment `seg` of one worker's vector and store its B packed words at dst.
 // load4(k) returns coordinates 4k..4k+3.  Returns the number of coordinates outside dom(delta, b).
-template <int B, bool COUNT, class Load4>
+template <int B, bool COUNT, bool SKIP, class Load4>
 __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams &q, const StreamKey &key,
                                                      uint32_t worker, int64_t seg, uint32_t *__restrict__ dst) {
   constexpr uint32_t mask = (B >= 32) ? 0xFFFFFFFFu : ((1u << B) - 1u);
@@ -323,7 +326,7 @@ __device__ __forceinline__ uint32_t quantize_segment(Load4 load4, const QParams 
 #pragma unroll
   for (int k = 0; k < 8; ++k) {
     int32_t code[4];
-    clipped += quantize_four<B, COUNT>(load4(k), q, key, worker, (uint32_t)(seg * 8 + k), code);
+    clipped += quantize_four<B, COUNT, SKIP>(load4(k), q, key, worker, (uint32_t)(seg * 8 + k), code);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       bitbuf |= (uint64_t)((uint32_t)code[t] & mask) << nb;
@@ -369,7 +372,7 @@ __device__ __forceinline__ uint32_t assemble_word(const int32_t *__restrict__ co
 
 // ---------------------------------------------------------------------------
 // Quantize + pack.  grid = (tiles of 8192 coordinates, N workers).
-template <int B, bool COUNT>
+template <int B, bool COUNT, bool SKIP>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad,
                                                             const QParams *__restrict__ qp, StreamKey key,
                                                             uint32_t *__restrict__ packed, int64_t W,
@@ -380,21 +383,30 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
   const uint32_t worker = blockIdx.y;
   const int64_t tile_base = (int64_t)blockIdx.x * kTileFloats;
   const float *u = U + (int64_t)worker * d_pad;
+  if (tile_base + kTileFloats <= d) {  // uniform: a tile inside the vector needs no checks
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int e = r * kThreads + tid;
-    const int64_t j = tile_base + (int64_t)e * 4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (j < d_pad) {
-      v = *reinterpret_cast<const float4 *>(u + j);
-      if (j + 3 >= d) {  // the zero padding of the last segment carries code 0 whatever the buffer holds
-        if (j + 0 >= d) v.x = 0.f;
-        if (j + 1 >= d) v.y = 0.f;
-        if (j + 2 >= d) v.z = 0.f;
-        v.w = 0.f;
-      }
+    for (int r = 0; r < 8; ++r) {
+      const int e = r * kThreads + tid;
+      *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) =
+          *reinterpret_cast<const float4 *>(u + tile_base + (int64_t)e * 4);
     }
-    *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) = v;
+  } else {
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int e = r * kThreads + tid;
+      const int64_t j = tile_base + (int64_t)e * 4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j < d_pad) {
+        v = *reinterpret_cast<const float4 *>(u + j);
+        if (j + 3 >= d) {  // the zero padding of the last segment carries code 0 whatever the buffer holds
+          if (j + 0 >= d) v.x = 0.f;
+          if (j + 1 >= d) v.y = 0.f;
+          if (j + 2 >= d) v.z = 0.f;
+          v.w = 0.f;
+        }
+      }
+      *reinterpret_cast<float4 *>(&tile[(e >> 3) * kPitch + (e & 7) * 4]) = v;
+    }
   }
   __syncthreads();
   const QParams q = qp[worker];
@@ -404,7 +416,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
   uint32_t clipped = 0;
   if (active) {
     const float *mine = &tile[tid * kPitch];
-    clipped = quantize_segment<B, COUNT>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key,
+    clipped = quantize_segment<B, COUNT, SKIP>([&](int k) { return *reinterpret_cast<const float4 *>(mine + k * 4); }, q, key,
                                          worker, seg, packed + (int64_t)worker * W + seg * B);
   }
   if (COUNT) {
@@ -1282,12 +1294,17 @@ template <int B>
 void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
                      uint32_t *n_clipped, hipStream_t st) {
   const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats), (unsigned)c->cfg.N);
+  // evaluation runs and callers of lpc_quantize_clip want the clip counts; the epoch's own launches do not, and
+  // on dense vectors they also draw unconditionally
   if (n_clipped)
-    hipLaunchKernelGGL((quantize_kernel<B, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key,
-                       packed, c->W, delta_out, n_clipped);
+    hipLaunchKernelGGL((quantize_kernel<B, true, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams,
+                       key, packed, c->W, delta_out, n_clipped);
+  else if (c->csr)
+    hipLaunchKernelGGL((quantize_kernel<B, false, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams,
+                       key, packed, c->W, delta_out, n_clipped);
   else
-    hipLaunchKernelGGL((quantize_kernel<B, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams, key,
-                       packed, c->W, delta_out, n_clipped);
+    hipLaunchKernelGGL((quantize_kernel<B, false, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                       c->s.qparams, key, packed, c->W, delta_out, n_clipped);
 }
 
 template <int B, bool PROX>
