@@ -516,7 +516,7 @@ __global__ __launch_bounds__(TPB) void dequantize_kernel(const uint32_t *packed,
     for (int c = 0; c < 32; ++c) acc[c] = 0.0f;
     // several messages in flight at a time (as many as the word count lets the registers hold);
     // accumulation stays in worker order
-    constexpr int kInFlight = B <= 4 ? 16 : (B <= 8 ? 8 : 4);
+    constexpr int kInFlight = B <= 2 ? 16 : (B <= 8 ? 8 : 4);  // measured for B = 4: 8 in flight 22.5 us, 16: 29.2, 4: 23.6
     uint64_t nonzero = 0;
     for (int32_t i0 = 0; i0 < N; i0 += kInFlight) {
       uint32_t wds[kInFlight][B];
