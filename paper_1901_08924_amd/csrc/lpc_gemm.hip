@@ -87,35 +87,93 @@ __device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float
 // values (per thread in fp32 -- at most 64 terms --, in fp64 across threads).
 // Accumulator layout of the 32x32 MFMA: lane l holds column (l % 32); register v holds row
 // 8*(v/4) + 4*(l/32) + (v%4).
-template <int TN>
-__device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&acc)[2][TN / 64], int m0, int n0,
-                                           int64_t bz, int lane, int wm, int wn, float &fmx, float &ssum, float &ssq,
-                                           float &sbad) {
+// The options are compile-time so that the 32 stores of a thread are straight-line code: FULL = the tile lies
+// inside C (no row / column checks).  Rows are reached by pointer steps of ldc, not by a product per element.
+template <int TN, bool FULL, bool BIAS, bool RELU, bool MASK, bool ACC, bool STAT>
+__device__ __forceinline__ void store_tile_as(const GemmArgs &g, const floatx16 (&acc)[2][TN / 64], int m0, int n0,
+                                              int64_t bz, int lane, int wm, int wn, float &fmx, float &ssum,
+                                              float &ssq, float &sbad) {
   constexpr int NJ = TN / 64;
-  float *C = g.C + bz * g.strideC;
-  const float *mask = g.relu_mask ? g.relu_mask + bz * g.strideC : nullptr;
+  const int64_t ldc = g.ldc;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int col = n0 + wn + 32 * j + (lane & 31);
-      if (col >= g.N) continue;
-      const float bias = g.bias ? g.bias[bz * g.strideBias + col] : 0.0f;
+      if (!FULL && col >= g.N) continue;
+      const float bias = BIAS ? g.bias[bz * g.strideBias + col] : 0.0f;
+      const int row0 = m0 + wm + 32 * i + 4 * (lane >> 5);
+      const int64_t off0 = bz * g.strideC + (int64_t)row0 * ldc + col;
+      float *crow = g.C + off0;
+      const float *mrow = MASK ? g.relu_mask + off0 : nullptr;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row >= g.M) continue;
-        const int64_t off = (int64_t)row * g.ldc + col;
+        const int dr = 8 * (v >> 2) + (v & 3);
+        if (!FULL && row0 + dr >= g.M) continue;
+        float *cp = crow + dr * ldc;
         float val = g.alpha * acc[i][j][v] + bias;
-        if (g.relu) val = val > 0.0f ? val : 0.0f;
-        if (mask) val = mask[off] > 0.0f ? val : 0.0f;
-        if (g.accumulate) val += C[off];
-        C[off] = val;
-        if (g.stat_part) {  // uniform
+        if (RELU) val = val > 0.0f ? val : 0.0f;
+        if (MASK) val = mrow[dr * ldc] > 0.0f ? val : 0.0f;
+        if (ACC) val += *cp;
+        *cp = val;
+        if (STAT) {
           if (isfinite(val)) {
             fmx = fmaxf(fmx, fabsf(val)); ssum += val; ssq = fmaf(val, val, ssq);
           } else {
             sbad += 1.0f;
+          }
+        }
+      }
+    }
+  }
+}
+
+// Picks the instantiation for the (uniform) options of this launch: the MLP's products use four combinations;
+// anything else takes the general one.
+template <int TN, bool FULL>
+__device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&acc)[2][TN / 64], int m0, int n0,
+                                           int64_t bz, int lane, int wm, int wn, float &fmx, float &ssum, float &ssq,
+                                           float &sbad) {
+  const bool bias = g.bias != nullptr, relu = g.relu != 0, mask = g.relu_mask != nullptr, accu = g.accumulate != 0,
+             stat = g.stat_part != nullptr;
+  if (bias && relu && !mask && !accu && !stat)          // forward layer
+    store_tile_as<TN, FULL, true, true, false, false, false>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  else if (!bias && !relu && mask && !accu && !stat)    // data gradient
+    store_tile_as<TN, FULL, false, false, true, false, false>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  else if (!bias && !relu && !mask && !accu && stat)    // a worker's weight gradient, with its statistics
+    store_tile_as<TN, FULL, false, false, false, false, true>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  else if (!bias && !relu && !mask && !stat && accu)    // snapshot weight gradient, accumulating
+    store_tile_as<TN, FULL, false, false, false, true, false>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  else if (!bias && !relu && !mask && !stat)            // snapshot weight gradient, first chunk or block
+    store_tile_as<TN, FULL, false, false, false, false, false>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  else {
+    // general: every option decided per element
+    constexpr int NJ = TN / 64;
+    float *C = g.C + bz * g.strideC;
+    const float *mk = mask ? g.relu_mask + bz * g.strideC : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int col = n0 + wn + 32 * j + (lane & 31);
+        if (col >= g.N) continue;
+        const float bv = bias ? g.bias[bz * g.strideBias + col] : 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          if (row >= g.M) continue;
+          const int64_t off = (int64_t)row * g.ldc + col;
+          float val = g.alpha * acc[i][j][v] + bv;
+          if (relu) val = val > 0.0f ? val : 0.0f;
+          if (mk) val = mk[off] > 0.0f ? val : 0.0f;
+          if (accu) val += C[off];
+          C[off] = val;
+          if (stat) {
+            if (isfinite(val)) {
+              fmx = fmaxf(fmx, fabsf(val)); ssum += val; ssq = fmaf(val, val, ssq);
+            } else {
+              sbad += 1.0f;
+            }
           }
         }
       }
@@ -219,7 +277,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 
   float fmx = 0.0f, ssum = 0.0f, ssq = 0.0f, sbad = 0.0f;
-  store_tile<TN>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
+  store_tile<TN, FULL>(g, acc, m0, n0, bz, lane, wm, wn, fmx, ssum, ssq, sbad);
   // LDS is free for the statistics: the K loop ended with a barrier
   if (g.stat_part)
     tile_statistics(g, reinterpret_cast<double *>(&As[0][0][0]), tid, bz,
