@@ -66,6 +66,34 @@ __device__ __forceinline__ void fetch_slab(const float *__restrict__ p, int64_t 
   }
 }
 
+// The same shares for whole tiles (FULL), slab after slab: the thread's address is set up once per segment and
+// then moved by pointer steps, so no product is formed per load.  fetch() reads the next slab, in order.
+template <bool TRANS, int TILE>
+struct SlabWalker {
+  const float *p;
+  int64_t hstep, kstep;
+  __device__ __forceinline__ void init(const float *base, int64_t ld, int mn0, int tid) {
+    if (!TRANS) {
+      p = base + (int64_t)(mn0 + tid / (BK / 4)) * ld + 4 * (tid % (BK / 4));
+      hstep = (int64_t)(1024 / BK) * ld;
+      kstep = BK;
+    } else {
+      p = base + (int64_t)(tid / (TILE / 4)) * ld + mn0 + 4 * (tid % (TILE / 4));
+      hstep = (int64_t)(1024 / TILE) * ld;
+      kstep = (int64_t)BK * ld;
+    }
+  }
+  __device__ __forceinline__ void fetch(float (&r)[TILE * BK / 256]) {
+    constexpr int G = TILE * BK / 1024;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float4 v = *reinterpret_cast<const float4 *>(p + h * hstep);
+      r[4 * h + 0] = v.x; r[4 * h + 1] = v.y; r[4 * h + 2] = v.z; r[4 * h + 3] = v.w;
+    }
+    p += kstep;
+  }
+};
+
 // Store the registers k-major into an LDS slab T[k][mn].
 template <bool TRANS, int TILE>
 __device__ __forceinline__ void stash_slab(float (*T)[LDT], int tid, const float (&r)[TILE * BK / 256]) {
@@ -243,12 +271,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const bool vb = (ldb % 4 == 0) && (((uintptr_t)B & 15u) == 0);
     const int K = g.K;
     const int nslab = (K + BK - 1) / BK;
-    fetch_slab<TA, BM, FULL>(A, lda, m0, 0, g.M, K, va, tid, ra[0]);
-    fetch_slab<!TB, TN, FULL>(B, ldb, n0, 0, g.N, K, vb, tid, rb[0]);
-    if (nslab > 1) {
-      fetch_slab<TA, BM, FULL>(A, lda, m0, BK, g.M, K, va, tid, ra[1]);
-      fetch_slab<!TB, TN, FULL>(B, ldb, n0, BK, g.N, K, vb, tid, rb[1]);
+    SlabWalker<TA, BM> wa;
+    SlabWalker<!TB, TN> wb;
+    if constexpr (FULL) {
+      wa.init(A, lda, m0, tid);
+      wb.init(B, ldb, n0, tid);
     }
+    // slab `at` into register set P (whole tiles: the walkers deliver the slabs in order, `at` is implied)
+#define LPC_GEMM_FETCH(P, at)                                                          \
+    if constexpr (FULL) {                                                              \
+      wa.fetch(ra[(P)]);                                                               \
+      wb.fetch(rb[(P)]);                                                               \
+    } else {                                                                           \
+      fetch_slab<TA, BM, false>(A, lda, m0, (at)*BK, g.M, K, va, tid, ra[(P)]);        \
+      fetch_slab<!TB, TN, false>(B, ldb, n0, (at)*BK, g.N, K, vb, tid, rb[(P)]);       \
+    }
+    LPC_GEMM_FETCH(0, 0)
+    if (nslab > 1) { LPC_GEMM_FETCH(1, 1) }
     __syncthreads();  // the previous segment's last slab has been consumed
     stash_slab<TA, BM>(As[0], tid, ra[0]);
     stash_slab<!TB, TN>(Bs[0], tid, rb[0]);
@@ -258,10 +297,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #define LPC_GEMM_STEP(P)                                                                        \
     {                                                                                           \
       const int slab = t + (P);                                                                 \
-      if (slab + 2 < nslab) {                                                                   \
-        fetch_slab<TA, BM, FULL>(A, lda, m0, (slab + 2) * BK, g.M, K, va, tid, ra[(P)]);        \
-        fetch_slab<!TB, TN, FULL>(B, ldb, n0, (slab + 2) * BK, g.N, K, vb, tid, rb[(P)]);       \
-      }                                                                                         \
+      if (slab + 2 < nslab) { LPC_GEMM_FETCH((P), slab + 2) }                                   \
       consume((P));                                                                             \
       if (slab + 1 < nslab) {                                                                   \
         stash_slab<TA, BM>(As[1 - (P)], tid, ra[1 - (P)]);                                      \
@@ -274,6 +310,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
       if (t + 1 < nslab) LPC_GEMM_STEP(1)
     }
 #undef LPC_GEMM_STEP
+#undef LPC_GEMM_FETCH
   }
 
   float fmx = 0.0f, ssum = 0.0f, ssq = 0.0f, sbad = 0.0f;
