@@ -447,6 +447,8 @@ __device__ __forceinline__ void load_words(const uint32_t *__restrict__ src, uin
   }
 }
 
+constexpr int kQuarterThreads = 128;
+
 // acc[c] = fma(delta, code_c, acc[c]) for the 32 codes of one segment; returns the OR of the words
 template <int B>
 __device__ __forceinline__ uint32_t accumulate_words(const uint32_t (&words)[B], float delta, float (&acc)[32]) {
@@ -576,6 +578,99 @@ __global__ __launch_bounds__(TPB) void dequantize_kernel(const uint32_t *packed,
         if (u_avg) u_avg[j + t] = av[t];
         if constexpr (PROX) pa.w[j + t] = prox_scalar(pa.w[j + t], av[t] + pa.mu[j + t], pa.step, pa.thr, pa.shrink);
       }
+    }
+  }
+}
+
+// The receiver for short vectors and B in {1, 2, 4}: eight coordinates per thread, which lie in one word of
+// each message (8B divides 32).  Four times as many threads as one-segment-per-thread, each with a quarter
+// of the arithmetic between its loads and its stores, and a thread's eight results are contiguous, so no
+// transposition through LDS.  Accumulation order (worker 0 first) and every operation are those of
+// dequantize_kernel.  The threads that share a word sit in one wavefront and load it in one instruction,
+// which has returned before the thread at bit 0 sets the word back to zero.
+template <int B, bool PROX>
+__global__ __launch_bounds__(kQuarterThreads) void dequantize_quarter_kernel(const uint32_t *packed, int64_t W,
+                                                                           const float *__restrict__ delta,
+                                                                           int32_t N, int64_t d, int64_t d_pad,
+                                                                           float *__restrict__ u_avg, ProxArgs pa) {
+  static_assert(32 % (8 * B) == 0, "eight codes in one word");
+  const int64_t q = (int64_t)blockIdx.x * kQuarterThreads + threadIdx.x;
+  const int64_t j = q * 8;
+  if (j >= d_pad) return;
+  const bool whole = j + 8 <= d;
+  float4 w_pre[2], mu_pre[2];
+  if constexpr (PROX) {
+    if (whole) {
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        mu_pre[r] = *reinterpret_cast<const float4 *>(pa.mu + j + 4 * r);
+        w_pre[r] = *reinterpret_cast<const float4 *>(pa.w + j + 4 * r);
+      }
+    }
+  }
+  const int64_t word = (q * B) >> 2;
+  const int shift = (int)((q * 8 * B) & 31);
+  float acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
+  constexpr int kInFlight = 16;
+  uint64_t nonzero = 0;
+  for (int32_t i0 = 0; i0 < N; i0 += kInFlight) {
+    uint32_t wd[kInFlight];
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      const int32_t i = i0 + k < N ? i0 + k : N - 1;
+      wd[k] = packed[(int64_t)i * W + word];
+    }
+#pragma unroll
+    for (int k = 0; k < kInFlight; ++k) {
+      if (i0 + k < N) {
+        const float dl = delta[i0 + k];
+        if (wd[k]) nonzero |= 1ull << ((i0 + k) & 63);
+        const uint32_t part = wd[k] >> shift;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const int32_t code = (int32_t)(part << (32 - B - c * B)) >> (32 - B);
+          acc[c] = __builtin_fmaf(dl, (float)code, acc[c]);
+        }
+      }
+    }
+  }
+  if constexpr (PROX) {
+    if (pa.rezero) {
+      if (shift == 0) {
+        while (nonzero) {
+          const int k = __builtin_ctzll(nonzero);
+          nonzero &= nonzero - 1;
+          pa.rezero[(int64_t)k * W + word] = 0u;
+        }
+      }
+      if ((q & 127) == 0)
+        for (int32_t k = 0; k < N; ++k) pa.touched[(int64_t)k * pa.bitmap_words + (q >> 7)] = 0u;
+    }
+  }
+  const float inv_n = 1.0f / (float)N;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] *= inv_n;
+  if (whole) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const float4 a = make_float4(acc[4 * r], acc[4 * r + 1], acc[4 * r + 2], acc[4 * r + 3]);
+      if (u_avg) *reinterpret_cast<float4 *>(u_avg + j + 4 * r) = a;
+      if constexpr (PROX) {
+        const float4 m = mu_pre[r];
+        float4 w = w_pre[r];
+        w.x = prox_scalar(w.x, a.x + m.x, pa.step, pa.thr, pa.shrink);
+        w.y = prox_scalar(w.y, a.y + m.y, pa.step, pa.thr, pa.shrink);
+        w.z = prox_scalar(w.z, a.z + m.z, pa.step, pa.thr, pa.shrink);
+        w.w = prox_scalar(w.w, a.w + m.w, pa.step, pa.thr, pa.shrink);
+        *reinterpret_cast<float4 *>(pa.w + j + 4 * r) = w;
+      }
+    }
+  } else {
+    for (int t = 0; t < 8 && j + t < d; ++t) {
+      if (u_avg) u_avg[j + t] = acc[t];
+      if constexpr (PROX) pa.w[j + t] = prox_scalar(pa.w[j + t], acc[t] + pa.mu[j + t], pa.step, pa.thr, pa.shrink);
     }
   }
 }
@@ -1314,6 +1409,11 @@ void dequantize_launch(const lpc_ctx *c, const uint32_t *packed, const float *de
   if (wide >= 2 * c->cus) {
     hipLaunchKernelGGL((dequantize_kernel<B, PROX, kThreads>), dim3((unsigned)wide), dim3(kThreads), 0, st, packed, c->W,
                        delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+  } else if constexpr (32 % (8 * B) == 0) {
+    const int64_t threads = c->d_pad / 8;
+    hipLaunchKernelGGL((dequantize_quarter_kernel<B, PROX>),
+                       dim3((unsigned)((threads + kQuarterThreads - 1) / kQuarterThreads)), dim3(kQuarterThreads), 0, st,
+                       packed, c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
   } else {
     const int64_t tile = 64 * kSegFloats;
     hipLaunchKernelGGL((dequantize_kernel<B, PROX, 64>), dim3((unsigned)((c->d_pad + tile - 1) / tile)), dim3(64), 0, st,
