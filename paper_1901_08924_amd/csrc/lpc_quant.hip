@@ -490,7 +490,8 @@ struct ProxArgs {
   int64_t bitmap_words;
 };
 
-// TPB threads per workgroup (one segment each): 256 for long vectors, 64 when that would leave CUs without work
+// The receiver for the bit widths that do not divide a word.  TPB threads per workgroup (one segment each): 256
+// for long vectors, 64 when that would leave CUs without work
 template <int B, bool PROX, int TPB>
 __global__ __launch_bounds__(TPB) void dequantize_kernel(const uint32_t *packed, int64_t W,
                                                               const float *__restrict__ delta, int32_t N, int64_t d,
@@ -582,7 +583,7 @@ __global__ __launch_bounds__(TPB) void dequantize_kernel(const uint32_t *packed,
   }
 }
 
-// The receiver for short vectors and B in {1, 2, 4}: eight coordinates per thread, which lie in one word of
+// The receiver for B in {2, 4}: eight coordinates per thread, which lie in one word of
 // each message (8B divides 32).  Four times as many threads as one-segment-per-thread, each with a quarter
 // of the arithmetic between its loads and its stores, and a thread's eight results are contiguous, so no
 // transposition through LDS.  Accumulation order (worker 0 first) and every operation are those of
@@ -1405,19 +1406,21 @@ void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *
 template <int B, bool PROX>
 void dequantize_launch(const lpc_ctx *c, const uint32_t *packed, const float *delta, float *u_avg, ProxArgs pa,
                        hipStream_t st) {
-  const int64_t wide = (c->d_pad + kTileFloats - 1) / kTileFloats;
-  if (wide >= 2 * c->cus) {
-    hipLaunchKernelGGL((dequantize_kernel<B, PROX, kThreads>), dim3((unsigned)wide), dim3(kThreads), 0, st, packed, c->W,
-                       delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
-  } else if constexpr (32 % (8 * B) == 0) {
+  if constexpr (32 % (8 * B) == 0) {
     const int64_t threads = c->d_pad / 8;
     hipLaunchKernelGGL((dequantize_quarter_kernel<B, PROX>),
                        dim3((unsigned)((threads + kQuarterThreads - 1) / kQuarterThreads)), dim3(kQuarterThreads), 0, st,
                        packed, c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
   } else {
-    const int64_t tile = 64 * kSegFloats;
-    hipLaunchKernelGGL((dequantize_kernel<B, PROX, 64>), dim3((unsigned)((c->d_pad + tile - 1) / tile)), dim3(64), 0, st,
-                       packed, c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+    const int64_t wide = (c->d_pad + kTileFloats - 1) / kTileFloats;
+    if (wide >= 2 * c->cus) {
+      hipLaunchKernelGGL((dequantize_kernel<B, PROX, kThreads>), dim3((unsigned)wide), dim3(kThreads), 0, st, packed,
+                         c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+    } else {
+      const int64_t tile = 64 * kSegFloats;
+      hipLaunchKernelGGL((dequantize_kernel<B, PROX, 64>), dim3((unsigned)((c->d_pad + tile - 1) / tile)), dim3(64), 0,
+                         st, packed, c->W, delta, c->cfg.N, c->d, c->d_pad, u_avg, pa);
+    }
   }
 }
 
