@@ -582,6 +582,77 @@ int gemm_tiles(const GemmArgs &g) {
   return ((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
 }
 
+// The same product when K <= 128 (a worker's rows of one batch): every row of A and B that the workgroup needs
+// is requested before anything is consumed, one round trip instead of one per operand and parameter set.
+// Rows are taken in the order of gemm_skinny_tn_kernel, so the sums are the same to the bit.
+__global__ __launch_bounds__(256) void gemm_skinny_tn_short_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) float Bs[2 * 128 * kSkinnyN];  // [segment][k][16], then [4][64][16]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t bz = blockIdx.y;
+  const int m = blockIdx.x * 64 + lane;
+  const int kn = g.K;
+  float a[2][32];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const float *A = g.A[s < g.nseg ? s : 0] + bz * g.strideA[s < g.nseg ? s : 0];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      const int k = wave + 4 * j;
+      a[s][j] = (s < g.nseg && k < kn && m < g.M) ? A[(int64_t)k * g.lda[s < g.nseg ? s : 0] + m] : 0.0f;
+    }
+  }
+  float t[2][8];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const float *B = g.B[s < g.nseg ? s : 0] + bz * g.strideB[s < g.nseg ? s : 0];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = tid + j * 256, k = i >> 4, c = i & 15;
+      t[s][j] = (s < g.nseg && k < kn && c < g.N) ? B[(int64_t)k * g.ldb[s < g.nseg ? s : 0] + c] : 0.0f;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) Bs[s * 128 * kSkinnyN + tid + j * 256] = t[s][j];
+  __syncthreads();
+  float acc[kSkinnyN];
+#pragma unroll
+  for (int c = 0; c < kSkinnyN; ++c) acc[c] = 0.0f;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+      // rows past K and the absent second segment hold zeros in a[][] and in Bs
+      const float4 *b = reinterpret_cast<const float4 *>(&Bs[(s * 128 + wave + 4 * j) * kSkinnyN]);
+      const float4 b0 = b[0], b1 = b[1], b2 = b[2], b3 = b[3];
+      const float av = a[s][j];
+      acc[0] = fmaf(av, b0.x, acc[0]); acc[1] = fmaf(av, b0.y, acc[1]);
+      acc[2] = fmaf(av, b0.z, acc[2]); acc[3] = fmaf(av, b0.w, acc[3]);
+      acc[4] = fmaf(av, b1.x, acc[4]); acc[5] = fmaf(av, b1.y, acc[5]);
+      acc[6] = fmaf(av, b1.z, acc[6]); acc[7] = fmaf(av, b1.w, acc[7]);
+      acc[8] = fmaf(av, b2.x, acc[8]); acc[9] = fmaf(av, b2.y, acc[9]);
+      acc[10] = fmaf(av, b2.z, acc[10]); acc[11] = fmaf(av, b2.w, acc[11]);
+      acc[12] = fmaf(av, b3.x, acc[12]); acc[13] = fmaf(av, b3.y, acc[13]);
+      acc[14] = fmaf(av, b3.z, acc[14]); acc[15] = fmaf(av, b3.w, acc[15]);
+    }
+  }
+  __syncthreads();
+  float *red = Bs;  // [4][64][16]
+#pragma unroll
+  for (int c = 0; c < kSkinnyN; ++c) red[(wave * 64 + lane) * kSkinnyN + c] = acc[c];
+  __syncthreads();
+  float *C = g.C + bz * g.strideC;
+  for (int i = tid; i < 64 * kSkinnyN; i += 256) {
+    const int l = i >> 4, c = i & 15, row = blockIdx.x * 64 + l;
+    if (row < g.M && c < g.N) {
+      const float r = ((red[(0 * 64 + l) * kSkinnyN + c] + red[(1 * 64 + l) * kSkinnyN + c]) +
+                       red[(2 * 64 + l) * kSkinnyN + c]) + red[(3 * 64 + l) * kSkinnyN + c];
+      skinny_store(g, C, bz, row, c, r);
+    }
+  }
+}
+
 // Validates shapes on the host (every access in the kernel is guarded by M, N, K).
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.nseg < 1 || g.nseg > 2 || g.batch < 1) return hipErrorInvalidValue;
@@ -593,6 +664,9 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
       const size_t lds = (size_t)g.N * (kc + 4) * sizeof(float);
       hipLaunchKernelGGL(gemm_skinny_nn_kernel, dim3((unsigned)((g.M + 15) / 16), (unsigned)g.batch), dim3(256), lds, st,
                          g, kc);
+    } else if (g.K <= 128) {
+      hipLaunchKernelGGL(gemm_skinny_tn_short_kernel, dim3((unsigned)((g.M + 63) / 64), (unsigned)g.batch), dim3(256), 0,
+                         st, g);
     } else {
       int kc = 768;  // 48 KB of B rows; the reduction buffer needs 16 KB
       if (kc > g.K) kc = g.K;
