@@ -80,7 +80,9 @@ struct LastArgs {
   double *row_loss;     // set 0 only, or nullptr
 };
 
-__global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
+template <int R>
+__global__ __launch_bounds__(64 * kLastRows / R) void last_layer_kernel(LastArgs g) {
+  constexpr int kThreadsLast = 64 * kLastRows / R;
   extern __shared__ float Wt[];  // [C][K + 4], then bias [C]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int set = blockIdx.y;
@@ -88,13 +90,13 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
   const float *W = g.W + (int64_t)set * g.w_set_stride;
   float *bias = Wt + g.C * pitch;
   const float sign = set == 0 ? 1.0f : -1.0f;
-  const int row0 = blockIdx.x * kLastRows + wave * 4;
+  const int row0 = blockIdx.x * kLastRows + wave * R;
   const int lc = lane & 15;
   const float *a = g.a + (int64_t)set * g.a_set_stride;
-  // this lane's activations of the wavefront's four rows (K <= 1024: at most four groups of four per row)
-  float4 av[4][4];
+  // this lane's activations of the wavefront's R rows (K <= 1024: at most four groups of four per row)
+  float4 av[R][4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+  for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int k = 256 * q + 4 * lane;
@@ -103,49 +105,52 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
     }
   // W goes to LDS while the activations are on their way
   const uint32_t inv_c = (uint32_t)((0x100000000ull + (uint32_t)g.C - 1) / (uint32_t)g.C);
-  for (int i0 = tid; i0 < g.K * g.C; i0 += 20 * 256) {  // twenty elements in flight per thread
-    float t[20];
+  constexpr int kStage = 20;  // elements in flight per thread
+  for (int i0 = tid; i0 < g.K * g.C; i0 += kStage * kThreadsLast) {
+    float t[kStage];
 #pragma unroll
-    for (int j = 0; j < 20; ++j) t[j] = i0 + j * 256 < g.K * g.C ? W[i0 + j * 256] : 0.0f;
+    for (int j = 0; j < kStage; ++j) t[j] = i0 + j * kThreadsLast < g.K * g.C ? W[i0 + j * kThreadsLast] : 0.0f;
 #pragma unroll
-    for (int j = 0; j < 20; ++j) {
+    for (int j = 0; j < kStage; ++j) {
       // i / C by a multiply: exact for i < 2^16 and C <= 16 with the rounded-up reciprocal 2^32 / C
-      const int i = i0 + j * 256, k = (int)__umulhi((uint32_t)i, inv_c), c = i - k * g.C;
+      const int i = i0 + j * kThreadsLast, k = (int)__umulhi((uint32_t)i, inv_c), c = i - k * g.C;
       if (i < g.K * g.C) Wt[c * pitch + k] = t[j];
     }
   }
   if (tid < g.C) bias[tid] = W[g.bias_off + tid];
   __syncthreads();
-  // logits: one read of a column of W serves the four rows; lane (16j + c) keeps z[c] of each row
-  float z[4];
+  // logits: one read of a column of W serves the wavefront's rows; lane (16j + c) keeps z[c] of each row
+  float z[R];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) z[r] = -INFINITY;
+  for (int r = 0; r < R; ++r) z[r] = -INFINITY;
 #pragma unroll
   for (int c = 0; c < kLastMaxC; ++c) {
     if (c < g.C) {  // uniform
-      float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      float s[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) s[r] = 0.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int k = 256 * q + 4 * lane;
         if (k < g.K) {
           const float4 w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
 #pragma unroll
-          for (int r = 0; r < 4; ++r)
+          for (int r = 0; r < R; ++r)
             s[r] = fmaf(av[r][q].x, w4.x, fmaf(av[r][q].y, w4.y, fmaf(av[r][q].z, w4.z, fmaf(av[r][q].w, w4.w, s[r]))));
         }
       }
       const float bc = bias[c];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < R; ++r) {
         const float t = wave_sum(s[r]) + bc;
         z[r] = lc == c ? t : z[r];
       }
     }
   }
   // softmax cross-entropy inside each row of 16 lanes (lanes c >= C hold -inf and contribute exp = 0)
-  float dl[4];
+  float dl[R];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
+  for (int r = 0; r < R; ++r) {
     const int row = row0 + r < g.rows ? row0 + r : g.rows - 1;
     const float mx = row16_max(z[r]);
     const float e = lc < g.C ? expf(z[r] - mx) : 0.0f;
@@ -164,16 +169,16 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int k = 256 * q + 4 * lane;
-      float4 o[4];
+      float4 o[R];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) o[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int r = 0; r < R; ++r) o[r] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int c = 0; c < kLastMaxC; ++c) {
         if (c < g.C) {
           float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
           if (k < g.K) w4 = *reinterpret_cast<const float4 *>(&Wt[c * pitch + k]);
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
+          for (int r = 0; r < R; ++r) {
             const float dc = read_lane(dl[r], c);
             o[r].x = fmaf(dc, w4.x, o[r].x); o[r].y = fmaf(dc, w4.y, o[r].y);
             o[r].z = fmaf(dc, w4.z, o[r].z); o[r].w = fmaf(dc, w4.w, o[r].w);
@@ -181,7 +186,7 @@ __global__ __launch_bounds__(256) void last_layer_kernel(LastArgs g) {
         }
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 0; r < R; ++r) {
         if (row0 + r >= g.rows || k >= g.K) continue;
         float4 t = o[r];
         t.x = av[r][q].x > 0.0f ? t.x : 0.0f; t.y = av[r][q].y > 0.0f ? t.y : 0.0f;
@@ -351,8 +356,10 @@ hipError_t backward_data(const Net &nn, const float *W, int64_t wstride, int nse
     g.delta_prev = l >= 1 ? nn.del(l, 0) : nullptr; g.dp_set_stride = nn.rows_cap * nn.dims[l];
     g.row_loss = row_loss;
     const size_t lds = ((size_t)classes * (g.K + 4) + classes) * sizeof(float);
-    hipLaunchKernelGGL(last_layer_kernel, dim3((unsigned)((rows + kLastRows - 1) / kLastRows), (unsigned)nsets),
-                       dim3(256), lds, st, g);
+    constexpr int kRowsPerWave = 2;  // eight wavefronts per workgroup: 21.7 us per worker pass; four rows each 24.2, one row 29.6
+    hipLaunchKernelGGL(last_layer_kernel<kRowsPerWave>,
+                       dim3((unsigned)((rows + kLastRows - 1) / kLastRows), (unsigned)nsets),
+                       dim3(64 * kLastRows / kRowsPerWave), lds, st, g);
     first = nn.L - 2;
   } else {
     for (int set = 0; set < nsets; ++set)
