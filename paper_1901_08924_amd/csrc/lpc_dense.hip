@@ -331,9 +331,10 @@ int dense_full_grad_wgs(int64_t n, int64_t d, int cus) {
 int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus) {
   (void)d;
   int64_t rows = (int64_t)N * B / cus;
-  // measured: two rows per workgroup beat four up to four sampled rows per CU (more workgroups pulling rows
-  // outweigh the extra partial rows the fold has to read)
-  int rpw = rows >= 8 ? 4 : (rows >= 2 ? 2 : 1);
+  // measured: below four sampled rows per CU two rows per workgroup beat four (more workgroups pulling rows
+  // outweigh the extra partial rows the fold has to read); at four rows per CU four per workgroup win (worker
+  // pass +0.8 us, fold -1.3 us)
+  int rpw = rows >= 4 ? 4 : (rows >= 2 ? 2 : 1);
   return (B + rpw - 1) / rpw;
 }
 
