@@ -1340,10 +1340,11 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
   // `out` and `stats_out` point at the row of the first vector of this launch; vec_begin only selects
   // the scratch slots (statistics, quantizer parameters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
-  // a wavefront takes eight partial rows per step: two wavefronts for up to 16 rows, four beyond (measured back
-  // to back on one machine: 16 rows, two against four wavefronts +0.9 % inner iterations/s, eight -3.9 %;
+  // a wavefront takes eight partial rows per step: two wavefronts for up to 16 rows when the launch has
+  // workgroups to spare, four otherwise (measured back to back on one machine: 16 rows and 2176 workgroups, two
+  // against four wavefronts +0.9 % inner iterations/s, eight -3.9 %; 16 rows and 4 workgroups, two -2 %;
   // 32 rows, two -2.3 %, eight +0.2 %)
-  if (parts <= 16)
+  if (parts <= 16 && (int64_t)grid.x * grid.y >= 2 * c->cus)
     hipLaunchKernelGGL(reduce_parts_kernel<2>, grid, dim3(128), 0, st, part, parts, c->d, c->d_pad, scale, out,
                        ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
   else
