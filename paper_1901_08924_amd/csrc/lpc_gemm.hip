@@ -249,6 +249,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   // is in flight, so a slab's loads have two slabs' worth of matrix-unit time to arrive.
   float ra[2][BM * BK / 256], rb[2][TN * BK / 256];
   auto consume = [&](int cur) {
+    // the wavefront that has its operands in LDS goes first: +0.5 % on the MLP workload, back to back
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
       const int kr = kk + (lane >> 5), c = lane & 31;
@@ -262,6 +264,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   for (int s = 0; s < g.nseg; ++s) {
     const float *A = g.A[s] + bz * g.strideA[s];
