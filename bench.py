@@ -119,13 +119,9 @@ def cpu_baseline(sp, cfgkw, alpc):
 def contraction_shapes():
     """The products of C5's layers (2048 rows per worker pass, 16 workers, snapshot chunks of 2048 rows) and a
     4096^3 reference, each timed alone with HIP events: M, N, K, transposed operands, time, TFLOP/s."""
-    import ctypes as C
     import torch
     from paper_1901_08924_amd import lpc
     fn = lpc.lib.lpc_debug_gemm
-    fn.restype = C.c_int
-    fn.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_float, C.c_void_p,
-                                                                        C.c_int, C.c_int, C.c_void_p]
     st = torch.cuda.Stream()
     torch.cuda.set_stream(st)
     shapes = [("forward layer 1", 2048, 1024, 3072, 0, 0), ("forward layer 2", 2048, 1024, 1024, 0, 0),
@@ -168,6 +164,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--iter-launches", type=int, default=None, choices=[2, 3],
+                    help="launches per dense inner iteration (lpc_tune; default: the library's choice)")
+    ap.add_argument("--iter-tile", type=int, default=None, choices=[64, 128])
+    ap.add_argument("--iter-threads", type=int, default=None, choices=[256, 512])
     ap.add_argument("--small", action="store_true", help="scaled-down problem (quick functional run)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run ten 1 GiB device-to-device copies (a kernel of known traffic: 1 GiB read, "
@@ -217,6 +217,10 @@ def main():
     cfgkw = dict(algo=sp.algo, N=sp.N, B=sp.B, m=sp.m, bits=sp.bits, clip_mode=sp.clip_mode, clip=sp.clip,
                  eta=sp.eta, L=sp.L, seed=sp.seed, n_full=sp.n_full)
     ctx = lpc.context_from_problem(sp)
+    for key, val in ((lpc.TUNE_ITER_LAUNCHES, args.iter_launches), (lpc.TUNE_ITER_TILE, args.iter_tile),
+                     (lpc.TUNE_ITER_THREADS, args.iter_threads)):
+        if val is not None:
+            ctx.tune(key, val)
     n, d, N, B, m, bits = sp.n, sp.d, sp.N, sp.B, sp.m, sp.bits
     dp = lpc.d_pad(d)
     nnz = int(sp.csr[2].size) if sp.csr is not None else 0

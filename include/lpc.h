@@ -188,7 +188,8 @@ lpc_status lpc_objective(lpc_ctx *ctx, const float *w, double *P_out_host, void 
 
 /* Reads and clears the context's device-side flags (synchronises the stream):
  * returns LPC_ENONFINITE if any vector seen by the statistics pass since the last
- * call held a NaN or Inf, else LPC_OK. */
+ * call held a NaN or Inf; LPC_EDEVICE if a workgroup of the two-launch inner iteration gave up
+ * waiting for the others (the iterates since then are not to be trusted); else LPC_OK. */
 lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream);
 
 /* ---- evaluators (outside the timed path) --------------------------------------------------
@@ -275,6 +276,33 @@ typedef enum {
 } lpc_prof_class;
 lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on);
 lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, void *stream);
+
+/* ---- unit-test and benchmark entry of the MLP instance's contraction kernel (no passage of the paper) ----
+ * C (M x N, row-major, leading dimension ldc) = [C +] alpha * op(A) * op(B) [+ bias[n]] [then ReLU] in fp32 on
+ * the matrix cores (output widths of at most 16 columns take the vector units): op(A) is M x K, stored
+ * [M][K] (lda >= K), or [K][M] with transA (lda >= M); op(B) is K x N, stored [K][N] (ldb >= N), or [N][K]
+ * with transB (ldb >= K).  bias: N floats or NULL.  All pointers are device pointers.  Only enqueues. */
+lpc_status lpc_debug_gemm(const float *A, const float *B, float *C, int32_t M, int32_t N, int32_t K, int64_t lda,
+                          int64_t ldb, int64_t ldc, int32_t transA, int32_t transB, float alpha, const float *bias,
+                          int32_t relu, int32_t accumulate, void *stream);
+
+/* ---- tuning and test aid (no passage of the paper) -----------------------------------------
+ * Launch-shape knobs of the inner iteration on small dense problems, which lpc_epoch can run as two launches
+ * (the workers' rows; then fold of the partial rows + exchange + update, whose workgroups wait, for a bounded
+ * number of polls, for each other's statistics) instead of three.  Results do not depend on any of them.
+ *   LPC_TUNE_ITER_LAUNCHES: 3 (default: fold and exchange as separate launches) or 2;
+ *   LPC_TUNE_ITER_TILE: coordinates per workgroup of the second launch, 64 or 128;
+ *   LPC_TUNE_ITER_THREADS: its threads per workgroup, 256 or 512;
+ *   LPC_TUNE_SPIN_LIMIT: polls before a workgroup gives up waiting (it then finishes normally with what it has
+ *     and lpc_take_device_flags reports LPC_EDEVICE); 0 makes every wait give up at once (tests of that path).
+ * LPC_EINVAL for an unknown key or value, LPC_EUNSUPPORTED where the context cannot run two launches. */
+typedef enum {
+  LPC_TUNE_ITER_LAUNCHES = 0,
+  LPC_TUNE_ITER_TILE = 1,
+  LPC_TUNE_ITER_THREADS = 2,
+  LPC_TUNE_SPIN_LIMIT = 3
+} lpc_tune_key;
+lpc_status lpc_tune(lpc_ctx *ctx, int32_t key, int64_t value);
 
 #ifdef __cplusplus
 }

@@ -25,6 +25,9 @@
  *   LPC-SVRG loop     : quantization off == separately written prox-SVRG
  *                       (Theorem 1 setting); minimiser vs library solvers
  *   ALPC-SVRG         : ridge closed form, m=1 snapshot rule, unbiased v-hat
+ *   MLP               : autograd of the same network (library routine); the
+ *                       ReLU-margin helper on a hand-built network with known
+ *                       pre-activations
  *   parity unpinned   : the c*sigma clip convention, the choice of eta, and the
  *                       softmax-MLP gradient beyond finite differences
  */

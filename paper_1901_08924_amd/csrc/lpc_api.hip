@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "lpc_internal.h"
@@ -43,7 +44,8 @@ struct ProfScope {
 lpc_status check_problem(const lpc_problem *p) {
   if (!p) return LPC_ENULL;
   if (p->n <= 0 || p->d <= 0) return LPC_ESHAPE;
-  if (p->n > (int64_t)0xFFFFFFFFll) return LPC_ESHAPE;
+  // row indices, coordinate indices and segment counters are 32-bit (the random stream's counter word too)
+  if (p->n > (int64_t)0xFFFFFFFFll || p->d > (int64_t)0xFFFFFFFFll) return LPC_ESHAPE;
   if (!p->y) return LPC_ENULL;
   if (p->loss != LPC_LOSS_LOGISTIC && p->loss != LPC_LOSS_SQUARED && p->loss != LPC_LOSS_MLP_SOFTMAX)
     return LPC_EINVAL;
@@ -134,6 +136,7 @@ size_t layout(lpc_ctx *c, char *base) {
   s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * c->cfg.N * c->cfg.B : 1) * sizeof(RowPlan));
   s.warm_sink = (float *)take(sizeof(float));
   s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
+  s.iter_slots = (unsigned long long *)take((c->iter2_capable ? (size_t)fused_iter_slot_words(c) : 1) * sizeof(unsigned long long));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
     s.mlp_yb = (float *)take((size_t)c->mlp_rows * sizeof(float));
@@ -212,6 +215,10 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
       need += (int64_t)(c->mlp_dims[l] / 128 + 1) * (c->mlp_dims[l + 1] / 64 + 1) + 2;
     if (need > c->stat_slots) c->stat_slots = (int32_t)need;
   }
+  // measured on MI355X: the statistics' trip through device-scope atomics (about 3 us a round) costs more than the
+  // launch it saves (d = 4096, N = 8: 50.6 k against 59.1 k inner iterations/s), so three launches stay the default
+  c->iter2_capable = fused_iter_supported(c);
+  c->iter2 = false;
   return LPC_OK;
 }
 
@@ -439,6 +446,30 @@ void lpc_destroy(lpc_ctx *ctx) {
   delete ctx;
 }
 
+lpc_status lpc_tune(lpc_ctx *ctx, int32_t key, int64_t value) {
+  if (!ctx) return LPC_ENULL;
+  switch (key) {
+    case LPC_TUNE_ITER_LAUNCHES:
+      if (value != 2 && value != 3) return LPC_EINVAL;
+      if (value == 2 && !ctx->iter2_capable) return LPC_EUNSUPPORTED;
+      ctx->iter2 = value == 2;
+      return LPC_OK;
+    case LPC_TUNE_ITER_TILE:
+      if (value != 64 && value != 128) return LPC_EINVAL;
+      ctx->iter_tile = (int32_t)value;
+      return LPC_OK;
+    case LPC_TUNE_ITER_THREADS:
+      if (value != 256 && value != 512) return LPC_EINVAL;
+      ctx->iter_threads = (int32_t)value;
+      return LPC_OK;
+    case LPC_TUNE_SPIN_LIMIT:
+      if (value < 0 || value > (int64_t)(1 << 24)) return LPC_EINVAL;
+      ctx->spin_limit = (uint32_t)value;
+      return LPC_OK;
+  }
+  return LPC_EINVAL;
+}
+
 lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on) {
   if (!ctx) return LPC_ENULL;
   ctx->prof_on = on != 0;
@@ -563,7 +594,9 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
     const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A && !tracing;
+    const bool two = fused && c->iter2;
     const bool sparse = c->csr_sparse && !tracing;
+    if (two) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
     if (sparse) {
       // the sparse passes rely on U, the bitmap and the packed words being zero where nothing was written
       LPC_TRY_HIP(launch_zero(s.U, (int64_t)g.N * c->d_pad, st));
@@ -586,6 +619,14 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
         ProfScope ps(c, LPC_PROF_EXCHANGE, st);
         LPC_TRY_HIP(launch_sparse_quantize(c, key, st));
         LPC_TRY_HIP(launch_sparse_receive_prox(c, s.mu, g.eta, s.w, st));
+      } else if (two) {
+        // two launches per inner iteration: rows; fold + exchange + prox
+        {
+          ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+          LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, false, st));
+        }
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        LPC_TRY_HIP(launch_fused_iter(c, key, s.packed, s.delta, s.mu, g.eta, s.w, nullptr, st));
       } else if (fused) {
         // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
         int32_t slots = 0;
@@ -613,11 +654,25 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
     // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
+    if (c->iter2) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       {
         ProfScope ps(c, LPC_PROF_VR_ROWS, st);
         LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, true, st));
+      }
+      if (c->iter2) {
+        // two launches per inner iteration: the rows above; fold + exchange + Alg. 2 steps 13-15 + next step 6
+        AlpcStep al{};
+        al.x = s.w; al.u_hat = nullptr; al.w_snap = w_snap; al.mu = s.mu;
+        al.y = y; al.z = z; al.ysum = s.ysum; al.x_next = s.w;
+        al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
+        al.first = t == 0 ? 1 : 0;
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        LPC_TRY_HIP(launch_fused_iter(c, key, s.packed, s.delta, nullptr, 0.0f, nullptr, &al, st));
+        wsum += weight;
+        weight *= (double)ap.theta;
+        continue;
       }
       {
         ProfScope ps(c, LPC_PROF_VR_FOLD, st);
@@ -800,6 +855,7 @@ lpc_status lpc_take_device_flags(lpc_ctx *ctx, void *stream) {
   LPC_TRY_HIP(hipMemcpyAsync(flags, ctx->s.flags, sizeof(flags), hipMemcpyDeviceToHost, st));
   LPC_TRY_HIP(hipStreamSynchronize(st));
   LPC_TRY_HIP(launch_fill_u32(ctx->s.flags, 0u, 4, st));
+  if (flags[0] & 2u) return LPC_EDEVICE;  // a workgroup of the two-launch iteration gave up waiting for the others
   return (flags[0] & 1u) ? LPC_ENONFINITE : LPC_OK;
 }
 

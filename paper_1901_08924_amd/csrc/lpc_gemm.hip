@@ -708,14 +708,16 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t st) {
 
 }  // namespace lpc
 
-// Exported for the unit test of the contraction itself (not part of include/lpc.h): all pointers are
-// device pointers, row-major, C is M x N.
-extern "C" int lpc_debug_gemm(const float *A, const float *B, float *C, int M, int N, int K, int64_t lda, int64_t ldb,
-                              int64_t ldc, int transA, int transB, float alpha, const float *bias, int relu,
-                              int accumulate, void *stream) {
+// Declared in include/lpc.h among the measurement and test aids.
+extern "C" lpc_status lpc_debug_gemm(const float *A, const float *B, float *C, int32_t M, int32_t N, int32_t K,
+                                     int64_t lda, int64_t ldb, int64_t ldc, int32_t transA, int32_t transB,
+                                     float alpha, const float *bias, int32_t relu, int32_t accumulate, void *stream) {
+  if (!A || !B || !C) return LPC_ENULL;
+  if (M <= 0 || N <= 0 || K <= 0) return LPC_ESHAPE;
+  if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N) return LPC_ESHAPE;
   lpc::GemmArgs g{};
   g.A[0] = A; g.B[0] = B; g.C = C; g.M = M; g.N = N; g.K = K; g.lda[0] = lda; g.ldb[0] = ldb; g.ldc = ldc;
   g.transA = transA; g.transB = transB; g.alpha = alpha; g.bias = bias; g.relu = relu; g.accumulate = accumulate;
   g.nseg = 1; g.batch = 1;
-  return lpc::launch_gemm(g, (hipStream_t)stream) == hipSuccess ? 0 : -6;
+  return lpc::launch_gemm(g, (hipStream_t)stream) == hipSuccess ? LPC_OK : LPC_EDEVICE;
 }

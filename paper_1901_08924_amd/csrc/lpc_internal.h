@@ -98,6 +98,8 @@ struct Scratch {
   int32_t *csc_rows;    // [nnz] row index per entry, ascending inside a column
   float *csc_vals;      // [nnz]
   float *csc_coef;      // [n] per-row loss slopes of the snapshot pass
+  unsigned long long *iter_slots;  // two sets of [tiles][N][4] statistics exchanged between the workgroups of the
+                                   // two-launch inner iteration (all ones = empty)
   uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
   // MLP instance: gathered inputs/labels and per-layer activations / deltas for the two parameter sets
   float *mlp_xb;        // [rows][dims[0]]
@@ -134,6 +136,10 @@ struct lpc_ctx {
   int32_t stat_slots;     // statistic partials per vector
   int32_t cus;            // compute units of the device (256 on MI355X)
   int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
+  bool iter2 = false;      // dense inner iterations run as two launches (rows; fold + exchange + update)
+  bool iter2_capable = false;  // ... and the context's scratch holds what that needs
+  int32_t iter_tile = 128, iter_threads = 512;  // launch shape of the second one
+  uint32_t spin_limit = 1u << 15;               // polls a workgroup of it waits for the others' statistics
   bool csc_ready = false;  // the column-major tail copy exists (CSR snapshot pass without atomics)
   int32_t csc_medium = 0, csc_long = 0;  // tail columns served by 16 lanes / by a wavefront
   bool csr_sparse = false; // inner iterations of Alg. 1 keep u^i sparse (CSR rows that touch few columns)
@@ -216,6 +222,13 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
 // stats_mode values of launch_reduce_parts
 constexpr int kStatsNone = 0, kStatsFinal = 1, kStatsPartial = 2;
 bool fused_exchange_supported(const lpc_ctx *c);
+int reduce_parts_waves(const lpc_ctx *c, int32_t parts, int32_t nvec);
+struct AlpcStep;
+bool fused_iter_supported(const lpc_ctx *c);
+int64_t fused_iter_slot_words(const lpc_ctx *c);
+hipError_t launch_fused_iter_reset(const lpc_ctx *c, hipStream_t st);
+hipError_t launch_fused_iter(const lpc_ctx *c, StreamKey key, uint32_t *packed, float *delta_out, const float *mu,
+                             float step, float *w, const AlpcStep *al, hipStream_t st);
 hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslots, StreamKey key, uint32_t *packed,
                                  float *delta_out, const float *mu, float step, float *w, float *u_avg_out,
                                  hipStream_t st);

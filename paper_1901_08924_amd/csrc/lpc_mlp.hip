@@ -521,8 +521,12 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const int in0 = nn.dims[0];
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, c->prob.X, c->prob.ldx, c->prob.y,
                      c->n, in0, key, tag, worker_begin, B, c->s.mlp_xb, c->s.mlp_yb);
-  // both parameter sets ride in one batched product per layer (set 1 = the snapshot, w_snap - w floats away)
-  const int64_t wstride = w_snap - w;
+  // both parameter sets ride in one batched product per layer: set 1 = the snapshot, addressed as set 0's device
+  // address plus a signed distance.  The two vectors are separate allocations of one flat device address space,
+  // so the distance is formed from the addresses as integers (both are 16-byte aligned: the ABI layer checks).
+  const intptr_t wbytes = (intptr_t)w_snap - (intptr_t)w;
+  if (wbytes % 16 != 0) return hipErrorInvalidValue;
+  const int64_t wstride = (int64_t)(wbytes / (intptr_t)sizeof(float));
   hipError_t e = forward(nn, w, wstride, 2, c->s.mlp_xb, in0, rows, st);
   if (e != hipSuccess) return e;
   e = backward_data(nn, w, wstride, 2, c->s.mlp_xb, in0, c->s.mlp_yb, rows, nullptr, st);

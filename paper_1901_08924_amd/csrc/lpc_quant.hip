@@ -312,6 +312,7 @@ __device__ __forceinline__ uint32_t quantize_four(const float4 v4, const QParams
   for (int t = 0; t < 4; ++t) {
     const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
     code[t] = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);  // rule (1)
+    if (!(q.delta > 0.0f)) code[t] = 0;  // an all-zero vector: every code is 0, also where the vector holds a NaN
   }
   return clipped;
 }
@@ -1065,7 +1066,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         const float unif = (float)(rnd[t] >> 8) * 0x1.0p-24f;
-        codes[i][4 * l + t] = (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0);
+        codes[i][4 * l + t] = q.delta > 0.0f ? (int32_t)base[t] + ((unif < frac[t]) ? 1 : 0) : 0;
       }
     }
   }
@@ -1106,6 +1107,311 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
         a.z[j] = zn;
         a.ysum[j] = a.first ? a.weight * yn : ysum_j + a.weight * yn;
         a.x_next[j] = (a.t1 * zn + a.t2 * snap_j) + a.t3 * yn;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Small-d inner iteration in TWO launches: the workers' rows kernel, then this one, which is the exchange above
+// with the fold of the partial rows taken in.  A workgroup owns TILE coordinates of ALL vectors: it folds their
+// partial rows itself (same order as reduce_parts_kernel, so u^i has the same bits), keeps u^i in registers,
+// and needs from the other workgroups only the statistics of their tiles (eq. (3) wants |u^i|_inf over all d
+// coordinates).  Those travel through memory as self-validating words: every workgroup stores the four
+// statistics of each of its (tile, vector) pairs as 64-bit device-scope atomic stores into its own slots, and
+// reads everyone's slots with device-scope atomic loads until none holds the "empty" pattern (all ones: no
+// finite double).  No other data crosses workgroups, so no fence is needed.  Two slot sets alternate between
+// consecutive launches: a launch empties its slots of the other set, which nobody reads meanwhile.  The wait
+// is bounded: after spin_limit polls a workgroup gives up, raises flag bit 1 and finishes with what it has,
+// so every wave exits whatever happens; the host reports the flag as LPC_EDEVICE.  All tile workgroups must
+// be resident together for the wait to end quickly: the host launches at most one per CU's worth of them,
+// ahead (in dispatch order) of the warming workgroups, which never wait.
+constexpr unsigned long long kSlotEmpty = ~0ull;
+
+struct IterArgs {
+  FusedArgs f;            // as for fused_exchange_kernel; U, stat_part, nslots are unused
+  const float *part;      // [nvec][parts][d] partial rows of the workers' pass
+  int32_t parts, nvec;    // nvec = N, or N + 1 with the shared batch's vector last
+  int32_t nwf;            // interleaved accumulators of the fold: 2 or 4, as launch_reduce_parts picks
+  int32_t vec4;           // partial rows may be read 16 bytes at a time
+  float scale;
+  unsigned long long *slots_cur, *slots_next;  // [ntiles][N][4]
+  uint32_t spin_limit;
+};
+
+template <int NWF>
+__device__ __forceinline__ float4 fold_partial_rows(const float *__restrict__ src, int32_t parts, int64_t d,
+                                                    int64_t room, bool vec4, float scale) {
+  // room = coordinates of this chunk inside the vector (4, or fewer at a ragged end)
+  float4 acc[NWF];
+#pragma unroll
+  for (int q = 0; q < NWF; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int32_t p0 = 0; p0 < parts; p0 += 16) {  // sixteen partial rows in flight
+    float4 t[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      t[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (p0 + k < parts) {
+        const float *s = src + (int64_t)(p0 + k) * d;
+        if (vec4) {
+          t[k] = *reinterpret_cast<const float4 *>(s);
+        } else {
+          t[k].x = s[0];
+          if (room > 1) t[k].y = s[1];
+          if (room > 2) t[k].z = s[2];
+          if (room > 3) t[k].w = s[3];
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {  // row p joins accumulator p mod NWF, rows in increasing order
+      float4 &c = acc[k % NWF];
+      c.x += t[k].x; c.y += t[k].y; c.z += t[k].z; c.w += t[k].w;
+    }
+  }
+  float4 v = acc[0];
+#pragma unroll
+  for (int q = 1; q < NWF; ++q) { v.x += acc[q].x; v.y += acc[q].y; v.z += acc[q].z; v.w += acc[q].w; }
+  v.x *= scale; v.y *= scale; v.z *= scale; v.w *= scale;
+  if (room < 4) v.w = 0.f;
+  if (room < 3) v.z = 0.f;
+  if (room < 2) v.y = 0.f;
+  return v;
+}
+
+// sum / max over the LPV (16 or 32) adjacent lanes that share a vector; every lane of the wavefront takes part
+template <int LPV>
+__device__ __forceinline__ double group_sum(double v, int lane) {
+  v = row16_sum(v);
+  if constexpr (LPV == 32) {
+    const double lo = read_lane(v, 0) + read_lane(v, 16), hi = read_lane(v, 32) + read_lane(v, 48);
+    v = lane < 32 ? lo : hi;
+  }
+  return v;
+}
+template <int LPV>
+__device__ __forceinline__ float group_max(float v, int lane) {
+  v = row16_max(v);
+  if constexpr (LPV == 32) {
+    const float lo = fmaxf(read_lane(v, 0), read_lane(v, 16)), hi = fmaxf(read_lane(v, 32), read_lane(v, 48));
+    v = lane < 32 ? lo : hi;
+  }
+  return v;
+}
+
+__device__ __forceinline__ unsigned long long slot_load(const unsigned long long *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void slot_store(unsigned long long *p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int THREADS, int TILE>
+__global__ __launch_bounds__(THREADS) void fused_iter_kernel(IterArgs ia) {
+  const FusedArgs &a = ia.f;
+  constexpr int LPV = TILE / 4;          // lanes per vector: four coordinates (one Philox block) each
+  constexpr int GROUPS = THREADS / LPV;  // vectors served per round
+  constexpr int NW = THREADS / 64;
+  constexpr int ROUNDS = (kFusedMaxN + GROUPS) / GROUPS;  // rounds over up to kFusedMaxN + 1 vectors
+  __shared__ QParams qp[kFusedMaxN];
+  __shared__ int32_t codes[kFusedMaxN][TILE];
+  __shared__ double st[kFusedMaxN][4];
+  __shared__ float uhat_sh[TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int ntiles = (int)((a.d_pad + TILE - 1) / TILE);
+  if ((int)blockIdx.x >= ntiles) {  // whole workgroups: no barrier below is skipped by part of one
+    warm_next_rows(a, ntiles);
+    return;
+  }
+  const int64_t tile0 = (int64_t)blockIdx.x * TILE;
+  const int g = tid / LPV, l = tid % LPV;
+  const int64_t j = tile0 + 4 * l;
+  // the epilogue's operands are requested first, the partial rows right behind them
+  float w_old = 0.0f, mu_j = 0.0f, x_j = 0.0f, z_j = 0.0f, ysum_j = 0.0f, snap_j = 0.0f;
+  if (tid < TILE && tile0 + tid < a.d) {
+    const int64_t jj = tile0 + tid;
+    if (a.do_prox) {
+      w_old = a.w[jj];
+      mu_j = a.mu[jj];
+    }
+    if (a.do_alpc) {
+      mu_j = a.mu[jj]; x_j = a.x[jj]; z_j = a.z[jj]; snap_j = a.w_snap[jj];
+      ysum_j = a.first ? 0.0f : a.ysum[jj];
+    }
+  }
+  float4 v_all[ROUNDS];
+#pragma unroll
+  for (int q = 0; q < ROUNDS; ++q) {
+    v_all[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (q * GROUPS >= ia.nvec) break;  // uniform
+    const int32_t i = g + GROUPS * q;
+    if (i < ia.nvec && j < a.d) {
+      const float *src = ia.part + (int64_t)i * ia.parts * a.d + j;
+      const int64_t room = a.d - j < 4 ? a.d - j : 4;
+      v_all[q] = ia.nwf == 2 ? fold_partial_rows<2>(src, ia.parts, a.d, room, ia.vec4 != 0, ia.scale)
+                             : fold_partial_rows<4>(src, ia.parts, a.d, room, ia.vec4 != 0, ia.scale);
+    }
+  }
+  // statistics of this tile of every worker's vector
+#pragma unroll
+  for (int q = 0; q < ROUNDS; ++q) {
+    if (q * GROUPS >= a.N) break;  // uniform
+    const int32_t i = g + GROUPS * q;
+    const float vals[4] = {v_all[q].x, v_all[q].y, v_all[q].z, v_all[q].w};
+    float fmx = 0.0f;
+    double sum = 0.0, sumsq = 0.0, bad = 0.0;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (isfinite(vals[t])) {
+        fmx = fmaxf(fmx, fabsf(vals[t])); sum += (double)vals[t]; sumsq += (double)vals[t] * (double)vals[t];
+      } else {
+        bad += 1.0;
+      }
+    }
+    fmx = group_max<LPV>(fmx, lane);
+    sum = group_sum<LPV>(sum, lane); sumsq = group_sum<LPV>(sumsq, lane); bad = group_sum<LPV>(bad, lane);
+    if (l == 0 && i < a.N) { st[i][0] = (double)fmx; st[i][1] = sum; st[i][2] = sumsq; st[i][3] = bad; }
+  }
+  __syncthreads();
+  if (tid < 4 * a.N) {
+    const int64_t at = ((int64_t)blockIdx.x * a.N + (tid >> 2)) * 4 + (tid & 3);
+    slot_store(ia.slots_cur + at, __builtin_bit_cast(unsigned long long, st[tid >> 2][tid & 3]));
+    slot_store(ia.slots_next + at, kSlotEmpty);
+  }
+  // the random draws do not depend on the scale: they are taken while the statistics travel
+  uint32_t rnd[ROUNDS][4];
+#pragma unroll
+  for (int q = 0; q < ROUNDS; ++q) {
+    rnd[q][0] = rnd[q][1] = rnd[q][2] = rnd[q][3] = 0u;
+    if (q * GROUPS >= a.N) break;  // uniform
+    const int32_t i = g + GROUPS * q;
+    if (i < a.N && j < a.d_pad) {
+      const Philox4 blk = stream_block(a.key, kTagQuant, (uint32_t)i, (uint32_t)(j >> 2));
+      rnd[q][0] = blk.x; rnd[q][1] = blk.y; rnd[q][2] = blk.z; rnd[q][3] = blk.w;
+    }
+  }
+  // wavefront wv gathers the statistics of vectors wv, wv+NW, ... from all tiles, four vectors at a time; lane k
+  // takes tiles k, k+64, ..., then the butterflies: a fixed order, the same in every workgroup
+  bool gave_up = false;
+  for (int32_t i0 = wv; i0 < a.N; i0 += 4 * NW) {
+    double am[4], s[4], s2[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { am[q] = 0.0; s[q] = 0.0; s2[q] = 0.0; b[q] = 0.0; }
+    for (int32_t k0 = 0; k0 < ntiles; k0 += 64) {
+      const int32_t k = k0 + lane;
+      const bool mine = k < ntiles;
+      unsigned long long wd[4][4];
+      bool ok[4];
+      uint32_t polls = 0;
+      for (;;) {
+        bool all_ok = true;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int32_t i = i0 + NW * q < a.N ? i0 + NW * q : i0;
+          const unsigned long long *p = ia.slots_cur + ((int64_t)(mine ? k : 0) * a.N + i) * 4;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) wd[q][t] = slot_load(p + t);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          ok[q] = wd[q][0] != kSlotEmpty && wd[q][1] != kSlotEmpty && wd[q][2] != kSlotEmpty && wd[q][3] != kSlotEmpty;
+          all_ok = all_ok && (ok[q] || !mine);
+        }
+        if (__ballot(!all_ok) == 0ull) break;
+        if (++polls > ia.spin_limit) { gave_up = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (mine && ok[q]) {
+          am[q] = fmax(am[q], __builtin_bit_cast(double, wd[q][0]));
+          s[q] += __builtin_bit_cast(double, wd[q][1]);
+          s2[q] += __builtin_bit_cast(double, wd[q][2]);
+          b[q] += __builtin_bit_cast(double, wd[q][3]);
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int32_t i = i0 + NW * q;
+      if (i >= a.N) break;  // uniform over the wavefront
+      const double am_w = wave_max(am[q]), s_w = wave_sum(s[q]), s2_w = wave_sum(s2[q]), b_w = wave_sum(b[q]);
+      if (lane == 0) {
+        const QParams q_i = make_qparams(a.qs, am_w, s_w, s2_w, a.d);
+        qp[i] = q_i;
+        if (blockIdx.x == 0) {
+          a.delta_out[i] = q_i.delta;
+          double *o = a.stats + (int64_t)i * 4;
+          o[0] = am_w; o[1] = s_w; o[2] = s2_w; o[3] = b_w;
+          if (b_w > 0.0) atomicOr(&a.flags[0], 1u);
+        }
+      }
+    }
+  }
+  if (gave_up && lane == 0) atomicOr(&a.flags[0], 2u);
+  __syncthreads();
+  {
+    const float hi = (float)((1 << (a.bits - 1)) - 1);
+    const float lo = -(float)(1 << (a.bits - 1));
+#pragma unroll
+    for (int qi = 0; qi < ROUNDS; ++qi) {
+      if (qi * GROUPS >= ia.nvec) break;  // uniform
+      const int32_t i = g + GROUPS * qi;
+      const float vals[4] = {v_all[qi].x, v_all[qi].y, v_all[qi].z, v_all[qi].w};
+      if (i < a.N) {
+        const QParams q = qp[i];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          float s = vals[t] * q.rdelta;
+          s = fminf(fmaxf(s, lo), hi);
+          const float base = floorf(s);
+          const float frac = s - base;
+          const float unif = (float)(rnd[qi][t] >> 8) * 0x1.0p-24f;
+          codes[i][4 * l + t] = q.delta > 0.0f ? (int32_t)base + ((unif < frac) ? 1 : 0) : 0;
+        }
+      } else if (i == a.N && ia.nvec > a.N) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) uhat_sh[4 * l + t] = vals[t];  // the shared batch's difference, full precision
+      }
+    }
+  }
+  __syncthreads();
+  // pack: one thread per output word of the tile
+  {
+    const int32_t bits = a.bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    const int32_t words_per_worker = (TILE / kSegFloats) * bits;
+    const int64_t seg0 = tile0 / kSegFloats;
+    for (int32_t idx = tid; idx < a.N * words_per_worker; idx += THREADS) {
+      const int32_t i = idx / words_per_worker, rem = idx % words_per_worker;
+      const int32_t sgm = rem / bits, wd = rem % bits;
+      if ((seg0 + sgm) * kSegFloats >= a.d_pad) continue;
+      const int32_t bit0 = 32 * wd;
+      uint32_t word = 0u;
+      for (int32_t c = bit0 / bits; c < 32 && c * bits < bit0 + 32; ++c) {
+        const uint32_t field = (uint32_t)codes[i][32 * sgm + c] & mask;
+        const int32_t sh = c * bits - bit0;
+        word |= sh >= 0 ? (field << sh) : (field >> (-sh));
+      }
+      a.packed[(int64_t)i * a.W + (seg0 + sgm) * bits + wd] = word;
+    }
+  }
+  // eq. (4) in worker order, then Alg. 1 steps 9-10 (or Alg. 2 steps 13-15 and the next step 6)
+  if (tid < TILE) {
+    const int64_t jj = tile0 + tid;
+    if (jj < a.d) {
+      float acc = 0.0f;
+      for (int32_t i = 0; i < a.N; ++i) acc = __builtin_fmaf(qp[i].delta, (float)codes[i][tid], acc);
+      const float avg = acc * (1.0f / (float)a.N);
+      if (a.u_avg_out) a.u_avg_out[jj] = avg;
+      if (a.do_prox) a.w[jj] = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
+      if (a.do_alpc) {
+        const float yn = prox_scalar(x_j, avg + mu_j, a.step_y, a.thr_y, a.shrink_y);          // low-precision gradient
+        const float zn = prox_scalar(z_j, uhat_sh[tid] + mu_j, a.alpha, a.thr_z, a.shrink_z);  // full precision
+        a.y[jj] = yn;
+        a.z[jj] = zn;
+        a.ysum[jj] = a.first ? a.weight * yn : ysum_j + a.weight * yn;
+        a.x_next[jj] = (a.t1 * zn + a.t2 * snap_j) + a.t3 * yn;
       }
     }
   }
@@ -1334,17 +1640,23 @@ inline dim3 grid1d(int64_t n, int threads) { return dim3((unsigned)((n + threads
 
 }  // namespace
 
+// Wavefronts per workgroup of the fold of `parts` partial rows into nvec vectors (they take interleaved rows, which
+// fixes the order of the sum).  A wavefront takes eight partial rows per step: two wavefronts for up to 16 rows
+// when the launch has workgroups to spare, four otherwise (measured back to back on one machine: 16 rows and 2176
+// workgroups, two against four wavefronts +0.9 % inner iterations/s, eight -3.9 %; 16 rows and 4 workgroups,
+// two -2 %; 32 rows, two -2.3 %, eight +0.2 %)
+int reduce_parts_waves(const lpc_ctx *c, int32_t parts, int32_t nvec) {
+  const int64_t wgs = ((c->d_pad + 63) / 64) * (int64_t)nvec;
+  return (parts <= 16 && wgs >= 2 * c->cus) ? 2 : 4;
+}
+
 hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t parts, float scale, float *out,
                                int64_t ld_out, int32_t vec_begin, int32_t nvec, int stats_mode, double *stats_out,
                                hipStream_t st) {
   // `out` and `stats_out` point at the row of the first vector of this launch; vec_begin only selects
   // the scratch slots (statistics, quantizer parameters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
-  // a wavefront takes eight partial rows per step: two wavefronts for up to 16 rows when the launch has
-  // workgroups to spare, four otherwise (measured back to back on one machine: 16 rows and 2176 workgroups, two
-  // against four wavefronts +0.9 % inner iterations/s, eight -3.9 %; 16 rows and 4 workgroups, two -2 %;
-  // 32 rows, two -2.3 %, eight +0.2 %)
-  if (parts <= 16 && (int64_t)grid.x * grid.y >= 2 * c->cus)
+  if (reduce_parts_waves(c, parts, nvec) == 2)
     hipLaunchKernelGGL(reduce_parts_kernel<2>, grid, dim3(128), 0, st, part, parts, c->d, c->d_pad, scale, out,
                        ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
   else
@@ -1559,7 +1871,7 @@ int warm_setup(const lpc_ctx *c, StreamKey key, bool shared, FusedArgs *a) {
 }  // namespace
 
 bool fused_exchange_supported(const lpc_ctx *c) {
-  return c->quant && c->cfg.N <= kFusedMaxN && c->stat_slots <= 256;
+  return c->quant && c->cfg.N <= kFusedMaxN && c->stat_slots <= 256 && c->d_pad <= 16384;
 }
 
 // One launch for eq. (3), quantize, pack, eq. (4) and (optionally) the proximal step; reads the statistic
@@ -1596,6 +1908,64 @@ hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t 
   const int extra = warm_setup(c, key, true, &a);
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords + extra));
   hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kFusedThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+bool fused_iter_supported(const lpc_ctx *c) {
+  return fused_exchange_supported(c) && c->grad_ok && !c->csr && !c->mlp;
+}
+
+// 64-bit words of the two slot sets the workgroups of launch_fused_iter exchange their statistics through
+int64_t fused_iter_slot_words(const lpc_ctx *c) {
+  return 2 * ((c->d_pad + 63) / 64) * (int64_t)c->cfg.N * 4;
+}
+
+hipError_t launch_fused_iter_reset(const lpc_ctx *c, hipStream_t st) {
+  return launch_fill_u32(reinterpret_cast<uint32_t *>(c->s.iter_slots), 0xFFFFFFFFu, 2 * fused_iter_slot_words(c), st);
+}
+
+// Fold of the workers' partial rows (and of the shared batch's when `al` is given), eq. (3), quantize, pack, eq. (4)
+// and the update in one launch; iteration key.iter uses slot set key.iter & 1.
+hipError_t launch_fused_iter(const lpc_ctx *c, StreamKey key, uint32_t *packed, float *delta_out, const float *mu,
+                             float step, float *w, const AlpcStep *al, hipStream_t st) {
+  IterArgs ia{};
+  FusedArgs &a = ia.f;
+  a.d = c->d; a.d_pad = c->d_pad; a.W = c->W;
+  a.N = c->cfg.N; a.bits = c->cfg.bits; a.stat_slots = c->stat_slots;
+  a.qs = spec_of(c); a.key = key;
+  a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
+  int extra;
+  if (al) {
+    a.mu = al->mu; a.do_alpc = 1;
+    a.x = al->x; a.w_snap = al->w_snap; a.y = al->y; a.z = al->z; a.ysum = al->ysum; a.x_next = al->x_next;
+    a.step_y = al->step_y; a.alpha = al->alpha; a.weight = al->weight; a.first = al->first;
+    a.t1 = al->tau1; a.t2 = al->tau2; a.t3 = (float)(1.0 - (double)al->tau1 - (double)al->tau2);
+    prox_consts(c, al->step_y, &a.thr_y, &a.shrink_y);
+    prox_consts(c, al->alpha, &a.thr_z, &a.shrink_z);
+    extra = warm_setup(c, key, true, &a);
+  } else {
+    a.mu = mu; a.w = w; a.step = step; a.do_prox = 1;
+    prox_consts(c, step, &a.thr, &a.shrink);
+    extra = warm_setup(c, key, false, &a);
+  }
+  ia.part = c->s.part; ia.parts = c->vr_parts; ia.nvec = c->cfg.N + (al ? 1 : 0);
+  ia.nwf = reduce_parts_waves(c, c->vr_parts, ia.nvec);
+  ia.vec4 = (c->d % 4 == 0) ? 1 : 0;
+  ia.scale = (float)(1.0 / (double)c->cfg.B);
+  const int64_t set_words = fused_iter_slot_words(c) / 2;
+  ia.slots_cur = c->s.iter_slots + (key.iter & 1u) * set_words;
+  ia.slots_next = c->s.iter_slots + ((key.iter + 1u) & 1u) * set_words;
+  ia.spin_limit = c->spin_limit;
+  const int tile = c->iter_tile == 64 ? 64 : 128;
+  const dim3 grid((unsigned)((c->d_pad + tile - 1) / tile + extra));
+  if (tile == 64 && c->iter_threads == 256)
+    hipLaunchKernelGGL((fused_iter_kernel<256, 64>), grid, dim3(256), 0, st, ia);
+  else if (tile == 64)
+    hipLaunchKernelGGL((fused_iter_kernel<512, 64>), grid, dim3(512), 0, st, ia);
+  else if (c->iter_threads == 256)
+    hipLaunchKernelGGL((fused_iter_kernel<256, 128>), grid, dim3(256), 0, st, ia);
+  else
+    hipLaunchKernelGGL((fused_iter_kernel<512, 128>), grid, dim3(512), 0, st, ia);
   return hipGetLastError();
 }
 

@@ -64,9 +64,13 @@ EXPORTS = {
     "lpc_code_histogram": (C.c_int, [_vp, _vp, _vp, _vp]),
     "lpc_huffman_bits": (C.c_int, [_vp, C.c_int32, _vp, C.POINTER(C.c_uint64)]),
     "lpc_huffman_encode": (C.c_int, [_vp, _vp, _vp, _vp, C.c_int64, C.POINTER(C.c_uint64), _vp]),
+    "lpc_tune": (C.c_int, [_vp, C.c_int32, C.c_int64]),
+    "lpc_debug_gemm": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
+                                 C.c_int32, C.c_int32, C.c_float, _vp, C.c_int32, C.c_int32, _vp]),
     "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
     "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), _vp]),
 }
+TUNE_ITER_LAUNCHES, TUNE_ITER_TILE, TUNE_ITER_THREADS, TUNE_SPIN_LIMIT = 0, 1, 2, 3
 PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblpc_hip.so")
@@ -275,6 +279,9 @@ class Context:
             counts = torch.empty(1 << self.config.bits, dtype=torch.int64, device=packed.device)
         _chk(lib.lpc_code_histogram(self._h, _ptr(packed), _ptr(counts), _stream(stream)), "lpc_code_histogram")
         return counts
+
+    def tune(self, key, value):
+        _chk(lib.lpc_tune(self._h, key, value), "lpc_tune")
 
     def profile_enable(self, on):
         _chk(lib.lpc_profile_enable(self._h, 1 if on else 0), "lpc_profile_enable")

@@ -37,3 +37,22 @@ def gpu_context(sp, **over):
 def to_dev(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def batch_grad_inf(sp, w, epoch, iter_, tag, worker):
+    """|grad f_B(w)|_inf for the batch B that `worker` draws at (epoch, iter): the oracle's full gradient over a
+    problem made of exactly the sampled rows (duplicates kept).  The scale a variance-reduced difference of
+    nearly equal per-sample gradients is compared against."""
+    field = 0xFFFFFF if tag == lpco.TAG_SHARED else worker
+    idx = lpco.sample_batch(sp.seed, epoch, iter_, tag, field, sp.B, sp.n)
+    if sp.csr is not None:
+        rp, ci, va = sp.csr
+        lens = (rp[idx + 1] - rp[idx]).astype(np.int64)
+        sub_rp = np.zeros(idx.size + 1, dtype=np.int32)
+        np.cumsum(lens, out=sub_rp[1:])
+        take = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in idx]) if lens.sum() else np.zeros(0, np.int64)
+        sub, _k = lpco.make_problem(sp.loss, sp.y[idx], csr=(sub_rp, ci[take], va[take], sp.d))
+    else:
+        sub, _k = lpco.make_problem(sp.loss, sp.y[idx], X=np.ascontiguousarray(sp.X[idx]), d=sp.d,
+                                    mlp_dims=sp.mlp_dims)
+    return float(np.abs(lpco.full_grad(sub, w)[0]).max())

@@ -25,10 +25,7 @@ def test_matrix_core_contraction(M, N, K, tA, tB):
     bias = rng.standard_normal(N).astype(np.float32)
     C0 = rng.standard_normal((M, N)).astype(np.float32)
     ref = (A.T if tA else A).astype(np.float64) @ (B.T if tB else B).astype(np.float64)
-    fn = lpc.lib.lpc_debug_gemm
-    fn.restype = C.c_int
-    fn.argtypes = [C.c_void_p] * 3 + [C.c_int] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_float, C.c_void_p,
-                                                                        C.c_int, C.c_int, C.c_void_p]
+    fn = lpc.lib.lpc_debug_gemm      # declared in include/lpc.h, bound in lpc.EXPORTS
     dA, dB, dbias = to_dev(A), to_dev(B), to_dev(bias)
     st = torch.cuda.current_stream().cuda_stream
     for relu, acc in [(0, 0), (1, 0), (0, 1)]:

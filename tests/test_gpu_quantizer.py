@@ -110,6 +110,23 @@ def test_quantizer_degenerate_inputs():
     ctx.vector_stats(dU, N, stats)
     assert stats[1, 3].item() == 1
     assert ctx.take_device_flags() == -5 and ctx.take_device_flags() == 0
+    # a vector whose finite entries are all zero but that holds a NaN: scale 0, so the message is all zeros (code
+    # 0 at the NaN too), on both sides, through the separate calls and through the one-launch exchange
+    U0 = np.zeros((N, lpco.d_pad(d)), dtype=np.float32)
+    U0[1, :d] = np.linspace(-1, 1, d)
+    U0[0, 7] = np.nan
+    po, do, _, _ = lpco.quantize_clip(U0, d, bits, seed=0, epoch=1, iter_=2)
+    assert do[0] == 0 and not po[0].any()
+    dU0 = to_dev(U0)
+    ctx.vector_stats(dU0, N, stats)
+    ctx.quantize_clip(dU0, stats, None, 1, 2, packed, delta, ncl)
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), po) and np.array_equal(delta.cpu().numpy(), do)
+    assert ctx.take_device_flags() == -5
+    avg = torch.zeros(d, device="cuda")
+    packed.fill_(-1)
+    ctx.exchange(dU0, 1, 2, packed, delta, avg)
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), po) and np.array_equal(delta.cpu().numpy(), do)
+    assert ctx.take_device_flags() == -5
     ctx.close()
 
 

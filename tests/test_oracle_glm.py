@@ -225,6 +225,35 @@ def test_mlp_gradient_against_autograd():
         assert np.allclose(U[i, :w.size], ref, rtol=0, atol=1e-6 * max(np.abs(ref).max(), 1e-3))
 
 
+def test_relu_margin_on_a_hand_built_network():
+    """lpco_mlp_relu_margin against a 3-2-2-2 network whose hidden pre-activations are known by construction
+    (all numbers exactly representable): a unit that is exactly zero, the minimum taken over both hidden layers
+    and over the rows of the batch, negative pre-activations counted by magnitude, the last (softmax) layer's
+    tiny logits ignored, and the [in][out] row-major weight layout (a transposed read changes every value)."""
+    dims = (3, 2, 2, 2)
+    X = np.array([[1.0, 2.0, -1.0], [0.0, 0.0, 0.0]], dtype=np.float32)
+    y = np.array([0.0, 1.0], dtype=np.float32)
+    W1 = [[1.0, 0.5], [1.0, -1.0], [3.0, 0.25]]          # unit 0 of row 0: 1 + 2 - 3 = 0; unit 1: 0.5 - 2 - 0.25
+    W2 = [[2.0, -4.0], [100.0, 100.0]]
+    W3 = [[1e-3, 0.0], [0.0, 1e-3]]                      # logits of order 1e-3: not hidden units
+
+    def net(b1, b2):
+        return np.concatenate([np.ravel(W1), b1, np.ravel(W2), b2, np.ravel(W3), [0.0, 0.0]]).astype(np.float32)
+
+    p, _k = lpco.make_problem(lpco.LOSS_MLP_SOFTMAX, y, X=X, d=20, mlp_dims=dims)
+    # row 0, no biases: layer 1 = (0, -1.75)
+    assert lpco.mlp_relu_margin(p, net([0.0, 0.0], [0.25, 0.5]), [0]) == 0.0
+    # row 0, b1 = (0.75, 0.5): layer 1 = (0.75, -1.25), h = (0.75, 0); layer 2 = (1.75, -2.5)
+    w = net([0.75, 0.5], [0.25, 0.5])
+    assert lpco.mlp_relu_margin(p, w, [0]) == 0.75
+    # row 1 (x = 0): layer 1 = b1 = (0.75, 0.5); layer 2 = (1.5 + 50 + 0.25, -3 + 50 + 0.5)
+    assert lpco.mlp_relu_margin(p, w, [1]) == 0.5
+    assert lpco.mlp_relu_margin(p, w, [0, 1]) == 0.5 and lpco.mlp_relu_margin(p, w, [1, 0, 0]) == 0.5
+    # the second hidden layer decides when it holds the smallest value: b2 = (-1.5, 0.5) -> row 0: (0, -2.5)
+    assert lpco.mlp_relu_margin(p, net([0.75, 0.5], [-1.5, 0.5]), [0]) == 0.0
+    assert lpco.mlp_relu_margin(p, net([0.75, 0.5], [-1.625, 0.5]), [0]) == 0.125
+
+
 # ---------------------------------------------------------------- argument checking
 
 def test_bad_arguments_return_errors():
