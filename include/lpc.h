@@ -173,6 +173,22 @@ lpc_status lpc_dequantize_shared(lpc_ctx *ctx, const uint32_t *packed, const flo
 lpc_status lpc_exchange(lpc_ctx *ctx, const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed,
                         float *delta_out, float *u_avg, void *stream);
 
+/* lpc_exchange for callers that cannot allocate device memory or hold a context's workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  It takes no context: the configuration
+ * comes as arguments, and the scratch lpc_exchange keeps in a workspace (statistic partials, statistics,
+ * quantizer parameters, clip counts; about 0.6 MB) lives in a device array inside the library, of which every
+ * GPU the library runs on holds one copy until the process ends.  The call allocates and frees nothing and only
+ * enqueues kernels on `stream` (its first call on a device also looks the array's address up).  Same outputs, bit
+ * for bit, as lpc_exchange with the same d, N, bits, clip mode, clip and seed: packed [N][W], delta_out [N],
+ * u_avg [d].  Limits: d <= 8388608 (2^23) coordinates and N <= 64 vectors; beyond either the call returns
+ * LPC_EWORKSPACE (the static scratch is too small) and does nothing.  flags_out (device, one uint32, may be NULL):
+ * bit 0 is OR-ed in when a vector held a NaN or Inf; the caller clears it.  All calls on one GPU share the one
+ * array, which keeps the previous call's contents (each call overwrites what it reads): calls that overlap on
+ * one GPU (different streams, no ordering between them) race and must be serialised by the caller. */
+lpc_status lpc_exchange_static(int64_t d, int32_t N, int32_t bits, int32_t clip_mode, float clip, uint64_t seed,
+                               const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed, float *delta_out,
+                               float *u_avg, uint32_t *flags_out, void *stream);
+
 /* Alg. 1 steps 9-10: v = u_avg + mu;  w <- prox_{step*h}(w - step*v), in place,
  * prox(p)_j = sign(p_j)*max(|p_j| - step*lambda1, 0)/(1 + step*lambda2) (Sec. 3.3). */
 lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream);

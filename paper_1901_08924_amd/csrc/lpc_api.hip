@@ -573,6 +573,90 @@ lpc_status lpc_exchange(lpc_ctx *ctx, const float *U, uint32_t epoch, uint32_t i
   return LPC_OK;
 }
 
+// ---- lpc_exchange for callers that cannot allocate ---------------------------------------------------------
+// The scratch lpc_exchange takes from a context's workspace (statistic partials, statistics, quantizer
+// parameters, clip counts, the non-finite flag) lives in a file-scope device array instead.  Every GPU the
+// library runs on holds its own copy of the array at its own address until the process ends; host code reaches
+// it only through the address hipGetSymbolAddress returns for the current device.
+namespace {
+constexpr int64_t kStaticMaxD = (int64_t)1 << 23;  // coordinates per vector
+constexpr int32_t kStaticMaxN = 64;                // vectors
+constexpr int32_t kStaticSlots = 256;              // statistic partials per vector (32768 coordinates each at the maximum)
+constexpr size_t kStaticStatPart = (size_t)kStaticMaxN * kStaticSlots * 4 * sizeof(double);
+constexpr size_t kStaticStats = (size_t)kStaticMaxN * 4 * sizeof(double);
+constexpr size_t kStaticQParams = (size_t)kStaticMaxN * sizeof(QParams);
+constexpr size_t kStaticClipped = (size_t)kStaticMaxN * sizeof(uint32_t);
+constexpr size_t kStaticFlags = 256;
+constexpr size_t kStaticBytes = kStaticStatPart + kStaticStats + kStaticQParams + kStaticClipped + kStaticFlags;
+static_assert(kStaticStatPart % 256 == 0 && kStaticStats % 256 == 0 && kStaticQParams % 256 == 0 &&
+              kStaticClipped % 256 == 0, "every part of the static scratch starts 256-byte aligned");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex static_mu;
+unsigned char *static_ptr[kMaxDevices];  // the array's device address, per device; nullptr = not looked up yet
+
+// Device address of `scratch` on the current device (looked up once per device; its flag word is cleared then).
+lpc_status static_scratch(hipStream_t st, unsigned char **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LPC_EDEVICE;
+  std::lock_guard<std::mutex> lock(static_mu);
+  if (!static_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LPC_EDEVICE;
+    // a fill kernel, not a memset: the caller may be capturing the stream
+    unsigned char *base = static_cast<unsigned char *>(p);
+    if (launch_fill_u32(reinterpret_cast<uint32_t *>(base + kStaticBytes - kStaticFlags), 0u, kStaticFlags / 4, st) !=
+        hipSuccess)
+      return LPC_EDEVICE;
+    static_ptr[dev] = base;
+  }
+  *out = static_ptr[dev];
+  return LPC_OK;
+}
+}  // namespace
+
+lpc_status lpc_exchange_static(int64_t d, int32_t N, int32_t bits, int32_t clip_mode, float clip, uint64_t seed,
+                               const float *U, uint32_t epoch, uint32_t iter, uint32_t *packed, float *delta_out,
+                               float *u_avg, uint32_t *flags_out, void *stream) {
+  if (!U || !packed || !delta_out || !u_avg) return LPC_ENULL;
+  if (d <= 0 || N <= 0) return LPC_ESHAPE;
+  if (d > kStaticMaxD || N > kStaticMaxN) return LPC_EWORKSPACE;  // beyond what the static scratch holds
+  if (bits < 2 || bits > 16) return LPC_EINVAL;
+  if (clip_mode != LPC_CLIP_LAMBDA && clip_mode != LPC_CLIP_CSIGMA) return LPC_EINVAL;
+  if (!(clip > 0.0f) || (clip_mode == LPC_CLIP_LAMBDA && clip > 1.0f)) return LPC_EINVAL;
+  if (!aligned(U, 16) || !aligned(packed, 16) || !aligned(u_avg, 16) || !aligned(delta_out, 4) ||
+      (flags_out && !aligned(flags_out, 4)))
+    return LPC_ESHAPE;
+  hipStream_t st = as_stream(stream);
+  unsigned char *base = nullptr;
+  LPC_TRY(static_scratch(st, &base));
+  // a context on the stack that owns nothing: only the fields the exchange's launchers read
+  lpc_ctx c{};
+  c.cfg.N = N; c.cfg.B = 1; c.cfg.m = 1; c.cfg.bits = bits; c.cfg.clip_mode = clip_mode; c.cfg.clip = clip;
+  c.cfg.seed = seed; c.cfg.scheme = LPC_SCHEME_A;
+  c.d = d; c.d_pad = lpc_d_pad(d); c.W = lpc_words_per_msg(d, bits);
+  c.quant = true; c.cus = 256; c.stat_slots = kStaticSlots;
+  Scratch &s = c.s;
+  s.stat_part = reinterpret_cast<double *>(base);
+  s.stats = reinterpret_cast<double *>(base + kStaticStatPart);
+  s.qparams = reinterpret_cast<QParams *>(base + kStaticStatPart + kStaticStats);
+  s.n_clipped = reinterpret_cast<uint32_t *>(base + kStaticStatPart + kStaticStats + kStaticQParams);
+  s.flags = flags_out ? flags_out : reinterpret_cast<uint32_t *>(base + kStaticBytes - kStaticFlags);
+  const StreamKey key = key_of(&c, epoch, iter);
+  if (fused_exchange_supported(&c)) {
+    int32_t slots = 0;
+    LPC_TRY_HIP(launch_vector_stats(&c, U, c.d_pad, 0, N, nullptr, kStatsPartial, &slots, st));
+    LPC_TRY_HIP(launch_fused_exchange(&c, U, slots, key, packed, delta_out, nullptr, 0.0f, nullptr, u_avg, st));
+    return LPC_OK;
+  }
+  LPC_TRY_HIP(launch_vector_stats(&c, U, c.d_pad, 0, N, nullptr, kStatsFinal, nullptr, st));
+  LPC_TRY_HIP(launch_quantize(&c, U, key, packed, delta_out, s.n_clipped, st));
+  LPC_TRY_HIP(launch_dequantize_avg(&c, packed, delta_out, u_avg, st));
+  return LPC_OK;
+}
+
 lpc_status lpc_prox_step(lpc_ctx *ctx, float *w, const float *u_avg, const float *mu, float step, void *stream) {
   if (!ctx || !w || !u_avg || !mu) return LPC_ENULL;
   if (!(step > 0.0f)) return LPC_EINVAL;

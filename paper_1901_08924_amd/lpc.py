@@ -51,6 +51,8 @@ EXPORTS = {
     "lpc_dequantize_avg": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
     "lpc_dequantize_shared": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_uint32, C.c_uint32, _vp, _vp]),
     "lpc_exchange": (C.c_int, [_vp, _vp, C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp]),
+    "lpc_exchange_static": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_uint64, _vp,
+                                      C.c_uint32, C.c_uint32, _vp, _vp, _vp, _vp, _vp]),
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, C.POINTER(C.c_uint64), _vp]),
@@ -137,6 +139,14 @@ def huffman_bits(counts):
 def make_config(algo=ALGO_LPC, N=1, B=1, m=1, bits=32, clip_mode=CLIP_LAMBDA, clip=1.0, scheme=SCHEME_A, eta=0.1,
                 L=0.0, sigma=0.0, tau1=0.0, tau2=0.0, alpha=0.0, seed=0, n_full=0):
     return Config(algo, N, B, m, bits, clip_mode, clip, scheme, eta, L, sigma, tau1, tau2, alpha, seed, n_full)
+
+
+def exchange_static(d, N, bits, clip_mode, clip, seed, U, epoch, iter_, packed, delta_out, u_avg, flags_out=None,
+                    stream=None):
+    """lpc_exchange without a context: allocates nothing (the library's static device scratch)."""
+    _chk(lib.lpc_exchange_static(d, N, bits, clip_mode, clip, seed, _ptr(U), epoch, iter_, _ptr(packed),
+                                 _ptr(delta_out), _ptr(u_avg), _ptr(flags_out), _stream(stream)),
+         "lpc_exchange_static")
 
 
 class Context:

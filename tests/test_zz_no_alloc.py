@@ -1,0 +1,77 @@
+"""The entry point that allocates nothing (lpc_exchange_static, for callers that cannot call hipMalloc) against
+lpc_exchange: the same packed words, scale factors and average, bit for bit, on two calls in a row, the second
+with a smaller input (the static scratch keeps the first call's contents)."""
+import numpy as np
+import pytest
+
+import lpc_synth
+from _common import gpu_context, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(d, N, bits, clip_mode, clip, seed, epoch, it):
+    import torch
+    from paper_1901_08924_amd import lpc
+    sp = lpc_synth.make("c1", n=max(64, N), d=d, N=N, B=1, bits=bits, seed=seed)
+    ctx = gpu_context(sp, clip_mode=clip_mode, clip=clip, bits=bits, m=1)
+    U = lpc_synth.gaussian_u(N, d, seed=seed + 5)
+    U *= np.linspace(0.5, 3.0, N, dtype=np.float32)[:, None]
+    dU = to_dev(U)
+    out = []
+    for static in (False, True):
+        packed = torch.full((N, ctx.W), -1, dtype=torch.int32, device="cuda")
+        delta = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
+        avg = torch.full((d,), -1.0, dtype=torch.float32, device="cuda")
+        if static:
+            before = torch.cuda.memory_allocated()
+            lpc.exchange_static(d, N, bits, clip_mode, clip, seed, dU, epoch, it, packed, delta, avg)
+            assert torch.cuda.memory_allocated() == before
+        else:
+            ctx.exchange(dU, epoch, it, packed, delta, avg)
+        torch.cuda.synchronize()
+        out.append((packed.cpu().numpy(), delta.cpu().numpy(), avg.cpu().numpy()))
+    ctx.close()
+    return out
+
+
+@pytest.mark.parametrize("first,second", [
+    ((300_007, 16, 4, 0, 0.85), (4096, 8, 4, 0, 1.0)),     # large-d launches, then the one-launch small-d path
+    ((8192, 16, 3, 1, 2.0), (45, 3, 5, 0, 1.0)),           # c*sigma mode, odd width; then less than two segments
+    ((4096, 8, 4, 0, 0.9), (100_003, 4, 2, 0, 1.0)),       # small first, then a larger d with fewer vectors
+])
+def test_static_exchange_equals_exchange_on_two_calls_in_a_row(first, second):
+    for k, (d, N, bits, mode, clip) in enumerate((first, second)):
+        (p0, d0, a0), (p1, d1, a1) = _pair(d, N, bits, mode, clip, seed=3, epoch=1, it=k)
+        assert np.array_equal(p0, p1)
+        assert np.array_equal(d0, d1)
+        assert np.array_equal(a0, a1)
+        assert d0.min() > 0 and np.abs(a0).max() > 0
+
+
+def test_static_exchange_rejects_what_its_scratch_cannot_hold():
+    import torch
+    from paper_1901_08924_amd import lpc
+    t = torch.zeros(64, device="cuda")
+    ti = torch.zeros(64, dtype=torch.int32, device="cuda")
+    for d, N in (((1 << 23) + 1, 4), (1024, 65)):
+        with pytest.raises(lpc.LpcError) as e:
+            lpc.exchange_static(d, N, 4, 0, 1.0, 0, t, 0, 0, ti, t, t)
+        assert e.value.code == lpc.EWORKSPACE
+    with pytest.raises(lpc.LpcError) as e:
+        lpc.exchange_static(1024, 4, 1, 0, 1.0, 0, t, 0, 0, ti, t, t)
+    assert e.value.code == lpc.EINVAL
+
+
+def test_static_exchange_reports_non_finite_input_through_the_callers_flag():
+    import torch
+    from paper_1901_08924_amd import lpc
+    d, N = 5000, 2
+    U = to_dev(lpc_synth.gaussian_u(N, d, seed=1))
+    U[1, 17] = float("inf")
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    packed = torch.zeros(N, lpc.words_per_msg(d, 4), dtype=torch.int32, device="cuda")
+    delta = torch.zeros(N, device="cuda")
+    avg = torch.zeros(d, device="cuda")
+    lpc.exchange_static(d, N, 4, 0, 1.0, 0, U, 0, 0, packed, delta, avg, flags_out=flags)
+    assert flags.item() & 1
