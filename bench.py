@@ -3,16 +3,19 @@
 
 A "step" is one pass of the whole hot path: one lpc_epoch = the snapshot full-gradient pass, then
 m inner iterations of (workers' variance-reduced differences -> clip/quantize/pack ->
-dequantize+average -> prox [+ ALPC double sampling]).  The default workload is configuration C2
-(dense L1+L2 logistic regression, n=65536, d=4096, N=8 workers, minibatch 64 per worker, b=4 bits,
-m=128); --workload c1|c3|c4|c5 selects the other configurations.  Inputs are synthetic, seeded, and
-resident in HBM before the timed region.
+dequantize+average -> prox [+ ALPC double sampling]).  With no --workload the headline is configuration
+C4, the largest that one GPU holds (ALPC-SVRG on dense ridge least squares, n=262144, d=8192, 8.6 GB, N=16
+workers, minibatch 64 per worker, b=3 bits, m=256), and the other single-GPU configurations C2 (dense
+logistic, 1 GiB), C3 (CSR logistic, n=d=2^20) and C5 (3-layer MLP, 4.2 M parameters) follow as sub-records
+under "workloads", each with its own roofline, snapshot-pass figure and CPU baseline.  --workload cN runs one
+configuration alone.  Inputs are synthetic, seeded, and resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` = inner iterations per second over whole steps (the snapshot pass
-included).  After the timed region the same steps are run once more with the library's event
-profiling on (HIP events on the launch stream around each kernel class); `kernels` lists every
-class with its algorithmic bytes (or flops) per launch, `roofline` is the class that carries most of
-the step's algorithmic work (launches per step x work per launch, weighed by its own peak).  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
+included).  After the timed region the same steps are run once more with the library's per-class timing on;
+`kernels` lists every class with its algorithmic bytes (or flops) per launch, `roofline` is the class that
+carries most of the step's algorithmic work (launches per step x work per launch, weighed by its own peak).
+A class that is one kernel is timed by that dispatch's own begin and end (the figure a rocprofv3 kernel trace
+gives).  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -81,21 +84,28 @@ def measured_traffic(workload):
     return out
 
 
+def host_cores():
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
 def cpu_baseline(sp, cfgkw, alpc):
-    """The oracle as it stands, one host thread, on a bounded sample of the workload."""
+    """The oracle as it stands on a bounded sample of the workload: whole epochs on one host thread (its inner
+    loop has no threaded form), and for the linear models the snapshot pass once more on all host cores."""
     from oracle import lpco
     sample = dict(cfgkw)
     scale, note = 1.0, ""
     if sp.name == "c5":       # one inner iteration of the full size is ~1 minute of plain loops: shrink the batch
-        sample.update(N=2, B=4, m=1, n_full=8)
+        sample.update(N=2, B=16, m=1, n_full=32)
         scale = (sample["N"] * sample["B"]) / float(sp.N * sp.B)
-        note = " with N=2, B=4, snapshot over 8 rows; rate scaled by sampled rows per iteration"
+        note = " with N=2, B=16, snapshot over 32 rows; rate scaled by sampled rows per iteration"
         epochs = 1
     elif sp.name == "c3":
-        sample.update(m=16)
+        sample.update(m=32)
         epochs = 1
     elif sp.name == "c4":
-        sample.update(m=64)
         epochs = 1
     else:
         epochs = 16 if sp.name == "c2" else 200
@@ -111,9 +121,23 @@ def cpu_baseline(sp, cfgkw, alpc):
         lpco.epoch(p, ocfg, wo, s, yo, zo)
     tc = time.perf_counter() - t0
     iters = sample["m"] * epochs
-    return {"value": iters / tc * scale, "unit": "inner iterations/s", "cores": 1, "kind": "oracle",
-            "sample": "%d epoch(s) of %d inner iterations (snapshot pass included)%s: %.1f s"
-                      % (epochs, sample["m"], note, tc)}
+    cores = host_cores()
+    out = {"value": iters / tc * scale, "unit": "inner iterations/s", "cores": 1, "host_cores": cores,
+           "kind": "oracle",
+           "sample": "%d epoch(s) of %d inner iterations (snapshot pass included)%s: %.1f s"
+                     % (epochs, sample["m"], note, tc)}
+    if sp.loss != 2:          # the oracle's snapshot pass has a row-parallel form: time it on one and on all cores
+        n_full = sp.n_full or sp.n
+        t0 = time.perf_counter()
+        lpco.full_grad(p, sp.w0)
+        t1 = time.perf_counter() - t0
+        lpco.set_threads(cores)
+        t0 = time.perf_counter()
+        lpco.full_grad(p, sp.w0)
+        ta = time.perf_counter() - t0
+        lpco.set_threads(1)
+        out["full_grad_pass"] = {"seconds_one_core": t1, "seconds_all_cores": ta, "cores": cores, "rows": n_full}
+    return out
 
 
 def contraction_shapes():
@@ -157,69 +181,46 @@ def contraction_shapes():
                           "tflops": round(2.0 * M * N * K / us * 1e-6, 1)}), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--iter-launches", type=int, default=None, choices=[2, 3],
-                    help="launches per dense inner iteration (lpc_tune; default: the library's choice)")
-    ap.add_argument("--iter-tile", type=int, default=None, choices=[64, 128])
-    ap.add_argument("--iter-threads", type=int, default=None, choices=[256, 512])
-    ap.add_argument("--small", action="store_true", help="scaled-down problem (quick functional run)")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run ten 1 GiB device-to-device copies (a kernel of known traffic: 1 GiB read, "
-                         "1 GiB written) so that rocprofv3's FETCH_SIZE / WRITE_SIZE counters can be scaled")
-    ap.add_argument("--contractions", action="store_true",
-                    help="only time the MLP workload's matrix products one by one (the contraction kernel's "
-                         "unit-test entry point), one line per shape")
-    args = ap.parse_args()
-    if args.contractions:
-        contraction_shapes()
-        return
-    if args.copy_calibration:
-        import torch
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
-        dst = torch.empty_like(src)
+def copy_calibration():
+    """What this machine's HBM delivers to a kernel with no arithmetic: 1 GiB device-to-device copies."""
+    import torch
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for _ in range(9):  # ten copies in all, the first untimed
         dst.copy_(src)
-        torch.cuda.synchronize()
-        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0.record()
-        for _ in range(9):  # ten copies in all, the first untimed
-            dst.copy_(src)
-        t1.record()
-        torch.cuda.synchronize()
-        us = t0.elapsed_time(t1) * 1000.0 / 9.0  # per copy
-        # a plain copy's read + write rate: what this machine's HBM delivers to a kernel with no arithmetic
-        print(json.dumps({"copy_calibration": {"bytes_read": 4 * src.numel(), "bytes_written": 4 * src.numel(),
-                                               "launches": 10, "us_per_copy": round(us, 1),
-                                               "achieved_GBps": round(8 * src.numel() / us * 1e-3, 1)}}))
-        return
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (the N workers are shards on one device); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-    default_steps = {"c1": 50, "c2": 20, "c3": 3, "c4": 5, "c5": 3}[args.workload]
-    steps = args.steps if args.steps is not None else default_steps
-    warmup = args.warmup if args.warmup is not None else (3 if args.workload in ("c1", "c2") else 1)
+    t1.record()
+    torch.cuda.synchronize()
+    us = t0.elapsed_time(t1) * 1000.0 / 9.0  # per copy
+    out = {"bytes_read": 4 * src.numel(), "bytes_written": 4 * src.numel(), "launches": 10,
+           "us_per_copy": round(us, 1), "achieved_GBps": round(8 * src.numel() / us * 1e-3, 1)}
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
 
+
+DEFAULT_STEPS = {"c1": (50, 3), "c2": (20, 3), "c3": (3, 1), "c4": (5, 1), "c5": (3, 1)}
+SMALL = {"c1": {}, "c2": dict(n=4096, d=1024), "c3": dict(n=1 << 14, d=1 << 14), "c4": dict(n=4096, d=1024),
+         "c5": dict(n=2048, dims=(256, 128, 128, 10), n_full=512, m=4)}
+
+
+def run_workload(name, steps, warmup, args, achievable):
+    """K timed epochs of one configuration, then the same epochs with per-class timing; returns its record."""
     import torch
     import lpc_synth
     from paper_1901_08924_amd import lpc
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    small = {"c1": {}, "c2": dict(n=4096, d=1024), "c3": dict(n=1 << 14, d=1 << 14), "c4": dict(n=4096, d=1024),
-             "c5": dict(n=2048, dims=(256, 128, 128, 10), n_full=512, m=4)}[args.workload]
-    sp = lpc_synth.make(args.workload, **(small if args.small else {}))
+    sp = lpc_synth.make(name, **(SMALL[name] if args.small else {}))
     cfgkw = dict(algo=sp.algo, N=sp.N, B=sp.B, m=sp.m, bits=sp.bits, clip_mode=sp.clip_mode, clip=sp.clip,
                  eta=sp.eta, L=sp.L, seed=sp.seed, n_full=sp.n_full)
     ctx = lpc.context_from_problem(sp)
     for key, val in ((lpc.TUNE_ITER_LAUNCHES, args.iter_launches), (lpc.TUNE_ITER_TILE, args.iter_tile),
                      (lpc.TUNE_ITER_THREADS, args.iter_threads)):
-        if val is not None:
+        if val is not None and sp.loss != 2 and sp.csr is None:
             ctx.tune(key, val)
     n, d, N, B, m, bits = sp.n, sp.d, sp.N, sp.B, sp.m, sp.bits
     dp = lpc.d_pad(d)
@@ -227,10 +228,6 @@ def main():
     alpc = sp.algo != lpc.ALGO_LPC
     w = torch.from_numpy(sp.w0).to(dev)
     ya, za = (w.clone(), w.clone()) if alpc else (None, None)
-
-    # all library work goes to a stream of its own (not the legacy default stream)
-    stream = torch.cuda.Stream(device=dev)
-    torch.cuda.set_stream(stream)
 
     # ---- the timed region: K whole epochs --------------------------------------------------
     P0 = ctx.objective(w)
@@ -245,22 +242,27 @@ def main():
     ms_per_step = 1e3 * elapsed / steps
     iters_per_sec = m * steps / elapsed
     P_end = ctx.objective(w)
+    assert ctx.take_device_flags() == 0
 
-    # ---- the same steps again with HIP events around every kernel class ---------------------
+    # ---- the same steps again with HIP events on every kernel class ------------------------
     ctx.profile_enable(True)
     s0 = warmup + steps
-    for s in range(s0, s0 + steps):
+    psteps = min(steps, 5)
+    for s in range(s0, s0 + psteps):
         ctx.epoch(w, s, ya, za)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
     work = algorithmic_work(sp, dp, nnz)
     kernels = {}
-    for k, (ms, cnt) in prof.items():
+    for k, (ms, cnt, exact) in prof.items():
         if cnt == 0:
             continue
         avg_ms = ms / cnt
-        ent = {"name": KERNEL_NAMES[k], "launches_per_step": cnt / steps, "avg_us": 1e3 * avg_ms,
-               "share_of_step": (ms / steps) / ms_per_step}
+        ent = {"name": KERNEL_NAMES[k], "launches_per_step": cnt / psteps, "avg_us": 1e3 * avg_ms,
+               "share_of_step": (ms / psteps) / ms_per_step,
+               # one kernel timed by its own dispatch (what a kernel trace reports), or several launches between
+               # two event records (adds a few microseconds of event handling)
+               "timing": "kernel dispatch begin to end" if exact else "event records around the launches"}
         if k in work:
             amount, kind = work[k]
             rate = amount / (avg_ms * 1e-3)
@@ -270,16 +272,13 @@ def main():
             else:
                 ent.update({"bound": "mfma", "algorithmic_flops": amount, "achieved": rate / 1e12, "unit": "TFLOP/s",
                             "peak": MFMA_FP32_PEAK_TFLOPS, "frac": rate / 1e12 / MFMA_FP32_PEAK_TFLOPS})
-        if 1e3 * avg_ms < 20.0:
-            # the two event records around a launch cost about 2.8 us themselves (rocprofv3's kernel trace of
-            # the same command, kept under profiles/, gives the GPU-side duration)
-            ent["note"] = "HIP-event interval of a microsecond-scale launch: includes ~2.8 us of event overhead"
         kernels[k] = ent
-    traffic = {} if args.small else measured_traffic(args.workload)
+    traffic = {} if args.small else measured_traffic(name)
     for k in kernels:
         if k in traffic:
             kernels[k]["traffic_bytes"] = traffic[k]
     rated = [k for k in kernels if "frac" in kernels[k]]
+
     # the dominant class: the one that carries most of the step's algorithmic work, measured as the time it
     # would take at its own roofline (launches per step x bytes or flops per launch / peak); time shares of
     # microsecond-scale launches are within each other's measurement noise and would make the choice flip
@@ -291,26 +290,25 @@ def main():
     dom = max(rated, key=roofline_seconds)
     kd = kernels[dom]
     roofline = {"kernel": kd["name"], "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"],
-                "unit": kd["unit"], "frac": kd["frac"], "traffic": kd.get("traffic_bytes"), "us_per_launch": kd["avg_us"],
-                "launches_per_step": kd["launches_per_step"]}
+                "unit": kd["unit"], "frac": kd["frac"], "traffic": kd.get("traffic_bytes"),
+                "traffic_source": ("profiles/%s_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, stored)" % name
+                                   if kd.get("traffic_bytes") is not None else None),
+                "us_per_launch": kd["avg_us"], "timing": kd["timing"], "launches_per_step": kd["launches_per_step"]}
+    if kd["bound"] == "hbm" and achievable:
+        roofline["measured_achievable"] = {"GBps": achievable["achieved_GBps"],
+                                           "what": "1 GiB device-to-device copy on this machine, read + write",
+                                           "frac_of_it": kd["achieved"] / achievable["achieved_GBps"]}
     if dom == "vr_rows" and kd["bound"] == "hbm" and kd["avg_us"] < 20:
         roofline["note"] = ("one launch moves only %.1f MB, so it is bound by launch and dependency latency, not by "
                             "HBM; the HBM-bound kernel of the step is the snapshot pass (kernels.full_rows)"
                             % (kd["algorithmic_bytes"] / 1e6))
     t_full_ms = (prof["full_rows"][0] + prof["full_fold"][0]) / max(1, prof["full_rows"][1])
-    out = {
-        "metric": "svrg_inner_iters_per_sec",
+    rec = {
         "value": iters_per_sec,
         "unit": "inner iterations/s",
-        "n_gpus": 1,
         "steps": steps,
         "warmup": warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
         "config": {"workload": "%s%s: %s n=%d d=%d%s N=%d B=%d bits=%d m=%d clip=%s%g algo=%s"
                    % (sp.name, " (scaled down)" if args.small else "",
                       {0: "logistic", 1: "squared loss", 2: "MLP softmax"}[sp.loss] + (" CSR" if sp.csr else " dense"),
@@ -326,13 +324,83 @@ def main():
     if "frac" in kernels.get("full_rows", {}):
         amount, kind = work["full_rows"]
         rate = amount / (t_full_ms * 1e-3)
-        out["full_grad_pass"].update({"achieved": rate / (1e9 if kind == "bytes" else 1e12),
+        rec["full_grad_pass"].update({"achieved": rate / (1e9 if kind == "bytes" else 1e12),
                                       "unit": "GB/s" if kind == "bytes" else "TFLOP/s",
                                       "frac_of_peak": rate / (1e9 * HBM_PEAK_GBPS if kind == "bytes"
                                                               else 1e12 * MFMA_FP32_PEAK_TFLOPS)})
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(sp, cfgkw, alpc)
     ctx.close()
+    del ctx, w, ya, za
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(sp, cfgkw, alpc)
+    return rec
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="all", choices=["all", "c1", "c2", "c3", "c4", "c5"],
+                    help="all (default): the headline on c4, the largest configuration, with c2, c3 and c5 as "
+                         "sub-records under 'workloads'; or one configuration alone")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--iter-launches", type=int, default=None, choices=[2, 3],
+                    help="launches per dense inner iteration (lpc_tune; default: the library's choice)")
+    ap.add_argument("--iter-tile", type=int, default=None, choices=[64, 128])
+    ap.add_argument("--iter-threads", type=int, default=None, choices=[256, 512])
+    ap.add_argument("--small", action="store_true", help="scaled-down problems (quick functional run)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run ten 1 GiB device-to-device copies (a kernel of known traffic: 1 GiB read, "
+                         "1 GiB written) so that rocprofv3's FETCH_SIZE / WRITE_SIZE counters can be scaled")
+    ap.add_argument("--contractions", action="store_true",
+                    help="only time the MLP workload's matrix products one by one (the contraction kernel's "
+                         "unit-test entry point), one line per shape")
+    args = ap.parse_args()
+    if args.contractions:
+        contraction_shapes()
+        return
+    if args.copy_calibration:
+        print(json.dumps({"copy_calibration": copy_calibration()}))
+        return
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the N workers are shards on one device); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    # all library work goes to a stream of its own (not the legacy default stream)
+    stream = torch.cuda.Stream(device=torch.device("cuda:0"))
+    torch.cuda.set_stream(stream)
+    achievable = copy_calibration()
+
+    head = "c4" if args.workload == "all" else args.workload
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[head][0]
+    warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[head][1]
+    rec = run_workload(head, steps, warmup, args, achievable)
+    out = {
+        "metric": "svrg_inner_iters_per_sec",
+        "value": rec["value"],
+        "unit": rec["unit"],
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": rec["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+    }
+    out.update({k: v for k, v in rec.items() if k not in out})
+    out["copy_calibration"] = achievable
+    if args.workload == "all":
+        # the other single-GPU configurations, each with its own steps (the headline above is the largest one)
+        out["workloads"] = {}
+        for name in ("c2", "c3", "c5"):
+            k, wu = DEFAULT_STEPS[name]
+            out["workloads"][name] = run_workload(name, k, wu, args, achievable)
     print(json.dumps(out))
 
 

@@ -279,9 +279,13 @@ lpc_status lpc_huffman_encode(lpc_ctx *ctx, const uint32_t *packed, const int32_
 /* ---- measurement aid (benchmarks; no passage of the paper) ------------------------------
  * While enabled, every launch of the kernel classes below made by this context is bracketed by
  * two HIP events on its stream (this allocates events and perturbs the pipeline slightly, so it
- * is off by default).  lpc_profile_read synchronises the stream, returns per class the summed
- * duration in milliseconds and the number of launches since the last read (two HOST arrays of
- * LPC_PROF_NCLASS entries), and clears the records. */
+ * is off by default).  Where a class is a single kernel launch the two events ride on that launch
+ * itself, so their interval is the dispatch's own begin-to-end time (what a kernel trace reports);
+ * where it is several launches the events are recorded before and after them, which adds a few
+ * microseconds of event handling.  lpc_profile_read synchronises the stream, returns per class the
+ * summed duration in milliseconds, the number of records since the last read and (exact, may be NULL)
+ * whether every record of the class was of the first kind (three HOST arrays of LPC_PROF_NCLASS
+ * entries), and clears the records. */
 typedef enum {
   LPC_PROF_FULL_ROWS = 0, /* snapshot pass: rows kernel                         */
   LPC_PROF_FULL_FOLD = 1, /* snapshot pass: fold of the partial gradient rows   */
@@ -291,7 +295,7 @@ typedef enum {
   LPC_PROF_NCLASS = 5
 } lpc_prof_class;
 lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on);
-lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, void *stream);
+lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, int32_t *exact, void *stream);
 
 /* ---- unit-test and benchmark entry of the MLP instance's contraction kernel (no passage of the paper) ----
  * C (M x N, row-major, leading dimension ldc) = [C +] alpha * op(A) * op(B) [+ bias[n]] [then ReLU] in fp32 on

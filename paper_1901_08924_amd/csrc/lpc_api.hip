@@ -12,6 +12,8 @@
 
 using namespace lpc;
 
+thread_local lpc::LaunchTimer *lpc::g_launch_timer = nullptr;
+
 namespace {
 
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
@@ -22,22 +24,33 @@ inline hipStream_t as_stream(void *s) { return (hipStream_t)s; }
 bool is_csr(const lpc_problem &p) { return p.X == nullptr; }
 
 // Optional timing of kernel classes with HIP events on the launch stream (benchmarks only; the
-// events cost a little pipeline time, so the hot path leaves this off).
+// events cost a little pipeline time, so the hot path leaves this off).  single = the scope issues exactly ONE
+// kernel, through LPC_LAUNCH_TIMED: that launch then carries the two events itself (dispatch begin / end).
 struct ProfScope {
   lpc_ctx *c;
   hipStream_t st;
   hipEvent_t stop = nullptr;
-  ProfScope(lpc_ctx *ctx, int cls, hipStream_t s) : c(ctx), st(s) {
+  bool single;
+  LaunchTimer timer;
+  ProfScope(lpc_ctx *ctx, int cls, hipStream_t s, bool single_kernel = false) : c(ctx), st(s), single(single_kernel) {
     if (!c->prof_on) return;
     hipEvent_t start = nullptr;
     if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) { stop = nullptr; return; }
     c->prof_start.push_back(start);
     c->prof_stop.push_back(stop);
     c->prof_cls.push_back(cls);
-    (void)hipEventRecord(start, st);
+    c->prof_exact.push_back(single ? 1 : 0);
+    if (single) {
+      timer.start = start; timer.stop = stop;
+      g_launch_timer = &timer;
+    } else {
+      (void)hipEventRecord(start, st);
+    }
   }
   ~ProfScope() {
-    if (stop) (void)hipEventRecord(stop, st);
+    if (!stop) return;
+    if (single) g_launch_timer = nullptr;
+    else (void)hipEventRecord(stop, st);
   }
 };
 
@@ -237,7 +250,7 @@ lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, doubl
   if (!c->grad_ok) return LPC_EUNSUPPORTED;
   hipError_t e;
   {
-    ProfScope ps(c, LPC_PROF_FULL_ROWS, st);
+    ProfScope ps(c, LPC_PROF_FULL_ROWS, st, !c->mlp && !c->csr);
     if (c->mlp) return dev(launch_mlp_full_grad(c, w, mu, f_out, n_rows, st));
     e = c->csr ? launch_csr_full_grad(c, w, mu, z, f_out != nullptr, n_rows, st)
                : launch_dense_full_grad(c, w, z, f_out != nullptr, n_rows, st);
@@ -274,11 +287,11 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
     return dev(launch_vector_stats(c, U_row0, c->d_pad, slot0, we - wb, stats_row0, stats_mode, stat_slots_used, st));
   }
   {
-    ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+    ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
     e = launch_dense_vr_grad(c, w, w_snap, z_snap, key, tag, wb, we, false, st);
   }
   if (e != hipSuccess) return LPC_EDEVICE;
-  ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+  ProfScope ps(c, LPC_PROF_VR_FOLD, st, stats_mode != kStatsFinal);
   e = launch_reduce_parts(c, c->s.part, c->vr_parts, (float)(1.0 / (double)c->cfg.B), U_row0, c->d_pad, slot0,
                           we - wb, stats_mode, stats_row0, st);
   if (stat_slots_used) *stat_slots_used = (int32_t)((c->d_pad + 63) / 64);
@@ -476,20 +489,21 @@ lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on) {
   return LPC_OK;
 }
 
-lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, void *stream) {
+lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, int32_t *exact, void *stream) {
   if (!ctx || !ms_total || !launches) return LPC_ENULL;
   LPC_TRY_HIP(hipStreamSynchronize(as_stream(stream)));
-  for (int k = 0; k < LPC_PROF_NCLASS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
+  for (int k = 0; k < LPC_PROF_NCLASS; ++k) { ms_total[k] = 0.0; launches[k] = 0; if (exact) exact[k] = 1; }
   for (size_t i = 0; i < ctx->prof_cls.size(); ++i) {
     float ms = 0.0f;
     if (hipEventElapsedTime(&ms, ctx->prof_start[i], ctx->prof_stop[i]) == hipSuccess) {
       ms_total[ctx->prof_cls[i]] += (double)ms;
       launches[ctx->prof_cls[i]] += 1;
+      if (exact && !ctx->prof_exact[i]) exact[ctx->prof_cls[i]] = 0;
     }
     (void)hipEventDestroy(ctx->prof_start[i]);
     (void)hipEventDestroy(ctx->prof_stop[i]);
   }
-  ctx->prof_start.clear(); ctx->prof_stop.clear(); ctx->prof_cls.clear();
+  ctx->prof_start.clear(); ctx->prof_stop.clear(); ctx->prof_cls.clear(); ctx->prof_exact.clear();
   return LPC_OK;
 }
 
@@ -706,16 +720,16 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       } else if (two) {
         // two launches per inner iteration: rows; fold + exchange + prox
         {
-          ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+          ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
           LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, false, st));
         }
-        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
         LPC_TRY_HIP(launch_fused_iter(c, key, s.packed, s.delta, s.mu, g.eta, s.w, nullptr, st));
       } else if (fused) {
         // three launches per inner iteration: rows, fold (+ statistic partials), exchange + prox
         int32_t slots = 0;
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr, kStatsPartial, st, &slots));
-        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
         LPC_TRY_HIP(launch_fused_exchange(c, s.U, slots, key, s.packed, s.delta, s.mu, g.eta, s.w, nullptr, st));
       } else {
         LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
@@ -742,7 +756,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       {
-        ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+        ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
         LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, true, st));
       }
       if (c->iter2) {
@@ -752,14 +766,14 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
         al.y = y; al.z = z; al.ysum = s.ysum; al.x_next = s.w;
         al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
         al.first = t == 0 ? 1 : 0;
-        ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
         LPC_TRY_HIP(launch_fused_iter(c, key, s.packed, s.delta, nullptr, 0.0f, nullptr, &al, st));
         wsum += weight;
         weight *= (double)ap.theta;
         continue;
       }
       {
-        ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+        ProfScope ps(c, LPC_PROF_VR_FOLD, st, true);
         LPC_TRY_HIP(launch_reduce_parts(c, s.part, c->vr_parts, (float)(1.0 / (double)g.B), s.U, c->d_pad, 0,
                                         g.N + 1, kStatsPartial, nullptr, st));
       }
@@ -768,7 +782,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       al.y = y; al.z = z; al.ysum = s.ysum; al.x_next = s.w;
       al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
       al.first = t == 0 ? 1 : 0;
-      ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+      ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
       LPC_TRY_HIP(launch_fused_exchange_alpc(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, al,
                                              st));
       wsum += weight;

@@ -267,13 +267,11 @@ template <int VEC, int K, int T, int MODE>
 void launch_shape(const DenseArgs &a, int grid, int rows_hint, hipStream_t st) {
   constexpr int RMAX = (K >= 8) ? 1 : ((K * VEC >= 16 && MODE == 2) ? 2 : 4);
   if (RMAX >= 4 && rows_hint >= 4) {
-    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, (RMAX >= 4 ? 4 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), 0,
-                       st, a);
+    LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, (RMAX >= 4 ? 4 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), st, a);
   } else if (RMAX >= 2 && rows_hint >= 2) {
-    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, (RMAX >= 2 ? 2 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), 0,
-                       st, a);
+    LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, (RMAX >= 2 ? 2 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), st, a);
   } else {
-    hipLaunchKernelGGL((dense_rows_kernel<VEC, K, T, 1, MODE>), dim3((unsigned)grid), dim3(T), 0, st, a);
+    LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, 1, MODE>), dim3((unsigned)grid), dim3(T), st, a);
   }
 }
 

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <vector>
@@ -64,6 +65,25 @@ struct RowPlan {
 struct HuffEntry {
   uint32_t rev, len;
 };
+
+// Kernel-class timing (lpc_profile_enable): where a class is ONE kernel launch, that launch carries the class's two
+// events itself, so their interval is the dispatch's own begin and end time stamps (what a kernel trace reports)
+// instead of an interval between two event records around it, which adds a few microseconds.
+struct LaunchTimer {
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool used = false;
+};
+extern thread_local LaunchTimer *g_launch_timer;  // set while such a class's launch is being issued, else nullptr
+#define LPC_LAUNCH_TIMED(kernel, grid, block, st, ...)                                                        \
+  do {                                                                                                        \
+    lpc::LaunchTimer *lt_ = lpc::g_launch_timer;                                                              \
+    if (lt_ && !lt_->used) {                                                                                  \
+      lt_->used = true;                                                                                       \
+      hipExtLaunchKernelGGL(kernel, grid, block, 0, st, lt_->start, lt_->stop, 0, __VA_ARGS__);               \
+    } else {                                                                                                  \
+      hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                                            \
+    }                                                                                                         \
+  } while (0)
 
 // ---- device scratch owned by a context (all pointers into the workspace) ----
 struct Scratch {
@@ -151,6 +171,7 @@ struct lpc_ctx {
   bool prof_on = false;   // kernel-class timing (lpc_profile_enable)
   std::vector<hipEvent_t> prof_start, prof_stop;
   std::vector<int> prof_cls;
+  std::vector<char> prof_exact;  // the record is one kernel timed by its own dispatch
   lpc::Scratch s;
 };
 

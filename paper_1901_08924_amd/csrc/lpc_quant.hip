@@ -1657,11 +1657,11 @@ hipError_t launch_reduce_parts(const lpc_ctx *c, const float *part, int32_t part
   // the scratch slots (statistics, quantizer parameters).
   const dim3 grid((unsigned)((c->d_pad + 63) / 64), (unsigned)nvec);
   if (reduce_parts_waves(c, parts, nvec) == 2)
-    hipLaunchKernelGGL(reduce_parts_kernel<2>, grid, dim3(128), 0, st, part, parts, c->d, c->d_pad, scale, out,
-                       ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
+    LPC_LAUNCH_TIMED(reduce_parts_kernel<2>, grid, dim3(128), st, part, parts, c->d, c->d_pad, scale, out, ld_out,
+                     vec_begin, (int32_t)stats_mode, sinks_of(c, stats_out));
   else
-    hipLaunchKernelGGL(reduce_parts_kernel<4>, grid, dim3(256), 0, st, part, parts, c->d, c->d_pad, scale, out,
-                       ld_out, vec_begin, stats_mode, sinks_of(c, stats_out));
+    LPC_LAUNCH_TIMED(reduce_parts_kernel<4>, grid, dim3(256), st, part, parts, c->d, c->d_pad, scale, out, ld_out,
+                     vec_begin, (int32_t)stats_mode, sinks_of(c, stats_out));
   if (stats_mode == kStatsFinal)
     hipLaunchKernelGGL(finalize_stats_kernel, dim3((unsigned)nvec), dim3(64), 0, st, sinks_of(c, stats_out),
                        spec_of(c), vec_begin, (int32_t)grid.x, c->d);
@@ -1888,7 +1888,7 @@ hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslot
   prox_consts(c, step > 0.0f ? step : 1.0f, &a.thr, &a.shrink);
   const int extra = w != nullptr ? warm_setup(c, key, false, &a) : 0;
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords + extra));
-  hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kFusedThreads), 0, st, a);
+  LPC_LAUNCH_TIMED(fused_exchange_kernel, grid, dim3(kFusedThreads), st, a);
   return hipGetLastError();
 }
 
@@ -1907,7 +1907,7 @@ hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t 
   prox_consts(c, al.alpha, &a.thr_z, &a.shrink_z);
   const int extra = warm_setup(c, key, true, &a);
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords + extra));
-  hipLaunchKernelGGL(fused_exchange_kernel, grid, dim3(kFusedThreads), 0, st, a);
+  LPC_LAUNCH_TIMED(fused_exchange_kernel, grid, dim3(kFusedThreads), st, a);
   return hipGetLastError();
 }
 
@@ -1959,13 +1959,13 @@ hipError_t launch_fused_iter(const lpc_ctx *c, StreamKey key, uint32_t *packed, 
   const int tile = c->iter_tile == 64 ? 64 : 128;
   const dim3 grid((unsigned)((c->d_pad + tile - 1) / tile + extra));
   if (tile == 64 && c->iter_threads == 256)
-    hipLaunchKernelGGL((fused_iter_kernel<256, 64>), grid, dim3(256), 0, st, ia);
+    LPC_LAUNCH_TIMED((fused_iter_kernel<256, 64>), grid, dim3(256), st, ia);
   else if (tile == 64)
-    hipLaunchKernelGGL((fused_iter_kernel<512, 64>), grid, dim3(512), 0, st, ia);
+    LPC_LAUNCH_TIMED((fused_iter_kernel<512, 64>), grid, dim3(512), st, ia);
   else if (c->iter_threads == 256)
-    hipLaunchKernelGGL((fused_iter_kernel<256, 128>), grid, dim3(256), 0, st, ia);
+    LPC_LAUNCH_TIMED((fused_iter_kernel<256, 128>), grid, dim3(256), st, ia);
   else
-    hipLaunchKernelGGL((fused_iter_kernel<512, 128>), grid, dim3(512), 0, st, ia);
+    LPC_LAUNCH_TIMED((fused_iter_kernel<512, 128>), grid, dim3(512), st, ia);
   return hipGetLastError();
 }
 

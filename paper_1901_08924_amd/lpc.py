@@ -70,7 +70,7 @@ EXPORTS = {
     "lpc_debug_gemm": (C.c_int, [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, C.c_int64, C.c_int64,
                                  C.c_int32, C.c_int32, C.c_float, _vp, C.c_int32, C.c_int32, _vp]),
     "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
-    "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), _vp]),
+    "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int32), _vp]),
 }
 TUNE_ITER_LAUNCHES, TUNE_ITER_TILE, TUNE_ITER_THREADS, TUNE_SPIN_LIMIT = 0, 1, 2, 3
 PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange")
@@ -297,11 +297,13 @@ class Context:
         _chk(lib.lpc_profile_enable(self._h, 1 if on else 0), "lpc_profile_enable")
 
     def profile_read(self, stream=None):
-        """{class: (total ms, launches)} since the last read."""
+        """{class: (total ms, launches, exact)} since the last read; exact = every record was one kernel timed by
+        its own dispatch (no event-handling overhead in the interval)."""
         ms = (C.c_double * len(PROF_CLASSES))()
         cnt = (C.c_int64 * len(PROF_CLASSES))()
-        _chk(lib.lpc_profile_read(self._h, ms, cnt, _stream(stream)), "lpc_profile_read")
-        return {k: (ms[i], cnt[i]) for i, k in enumerate(PROF_CLASSES)}
+        exact = (C.c_int32 * len(PROF_CLASSES))()
+        _chk(lib.lpc_profile_read(self._h, ms, cnt, exact, _stream(stream)), "lpc_profile_read")
+        return {k: (ms[i], cnt[i], bool(exact[i])) for i, k in enumerate(PROF_CLASSES)}
 
     def take_device_flags(self, stream=None):
         return lib.lpc_take_device_flags(self._h, _stream(stream))
