@@ -149,6 +149,11 @@ size_t layout(lpc_ctx *c, char *base) {
   s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * c->cfg.N * c->cfg.B : 1) * sizeof(RowPlan));
   s.warm_sink = (float *)take(sizeof(float));
   s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
+  {
+    const size_t extra = c->csr_sparse ? (size_t)(csr_sparse_parts(c->cfg.B) - 1) : 0;
+    s.sparse_planes = (float *)take((extra ? (size_t)c->cfg.N * extra * c->d_pad : 4) * sizeof(float));
+    s.touched_parts = (uint32_t *)take((extra ? (size_t)c->cfg.N * extra * c->bitmap_words : 4) * sizeof(uint32_t));
+  }
   s.iter_slots = (unsigned long long *)take((c->iter2_capable ? (size_t)fused_iter_slot_words(c) : 1) * sizeof(unsigned long long));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
@@ -202,7 +207,8 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->bitmap_words = (c->d_pad / 32 + 31) / 32;
     const double touched = (double)cfg->B * (double)p->nnz / (double)p->n;
     c->csr_sparse = c->quant && cfg->algo == LPC_ALGO_LPC && cfg->scheme == LPC_SCHEME_A && cfg->N <= 64 &&
-                    p->d >= 4 * (int64_t)c->sparse_head && touched * 8.0 <= (double)p->d;
+                    p->d >= 4 * (int64_t)c->sparse_head && touched * 8.0 <= (double)p->d &&
+                    csr_sparse_parts(cfg->B) <= 8;  // tail planes per worker the statistics pass can merge
     if (c->csr_sparse) {
       const size_t head_parts = (size_t)cfg->N * csr_sparse_parts(cfg->B) * c->sparse_head;
       if (head_parts > c->part_floats) c->part_floats = head_parts;
@@ -698,6 +704,10 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     if (sparse) {
       // the sparse passes rely on U, the bitmap and the packed words being zero where nothing was written
       LPC_TRY_HIP(launch_zero(s.U, (int64_t)g.N * c->d_pad, st));
+      if (csr_sparse_parts(g.B) > 1) {
+        LPC_TRY_HIP(launch_zero(s.sparse_planes, (int64_t)g.N * (csr_sparse_parts(g.B) - 1) * c->d_pad, st));
+        LPC_TRY_HIP(launch_fill_u32(s.touched_parts, 0u, (int64_t)g.N * (csr_sparse_parts(g.B) - 1) * c->bitmap_words, st));
+      }
       LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
       LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
       // the epoch's draws with each row's extent, label and snapshot margin, looked up once

@@ -27,7 +27,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kGroup = 16;                     // lanes per row
-constexpr int kGroups = kThreads / kGroup;     // rows in flight per workgroup
 
 __device__ __forceinline__ float loss_slope(int32_t loss, float z, float y) {
   if (loss == LPC_LOSS_LOGISTIC) return -y / (1.0f + expf(y * z));
@@ -56,7 +55,9 @@ struct CsrArgs {
   float *part;        // snapshot pass: [workgroup][head] partial rows
   double *part_loss;  // snapshot pass
   float *U;           // worker pass: [N][d_pad], zeroed
+  float *planes;      // sparse worker pass: [N][parts-1][d_pad] tail planes of a worker's workgroups 1..parts-1
   uint32_t *touched;  // sparse worker pass: [N][bitmap_words], one bit per 32-coordinate segment
+  uint32_t *touched_parts;  // ... and [N][parts-1][bitmap_words] for the workgroups 1..parts-1 of a worker
   int64_t bitmap_words;
   int32_t parts, rows_per_part;  // sparse worker pass: workgroups per worker, sampled rows per workgroup
   const RowPlan *plan;           // sparse worker pass: [N][B] rows of this iteration, looked up ahead
@@ -75,12 +76,7 @@ __device__ __forceinline__ float group_sum(float v) {
   return row16_sum(v);
 }
 
-// Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kFullGroups-th row.
-// Built to keep many rows in flight: 1024 threads (64 row groups) share one LDS head, two such workgroups
-// fit a CU, the first 64 pairs of a row (most rows have no more) are requested one row ahead and the extent
-// of a row two rows ahead.
-constexpr int kFullThreads = 1024;
-constexpr int kFullGroups = kFullThreads / kGroup;
+constexpr int kFullThreads = 1024;  // snapshot pass: threads per workgroup
 
 struct RowExtent {
   int32_t lo, hi;
@@ -110,6 +106,29 @@ __device__ __forceinline__ void load_pairs(const CsrArgs &a, const RowExtent &x,
   }
 }
 
+// Ordered scatter.  Float additions into one accumulator must happen in a fixed order for the result not to
+// depend on scheduling; both passes below arrange that without giving up the atomics' convenience: one
+// wavefront's atomic additions to one address execute in issue order, in LDS and in memory, so it is enough that
+// every accumulator receives its contributions from wavefronts that take turns in a fixed order.
+struct RowRecord {
+  int32_t lo, len;
+  float coef;
+};
+
+// Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kFullGroups-th row.
+// Built to keep many rows in flight: 1024 threads (64 row groups) share one LDS head, two such workgroups
+// fit a CU, the first 64 pairs of a row (most rows have no more) are requested one row ahead and the extent
+// of a row two rows ahead.
+// The head columns' LDS accumulation is made independent of scheduling by a fixed rotation: a wavefront keeps
+// the pairs and slopes of kTurnRounds rounds of its rows in registers and adds them into the LDS accumulator only
+// when the counter `turn` reads block*NW + w (block = round / kTurnRounds, w = its index), then advances the
+// counter.  One wavefront's LDS instructions execute in issue order and the counter lives in LDS too, so one
+// turn's additions are complete before the next turn's begin: every accumulator receives its contributions in one
+// fixed order.  Every wavefront goes through the same number of blocks (rows past the end are empty rows) and
+// there is no barrier inside the loop, so the wavefront whose turn it is can always proceed.
+constexpr int kFullGroups = kFullThreads / kGroup;
+constexpr int kTurnRounds = 4;
+
 template <bool CSC>
 __global__ __launch_bounds__(kFullThreads) void csr_full_kernel(CsrArgs a, int64_t rows_per_wg) {
   // LDS: the head of the gradient accumulator, then a copy of the head of w.  Most entries fall into the
@@ -118,69 +137,102 @@ __global__ __launch_bounds__(kFullThreads) void csr_full_kernel(CsrArgs a, int64
   extern __shared__ float head_acc[];
   float *w_head = head_acc + a.head;
   __shared__ double loss_red[kFullGroups];
-  const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
+  __shared__ uint32_t turn;
+  constexpr int NW = kFullThreads / 64;
+  const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup, wv = tid >> 6;
   for (int32_t j = tid; j < a.head; j += kFullThreads) {
     head_acc[j] = 0.0f;
     w_head[j] = a.w[j];
   }
+  if (tid == 0) turn = 0u;
   __syncthreads();
   const int64_t r0 = (int64_t)blockIdx.x * rows_per_wg;
   int64_t r1 = r0 + rows_per_wg;
   if (r1 > a.n_rows) r1 = a.n_rows;
   double loss_acc = 0.0;
   if (r0 < r1) {  // uniform over the workgroup
+    const int64_t rounds = (r1 - r0 + kFullGroups - 1) / kFullGroups;
+    const int64_t blocks = (rounds + kTurnRounds - 1) / kTurnRounds;  // the same for every wavefront
     int64_t r = r0 + grp;
     RowExtent cur = load_extent(a, r, r1);
     RowExtent nxt = load_extent(a, r + kFullGroups, r1);
     int32_t c[4];
     float v[4];
     load_pairs(a, cur, gl, c, v);
-    while (r < r1) {
-      // the gathers of this row go out first: the wait for them then leaves the prefetches below in
-      // flight (memory operations complete in issue order as far as the wait counter is concerned)
-      float wv[4];
+    for (int64_t block = 0; block < blocks; ++block) {
+      int32_t kc[kTurnRounds][4], klo[kTurnRounds], khi[kTurnRounds];
+      float kg[kTurnRounds][4], kcoef[kTurnRounds];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        wv[q] = w_head[c[q] < a.head ? c[q] : 0];
-        if (c[q] >= a.head && v[q] != 0.0f) wv[q] = a.w[c[q]];  // only the lanes that need memory ask for it
-      }
-      const RowExtent nxt2 = load_extent(a, r + 2 * kFullGroups, r1);
-      int32_t cn[4];
-      float vn[4];
-      load_pairs(a, nxt, gl, cn, vn);
-      float s = 0.0f;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) s = fmaf(v[q], wv[q], s);
-      for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {  // rows longer than 64 entries
-        const int32_t col = a.col_idx[e];
-        s = fmaf(a.vals[e], col < a.head ? w_head[col] : a.w[col], s);
-      }
-      const float z = group_sum(s);
-      const float coef = loss_slope(a.loss, z, cur.y);
-      if (gl == 0) {
-        if (a.z_out) a.z_out[r] = z;
-        if (CSC) a.coef[r] = coef;
-        if (a.want_loss) loss_acc += (double)loss_value(a.loss, z, cur.y);
-      }
-      if (a.want_grad) {
+      for (int t = 0; t < kTurnRounds; ++t) {
+        // the gathers of this row go out first: the wait for them then leaves the prefetches below in
+        // flight (memory operations complete in issue order as far as the wait counter is concerned)
+        float wv4[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const float g = coef * v[q];
-          if (v[q] == 0.0f) continue;  // outside the row (a stored zero adds nothing either)
-          if (c[q] < a.head) atomicAdd(&head_acc[c[q]], g);  // LDS
-          else if (!CSC) atomicAdd(&a.tail[c[q]], g);
+          wv4[q] = w_head[c[q] < a.head ? c[q] : 0];
+          if (c[q] >= a.head && v[q] != 0.0f) wv4[q] = a.w[c[q]];  // only the lanes that need memory ask for it
         }
-        for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {
-          const int32_t col = a.col_idx[e];
-          const float g = coef * a.vals[e];
-          if (col < a.head) atomicAdd(&head_acc[col], g);
-          else if (!CSC) atomicAdd(&a.tail[col], g);
-        }
-      }
-      r += kFullGroups;
-      cur = nxt; nxt = nxt2;
+        const RowExtent nxt2 = load_extent(a, r + 2 * kFullGroups, r1);
+        int32_t cn[4];
+        float vn[4];
+        load_pairs(a, nxt, gl, cn, vn);
+        float s = 0.0f;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) { c[q] = cn[q]; v[q] = vn[q]; }
+        for (int q = 0; q < 4; ++q) s = fmaf(v[q], wv4[q], s);
+        for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {  // rows longer than 64 entries
+          const int32_t col = a.col_idx[e];
+          // two loads and a choice between the VALUES (a choice between an LDS and a memory address would make the
+          // load a generic one); rows this long are rare
+          const float from_lds = w_head[col < a.head ? col : 0], from_mem = a.w[col];
+          s = fmaf(a.vals[e], col < a.head ? from_lds : from_mem, s);
+        }
+        const float z = group_sum(s);
+        const float coef = loss_slope(a.loss, z, cur.y);
+        if (gl == 0 && r < r1) {
+          if (a.z_out) a.z_out[r] = z;
+          if (CSC) a.coef[r] = coef;
+          if (a.want_loss) loss_acc += (double)loss_value(a.loss, z, cur.y);
+        }
+        klo[t] = cur.lo; khi[t] = cur.hi; kcoef[t] = coef;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { kc[t][q] = c[q]; kg[t][q] = coef * v[q]; }
+        r += kFullGroups;
+        cur = nxt; nxt = nxt2;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { c[q] = cn[q]; v[q] = vn[q]; }
+      }
+      if (a.want_grad) {
+        const uint32_t ticket = (uint32_t)block * NW + (uint32_t)wv;
+        while (__hip_atomic_load(&turn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != ticket) {
+        }
+        asm volatile("" ::: "memory");  // the additions below stay behind the read of the counter
+#pragma unroll
+        for (int t = 0; t < kTurnRounds; ++t) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)  // a zero: outside the row (a stored zero adds nothing either)
+            if (kg[t][q] != 0.0f && kc[t][q] < a.head) atomicAdd(&head_acc[kc[t][q]], kg[t][q]);  // LDS
+          for (int32_t e = klo[t] + 4 * kGroup + gl; e < khi[t]; e += kGroup) {
+            const int32_t col = a.col_idx[e];
+            if (col < a.head) atomicAdd(&head_acc[col], kcoef[t] * a.vals[e]);
+          }
+        }
+        if (!CSC) {  // without the column-major copy the tail columns take float atomics in memory
+#pragma unroll
+          for (int t = 0; t < kTurnRounds; ++t) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+              if (kg[t][q] != 0.0f && kc[t][q] >= a.head) atomicAdd(&a.tail[kc[t][q]], kg[t][q]);
+            for (int32_t e = klo[t] + 4 * kGroup + gl; e < khi[t]; e += kGroup) {
+              const int32_t col = a.col_idx[e];
+              if (col >= a.head) atomicAdd(&a.tail[col], kcoef[t] * a.vals[e]);
+            }
+          }
+        }
+        // the additions above are LDS instructions issued before this store (the compiler keeps the order, the LDS
+        // executes a wavefront's instructions in issue order), so whoever reads the new count finds them done
+        asm volatile("" ::: "memory");
+        if ((tid & 63) == 0) __hip_atomic_store(&turn, ticket + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
     }
   }
   __syncthreads();
@@ -375,106 +427,148 @@ __global__ void csr_tail_kernel(const float *__restrict__ tail, float scale, int
   if (j < d) mu[j] = tail[j] * scale;
 }
 
-// Worker pass: sixteen lanes per sampled row, scatter into the worker's zeroed row of U.
-template <bool CACHED>
-__global__ __launch_bounds__(kThreads) void csr_vr_kernel(CsrArgs a, int32_t nworkers) {
-  const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
-  const int64_t slot = (int64_t)blockIdx.x * kGroups + grp;   // (worker, position) pair
-  if (slot >= (int64_t)nworkers * a.B) return;                // whole groups leave together
-  const int32_t wrel = (int32_t)(slot / a.B), pos = (int32_t)(slot % a.B);
-  const uint32_t worker = (a.tag == kTagShared) ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
-  const int64_t r = sample_row(a.key, a.tag, worker, (uint32_t)pos, a.n);
-  const int32_t lo = a.row_ptr[r], hi = a.row_ptr[r + 1];
-  const float yr = a.y[r];
-  float s = 0.0f, s2 = 0.0f;
-  for (int32_t e = lo + gl; e < hi; e += kGroup) {
-    const int32_t c = a.col_idx[e];
-    const float v = a.vals[e];
-    s = fmaf(v, a.w[c], s);
-    if (!CACHED) s2 = fmaf(v, a.w_snap[c], s2);
-  }
-  const float z = group_sum(s);
-  const float zs = CACHED ? a.z_snap[r] : group_sum(s2);
-  const float coef = (loss_slope(a.loss, z, yr) - loss_slope(a.loss, zs, yr)) * a.scale;
-  float *u = a.U + (int64_t)wrel * a.d_pad;
-  for (int32_t e = lo + gl; e < hi; e += kGroup) atomicAdd(&u[a.col_idx[e]], coef * a.vals[e]);
-}
-
-// Worker pass that keeps u^i sparse.  A workgroup takes rows_per_part sampled rows of one worker, sixteen
-// lanes per row.  Head columns accumulate in LDS and leave as one partial row per workgroup (a.part, folded by
-// the statistics pass); a tail column is added to the worker's row of U, which is all zero outside the
-// segments touched in this iteration, and its 32-coordinate segment is marked in the bitmap so that the
-// statistics, quantizer and receiver passes visit only marked segments (an unmarked segment codes to zero).
+// Worker pass, with the ordered scatter described above.  A workgroup takes rows_per_part consecutive batch
+// positions of one worker: wavefronts 0 and 1 scatter, the kRowGroups groups of the others take the rows.
+//   SPARSE = false: one workgroup per worker; u^i is the worker's zeroed row of U; the two scatter wavefronts
+//     split the columns by parity.
+//   SPARSE = true:  u^i stays sparse, and a worker's batch is cut into `parts` workgroups.  Head columns
+//     accumulate in LDS (scatter wavefront 0) and leave as the workgroup's head row (a.part); a tail column
+//     (scatter wavefront 1) is added to the workgroup's own plane of the worker's tail -- plane 0 is the worker's
+//     row of U, plane p > 0 lies in a.planes -- which is all zero outside the segments touched in this
+//     iteration, and its 32-coordinate segment is marked in the worker's bitmap.  The statistics pass adds head
+//     rows and planes in workgroup order, so the result is one fixed sum whatever the timing.
 constexpr int kSparseThreads = 1024;
-constexpr int kSparseGroups = kSparseThreads / kGroup;
+constexpr int kScatterWaves = 2;
+constexpr int kRowGroups = (kSparseThreads - 64 * kScatterWaves) / kGroup;  // rows per round: 56
 
-template <bool CACHED>
-__global__ __launch_bounds__(kSparseThreads) void csr_vr_sparse_kernel(CsrArgs a) {
-  extern __shared__ float head_acc[];
-  const int tid = threadIdx.x, gl = tid & (kGroup - 1), grp = tid / kGroup;
+template <bool CACHED, bool SPARSE>
+__global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs a) {
+  extern __shared__ float head_acc[];  // SPARSE: a.head floats
+  __shared__ RowRecord rec[2][kRowGroups];
+  __shared__ int2 stage[2][kRowGroups][64];  // a row's first 64 (column, coef * value) pairs
+  const int tid = threadIdx.x, gl = tid & (kGroup - 1), lane = tid & 63, wv = tid >> 6;
   const int32_t wrel = blockIdx.x / a.parts, part = blockIdx.x % a.parts;
   const int32_t pos0 = part * a.rows_per_part;
   const int32_t pos1 = pos0 + a.rows_per_part < a.B ? pos0 + a.rows_per_part : a.B;
-  // the draws and each row's extent, label and snapshot margin were looked up ahead of the inner loop; the
-  // group's first row is requested while the accumulators are cleared
-  const RowPlan *plan = a.plan + (int64_t)wrel * a.B;
-  RowPlan p{0, 0, 0.0f, 0.0f};
-  if (pos0 + grp < pos1) p = plan[pos0 + grp];
-  for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
-  __syncthreads();
-  float *u = a.U + (int64_t)wrel * a.d_pad;
-  uint32_t *bm = a.touched + (int64_t)wrel * a.bitmap_words;
-  for (int32_t pos = pos0 + grp; pos < pos1; pos += kSparseGroups) {
-    if (pos != pos0 + grp) p = plan[pos];
-    const int32_t lo = p.lo, hi = p.hi;
-    const float yr = p.y, zc = p.z;
-    // 64 entries of the row per step, all loads of a step in flight together (most rows need one step)
-    float s = 0.0f, s2 = 0.0f;
-    int32_t c[4];
-    float v[4];
-    for (int32_t base = lo; base < hi; base += 4 * kGroup) {
+  const uint32_t worker = (a.tag == kTagShared) ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
+  const int32_t rounds = (pos1 - pos0 + kRowGroups - 1) / kRowGroups;
+  if (SPARSE) {
+    for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
+    __syncthreads();
+  }
+  if (wv >= kScatterWaves) {
+    // ---- row wavefronts ------------------------------------------------------------------------------------
+    const int grp = (tid - 64 * kScatterWaves) / kGroup;
+    const RowPlan *plan = SPARSE ? a.plan + (int64_t)wrel * a.B : nullptr;
+    auto fetch_row = [&](int32_t pos) {  // extent, label and snapshot margin of batch position pos
+      RowPlan p{0, 0, 0.0f, 0.0f};
+      if (pos >= pos1) return p;
+      if (SPARSE) return plan[pos];
+      const int64_t r = sample_row(a.key, a.tag, worker, (uint32_t)pos, a.n);
+      p.lo = a.row_ptr[r]; p.hi = a.row_ptr[r + 1];
+      p.y = a.y[r];
+      p.z = CACHED ? a.z_snap[r] : 0.0f;
+      return p;
+    };
+    auto fetch_pairs = [&](const RowPlan &p, int32_t (&c)[4], float (&v)[4]) {  // the row's first 64 pairs
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int32_t e = base + q * kGroup + gl;
-        const bool ok = e < hi;
+        const int32_t e = p.lo + q * kGroup + gl;
+        const bool ok = e < p.hi;
         c[q] = ok ? a.col_idx[e] : 0;
         v[q] = ok ? a.vals[e] : 0.0f;
       }
-      float wv[4], wsv[4];
+    };
+    RowPlan cur = fetch_row(pos0 + grp), nxt = fetch_row(pos0 + kRowGroups + grp);
+    int32_t c[4];
+    float v[4];
+    fetch_pairs(cur, c, v);
+    for (int32_t round = 0; round < rounds; ++round) {
+      // this row's gathers first, then the requests for the rounds ahead stay in flight behind them
+      float wv4[4], wsv[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        wv[q] = a.w[c[q]];
+        wv4[q] = a.w[c[q]];
         wsv[q] = CACHED ? 0.0f : a.w_snap[c[q]];
       }
+      RowPlan nxt2{0, 0, 0.0f, 0.0f};
+      int32_t cn[4] = {0, 0, 0, 0};
+      float vn[4] = {0.f, 0.f, 0.f, 0.f};
+      if (round + 1 < rounds) {  // uniform
+        nxt2 = fetch_row(pos0 + (round + 2) * kRowGroups + grp);
+        fetch_pairs(nxt, cn, vn);
+      }
+      float s = 0.0f, s2 = 0.0f;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        s = fmaf(v[q], wv[q], s);
+        s = fmaf(v[q], wv4[q], s);
         if (!CACHED) s2 = fmaf(v[q], wsv[q], s2);
       }
-    }
-    const float z = group_sum(s);
-    const float zs = CACHED ? zc : group_sum(s2);
-    const float coef = (loss_slope(a.loss, z, yr) - loss_slope(a.loss, zs, yr)) * a.scale;
-    const bool one_step = hi - lo <= 4 * kGroup;  // then c[], v[] still hold the whole row
-    for (int32_t base = lo; base < hi; base += 4 * kGroup) {
+      for (int32_t e = cur.lo + 4 * kGroup + gl; e < cur.hi; e += kGroup) {  // rows longer than 64 entries
+        const int32_t col = a.col_idx[e];
+        const float val = a.vals[e];
+        s = fmaf(val, a.w[col], s);
+        if (!CACHED) s2 = fmaf(val, a.w_snap[col], s2);
+      }
+      const float z = group_sum(s);
+      const float zs = CACHED ? cur.z : group_sum(s2);
+      const float coef = (loss_slope(a.loss, z, cur.y) - loss_slope(a.loss, zs, cur.y)) * a.scale;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int32_t e = base + q * kGroup + gl;
-        if (e >= hi) continue;
-        const int32_t col = one_step ? c[q] : a.col_idx[e];
-        const float g = coef * (one_step ? v[q] : a.vals[e]);
-        if (col < a.head) {
-          atomicAdd(&head_acc[col], g);
-        } else {
+      for (int q = 0; q < 4; ++q)
+        stage[round & 1][grp][q * kGroup + gl] = make_int2(c[q], __float_as_int(coef * v[q]));
+      if (gl == 0) rec[round & 1][grp] = RowRecord{cur.lo, cur.hi - cur.lo, coef};
+      __syncthreads();  // barrier `round`: the round's records and staged pairs are complete
+      cur = nxt; nxt = nxt2;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) { c[q] = cn[q]; v[q] = vn[q]; }
+    }
+  } else {
+    // ---- scatter wavefronts --------------------------------------------------------------------------------
+    float *u = a.U + (int64_t)wrel * a.d_pad;
+    if (SPARSE && part > 0) u = a.planes + ((int64_t)wrel * (a.parts - 1) + (part - 1)) * a.d_pad;
+    uint32_t *bm = SPARSE ? a.touched + (int64_t)wrel * a.bitmap_words : nullptr;
+    if (SPARSE && part > 0) bm = a.touched_parts + ((int64_t)wrel * (a.parts - 1) + (part - 1)) * a.bitmap_words;
+    for (int32_t round = 0; round < rounds; ++round) {
+      __syncthreads();  // barrier `round`
+      // rows in batch-position order, eight staged rows read at a time; `mine` selects this wavefront's columns
+      auto walk = [&](auto mine, auto add) {
+        const int buf = round & 1;
+        for (int32_t row0 = 0; row0 < kRowGroups; row0 += 8) {
+          RowRecord m[8];
+          int2 t[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            m[q] = rec[buf][row0 + q];
+            t[q] = stage[buf][row0 + q][lane];
+          }
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            if (lane < m[q].len && mine(t[q].x)) add(t[q].x, __int_as_float(t[q].y));
+            for (int32_t k = 64 + lane; k < m[q].len; k += 64) {  // the rest of a long row comes from memory
+              const int32_t col = a.col_idx[m[q].lo + k];
+              if (mine(col)) add(col, m[q].coef * a.vals[m[q].lo + k]);
+            }
+          }
+        }
+      };
+      if (SPARSE && wv == 0) {
+        walk([&](int32_t col) { return col < a.head; }, [&](int32_t col, float g) { atomicAdd(&head_acc[col], g); });
+      } else if (SPARSE) {
+        walk([&](int32_t col) { return col >= a.head; }, [&](int32_t col, float g) {
           atomicAdd(&u[col], g);
           atomicOr(&bm[col >> 10], 1u << ((col >> 5) & 31));
-        }
+        });
+      } else {
+        walk([&](int32_t col) { return (col & (kScatterWaves - 1)) == wv; },
+             [&](int32_t col, float g) { atomicAdd(&u[col], g); });
       }
     }
   }
-  __syncthreads();
-  float *dst = a.part + (int64_t)blockIdx.x * a.head;
-  for (int32_t j = tid; j < a.head; j += kSparseThreads) dst[j] = head_acc[j];
+  if (SPARSE) {
+    __syncthreads();
+    float *dst = a.part + (int64_t)blockIdx.x * a.head;
+    for (int32_t j = tid; j < a.head; j += kSparseThreads) dst[j] = head_acc[j];
+  }
 }
 
 // plan[(t*N + i)*B + pos] for every inner iteration t < m of an epoch: the draws do not depend on the iterates,
@@ -630,15 +724,19 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const int32_t nworkers = worker_end - worker_begin;
   hipError_t e = launch_zero(U, (int64_t)nworkers * c->d_pad, st);
   if (e != hipSuccess) return e;
-  const int64_t slots = (int64_t)nworkers * c->cfg.B;
-  const dim3 grid((unsigned)((slots + kGroups - 1) / kGroups));
-  if (z_snap) hipLaunchKernelGGL(csr_vr_kernel<true>, grid, dim3(kThreads), 0, st, a, nworkers);
-  else hipLaunchKernelGGL(csr_vr_kernel<false>, grid, dim3(kThreads), 0, st, a, nworkers);
+  a.parts = 1;
+  a.rows_per_part = c->cfg.B;
+  const dim3 grid((unsigned)nworkers);
+  if (z_snap) hipLaunchKernelGGL((csr_vr_ordered_kernel<true, false>), grid, dim3(kSparseThreads), 0, st, a);
+  else hipLaunchKernelGGL((csr_vr_ordered_kernel<false, false>), grid, dim3(kSparseThreads), 0, st, a);
   return hipGetLastError();
 }
 
 // Sparse worker pass (all N workers).  s.U rows and the bitmap must be zero outside what this call adds.
-int csr_sparse_parts(int32_t B) { return (B + kSparseGroups - 1) / kSparseGroups; }
+// workgroups per worker of the sparse worker pass: one round of rows each
+// (measured on n = d = 2^20, N = 16, B = 256: two rounds per workgroup, hence three planes per worker instead of
+// five, make this pass 7 us slower and the statistics pass 3.4 us faster)
+int csr_sparse_parts(int32_t B) { return (B + kRowGroups - 1) / kRowGroups; }
 
 hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, hipStream_t st) {
   CsrArgs a{};
@@ -662,11 +760,12 @@ hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w
   a.key = key; a.tag = kTagBatch; a.worker_begin = 0; a.B = c->cfg.B;
   a.scale = (float)(1.0 / (double)c->cfg.B);
   a.parts = csr_sparse_parts(c->cfg.B);
-  a.rows_per_part = (c->cfg.B + a.parts - 1) / a.parts;
+  a.rows_per_part = kRowGroups;
+  a.planes = c->s.sparse_planes; a.touched_parts = c->s.touched_parts;
   const dim3 grid((unsigned)(c->cfg.N * a.parts));
   const size_t lds = (size_t)a.head * sizeof(float);
-  if (z_snap) hipLaunchKernelGGL(csr_vr_sparse_kernel<true>, grid, dim3(kSparseThreads), lds, st, a);
-  else hipLaunchKernelGGL(csr_vr_sparse_kernel<false>, grid, dim3(kSparseThreads), lds, st, a);
+  if (z_snap) hipLaunchKernelGGL((csr_vr_ordered_kernel<true, true>), grid, dim3(kSparseThreads), lds, st, a);
+  else hipLaunchKernelGGL((csr_vr_ordered_kernel<false, true>), grid, dim3(kSparseThreads), lds, st, a);
   return hipGetLastError();
 }
 

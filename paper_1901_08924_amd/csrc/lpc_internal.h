@@ -121,6 +121,9 @@ struct Scratch {
   unsigned long long *iter_slots;  // two sets of [tiles][N][4] statistics exchanged between the workgroups of the
                                    // two-launch inner iteration (all ones = empty)
   uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
+  uint32_t *touched_parts;  // [N][parts-1][bitmap_words]: the same for the worker pass's workgroups 1..parts-1
+  float *sparse_planes; // [N][parts-1][d_pad] sparse inner iteration: tail contributions of a worker's workgroups
+                        // 1..parts-1 (workgroup 0 adds into the worker's row of U); zero outside touched segments
   // MLP instance: gathered inputs/labels and per-layer activations / deltas for the two parameter sets
   float *mlp_xb;        // [rows][dims[0]]
   float *mlp_yb;        // [rows]

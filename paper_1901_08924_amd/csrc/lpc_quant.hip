@@ -687,8 +687,10 @@ __global__ __launch_bounds__(kQuarterThreads) void dequantize_quarter_kernel(con
 // the results of the dense passes.  One thread per (segment, worker) in all three kernels.
 struct SparseArgs {
   float *U;                 // [N][d_pad]
+  float *planes;            // [N][parts-1][d_pad]: tail contributions of the worker pass's workgroups 1..parts-1
   const float *head_part;   // [N][parts][head]: partial head rows of the worker pass
   uint32_t *touched;        // [N][bitmap_words]
+  uint32_t *touched_parts;  // [N][parts-1][bitmap_words]: segments marked by the worker pass's workgroups 1..parts-1
   int64_t d_pad, W, bitmap_words;
   int32_t head, parts, N;
 };
@@ -725,12 +727,58 @@ __device__ __forceinline__ int32_t compact_marked(const uint32_t *__restrict__ b
   return n;
 }
 
+// The same over the union of the bitmaps of the worker pass's workgroups ("planes"; plane 0's bitmap is the
+// worker's own, which receives the union, the others are cleared): masks[k] has bit p set when plane p holds a
+// contribution to listed segment k.  Every bitmap word belongs to exactly one wavefront of the launch.
+constexpr int kMaxPlanes = 8;
+
+__device__ __forceinline__ int32_t compact_marked_planes(uint32_t *bm0, uint32_t *bmp, int32_t parts,
+                                                         int64_t bitmap_words, int64_t first_word, int64_t stride,
+                                                         int64_t total_segs, int lane, int32_t *__restrict__ list,
+                                                         uint32_t *__restrict__ masks) {
+  const int64_t wi = first_word + lane * stride;
+  const bool valid = lane < kWaveWords && wi < bitmap_words;
+  uint32_t w[kMaxPlanes];
+  w[0] = valid ? bm0[wi] : 0u;
+  uint32_t uni = w[0];
+#pragma unroll
+  for (int p = 1; p < kMaxPlanes; ++p) {
+    w[p] = (valid && p < parts) ? bmp[(int64_t)(p - 1) * bitmap_words + wi] : 0u;
+    uni |= w[p];
+  }
+  if (valid && uni != w[0]) bm0[wi] = uni;
+#pragma unroll
+  for (int p = 1; p < kMaxPlanes; ++p)
+    if (w[p]) bmp[(int64_t)(p - 1) * bitmap_words + wi] = 0u;
+  int32_t n = 0;
+#pragma unroll 4
+  for (int c = 0; c < kWaveWords / 2; ++c) {  // chunk c = the 64 segments of words 2c, 2c+1 of this wavefront
+    const int k = 2 * c + (lane >> 5);
+    const int bit = lane & 31;
+    const uint32_t wu = __shfl(uni, k, 64);
+    uint32_t mask = 0u;
+#pragma unroll
+    for (int p = 0; p < kMaxPlanes; ++p) mask |= ((__shfl(w[p], k, 64) >> bit) & 1u) << p;
+    const int64_t seg = (first_word + k * stride) * 32 + bit;
+    const bool marked = ((wu >> bit) & 1u) && seg < total_segs;
+    const uint64_t m = __ballot(marked);
+    if (marked) {
+      const int32_t at = n + __popcll(m & ((1ull << lane) - 1ull));
+      list[at] = (int32_t)seg;
+      masks[at] = mask;
+    }
+    n += __popcll(m);
+  }
+  return n;
+}
+
 // Statistic partials of u^i.  Workgroups [0, head/1024) of a worker fold the head columns from the partial rows
 // of the worker pass (fixed order, one float4 per thread, coalesced) into U; in the others every wavefront
 // visits the marked ones of its kWaveSegs tail segments.
 __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, StatSinks sk) {
   __shared__ double red[4][4];
   __shared__ int32_t list[4][kWaveSegs];
+  __shared__ uint32_t masks[4][kWaveSegs];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t worker = blockIdx.y;
   const int32_t head_wgs = a.head / (4 * kThreads);
@@ -763,17 +811,54 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
   } else {
     const int64_t stride = (int64_t)(gridDim.x - head_wgs) * 4;  // tail wavefronts of this worker
     const int64_t first_word = a.head / (kSegFloats * 32) + ((int64_t)blockIdx.x - head_wgs) * 4 + wv;
-    const int32_t n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
-                                     a.d_pad / kSegFloats, lane, list[wv]);
+    const int32_t n = compact_marked_planes(
+        a.touched + (int64_t)worker * a.bitmap_words,
+        a.touched_parts + (int64_t)worker * (a.parts - 1) * a.bitmap_words, a.parts, a.bitmap_words, first_word, stride,
+        a.d_pad / kSegFloats, lane, list[wv], masks[wv]);
     __builtin_amdgcn_wave_barrier();
-    // eight lanes per segment, 32 segments (four independent loads per lane) per step
+    // eight lanes per segment, 32 segments (four independent loads per lane) per step.  A segment's value is the
+    // sum of the planes that hold it, in plane order (plane 0 = the row of U, which receives the sum; the other
+    // planes are set back to zero).  Nearly every segment lies in one plane only: that plane is read first, the
+    // rare further ones in a loop the wavefront enters only when some lane needs it.
+    float *pl = a.planes + (int64_t)worker * (a.parts - 1) * a.d_pad;
     for (int32_t i0 = 0; i0 < n; i0 += 32) {
       float4 v[4];
+      int64_t at[4];
+      uint32_t mk[4], rest_any = 0u;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int32_t i = i0 + q * 8 + (lane >> 3);
+        at[q] = -1; mk[q] = 0u;
         v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (i < n) v[q] = *reinterpret_cast<const float4 *>(urow + (int64_t)list[wv][i] * kSegFloats + (lane & 7) * 4);
+        if (i < n) {
+          at[q] = (int64_t)list[wv][i] * kSegFloats + (lane & 7) * 4;
+          mk[q] = masks[wv][i];
+          const int first = __builtin_ctz(mk[q]);  // a listed segment lies in at least one plane
+          const float *src = first == 0 ? urow + at[q] : pl + (int64_t)(first - 1) * a.d_pad + at[q];
+          v[q] = *reinterpret_cast<const float4 *>(src);
+          rest_any |= mk[q] & (mk[q] - 1u);
+        }
+      }
+      if (__ballot(rest_any != 0u) != 0ull) {
+        for (int32_t p = 1; p < a.parts; ++p) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t rest = mk[q] & (mk[q] - 1u);
+            if ((rest >> p) & 1u) {
+              const float4 t = *reinterpret_cast<const float4 *>(pl + (int64_t)(p - 1) * a.d_pad + at[q]);
+              v[q].x += t.x; v[q].y += t.y; v[q].z += t.z; v[q].w += t.w;
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (mk[q] >> 1) {  // some plane other than the row of U held it: the sum moves there, those planes are cleared
+          *reinterpret_cast<float4 *>(urow + at[q]) = v[q];
+          for (int32_t p = 1; p < a.parts; ++p)
+            if ((mk[q] >> p) & 1u)
+              *reinterpret_cast<float4 *>(pl + (int64_t)(p - 1) * a.d_pad + at[q]) = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) { take(v[q].x); take(v[q].y); take(v[q].z); take(v[q].w); }
@@ -1798,7 +1883,8 @@ hipError_t launch_dequantize_prox(const lpc_ctx *c, const uint32_t *packed, cons
 namespace {
 SparseArgs sparse_args_of(const lpc_ctx *c) {
   SparseArgs a{};
-  a.U = c->s.U; a.head_part = c->s.part; a.touched = c->s.touched;
+  a.U = c->s.U; a.planes = c->s.sparse_planes; a.head_part = c->s.part; a.touched = c->s.touched;
+  a.touched_parts = c->s.touched_parts;
   a.d_pad = c->d_pad; a.W = c->W; a.bitmap_words = c->bitmap_words;
   a.head = c->sparse_head; a.parts = csr_sparse_parts(c->cfg.B); a.N = c->cfg.N;
   return a;

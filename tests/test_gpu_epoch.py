@@ -77,6 +77,38 @@ def test_epoch_is_reproducible():
     ctx.close()
 
 
+@pytest.mark.parametrize("d,B,over", [
+    (50_000, 100, {}),                                  # sparse inner iteration, two rounds of rows per worker
+    (50_000, 16, dict(scheme=lpco.SCHEME_B)),           # dense-U worker pass (shared scale), large d
+    (2048, 70, {}),                                     # small d: many rows of a batch share columns
+    (3000, 32, dict(algo=lpco.ALGO_ALPC_GC, L=0.25, tau2=0.5)),
+])
+def test_csr_epoch_is_reproducible(d, B, over):
+    """CSR data: the snapshot gradient and the workers' differences are summed in a fixed order (no float atomics
+    whose arrival order could matter), so two runs give the same bits -- and with them the same stochastic
+    rounding decisions and the same iterates."""
+    import torch
+    sp = lpc_synth.make("c3", n=4096, d=d, nnz_mean=30, N=4, B=B)
+    runs = []
+    for _ in range(3):
+        ctx = gpu_context(sp, m=5, **over)
+        alpc = ctx.config.algo != 0
+        w = to_dev(sp.w0)
+        y, z = (to_dev(sp.w0), to_dev(sp.w0)) if alpc else (None, None)
+        for s in range(3):
+            ctx.epoch(w, s, y, z)
+        mu = torch.zeros(sp.d, device="cuda")
+        ctx.full_grad(w, mu, None, None)
+        U = torch.zeros(sp.N, lpco.d_pad(sp.d), device="cuda")
+        ctx.worker_vr_grad(w, to_dev(sp.w0), None, 7, 3, U, None)
+        runs.append((w.clone(), mu, U))
+        ctx.close()
+    assert runs[0][0].abs().max().item() > 0
+    for other in runs[1:]:
+        for a, b in zip(runs[0], other):
+            assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("d,bits", [(2048, 2), (40_000, 2), (40_000, 32)])
 def test_lpc_epochs_csr(d, bits):
     # sparse rows: small-d single-launch exchange and the large-d path
