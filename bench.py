@@ -218,7 +218,7 @@ def run_workload(name, steps, warmup, args, achievable):
     cfgkw = dict(algo=sp.algo, N=sp.N, B=sp.B, m=sp.m, bits=sp.bits, clip_mode=sp.clip_mode, clip=sp.clip,
                  eta=sp.eta, L=sp.L, seed=sp.seed, n_full=sp.n_full)
     ctx = lpc.context_from_problem(sp)
-    for key, val in ((lpc.TUNE_ITER_LAUNCHES, args.iter_launches), (lpc.TUNE_ITER_TILE, args.iter_tile),
+    for key, val in ((lpc.TUNE_ITER_FORM, args.iter_form), (lpc.TUNE_ITER_TILE, args.iter_tile),
                      (lpc.TUNE_ITER_THREADS, args.iter_threads)):
         if val is not None and sp.loss != 2 and sp.csr is None:
             ctx.tune(key, val)
@@ -345,8 +345,8 @@ def main():
                     help="all (default): the headline on c4, the largest configuration, with c2, c3 and c5 as "
                          "sub-records under 'workloads'; or one configuration alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--iter-launches", type=int, default=None, choices=[2, 3],
-                    help="launches per dense inner iteration (lpc_tune; default: the library's choice)")
+    ap.add_argument("--iter-form", type=int, default=None, choices=[0, 1, 2],
+                    help="form of the dense inner iteration (lpc_tune LPC_TUNE_ITER_FORM; default: the library's)")
     ap.add_argument("--iter-tile", type=int, default=None, choices=[64, 128])
     ap.add_argument("--iter-threads", type=int, default=None, choices=[256, 512])
     ap.add_argument("--small", action="store_true", help="scaled-down problems (quick functional run)")

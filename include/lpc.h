@@ -307,17 +307,27 @@ lpc_status lpc_debug_gemm(const float *A, const float *B, float *C, int32_t M, i
                           int32_t relu, int32_t accumulate, void *stream);
 
 /* ---- tuning and test aid (no passage of the paper) -----------------------------------------
- * Launch-shape knobs of the inner iteration on small dense problems, which lpc_epoch can run as two launches
- * (the workers' rows; then fold of the partial rows + exchange + update, whose workgroups wait, for a bounded
- * number of polls, for each other's statistics) instead of three.  Results do not depend on any of them.
- *   LPC_TUNE_ITER_LAUNCHES: 3 (default: fold and exchange as separate launches) or 2;
- *   LPC_TUNE_ITER_TILE: coordinates per workgroup of the second launch, 64 or 128;
- *   LPC_TUNE_ITER_THREADS: its threads per workgroup, 256 or 512;
- *   LPC_TUNE_SPIN_LIMIT: polls before a workgroup gives up waiting (it then finishes normally with what it has
- *     and lpc_take_device_flags reports LPC_EDEVICE); 0 makes every wait give up at once (tests of that path).
- * LPC_EINVAL for an unknown key or value, LPC_EUNSUPPORTED where the context cannot run two launches. */
+ * Form and launch shape of the inner iteration on small dense problems (d_pad <= 16384, N <= 64).
+ *   LPC_TUNE_ITER_FORM:
+ *     0 (default): three launches: the workers' rows (whole rows per workgroup, partial gradient rows out), their
+ *       fold, the exchange.
+ *     1: two launches: the workers' rows, then fold + exchange in one launch whose workgroups wait, for a bounded
+ *       number of polls, for each other's statistics.
+ *     2: two launches with nothing but the launch boundary between them.  The workers' pass runs in 128-column
+ *       tiles: a workgroup completes one tile of one u^i, taking each sampled row's margin as the sum of partial
+ *       dot products that the previous launch left; the exchange launch then also leaves the partial dots of
+ *       the next iteration's rows with the new iterate.
+ *     Measured on MI355X both two-launch forms are slower than form 0 (the first pays for device-scope atomics,
+ *     the second for reading the sampled rows twice); they are kept as tested alternatives.
+ *     Forms 0 and 1 give the same bits as each other; form 2 adds the same numbers in another order (the margins
+ *     in tiles), so its u^i differ from theirs in the last bits.
+ *   LPC_TUNE_ITER_TILE: form 1: coordinates per workgroup of the second launch, 64 or 128;
+ *   LPC_TUNE_ITER_THREADS: form 1: its threads per workgroup, 256 or 512;
+ *   LPC_TUNE_SPIN_LIMIT: form 1: polls before a workgroup gives up waiting (it then finishes normally with what it
+ *     has and lpc_take_device_flags reports LPC_EDEVICE); 0 makes every wait give up at once (tests of that path).
+ * LPC_EINVAL for an unknown key or value, LPC_EUNSUPPORTED where the context cannot run the form. */
 typedef enum {
-  LPC_TUNE_ITER_LAUNCHES = 0,
+  LPC_TUNE_ITER_FORM = 0,
   LPC_TUNE_ITER_TILE = 1,
   LPC_TUNE_ITER_THREADS = 2,
   LPC_TUNE_SPIN_LIMIT = 3

@@ -154,6 +154,9 @@ size_t layout(lpc_ctx *c, char *base) {
     s.sparse_planes = (float *)take((extra ? (size_t)c->cfg.N * extra * c->d_pad : 4) * sizeof(float));
     s.touched_parts = (uint32_t *)take((extra ? (size_t)c->cfg.N * extra * c->bitmap_words : 4) * sizeof(uint32_t));
   }
+  s.w2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
+  s.z2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
+  s.pd = (float *)take((c->cols_capable ? 2 * (size_t)N1 * c->cfg.B * dense_cols_tiles(c) : 4) * sizeof(float));
   s.iter_slots = (unsigned long long *)take((c->iter2_capable ? (size_t)fused_iter_slot_words(c) : 1) * sizeof(unsigned long long));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
@@ -234,10 +237,13 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
       need += (int64_t)(c->mlp_dims[l] / 128 + 1) * (c->mlp_dims[l + 1] / 64 + 1) + 2;
     if (need > c->stat_slots) c->stat_slots = (int32_t)need;
   }
-  // measured on MI355X: the statistics' trip through device-scope atomics (about 3 us a round) costs more than the
-  // launch it saves (d = 4096, N = 8: 50.6 k against 59.1 k inner iterations/s), so three launches stay the default
   c->iter2_capable = fused_iter_supported(c);
-  c->iter2 = false;
+  c->cols_capable = fused_exchange_supported(c) && dense_cols_supported(c);
+  // measured on MI355X (inner iterations/s, forms 0 / 1 / 2): d = 4096, N = 8, B = 64: 59.9 k / 50.6 k / 47.6 k;
+  // d = 8192, N = 16 (+ shared batch), B = 64: 32.3 k / - / 20.2 k.  Form 1 pays about 3 us per trip of the statistics
+  // through device-scope atomics; form 2 pays for reading the sampled rows a second time in 512-byte slices (its
+  // exchange launch takes 13.4 / 29.3 us against 6.3 / 8.7 us).  Three launches stay the default.
+  c->iter_form = 0;
   return LPC_OK;
 }
 
@@ -249,6 +255,16 @@ StreamKey key_of(const lpc_ctx *c, uint32_t epoch, uint32_t iter) {
   k.iter = iter;
   return k;
 }
+
+#define LPC_TRY(expr)                 \
+  do {                                \
+    lpc_status _s = (expr);           \
+    if (_s != LPC_OK) return _s;      \
+  } while (0)
+#define LPC_TRY_HIP(expr)                       \
+  do {                                          \
+    if ((expr) != hipSuccess) return LPC_EDEVICE; \
+  } while (0)
 
 // Alg. 1 step 4 into (mu, z), all on `st`
 lpc_status full_grad_impl(lpc_ctx *c, const float *w, float *mu, float *z, double *f_out, int64_t n_rows,
@@ -291,6 +307,20 @@ lpc_status vr_grad_impl(lpc_ctx *c, const float *w, const float *w_snap, const f
     if (stats_mode == kStatsNone) return LPC_OK;
     ProfScope ps(c, LPC_PROF_VR_FOLD, st);
     return dev(launch_vector_stats(c, U_row0, c->d_pad, slot0, we - wb, stats_row0, stats_mode, stat_slots_used, st));
+  }
+  if (c->iter_form == 2 && c->cols_capable && z_snap) {
+    // column tiles: the partial dots of the sampled rows with w, then u^i tile by tile with its statistic partials
+    const bool shared = tag == kTagShared;
+    LPC_TRY_HIP(launch_dense_dots(c, w, key, wb, we - wb, shared, tag, c->s.pd, st));
+    {
+      ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
+      LPC_TRY_HIP(launch_dense_cols(c, z_snap, c->s.pd, key, tag, wb, we - wb, shared, U_row0, c->d_pad,
+                                    stats_mode != kStatsNone, slot0, st));
+    }
+    if (stat_slots_used) *stat_slots_used = dense_cols_tiles(c);
+    if (stats_mode == kStatsFinal)
+      LPC_TRY_HIP(launch_finalize_stats(c, slot0, we - wb, dense_cols_tiles(c), stats_row0, st));
+    return LPC_OK;
   }
   {
     ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
@@ -336,16 +366,6 @@ lpc_status alpc_params(const lpc_ctx *c, uint32_t epoch, AlpcParams *out) {
   out->tau1 = (float)t1; out->tau2 = (float)t2; out->alpha = (float)a; out->theta = (float)th;
   return LPC_OK;
 }
-
-#define LPC_TRY(expr)                 \
-  do {                                \
-    lpc_status _s = (expr);           \
-    if (_s != LPC_OK) return _s;      \
-  } while (0)
-#define LPC_TRY_HIP(expr)                       \
-  do {                                          \
-    if ((expr) != hipSuccess) return LPC_EDEVICE; \
-  } while (0)
 
 // Evaluation runs only: row t of the traces <- this iteration's scale factors and clip counts (zeros with
 // quantization off), and the clip counts into the running total.
@@ -468,10 +488,10 @@ void lpc_destroy(lpc_ctx *ctx) {
 lpc_status lpc_tune(lpc_ctx *ctx, int32_t key, int64_t value) {
   if (!ctx) return LPC_ENULL;
   switch (key) {
-    case LPC_TUNE_ITER_LAUNCHES:
-      if (value != 2 && value != 3) return LPC_EINVAL;
-      if (value == 2 && !ctx->iter2_capable) return LPC_EUNSUPPORTED;
-      ctx->iter2 = value == 2;
+    case LPC_TUNE_ITER_FORM:
+      if (value < 0 || value > 2) return LPC_EINVAL;
+      if ((value == 1 && !ctx->iter2_capable) || (value == 2 && !ctx->cols_capable)) return LPC_EUNSUPPORTED;
+      ctx->iter_form = (int32_t)value;
       return LPC_OK;
     case LPC_TUNE_ITER_TILE:
       if (value != 64 && value != 128) return LPC_EINVAL;
@@ -698,7 +718,8 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
   if (g.algo == LPC_ALGO_LPC) {
     LPC_TRY_HIP(launch_copy(s.w, w_snap, c->d, st));  // x_0 = x~
     const bool fused = fused_exchange_supported(c) && g.scheme == LPC_SCHEME_A && !tracing;
-    const bool two = fused && c->iter2;
+    const bool two = fused && c->iter_form == 1 && c->iter2_capable;
+    const bool cols = fused && c->iter_form == 2 && c->cols_capable && zs != nullptr;
     const bool sparse = c->csr_sparse && !tracing;
     if (two) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
     if (sparse) {
@@ -712,6 +733,31 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
       // the epoch's draws with each row's extent, label and snapshot margin, looked up once
       LPC_TRY_HIP(launch_csr_plan(c, zs, key_of(c, epoch, 0), st));
+    }
+    if (cols) {
+      // two launches per inner iteration: column tiles of u^i from the partial dots; exchange + prox + the next
+      // iteration's partial dots.  The iterate alternates between two buffers.
+      float *wa = s.w, *wb = s.w2;
+      const size_t pd_set = (size_t)(g.N + 1) * g.B * dense_cols_tiles(c);
+      LPC_TRY_HIP(launch_dense_dots(c, wa, key_of(c, epoch, 0), 0, g.N, false, kTagBatch, s.pd, st));
+      for (int32_t t = 0; t < g.m; ++t) {
+        const StreamKey key = key_of(c, epoch, (uint32_t)t);
+        float *pd_cur = s.pd + (size_t)(t & 1) * pd_set;
+        float *pd_next = t + 1 < g.m ? s.pd + (size_t)((t + 1) & 1) * pd_set : nullptr;
+        {
+          ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
+          c->at_snapshot = t == 0;  // x_0 = x~: u_0 is exactly zero
+          const hipError_t e = launch_dense_cols(c, zs, pd_cur, key, kTagBatch, 0, g.N, false, s.U, c->d_pad, true, 0, st);
+          c->at_snapshot = false;
+          LPC_TRY_HIP(e);
+        }
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
+        LPC_TRY_HIP(launch_cols_exchange(c, s.U, key, s.packed, s.delta, s.mu, g.eta, wa, wb, nullptr, nullptr, pd_next,
+                                         st));
+        float *tmp = wa; wa = wb; wb = tmp;
+      }
+      LPC_TRY_HIP(launch_copy(w_snap, wa, c->d, st));  // x~ <- x_m
+      return LPC_OK;
     }
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
@@ -742,8 +788,11 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
         ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
         LPC_TRY_HIP(launch_fused_exchange(c, s.U, slots, key, s.packed, s.delta, s.mu, g.eta, s.w, nullptr, st));
       } else {
-        LPC_TRY(vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
-                             c->quant ? kStatsFinal : kStatsNone, st));
+        c->at_snapshot = t == 0;  // x_0 = x~ (only the column-tile worker pass needs telling)
+        const lpc_status rc = vr_grad_impl(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, s.U, nullptr,
+                                           c->quant ? kStatsFinal : kStatsNone, st);
+        c->at_snapshot = false;
+        LPC_TRY(rc);
         LPC_TRY(exchange_and_prox(c, key, s.w, tracing, st));
         if (tracing) LPC_TRY(record_iteration(c, t, st));
       }
@@ -762,14 +811,45 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
     // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
-    if (c->iter2) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
+    if (c->iter_form == 2 && c->cols_capable && zs != nullptr) {
+      // two launches per inner iteration, as for Alg. 1; x and z alternate between two buffers each
+      float *xa = s.w, *xb = s.w2, *za = z, *zb = s.z2;
+      const size_t pd_set = (size_t)(g.N + 1) * g.B * dense_cols_tiles(c);
+      LPC_TRY_HIP(launch_dense_dots(c, xa, key_of(c, epoch, 0), 0, g.N + 1, true, kTagBatch, s.pd, st));
+      for (int32_t t = 0; t < g.m; ++t) {
+        const StreamKey key = key_of(c, epoch, (uint32_t)t);
+        float *pd_cur = s.pd + (size_t)(t & 1) * pd_set;
+        float *pd_next = t + 1 < g.m ? s.pd + (size_t)((t + 1) & 1) * pd_set : nullptr;
+        {
+          ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
+          LPC_TRY_HIP(launch_dense_cols(c, zs, pd_cur, key, kTagBatch, 0, g.N + 1, true, s.U, c->d_pad, true, 0, st));
+        }
+        AlpcStep al{};
+        al.x = xa; al.u_hat = u_hat; al.w_snap = w_snap; al.mu = s.mu;
+        al.y = y; al.z = zb; al.ysum = s.ysum; al.x_next = xb;
+        al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
+        al.first = t == 0 ? 1 : 0;
+        ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
+        LPC_TRY_HIP(launch_cols_exchange(c, s.U, key, s.packed, s.delta, nullptr, 0.0f, nullptr, nullptr, &al, za,
+                                         pd_next, st));
+        float *tmp = xa; xa = xb; xb = tmp;
+        tmp = za; za = zb; zb = tmp;
+        wsum += weight;
+        weight *= (double)ap.theta;
+      }
+      if (za != z) LPC_TRY_HIP(launch_copy(z, za, c->d, st));
+      LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
+      return LPC_OK;
+    }
+    const bool two_alpc = c->iter_form == 1 && c->iter2_capable;
+    if (two_alpc) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
     for (int32_t t = 0; t < g.m; ++t) {
       const StreamKey key = key_of(c, epoch, (uint32_t)t);
       {
         ProfScope ps(c, LPC_PROF_VR_ROWS, st, true);
         LPC_TRY_HIP(launch_dense_vr_grad(c, s.w, w_snap, zs, key, kTagBatch, 0, g.N, true, st));
       }
-      if (c->iter2) {
+      if (two_alpc) {
         // two launches per inner iteration: the rows above; fold + exchange + Alg. 2 steps 13-15 + next step 6
         AlpcStep al{};
         al.x = s.w; al.u_hat = nullptr; al.w_snap = w_snap; al.mu = s.mu;

@@ -242,6 +242,127 @@ __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The worker pass in column tiles ("columns" form), for the small-d inner iteration.
+//
+// The rows kernel above needs all of w for a row's margin, so a workgroup owns whole rows and leaves a d-long
+// partial gradient that a second launch folds.  Here the margins come from outside: the launch that produced w
+// (the exchange, or dense_dots_kernel) also left, for every row the coming iteration samples, the partial dot
+// products of the row with each 128-column tile of w.  A workgroup then owns ONE tile of ONE vector: it adds a
+// row's partial dots (fixed order) to get the margin, forms the slope difference, and accumulates
+// slope * x[tile] over the vector's B rows in a fixed order -- u^i's tile is complete inside the workgroup, with
+// its statistics, and nothing is left to fold.  The rows are read twice (once for the dots, once here, the second
+// time out of the cache) instead of once plus a write and a read of the partial rows.
+// (kColTile = 128 columns per workgroup, kColThreads = 512: 16 groups of 32 lanes; a group takes one row at a time,
+// a lane four columns; both in lpc_device.h, which the exchange kernel shares)
+
+struct ColsArgs {
+  const float *X;
+  int64_t ldx, d, d_pad, n;
+  const float *y, *z_snap;
+  const float *pd;       // [rows][C]: partial dots of the sampled rows with w, rows = (vector, batch position)
+  int32_t C;             // tiles = ceil(d_pad / 128)
+  float *U;              // out: [nvec][ldu]
+  int64_t ldu;
+  double *stat_part;     // [vector][stat_slots][4]; slot = tile
+  int32_t stat_slots, stat_vec0;
+  StreamKey key;
+  uint32_t tag;
+  int32_t worker_begin, B, shared_rel, loss, vec4;
+  int32_t at_snapshot;   // the iterate IS the snapshot (t = 0 of an epoch of Alg. 1): every difference is exactly zero
+  float scale;
+};
+
+__global__ __launch_bounds__(kColThreads) void dense_cols_kernel(ColsArgs a) {
+  constexpr int GROUPS = kColThreads / 32;
+  __shared__ float4 part[GROUPS][kColTile / 4];
+  __shared__ double red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, rg = tid >> 5, l = tid & 31;
+  const int32_t c = blockIdx.x, wrel = blockIdx.y;
+  const uint32_t tag = wrel == a.shared_rel ? kTagShared : a.tag;
+  const uint32_t worker = tag == kTagShared ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
+  const int64_t j = (int64_t)c * kColTile + 4 * l;
+  const int64_t room = a.d - j;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int32_t pos0 = 0; pos0 < a.B; pos0 += 4 * GROUPS) {  // four rows per group in flight
+    int64_t row[4];
+    float4 x[4];
+    float yv[4], zsv[4], zp[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int32_t pos = pos0 + k * GROUPS + rg;
+      const bool live = pos < a.B;
+      row[k] = live ? sample_row(a.key, tag, worker, (uint32_t)pos, a.n) : 0;
+      x[k] = live ? load_slice(a.X + row[k] * a.ldx + j, room, a.vec4 != 0) : make_float4(0.f, 0.f, 0.f, 0.f);
+      yv[k] = live ? a.y[row[k]] : 0.0f;
+      zsv[k] = live ? a.z_snap[row[k]] : 0.0f;
+      // this lane's share of the row's partial dots: tiles l, l+32, ...
+      float s = 0.0f;
+      if (live) {
+        const float *pd = a.pd + ((int64_t)wrel * a.B + pos) * a.C;
+        for (int32_t t = l; t < a.C; t += 32) s += pd[t];
+      }
+      zp[k] = s;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float z = group32_sum(zp[k], lane);
+      const bool live = pos0 + k * GROUPS + rg < a.B;
+      // (at the snapshot the margin summed tile by tile equals the cached one only to rounding)
+      const float coef =
+          live && !a.at_snapshot ? loss_slope(a.loss, z, yv[k]) - loss_slope(a.loss, zsv[k], yv[k]) : 0.0f;
+      acc.x = fmaf(coef, x[k].x, acc.x); acc.y = fmaf(coef, x[k].y, acc.y);
+      acc.z = fmaf(coef, x[k].z, acc.z); acc.w = fmaf(coef, x[k].w, acc.w);
+    }
+  }
+  part[rg][l] = acc;
+  __syncthreads();
+  double amax = 0.0, sum = 0.0, sumsq = 0.0, bad = 0.0;
+  if (tid < kColTile) {
+    const float *col = reinterpret_cast<const float *>(&part[0][0]) + tid;
+    float v = col[0];
+#pragma unroll
+    for (int g = 1; g < GROUPS; ++g) v += col[g * kColTile];
+    v *= a.scale;
+    const int64_t jj = (int64_t)c * kColTile + tid;
+    if (jj >= a.d) v = 0.0f;
+    if (jj < a.d_pad) a.U[(int64_t)wrel * a.ldu + jj] = v;
+    if (isfinite(v)) {
+      amax = fabs((double)v); sum = (double)v; sumsq = (double)v * (double)v;
+    } else {
+      bad = 1.0;
+    }
+  }
+  if (a.stat_part && tid < kColTile) {  // two whole wavefronts
+    amax = wave_max(amax); sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
+    if (lane == 0) { red[tid >> 6][0] = amax; red[tid >> 6][1] = sum; red[tid >> 6][2] = sumsq; red[tid >> 6][3] = bad; }
+  }
+  __syncthreads();
+  if (a.stat_part && tid == 0) {
+    double *p = a.stat_part + ((int64_t)(a.stat_vec0 + wrel) * a.stat_slots + c) * 4;
+    p[0] = fmax(red[0][0], red[1][0]); p[1] = red[0][1] + red[1][1]; p[2] = red[0][2] + red[1][2];
+    p[3] = red[0][3] + red[1][3];
+  }
+}
+
+__global__ __launch_bounds__(kColThreads) void dense_dots_kernel(DotsArgs a) {
+  __shared__ __attribute__((aligned(16))) float wsh[kColTile];
+  const int tid = threadIdx.x;
+  const int32_t c = blockIdx.x;
+  if (tid < kColTile) {
+    const int64_t jj = (int64_t)c * kColTile + tid;
+    wsh[tid] = jj < a.d ? a.w[jj] : 0.0f;
+  }
+  __syncthreads();
+  const int32_t first = (int32_t)blockIdx.y * a.rows_per_wg;
+  for (int32_t i0 = 0; i0 < a.rows_per_wg; i0 += kDotRows) {
+    float4 x[8];
+    const int32_t count = a.rows_per_wg - i0 < kDotRows ? a.rows_per_wg - i0 : kDotRows;
+    tile_dots_load(a, c, first + i0, count, tid, x);
+    tile_dots_finish(a, wsh, c, first + i0, count, tid, x);
+  }
+}
+
 struct Shape {
   int vec, k, t;
 };
@@ -372,6 +493,56 @@ hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w
   a.shared_rel = plus_shared ? worker_end - worker_begin : -1;
   const int grid = (worker_end - worker_begin + (plus_shared ? 1 : 0)) * c->vr_parts;
   return z_snap ? dispatch<1>(s, a, grid, a.rows_per_part, st) : dispatch<2>(s, a, grid, a.rows_per_part, st);
+}
+
+bool dense_cols_supported(const lpc_ctx *c) {
+  return c->grad_ok && !c->csr && !c->mlp && c->d_pad <= 16384;
+}
+
+int dense_cols_tiles(const lpc_ctx *c) { return (int)((c->d_pad + kColTile - 1) / kColTile); }
+
+namespace {
+bool rows_vec4(const lpc_ctx *c) {
+  return c->d % 4 == 0 && c->prob.ldx % 4 == 0 && (((uintptr_t)c->prob.X) & 15u) == 0;
+}
+}  // namespace
+
+// row groups of a dots launch over `rows` rows: enough workgroups to fill the chip, at least 16 rows each
+int dense_dots_groups(const lpc_ctx *c, int32_t rows) {
+  const int tiles = dense_cols_tiles(c);
+  int groups = (2 * c->cus + tiles - 1) / tiles;
+  const int by_rows = (rows + 15) / 16;
+  if (groups > by_rows) groups = by_rows;
+  return groups < 1 ? 1 : groups;
+}
+
+hipError_t launch_dense_dots(const lpc_ctx *c, const float *w, StreamKey key, int32_t worker_begin, int32_t nvec,
+                             bool last_is_shared, uint32_t tag, float *pd, hipStream_t st) {
+  DotsArgs a{};
+  a.X = c->prob.X; a.ldx = c->prob.ldx; a.d = c->d; a.n = c->n; a.w = w; a.pd = pd;
+  a.C = dense_cols_tiles(c); a.B = c->cfg.B; a.nvec = nvec; a.worker_begin = worker_begin;
+  a.shared_rel = last_is_shared ? nvec - 1 : -1; a.vec4 = rows_vec4(c) ? 1 : 0; a.key = key; a.tag = tag;
+  const int32_t rows = nvec * c->cfg.B;
+  const int groups = dense_dots_groups(c, rows);
+  a.rows_per_wg = (rows + groups - 1) / groups;
+  hipLaunchKernelGGL(dense_dots_kernel, dim3((unsigned)a.C, (unsigned)groups), dim3(kColThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_dense_cols(const lpc_ctx *c, const float *z_snap, const float *pd, StreamKey key, uint32_t tag,
+                             int32_t worker_begin, int32_t nvec, bool last_is_shared, float *U, int64_t ldu,
+                             bool want_stats, int32_t stat_vec0, hipStream_t st) {
+  ColsArgs a{};
+  a.at_snapshot = c->at_snapshot ? 1 : 0;
+  a.X = c->prob.X; a.ldx = c->prob.ldx; a.d = c->d; a.d_pad = c->d_pad; a.n = c->n;
+  a.y = c->prob.y; a.z_snap = z_snap; a.pd = pd; a.C = dense_cols_tiles(c);
+  a.U = U; a.ldu = ldu;
+  a.stat_part = want_stats ? c->s.stat_part : nullptr; a.stat_slots = c->stat_slots; a.stat_vec0 = stat_vec0;
+  a.key = key; a.tag = tag; a.worker_begin = worker_begin; a.B = c->cfg.B;
+  a.shared_rel = last_is_shared ? nvec - 1 : -1; a.loss = c->prob.loss; a.vec4 = rows_vec4(c) ? 1 : 0;
+  a.scale = (float)(1.0 / (double)c->cfg.B);
+  LPC_LAUNCH_TIMED(dense_cols_kernel, dim3((unsigned)a.C, (unsigned)nvec), dim3(kColThreads), st, a);
+  return hipGetLastError();
 }
 
 }  // namespace lpc

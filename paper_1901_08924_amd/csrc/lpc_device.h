@@ -124,4 +124,79 @@ __device__ __forceinline__ double wave_max(double v) {
   return fmax(fmax(read_lane(v, 0), read_lane(v, 16)), fmax(read_lane(v, 32), read_lane(v, 48)));
 }
 
+// ---- partial dot products of sampled rows with one 128-column tile of an iterate -------------------------------
+// (the small-d inner iteration's margins: see the column-tile worker pass in lpc_dense.hip)
+constexpr int kColTile = 128;     // columns per tile / workgroup
+constexpr int kColThreads = 512;  // 16 groups of 32 lanes; a group takes one row at a time, a lane four columns
+constexpr int kDotRows = 8 * (kColThreads / 32);  // rows one load / finish pair covers: eight per group
+
+__device__ __forceinline__ float4 load_slice(const float *p, int64_t room, bool vec4) {
+  float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (room <= 0) return t;
+  if (vec4) return *reinterpret_cast<const float4 *>(p);
+  t.x = p[0];
+  if (room > 1) t.y = p[1];
+  if (room > 2) t.z = p[2];
+  if (room > 3) t.w = p[3];
+  return t;
+}
+
+// sum over the 32 adjacent lanes of a group (a fixed order); every lane of the wavefront takes part
+__device__ __forceinline__ float group32_sum(float v, int lane) {
+  v = row16_sum(v);
+  const float lo = read_lane(v, 0) + read_lane(v, 16), hi = read_lane(v, 32) + read_lane(v, 48);
+  return lane < 32 ? lo : hi;
+}
+
+// pd[row][c] = x_row[tile c] . w[tile c] for the rows that the vectors [worker_begin, worker_begin + nvec) sample at
+// `key` (the last one the shared batch when shared_rel says so); row = vector * B + batch position.
+struct DotsArgs {
+  const float *X;
+  int64_t ldx, d, n;
+  const float *w;
+  float *pd;
+  int32_t C, B, nvec, worker_begin, shared_rel, rows_per_wg, vec4;
+  StreamKey key;
+  uint32_t tag;
+};
+
+// request the tile-c slices of rows [first, first + count), count <= kDotRows, of the launch's row list
+__device__ __forceinline__ void tile_dots_load(const DotsArgs &a, int32_t c, int32_t first, int32_t count, int tid,
+                                               float4 (&x)[8]) {
+  constexpr int GROUPS = kColThreads / 32;
+  const int rg = tid >> 5, l = tid & 31;
+  const int64_t j = (int64_t)c * kColTile + 4 * l;
+  const int64_t room = a.d - j;
+  const int32_t total = a.nvec * a.B;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int32_t i = first + k * GROUPS + rg;
+    x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k * GROUPS + rg < count && i < total) {
+      const int32_t wrel = i / a.B, pos = i % a.B;
+      const uint32_t tag = wrel == a.shared_rel ? kTagShared : a.tag;
+      const uint32_t worker = tag == kTagShared ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
+      const int64_t row = sample_row(a.key, tag, worker, (uint32_t)pos, a.n);
+      x[k] = load_slice(a.X + row * a.ldx + j, room, a.vec4 != 0);
+    }
+  }
+}
+
+// ... and their dot products with the tile's slice of the iterate held in wsh (LDS, 128 floats, zero past d)
+__device__ __forceinline__ void tile_dots_finish(const DotsArgs &a, const float *wsh, int32_t c, int32_t first,
+                                                 int32_t count, int tid, const float4 (&x)[8]) {
+  constexpr int GROUPS = kColThreads / 32;
+  const int lane = tid & 63, rg = tid >> 5, l = tid & 31;
+  const float4 w4 = *reinterpret_cast<const float4 *>(wsh + 4 * l);
+  const int32_t total = a.nvec * a.B;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float s = x[k].x * w4.x;
+    s = fmaf(x[k].y, w4.y, s); s = fmaf(x[k].z, w4.z, s); s = fmaf(x[k].w, w4.w, s);
+    s = group32_sum(s, lane);
+    const int32_t i = first + k * GROUPS + rg;
+    if (l == 0 && k * GROUPS + rg < count && i < total) a.pd[(int64_t)i * a.C + c] = s;
+  }
+}
+
 }  // namespace lpc

@@ -118,6 +118,9 @@ struct Scratch {
   int32_t *csc_rows;    // [nnz] row index per entry, ascending inside a column
   float *csc_vals;      // [nnz]
   float *csc_coef;      // [n] per-row loss slopes of the snapshot pass
+  float *w2;            // [d] second buffer of the inner iterate (form 2 reads one and writes the other)
+  float *z2;            // [d] second buffer of ALPC-SVRG's z
+  float *pd;            // two sets of [(N+1)*B][tiles] partial dots of the sampled rows with the iterate
   unsigned long long *iter_slots;  // two sets of [tiles][N][4] statistics exchanged between the workgroups of the
                                    // two-launch inner iteration (all ones = empty)
   uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
@@ -159,8 +162,13 @@ struct lpc_ctx {
   int32_t stat_slots;     // statistic partials per vector
   int32_t cus;            // compute units of the device (256 on MI355X)
   int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
-  bool iter2 = false;      // dense inner iterations run as two launches (rows; fold + exchange + update)
-  bool iter2_capable = false;  // ... and the context's scratch holds what that needs
+  // form of the small-d dense inner iteration (lpc_tune): 0 = rows, fold, exchange (three launches); 1 = rows,
+  // then fold + exchange in one launch whose workgroups wait for each other's statistics; 2 = column tiles fed by
+  // partial dot products, then the exchange, which also leaves the next iteration's partial dots (two launches)
+  int32_t iter_form = 0;
+  bool at_snapshot = false;    // set by lpc_epoch while it issues t = 0 of Alg. 1, where x_0 is the snapshot itself
+  bool iter2_capable = false;  // the context's scratch holds what form 1 needs
+  bool cols_capable = false;   // ... what form 2 needs
   int32_t iter_tile = 128, iter_threads = 512;  // launch shape of the second one
   uint32_t spin_limit = 1u << 15;               // polls a workgroup of it waits for the others' statistics
   bool csc_ready = false;  // the column-major tail copy exists (CSR snapshot pass without atomics)
@@ -192,6 +200,16 @@ hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bo
 hipError_t launch_dense_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                                 StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end,
                                 bool plus_shared, hipStream_t st);
+
+// the worker pass in column tiles, fed by partial dot products (small-d inner iteration)
+bool dense_cols_supported(const lpc_ctx *c);
+int dense_cols_tiles(const lpc_ctx *c);
+int dense_dots_groups(const lpc_ctx *c, int32_t rows);
+hipError_t launch_dense_dots(const lpc_ctx *c, const float *w, StreamKey key, int32_t worker_begin, int32_t nvec,
+                             bool last_is_shared, uint32_t tag, float *pd, hipStream_t st);
+hipError_t launch_dense_cols(const lpc_ctx *c, const float *z_snap, const float *pd, StreamKey key, uint32_t tag,
+                             int32_t worker_begin, int32_t nvec, bool last_is_shared, float *U, int64_t ldu,
+                             bool want_stats, int32_t stat_vec0, hipStream_t st);
 
 // CSR GLM passes (lpc_csr.hip)
 int csr_head_columns(int64_t d);
@@ -248,6 +266,9 @@ constexpr int kStatsNone = 0, kStatsFinal = 1, kStatsPartial = 2;
 bool fused_exchange_supported(const lpc_ctx *c);
 int reduce_parts_waves(const lpc_ctx *c, int32_t parts, int32_t nvec);
 struct AlpcStep;
+hipError_t launch_cols_exchange(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
+                                const float *mu, float step, const float *w_in, float *w_out, const AlpcStep *al,
+                                const float *z_in, float *next_pd, hipStream_t st);
 bool fused_iter_supported(const lpc_ctx *c);
 int64_t fused_iter_slot_words(const lpc_ctx *c);
 hipError_t launch_fused_iter_reset(const lpc_ctx *c, hipStream_t st);

@@ -1013,6 +1013,14 @@ struct FusedArgs {
   // Rows the NEXT worker pass will read (dense data, small batches): workgroups past the tiles draw them from
   // the next iteration's random stream and request them, so that they wait in the last-level cache instead of
   // in HBM.  warm_groups = 0: nothing to warm.
+  // Column-tile iteration (dots_R > 0): the launch has dots_R workgroups per tile.  Each repeats the tile's
+  // exchange and update (reading the old iterate from w_in / x / z_in, so that the one workgroup per tile that
+  // stores results, into w / x_next / z, disturbs nobody) and then leaves the partial dot products of its share of
+  // the NEXT iteration's sampled rows with the tile's new iterate (dots.pd).  dots_R = 0: one workgroup per tile,
+  // w_in = w, z_in = z, plus the warming workgroups below.
+  int32_t dots_R;
+  const float *w_in, *z_in;
+  DotsArgs dots;
   const float *warm_X, *warm_y, *warm_z;
   int64_t warm_ldx, warm_n;
   StreamKey warm_key;   // of the next iteration
@@ -1048,12 +1056,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
   __shared__ QParams qp[kFusedMaxN];
   __shared__ int32_t codes[kFusedMaxN][kFusedCoords];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ __attribute__((aligned(16))) float next_sh[kFusedCoords];  // the tile of the new iterate (dots_R > 0)
   const int ntiles = (int)((a.d_pad + kFusedCoords - 1) / kFusedCoords);
-  if ((int)blockIdx.x >= ntiles) {  // whole workgroups: no barrier below is skipped by part of one
+  if (a.dots_R == 0 && (int)blockIdx.x >= ntiles) {  // whole workgroups: no barrier below is skipped by part of one
     warm_next_rows(a, ntiles);
     return;
   }
-  const int64_t tile0 = (int64_t)blockIdx.x * kFusedCoords;
+  const int tile = a.dots_R > 0 ? (int)blockIdx.x % ntiles : (int)blockIdx.x;
+  const int share = a.dots_R > 0 ? (int)blockIdx.x / ntiles : 0;
+  const bool writer = share == 0;  // the one workgroup of the tile that stores the exchange's results
+  const int64_t tile0 = (int64_t)tile * kFusedCoords;
+  // the next iteration's rows are requested first of all: they come from HBM
+  float4 xpre[8];
+  if (a.dots_R > 0) tile_dots_load(a.dots, tile, share * a.dots.rows_per_wg, a.dots.rows_per_wg, tid, xpre);
   // everything this thread will need from memory is requested before the statistics fold, so the three
   // dependent round trips (statistics, U, w/mu) overlap
   float4 v_all[kFusedMaxN / GROUPS];  // this thread's four coordinates of workers g, g+GROUPS, ...
@@ -1068,12 +1083,12 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
   if (tid < kFusedCoords && tile0 + tid < a.d) {
     const int64_t j = tile0 + tid;
     if (a.do_prox) {
-      w_old = a.w[j];
+      w_old = a.w_in[j];
       mu_j = a.mu[j];
     }
     if (a.do_alpc) {
-      mu_j = a.mu[j]; x_j = a.x[j]; z_j = a.z[j]; uhat_j = a.u_hat[j]; snap_j = a.w_snap[j];
-      ysum_j = a.first ? 0.0f : a.ysum[j];
+      mu_j = a.mu[j]; x_j = a.x[j]; z_j = a.z_in[j]; uhat_j = a.u_hat[j]; snap_j = a.w_snap[j];
+      ysum_j = (a.first || !writer) ? 0.0f : a.ysum[j];
     }
   }
   // wavefront wv folds the statistics of vectors wv, wv+NW, ...; four vectors at a time so that their partials
@@ -1102,7 +1117,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
       if (lane == 0) {
         const QParams q_i = make_qparams(a.qs, am_w, s_w, s2_w, a.d);
         qp[i] = q_i;
-        if (blockIdx.x == 0) {
+        if (blockIdx.x == 0) {  // tile 0's writer
           a.delta_out[i] = q_i.delta;
           double *o = a.stats + (int64_t)i * 4;
           o[0] = am_w; o[1] = s_w; o[2] = s2_w; o[3] = b_w;
@@ -1165,7 +1180,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
     for (int32_t idx = tid; idx < a.N * words_per_worker; idx += kFusedThreads) {
       const int32_t i = idx / words_per_worker, rem = idx % words_per_worker;
       const int32_t sgm = rem / bits, wd = rem % bits;
-      if ((seg0 + sgm) * kSegFloats >= a.d_pad) continue;
+      if ((seg0 + sgm) * kSegFloats >= a.d_pad || !writer) continue;
       const int32_t bit0 = 32 * wd;
       uint32_t word = 0u;
       for (int32_t c = bit0 / bits; c < 32 && c * bits < bit0 + 32; ++c) {
@@ -1179,21 +1194,33 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
   // eq. (4) in worker order, then Alg. 1 steps 9-10
   if (tid < kFusedCoords) {
     const int64_t j = tile0 + tid;
+    float next = 0.0f;
     if (j < a.d) {
       float acc = 0.0f;
       for (int32_t i = 0; i < a.N; ++i) acc = __builtin_fmaf(qp[i].delta, (float)codes[i][tid], acc);
       const float avg = acc * (1.0f / (float)a.N);
-      if (a.u_avg_out) a.u_avg_out[j] = avg;
-      if (a.do_prox) a.w[j] = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
+      if (a.u_avg_out && writer) a.u_avg_out[j] = avg;
+      if (a.do_prox) {
+        next = prox_scalar(w_old, avg + mu_j, a.step, a.thr, a.shrink);
+        if (writer) a.w[j] = next;
+      }
       if (a.do_alpc) {
         const float yn = prox_scalar(x_j, avg + mu_j, a.step_y, a.thr_y, a.shrink_y);   // low-precision gradient
         const float zn = prox_scalar(z_j, uhat_j + mu_j, a.alpha, a.thr_z, a.shrink_z);  // full precision
-        a.y[j] = yn;
-        a.z[j] = zn;
-        a.ysum[j] = a.first ? a.weight * yn : ysum_j + a.weight * yn;
-        a.x_next[j] = (a.t1 * zn + a.t2 * snap_j) + a.t3 * yn;
+        next = (a.t1 * zn + a.t2 * snap_j) + a.t3 * yn;
+        if (writer) {
+          a.y[j] = yn;
+          a.z[j] = zn;
+          a.ysum[j] = a.first ? a.weight * yn : ysum_j + a.weight * yn;
+          a.x_next[j] = next;
+        }
       }
     }
+    next_sh[tid] = next;
+  }
+  if (a.dots_R > 0) {
+    __syncthreads();
+    tile_dots_finish(a.dots, next_sh, tile, share * a.dots.rows_per_wg, a.dots.rows_per_wg, tid, xpre);
   }
 }
 
@@ -1970,7 +1997,7 @@ hipError_t launch_fused_exchange(const lpc_ctx *c, const float *U, int32_t nslot
   a.N = c->cfg.N; a.bits = c->cfg.bits; a.nslots = nslots; a.stat_slots = c->stat_slots;
   a.stat_part = c->s.stat_part; a.qs = spec_of(c); a.key = key;
   a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
-  a.mu = mu; a.w = w; a.u_avg_out = u_avg_out; a.step = step; a.do_prox = w != nullptr ? 1 : 0;
+  a.mu = mu; a.w = w; a.w_in = w; a.u_avg_out = u_avg_out; a.step = step; a.do_prox = w != nullptr ? 1 : 0;
   prox_consts(c, step > 0.0f ? step : 1.0f, &a.thr, &a.shrink);
   const int extra = w != nullptr ? warm_setup(c, key, false, &a) : 0;
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords + extra));
@@ -1986,7 +2013,8 @@ hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t 
   a.stat_part = c->s.stat_part; a.qs = spec_of(c); a.key = key;
   a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
   a.mu = al.mu; a.do_alpc = 1;
-  a.x = al.x; a.u_hat = al.u_hat; a.w_snap = al.w_snap; a.y = al.y; a.z = al.z; a.ysum = al.ysum; a.x_next = al.x_next;
+  a.x = al.x; a.u_hat = al.u_hat; a.w_snap = al.w_snap; a.y = al.y; a.z = al.z; a.z_in = al.z; a.ysum = al.ysum;
+  a.x_next = al.x_next;
   a.step_y = al.step_y; a.alpha = al.alpha; a.weight = al.weight; a.first = al.first;
   a.t1 = al.tau1; a.t2 = al.tau2; a.t3 = (float)(1.0 - (double)al.tau1 - (double)al.tau2);
   prox_consts(c, al.step_y, &a.thr_y, &a.shrink_y);
@@ -1994,6 +2022,52 @@ hipError_t launch_fused_exchange_alpc(const lpc_ctx *c, const float *U, int32_t 
   const int extra = warm_setup(c, key, true, &a);
   const dim3 grid((unsigned)((c->d_pad + kFusedCoords - 1) / kFusedCoords + extra));
   LPC_LAUNCH_TIMED(fused_exchange_kernel, grid, dim3(kFusedThreads), st, a);
+  return hipGetLastError();
+}
+
+// The exchange of the column-tile iteration: reads U and the statistic partials the column-tile worker pass left
+// (one slot per tile), updates the iterate (Alg. 1: w_in -> w_out; Alg. 2/3: al->x -> al->x_next, z_in -> al->z),
+// and, when next_pd is given, leaves the partial dots of the rows iteration key.iter + 1 samples (nvec_next
+// vectors, the last one the shared batch for Alg. 2/3) with the new iterate.
+hipError_t launch_cols_exchange(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
+                                const float *mu, float step, const float *w_in, float *w_out, const AlpcStep *al,
+                                const float *z_in, float *next_pd, hipStream_t st) {
+  FusedArgs a{};
+  a.U = U; a.d = c->d; a.d_pad = c->d_pad; a.W = c->W;
+  a.N = c->cfg.N; a.bits = c->cfg.bits; a.nslots = dense_cols_tiles(c); a.stat_slots = c->stat_slots;
+  a.stat_part = c->s.stat_part; a.qs = spec_of(c); a.key = key;
+  a.packed = packed; a.delta_out = delta_out; a.stats = c->s.stats; a.flags = c->s.flags;
+  if (al) {
+    a.mu = al->mu; a.do_alpc = 1;
+    a.x = al->x; a.u_hat = al->u_hat; a.w_snap = al->w_snap; a.y = al->y; a.z = al->z; a.z_in = z_in;
+    a.ysum = al->ysum; a.x_next = al->x_next;
+    a.step_y = al->step_y; a.alpha = al->alpha; a.weight = al->weight; a.first = al->first;
+    a.t1 = al->tau1; a.t2 = al->tau2; a.t3 = (float)(1.0 - (double)al->tau1 - (double)al->tau2);
+    prox_consts(c, al->step_y, &a.thr_y, &a.shrink_y);
+    prox_consts(c, al->alpha, &a.thr_z, &a.shrink_z);
+  } else {
+    a.mu = mu; a.w = w_out; a.w_in = w_in; a.step = step; a.do_prox = 1;
+    prox_consts(c, step, &a.thr, &a.shrink);
+  }
+  const int tiles = dense_cols_tiles(c);
+  a.dots_R = 1;
+  if (next_pd) {
+    DotsArgs &dd = a.dots;
+    dd.X = c->prob.X; dd.ldx = c->prob.ldx; dd.d = c->d; dd.n = c->n; dd.w = nullptr; dd.pd = next_pd;
+    dd.C = tiles; dd.B = c->cfg.B; dd.nvec = c->cfg.N + (al ? 1 : 0); dd.worker_begin = 0;
+    dd.shared_rel = al ? c->cfg.N : -1;
+    dd.vec4 = (c->d % 4 == 0 && c->prob.ldx % 4 == 0 && (((uintptr_t)c->prob.X) & 15u) == 0) ? 1 : 0;
+    dd.key = key; dd.key.iter = key.iter + 1; dd.tag = kTagBatch;
+    const int32_t rows = dd.nvec * dd.B;
+    int groups = dense_dots_groups(c, rows);
+    const int least = (rows + kDotRows - 1) / kDotRows;  // a workgroup holds at most kDotRows rows in registers
+    if (groups < least) groups = least;
+    dd.rows_per_wg = (rows + groups - 1) / groups;
+    a.dots_R = groups;
+  } else {
+    a.dots.rows_per_wg = 0; a.dots.nvec = 0; a.dots.B = 1; a.dots.C = tiles;
+  }
+  LPC_LAUNCH_TIMED(fused_exchange_kernel, dim3((unsigned)(tiles * a.dots_R)), dim3(kFusedThreads), st, a);
   return hipGetLastError();
 }
 
@@ -2030,7 +2104,7 @@ hipError_t launch_fused_iter(const lpc_ctx *c, StreamKey key, uint32_t *packed, 
     prox_consts(c, al->alpha, &a.thr_z, &a.shrink_z);
     extra = warm_setup(c, key, true, &a);
   } else {
-    a.mu = mu; a.w = w; a.step = step; a.do_prox = 1;
+    a.mu = mu; a.w = w; a.w_in = w; a.step = step; a.do_prox = 1;
     prox_consts(c, step, &a.thr, &a.shrink);
     extra = warm_setup(c, key, false, &a);
   }

@@ -72,7 +72,7 @@ EXPORTS = {
     "lpc_profile_enable": (C.c_int, [_vp, C.c_int32]),
     "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int32), _vp]),
 }
-TUNE_ITER_LAUNCHES, TUNE_ITER_TILE, TUNE_ITER_THREADS, TUNE_SPIN_LIMIT = 0, 1, 2, 3
+TUNE_ITER_FORM, TUNE_ITER_TILE, TUNE_ITER_THREADS, TUNE_SPIN_LIMIT = 0, 1, 2, 3
 PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblpc_hip.so")
