@@ -230,6 +230,25 @@ lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double 
 lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch, float *delta_trace,
                             uint32_t *nclip_trace, uint64_t *coded_bits_host, void *stream);
 
+/* Table 1 (Sec. 4.2): bits transmitted per inner iteration by communication step 2 for d coordinates, `bits` bits
+ * per coordinate and N workers: scheme (a) (32 + b d) N (N - 1); (b) N (64 + 2 b d + d ceil(log2 N)); (c)
+ * N (64 + 2 b d).  bits >= 32 (quantization off): 32 d N (N - 1).  Host arithmetic only.  LPC_EINVAL for bits
+ * outside [2,16] and below 32, N < 1 or an unknown scheme. */
+lpc_status lpc_bits_per_iteration(int64_t d, int32_t bits, int32_t N, int32_t scheme, uint64_t *out_host);
+
+/* One epoch as lpc_epoch, with a summary returned to the HOST (synchronises the stream): bits_sent = m times the
+ * Table 1 figure of the context's scheme; messages = m*N; clipped = the coordinates outside dom(delta, b) summed
+ * over all messages (Sec. 3.2's d_lambda, the quantity Lemma 2 bounds the error with); max_delta = the largest
+ * scale factor any message was quantized with (eq. (3)); nonfinite = 1 if a vector handed to the quantizer held a
+ * NaN or Inf (the context's flag is cleared).  The epoch takes the unfused launches, as lpc_epoch_traced does. */
+typedef struct {
+  uint64_t bits_sent, messages, clipped;
+  float max_delta;
+  int32_t nonfinite;
+} lpc_epoch_stats;
+lpc_status lpc_epoch_report(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch,
+                            lpc_epoch_stats *stats_out_host, void *stream);
+
 /* Selection of the clipping parameter (Sec. 6.1 picks lambda by cross-validation, once): for each of the
  * n_clip candidates clips_host[k] (lambda in (0,1] or c > 0, in the context's clip mode) the method is run
  * for `epochs` epochs numbered epoch0, epoch0+1, ... from the same start w0 (ALPC-SVRG: y = z = w0) with

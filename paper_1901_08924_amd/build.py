@@ -24,6 +24,7 @@ SOURCES = [
     ("lpc_gemm.hip", []),
     ("lpc_mlp.hip", []),
     ("lpc_eval.hip", []),
+    ("lpc_host.cpp", []),      # host-only logic: no device code (also built with sanitizers by the tests)
 ]
 HEADERS = ["lpc_internal.h", "lpc_device.h"]
 
@@ -41,7 +42,7 @@ def _hipcc():
 
 
 def _compile(src, extra, verbose):
-    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+    obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o").replace(".cpp", ".o"))
     cmd = [_hipcc()] + COMMON + extra + ["-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -54,57 +54,6 @@ struct ProfScope {
   }
 };
 
-lpc_status check_problem(const lpc_problem *p) {
-  if (!p) return LPC_ENULL;
-  if (p->n <= 0 || p->d <= 0) return LPC_ESHAPE;
-  // row indices, coordinate indices and segment counters are 32-bit (the random stream's counter word too)
-  if (p->n > (int64_t)0xFFFFFFFFll || p->d > (int64_t)0xFFFFFFFFll) return LPC_ESHAPE;
-  if (!p->y) return LPC_ENULL;
-  if (p->loss != LPC_LOSS_LOGISTIC && p->loss != LPC_LOSS_SQUARED && p->loss != LPC_LOSS_MLP_SOFTMAX)
-    return LPC_EINVAL;
-  if (!(p->lambda1 >= 0.0f) || !(p->lambda2 >= 0.0f)) return LPC_EINVAL;
-  if (p->X) {
-    if (p->row_ptr || p->col_idx || p->vals) return LPC_EINVAL;  // exactly one storage format
-    if (!aligned(p->X, 4)) return LPC_ESHAPE;
-    if (p->loss != LPC_LOSS_MLP_SOFTMAX && p->ldx < p->d) return LPC_ESHAPE;
-  } else {
-    if (!p->row_ptr || !p->col_idx || !p->vals) return LPC_ENULL;
-    if (!aligned(p->col_idx, 4) || !aligned(p->vals, 4) || !aligned(p->row_ptr, 4)) return LPC_ESHAPE;
-    if (p->nnz < 0 || p->nnz > (int64_t)0x7FFFFFFFll) return LPC_ESHAPE;
-    if (p->loss == LPC_LOSS_MLP_SOFTMAX) return LPC_EINVAL;
-  }
-  if (p->loss == LPC_LOSS_MLP_SOFTMAX) {
-    if (!p->mlp_dims || p->mlp_nlayers < 1) return LPC_ENULL;
-    int64_t total = 0;
-    for (int32_t l = 0; l < p->mlp_nlayers; ++l) {
-      if (p->mlp_dims[l] <= 0 || p->mlp_dims[l + 1] <= 0) return LPC_ESHAPE;
-      total += (int64_t)p->mlp_dims[l] * p->mlp_dims[l + 1] + p->mlp_dims[l + 1];
-    }
-    if (total != p->d || p->ldx < p->mlp_dims[0]) return LPC_ESHAPE;
-  }
-  return LPC_OK;
-}
-
-lpc_status check_config(const lpc_problem *p, const lpc_config *c) {
-  if (!c) return LPC_ENULL;
-  if (c->algo != LPC_ALGO_LPC && c->algo != LPC_ALGO_ALPC_SC && c->algo != LPC_ALGO_ALPC_GC) return LPC_EINVAL;
-  if (c->N <= 0 || c->B <= 0 || c->m <= 0) return LPC_EINVAL;
-  if (c->N > 0xFFFFFE) return LPC_EINVAL;
-  // bits = 1 makes the denominator 2^(b-1)-1 of eq. (3) zero
-  if (c->bits < 2 || (c->bits > 16 && c->bits < 32)) return LPC_EINVAL;
-  if (c->clip_mode != LPC_CLIP_LAMBDA && c->clip_mode != LPC_CLIP_CSIGMA) return LPC_EINVAL;
-  if (!(c->clip > 0.0f)) return LPC_EINVAL;
-  if (c->clip_mode == LPC_CLIP_LAMBDA && c->clip > 1.0f) return LPC_EINVAL;  // lambda in (0,1]
-  if (c->scheme != LPC_SCHEME_A && c->scheme != LPC_SCHEME_B && c->scheme != LPC_SCHEME_C) return LPC_EINVAL;
-  if (!(c->eta > 0.0f)) return LPC_EINVAL;
-  if ((int64_t)c->N * c->B > p->n) return LPC_EINVAL;  // Theorem 1 assumes N*B <= n
-  if (c->n_full < 0 || c->n_full > p->n) return LPC_EINVAL;
-  if (c->algo != LPC_ALGO_LPC && !(c->L > 0.0f)) return LPC_EINVAL;
-  if (c->tau1 < 0.0f || c->tau2 < 0.0f || c->alpha < 0.0f || c->sigma < 0.0f) return LPC_EINVAL;
-  if (c->tau1 + c->tau2 > 1.0f) return LPC_EINVAL;
-  return LPC_OK;
-}
-
 // Computes sizes; when base != nullptr also assigns the scratch pointers.
 size_t layout(lpc_ctx *c, char *base) {
   size_t off = 0;
@@ -154,6 +103,9 @@ size_t layout(lpc_ctx *c, char *base) {
     s.sparse_planes = (float *)take((extra ? (size_t)c->cfg.N * extra * c->d_pad : 4) * sizeof(float));
     s.touched_parts = (uint32_t *)take((extra ? (size_t)c->cfg.N * extra * c->bitmap_words : 4) * sizeof(uint32_t));
   }
+  s.report_delta = (float *)take((size_t)c->cfg.m * c->cfg.N * sizeof(float));
+  s.report_nclip = (uint32_t *)take((size_t)c->cfg.m * c->cfg.N * sizeof(uint32_t));
+  s.report_out = (unsigned long long *)take(2 * sizeof(unsigned long long));
   s.w2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
   s.z2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
   s.pd = (float *)take((c->cols_capable ? 2 * (size_t)N1 * c->cfg.B * dense_cols_tiles(c) : 4) * sizeof(float));
@@ -426,23 +378,6 @@ lpc_status exchange_and_prox(lpc_ctx *c, StreamKey key, float *w, bool want_clip
 }  // namespace
 
 extern "C" {
-
-int64_t lpc_d_pad(int64_t d) { return (d + 31) / 32 * 32; }
-int64_t lpc_words_per_msg(int64_t d, int32_t bits) { return (d + 31) / 32 * (int64_t)bits; }
-
-const char *lpc_status_string(lpc_status s) {
-  switch (s) {
-    case LPC_OK: return "ok";
-    case LPC_EINVAL: return "invalid argument";
-    case LPC_ENULL: return "null pointer";
-    case LPC_ESHAPE: return "shape, leading dimension or alignment mismatch";
-    case LPC_EWORKSPACE: return "workspace missing, misaligned or too small";
-    case LPC_ENONFINITE: return "non-finite value in a vector handed to the quantizer";
-    case LPC_EDEVICE: return "HIP call failed";
-    case LPC_EUNSUPPORTED: return "not supported by this build";
-  }
-  return "unknown status";
-}
 
 size_t lpc_workspace_bytes(const lpc_problem *problem, const lpc_config *config) {
   lpc_ctx tmp{};
@@ -925,6 +860,29 @@ lpc_status lpc_epoch_traced(lpc_ctx *ctx, float *w_snap, float *y, float *z, uin
   return rc;
 }
 
+lpc_status lpc_epoch_report(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t epoch,
+                            lpc_epoch_stats *stats_out_host, void *stream) {
+  if (!ctx || !stats_out_host) return LPC_ENULL;
+  lpc_ctx *c = ctx;
+  hipStream_t st = as_stream(stream);
+  LPC_TRY(lpc_epoch_traced(c, w_snap, y, z, epoch, c->s.report_delta, c->s.report_nclip, nullptr, stream));
+  const int64_t cnt = (int64_t)c->cfg.m * c->cfg.N;
+  LPC_TRY_HIP(launch_epoch_report(c->s.report_delta, c->s.report_nclip, cnt, c->s.report_out, st));
+  unsigned long long out[2] = {0, 0};
+  LPC_TRY_HIP(hipMemcpyAsync(out, c->s.report_out, sizeof(out), hipMemcpyDeviceToHost, st));
+  const lpc_status flags = lpc_take_device_flags(c, stream);  // synchronises the stream
+  if (flags != LPC_OK && flags != LPC_ENONFINITE) return flags;
+  uint64_t per_iter = 0;
+  LPC_TRY(lpc_bits_per_iteration(c->d, c->cfg.bits, c->cfg.N, c->cfg.scheme, &per_iter));
+  stats_out_host->bits_sent = per_iter * (uint64_t)c->cfg.m;
+  stats_out_host->messages = (uint64_t)cnt;
+  stats_out_host->clipped = out[0];
+  const uint32_t mb = (uint32_t)out[1];
+  std::memcpy(&stats_out_host->max_delta, &mb, sizeof(float));
+  stats_out_host->nonfinite = flags == LPC_ENONFINITE ? 1 : 0;
+  return LPC_OK;
+}
+
 lpc_status lpc_clip_sweep(lpc_ctx *ctx, const float *w0, int32_t n_clip, const float *clips_host, int32_t epochs,
                           uint32_t epoch0, float *w_work, float *y_work, float *z_work, double *P_out_host,
                           uint64_t *clipped_out_host, void *stream) {
@@ -984,20 +942,6 @@ lpc_status lpc_gradient_mapping(lpc_ctx *ctx, const float *w, float eta, double 
   return LPC_OK;
 }
 
-lpc_status lpc_theorem2_lhs(int64_t d, int32_t bits, double lambda, int64_t d_lambda, int32_t N, int32_t B,
-                            int32_t m, double rho, int32_t scheme, double *out_host) {
-  if (!out_host) return LPC_ENULL;
-  if (bits < 2 || bits > 16 || d < 0 || d_lambda < 0 || N < 1 || B < 1 || m < 1) return LPC_EINVAL;
-  if (scheme != LPC_SCHEME_A && scheme != LPC_SCHEME_B && scheme != LPC_SCHEME_C) return LPC_EINVAL;
-  const double steps = (double)((1 << (bits - 1)) - 1);   // delta = lambda*|u|_inf/steps, eq. (3)
-  const double rounding = (scheme == LPC_SCHEME_C ? 0.375 : 0.25) * (double)d * (lambda / steps) * (lambda / steps);
-  const double clipping = (double)d_lambda * (1.0 - lambda) * (1.0 - lambda);
-  const double sampling = 1.0 / ((double)N * (double)B);
-  const double mr = (double)m * rho;
-  *out_host = 8.0 * mr * mr * (rounding + clipping + sampling) + rho;
-  return LPC_OK;
-}
-
 lpc_status lpc_code_histogram(lpc_ctx *ctx, const uint32_t *packed, uint64_t *counts, void *stream) {
   if (!ctx || !packed || !counts) return LPC_ENULL;
   if (!ctx->quant) return LPC_EINVAL;
@@ -1025,14 +969,6 @@ lpc_status lpc_huffman_encode(lpc_ctx *ctx, const uint32_t *packed, const int32_
   if (need > capacity_words) return LPC_ESHAPE;
   if (need == 0) return LPC_OK;
   LPC_TRY_HIP(launch_huffman_emit(ctx, packed, out_words, need, st));
-  return LPC_OK;
-}
-
-lpc_status lpc_huffman_bits(const uint64_t *counts_host, int32_t nsym, int32_t *lens_out_host,
-                            uint64_t *bits_out_host) {
-  if (!counts_host || !bits_out_host) return LPC_ENULL;
-  if (nsym < 1 || nsym > (1 << 16)) return LPC_EINVAL;
-  *bits_out_host = huffman_code_lengths(counts_host, nsym, lens_out_host);
   return LPC_OK;
 }
 

@@ -102,32 +102,6 @@ hipError_t launch_gradient_mapping(const lpc_ctx *c, const float *w, const float
   return hipGetLastError();
 }
 
-// Canonical prefix code: symbols ordered by (length, index); the first codeword is all zeros, each next one
-// is the previous plus one, shifted left when the length grows.  The table keeps every codeword bit-reversed
-// so that appending it to a little-endian bit stream puts its most significant bit first.
-int huffman_canonical_table(const int32_t *lens, int32_t nsym, HuffEntry *table) {
-  int32_t longest = 0;
-  for (int32_t k = 0; k < nsym; ++k) {
-    if (lens[k] < 0 || lens[k] > 32) return -1;
-    longest = lens[k] > longest ? lens[k] : longest;
-    table[k] = HuffEntry{0u, 0u};
-  }
-  uint64_t word = 0;   // next free codeword of the current length
-  int32_t cur = 0;
-  for (int32_t len = 1; len <= longest; ++len)
-    for (int32_t k = 0; k < nsym; ++k) {
-      if (lens[k] != len) continue;
-      word <<= (len - cur);
-      cur = len;
-      if (word >= (1ull << len)) return -1;  // Kraft's inequality violated
-      uint32_t rev = 0;
-      for (int32_t i = 0; i < len; ++i) rev |= (uint32_t)((word >> i) & 1ull) << (len - 1 - i);
-      table[k] = HuffEntry{rev, (uint32_t)len};
-      ++word;
-    }
-  return 0;
-}
-
 namespace {
 
 // symbol (bin index) of coordinate j of a 32-coordinate segment
@@ -241,6 +215,35 @@ hipError_t launch_huffman_emit(const lpc_ctx *c, const uint32_t *words, uint32_t
   return hipGetLastError();
 }
 
+// out[0] = sum of the n clip counts, out[1] = bits of the largest of the n scale factors (one workgroup, fixed order)
+__global__ __launch_bounds__(256) void epoch_report_kernel(const float *__restrict__ delta,
+                                                           const uint32_t *__restrict__ nclip, int64_t n,
+                                                           unsigned long long *__restrict__ out) {
+  __shared__ double sum_sh[4];
+  __shared__ float max_sh[4];
+  const int tid = threadIdx.x;
+  double sum = 0.0;
+  float mx = 0.0f;
+  for (int64_t k = tid; k < n; k += 256) {
+    sum += (double)nclip[k];
+    mx = fmaxf(mx, delta[k]);
+  }
+  sum = wave_sum(sum);
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) { sum_sh[tid >> 6] = sum; max_sh[tid >> 6] = mx; }
+  __syncthreads();
+  if (tid == 0) {
+    out[0] = (unsigned long long)(((sum_sh[0] + sum_sh[1]) + sum_sh[2]) + sum_sh[3]);
+    out[1] = (unsigned long long)__float_as_uint(fmaxf(fmaxf(max_sh[0], max_sh[1]), fmaxf(max_sh[2], max_sh[3])));
+  }
+}
+
+hipError_t launch_epoch_report(const float *delta, const uint32_t *nclip, int64_t n, unsigned long long *out,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(epoch_report_kernel, dim3(1), dim3(256), 0, st, delta, nclip, n, out);
+  return hipGetLastError();
+}
+
 hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st) {
   hipLaunchKernelGGL(accumulate_clipped_kernel, dim3(1), dim3(1), 0, st, n_clipped, N, total);
   return hipGetLastError();
@@ -257,45 +260,6 @@ hipError_t launch_code_histogram(const uint32_t *words, int64_t d, int32_t bits,
   if (wgs > 512) wgs = 512;
   hipLaunchKernelGGL(code_histogram_kernel, dim3((unsigned)wgs), dim3(256), 0, st, words, d, bits, cnt);
   return hipGetLastError();
-}
-
-// Optimal prefix-code lengths: repeatedly join the two lightest subtrees; each join puts every leaf below it
-// one level deeper.  Subtrees are kept in a min-heap of (weight, node); parents are recorded so that a leaf's
-// length is its distance to the root.  A lone used symbol still needs one bit per occurrence.
-uint64_t huffman_code_lengths(const uint64_t *counts, int32_t nsym, int32_t *lens) {
-  using Item = std::pair<uint64_t, int32_t>;
-  std::priority_queue<Item, std::vector<Item>, std::greater<Item>> heap;
-  std::vector<int32_t> parent((size_t)nsym, -1);
-  for (int32_t k = 0; k < nsym; ++k) {
-    if (lens) lens[k] = 0;
-    if (counts[k]) heap.push({counts[k], k});
-  }
-  if (heap.empty()) return 0;
-  if (heap.size() == 1) {
-    const Item only = heap.top();
-    if (lens) lens[only.second] = 1;
-    return only.first;
-  }
-  uint64_t total = 0;
-  while (heap.size() > 1) {
-    const Item a = heap.top(); heap.pop();
-    const Item b = heap.top(); heap.pop();
-    const int32_t node = (int32_t)parent.size();
-    parent.push_back(-1);
-    parent[(size_t)a.second] = node;
-    parent[(size_t)b.second] = node;
-    total += a.first + b.first;
-    heap.push({a.first + b.first, node});
-  }
-  if (lens) {
-    for (int32_t k = 0; k < nsym; ++k) {
-      if (!counts[k]) continue;
-      int32_t depth = 0;
-      for (int32_t v = k; parent[(size_t)v] >= 0; v = parent[(size_t)v]) ++depth;
-      lens[k] = depth;
-    }
-  }
-  return total;
 }
 
 }  // namespace lpc

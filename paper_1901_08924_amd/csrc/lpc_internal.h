@@ -3,7 +3,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
+#if defined(__HIPCC__)
+#include <hip/hip_ext.h>   // timed launches; device translation units only
+#endif
 #include <stdint.h>
 
 #include <vector>
@@ -118,6 +120,9 @@ struct Scratch {
   int32_t *csc_rows;    // [nnz] row index per entry, ascending inside a column
   float *csc_vals;      // [nnz]
   float *csc_coef;      // [n] per-row loss slopes of the snapshot pass
+  float *report_delta;       // [m][N] scale factors of an epoch run by lpc_epoch_report
+  uint32_t *report_nclip;    // [m][N] its clip counts
+  unsigned long long *report_out;  // [2] their reduction
   float *w2;            // [d] second buffer of the inner iterate (form 2 reads one and writes the other)
   float *z2;            // [d] second buffer of ALPC-SVRG's z
   float *pd;            // two sets of [(N+1)*B][tiles] partial dots of the sampled rows with the iterate
@@ -188,6 +193,10 @@ struct lpc_ctx {
 
 namespace lpc {
 
+// ---- host-only logic (lpc_host.cpp) ----
+lpc_status check_problem(const lpc_problem *p);
+lpc_status check_config(const lpc_problem *p, const lpc_config *c);
+
 // ---- launchers (each validates nothing: the ABI layer has done that) ----
 
 // Dense GLM passes (lpc_dense.hip)
@@ -243,6 +252,8 @@ constexpr int kSnapWide = 2048;  // rows per block of its weight-gradient produc
 int huffman_canonical_table(const int32_t *lens, int32_t nsym, HuffEntry *table);
 hipError_t launch_huffman_measure(const lpc_ctx *c, const uint32_t *words, hipStream_t st);
 hipError_t launch_huffman_emit(const lpc_ctx *c, const uint32_t *words, uint32_t *out, int64_t out_words,
+                               hipStream_t st);
+hipError_t launch_epoch_report(const float *delta, const uint32_t *nclip, int64_t n, unsigned long long *out,
                                hipStream_t st);
 hipError_t launch_accumulate_clipped(const uint32_t *n_clipped, int32_t N, unsigned long long *total, hipStream_t st);
 void mlp_plan(lpc_ctx *c);

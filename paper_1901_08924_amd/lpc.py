@@ -21,6 +21,11 @@ OK, EINVAL, ENULL, ESHAPE, EWORKSPACE, ENONFINITE, EDEVICE, EUNSUPPORTED = 0, -1
 _vp = C.c_void_p
 
 
+class EpochStats(C.Structure):
+    _fields_ = [("bits_sent", C.c_uint64), ("messages", C.c_uint64), ("clipped", C.c_uint64),
+                ("max_delta", C.c_float), ("nonfinite", C.c_int32)]
+
+
 class Problem(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int64), ("loss", C.c_int32),
                 ("X", _vp), ("ldx", C.c_int64),
@@ -56,6 +61,8 @@ EXPORTS = {
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, C.POINTER(C.c_uint64), _vp]),
+    "lpc_bits_per_iteration": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_uint64)]),
+    "lpc_epoch_report": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp]),
     "lpc_clip_sweep": (C.c_int, [_vp, _vp, C.c_int32, C.POINTER(C.c_float), C.c_int32, C.c_uint32, _vp, _vp, _vp,
                                  C.POINTER(C.c_double), C.POINTER(C.c_uint64), _vp]),
     "lpc_objective": (C.c_int, [_vp, _vp, C.POINTER(C.c_double), _vp]),
@@ -124,6 +131,12 @@ def theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme=SCHEME_A):
     out = C.c_double()
     _chk(lib.lpc_theorem2_lhs(d, bits, lam, d_lambda, N, B, m, rho, scheme, C.byref(out)), "lpc_theorem2_lhs")
     return out.value
+
+
+def bits_per_iteration(d, bits, N, scheme=SCHEME_A):
+    out = C.c_uint64()
+    _chk(lib.lpc_bits_per_iteration(d, bits, N, scheme, C.byref(out)), "lpc_bits_per_iteration")
+    return int(out.value)
 
 
 def huffman_bits(counts):
@@ -244,6 +257,13 @@ class Context:
         if coded:
             return dtr, ntr, [[int(sizes[t * self.N + i]) for i in range(self.N)] for t in range(m)]
         return dtr, ntr
+
+    def epoch_report(self, w_snap, epoch, y=None, z=None, stream=None):
+        """epoch() plus its summary (EpochStats on the host)."""
+        st = EpochStats()
+        _chk(lib.lpc_epoch_report(self._h, _ptr(w_snap), _ptr(y), _ptr(z), epoch, C.byref(st), _stream(stream)),
+             "lpc_epoch_report")
+        return st
 
     def clip_sweep(self, w0, clips, epochs, epoch0=0, stream=None):
         """Objective and total clipped coordinates after `epochs` epochs from w0 for each candidate clip value."""

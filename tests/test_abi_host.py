@@ -129,3 +129,18 @@ def test_theorem2_and_huffman_host_entry_points():
     assert lpc.huffman_bits([0, 0]) == (0, [0, 0])
     bits, lens = lpc.huffman_bits([3] * 8)
     assert bits == 72 and lens == [3] * 8
+
+
+def test_table1_bits_per_iteration(lpc):
+    """lpc_bits_per_iteration against the values worked out by hand from Table 1's formulas (tests/golden)."""
+    with open(os.path.join(ROOT, "tests", "golden", "table1_bits.txt")) as f:
+        rows = [[int(t) for t in line.split()] for line in f if line.strip() and not line.startswith("#")]
+    assert len(rows) >= 4
+    for d, b, N, bits_a, bits_b, bits_c, _msg in rows:
+        assert lpc.bits_per_iteration(d, b, N, lpc.SCHEME_A) == bits_a
+        assert lpc.bits_per_iteration(d, b, N, lpc.SCHEME_B) == bits_b
+        assert lpc.bits_per_iteration(d, b, N, lpc.SCHEME_C) == bits_c
+    assert lpc.bits_per_iteration(20, 32, 4) == 32 * 20 * 4 * 3
+    for bad in ((10, 1, 4, 0), (10, 17, 4, 0), (10, 4, 0, 0), (10, 4, 4, 3)):
+        with pytest.raises(lpc.LpcError):
+            lpc.bits_per_iteration(*bad)

@@ -6,7 +6,7 @@ import pytest
 
 import lpc_synth
 from oracle import lpco
-from _common import gpu_context, oracle_problem, to_dev
+from _common import gpu_context, oracle_config, oracle_problem, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -299,4 +299,34 @@ def test_traced_epoch_on_the_mlp_instance():
     assert np.abs(diff[1:]).max() <= 2
     P_o, P_g = lpco.objective(p, w_o), ctx.objective(w_b)
     assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,over,cfg_over", [
+    ("c2", dict(n=2048, d=512, N=4, B=16), dict(m=6, bits=4, clip_mode=0, clip=0.8)),
+    ("c2", dict(n=2048, d=512, N=4, B=16), dict(m=6, bits=3, clip_mode=0, clip=0.9, scheme=lpco.SCHEME_B)),
+    ("c4", dict(n=2048, d=256, N=4, B=16), dict(m=5, bits=3, clip_mode=1, clip=2.0, tau2=0.5)),
+    ("c3", dict(n=4096, d=50_000, nnz_mean=20, N=4, B=16), dict(m=4, bits=2, clip_mode=0, clip=0.7)),
+])
+def test_epoch_report_against_the_oracle(name, over, cfg_over):
+    """lpc_epoch_report: Table 1 bits (the oracle's epoch returns the same count), clipped coordinates and the
+    largest scale factor against the oracle's traced epoch."""
+    sp = lpc_synth.make(name, **over)
+    ctx = gpu_context(sp, **cfg_over)
+    p, _k = oracle_problem(sp)
+    cfg = oracle_config(sp, **cfg_over)
+    alpc = cfg.algo != lpco.ALGO_LPC
+    w_o, w_g = sp.w0.copy(), to_dev(sp.w0)
+    y_o, z_o = (sp.w0.copy(), sp.w0.copy()) if alpc else (None, None)
+    y_g, z_g = (to_dev(sp.w0), to_dev(sp.w0)) if alpc else (None, None)
+    for s in range(2):
+        st = ctx.epoch_report(w_g, s, y_g, z_g)
+        w_t, y_t, z_t = w_o.copy(), (y_o.copy() if alpc else None), (z_o.copy() if alpc else None)
+        dtr_o, ntr_o = lpco.epoch_traced(p, cfg, w_t, s, y_t, z_t)
+        sent = lpco.epoch(p, cfg, w_o, s, y_o, z_o)
+        assert st.bits_sent == sent and st.messages == cfg.m * cfg.N and st.nonfinite == 0
+        assert abs(st.max_delta - dtr_o.max()) <= 1e-3 * dtr_o.max()
+        assert abs(int(st.clipped) - int(ntr_o.sum())) <= max(3, 0.01 * int(ntr_o.sum()))
+    P_o = lpco.objective(p, w_o)
+    assert abs(ctx.objective(w_g) - P_o) <= 1e-4 * abs(P_o)
     ctx.close()
