@@ -36,6 +36,7 @@ KERNEL_NAMES = {
     "vr_rows": "worker pass (lpc_worker_vr_grad): all workers' sampled rows",
     "vr_fold": "worker pass: fold / statistics of U",
     "exchange": "exchange: eq. (3) + quantize + pack + eq. (4) + prox",
+    "resident": "inner loop of an epoch as one resident launch (m iterations: rows, fold, exchange, update)",
 }
 
 
@@ -66,9 +67,12 @@ def algorithmic_work(sp, dp, nnz):
         return {"full_rows": full,
                 "vr_rows": (8.0 * entries + 8.0 * N * dp, "bytes"),     # rows + zero and write U
                 "exchange": (msg, "bytes")}
+    nvec = N + (1 if sp.algo != 0 else 0)   # Alg. 2, 3 also draw the shared batch J
     return {"full_rows": (4.0 * n_full * d + 8.0 * n_full + 8.0 * d, "bytes"),  # X, y, w in; z, mu out
-            "vr_rows": (4.0 * N * B * d + 4.0 * N * d, "bytes"),               # each sampled row once; U out
-            "exchange": (msg, "bytes")}
+            "vr_rows": (4.0 * nvec * B * d + 4.0 * nvec * d, "bytes"),         # each sampled row once; U out
+            "exchange": (msg, "bytes"),
+            # one launch = m iterations; on the chip U never reaches HBM: the sampled rows in, the messages out
+            "resident": (sp.m * (4.0 * nvec * B * d + 8.0 * nvec * B + N * (bits * dp / 8.0 + 4.0)), "bytes")}
 
 
 def measured_traffic(workload):
@@ -345,7 +349,7 @@ def main():
                     help="all (default): the headline on c4, the largest configuration, with c2, c3 and c5 as "
                          "sub-records under 'workloads'; or one configuration alone")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--iter-form", type=int, default=None, choices=[0, 1, 2],
+    ap.add_argument("--iter-form", type=int, default=None, choices=[0, 1, 2, 3],
                     help="form of the dense inner iteration (lpc_tune LPC_TUNE_ITER_FORM; default: the library's)")
     ap.add_argument("--iter-tile", type=int, default=None, choices=[64, 128])
     ap.add_argument("--iter-threads", type=int, default=None, choices=[256, 512])

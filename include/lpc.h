@@ -311,9 +311,18 @@ typedef enum {
   LPC_PROF_VR_ROWS = 2,   /* worker pass: rows kernel (all workers, one launch) */
   LPC_PROF_VR_FOLD = 3,   /* worker pass: fold + statistics                     */
   LPC_PROF_EXCHANGE = 4,  /* quantize/pack + dequantize/average + prox          */
-  LPC_PROF_NCLASS = 5
+  LPC_PROF_RESIDENT = 5,  /* all inner iterations of an epoch in one launch     */
+  LPC_PROF_NCLASS = 6
 } lpc_prof_class;
 lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on);
+/* Phase time stamps of the resident inner loop (LPC_TUNE_ITER_FORM 3).  While switched on, every resident launch of
+ * the context leaves, per inner iteration, 11 readings of the device's constant 100 MHz counter taken by one
+ * workgroup at its phase boundaries (iteration start; rows done; partial vectors stored; first barrier of its die
+ * passed; fold done; statistics published; flags of the eight dies seen; operands and scale factors ready; codes
+ * ready; update stored; second barrier passed).  stamps_out_host (may be NULL): receives the last launch's stamps,
+ * m rows of 16 words (words 11-15 unused), after synchronising the stream.  `on` then switches the recording
+ * on or off for the launches that follow.  LPC_EUNSUPPORTED where the context cannot run that form. */
+lpc_status lpc_resident_trace(lpc_ctx *ctx, int32_t on, uint64_t *stamps_out_host, void *stream);
 lpc_status lpc_profile_read(lpc_ctx *ctx, double *ms_total, int64_t *launches, int32_t *exact, void *stream);
 
 /* ---- unit-test and benchmark entry of the MLP instance's contraction kernel (no passage of the paper) ----

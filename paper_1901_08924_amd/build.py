@@ -24,6 +24,7 @@ SOURCES = [
     ("lpc_gemm.hip", []),
     ("lpc_mlp.hip", []),
     ("lpc_eval.hip", []),
+    ("lpc_resident.hip", ["-ffp-contract=off"]),   # holds the quantizer's arithmetic too
     ("lpc_host.cpp", []),      # host-only logic: no device code (also built with sanitizers by the tests)
 ]
 HEADERS = ["lpc_internal.h", "lpc_device.h"]

@@ -109,6 +109,13 @@ size_t layout(lpc_ctx *c, char *base) {
   s.w2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
   s.z2 = (float *)take((c->cols_capable ? (size_t)c->d : 4) * sizeof(float));
   s.pd = (float *)take((c->cols_capable ? 2 * (size_t)N1 * c->cfg.B * dense_cols_tiles(c) : 4) * sizeof(float));
+  s.res_part = (float *)take((c->res_capable ? resident_part_floats(c) : 4) * sizeof(float));
+  s.res_ubuf = (float *)take((c->res_capable ? resident_ubuf_floats(c) : 4) * sizeof(float));
+  s.res_jbuf = (float *)take((c->res_capable ? resident_jbuf_floats(c) : 4) * sizeof(float));
+  s.res_stat = (double *)take((c->res_capable ? resident_stat_doubles(c) : 1) * sizeof(double));
+  s.res_wbuf = (float *)take((c->res_capable ? resident_wbuf_floats(c) : 4) * sizeof(float));
+  s.res_ctl = (uint32_t *)take((c->res_capable ? resident_ctl_words() : 4) * sizeof(uint32_t));
+  s.res_trace = (unsigned long long *)take((c->res_capable ? (size_t)c->cfg.m * 16 : 1) * sizeof(unsigned long long));
   s.iter_slots = (unsigned long long *)take((c->iter2_capable ? (size_t)fused_iter_slot_words(c) : 1) * sizeof(unsigned long long));
   if (c->mlp) {
     s.mlp_xb = (float *)take((size_t)c->mlp_rows * c->mlp_dims[0] * sizeof(float));
@@ -191,6 +198,7 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
   }
   c->iter2_capable = fused_iter_supported(c);
   c->cols_capable = fused_exchange_supported(c) && dense_cols_supported(c);
+  c->res_capable = resident_supported(c);
   // measured on MI355X (inner iterations/s, forms 0 / 1 / 2): d = 4096, N = 8, B = 64: 59.9 k / 50.6 k / 47.6 k;
   // d = 8192, N = 16 (+ shared batch), B = 64: 32.3 k / - / 20.2 k.  Form 1 pays about 3 us per trip of the statistics
   // through device-scope atomics; form 2 pays for reading the sampled rows a second time in 512-byte slices (its
@@ -424,8 +432,9 @@ lpc_status lpc_tune(lpc_ctx *ctx, int32_t key, int64_t value) {
   if (!ctx) return LPC_ENULL;
   switch (key) {
     case LPC_TUNE_ITER_FORM:
-      if (value < 0 || value > 2) return LPC_EINVAL;
-      if ((value == 1 && !ctx->iter2_capable) || (value == 2 && !ctx->cols_capable)) return LPC_EUNSUPPORTED;
+      if (value < 0 || value > 3) return LPC_EINVAL;
+      if ((value == 1 && !ctx->iter2_capable) || (value == 2 && !ctx->cols_capable) || (value == 3 && !ctx->res_capable))
+        return LPC_EUNSUPPORTED;
       ctx->iter_form = (int32_t)value;
       return LPC_OK;
     case LPC_TUNE_ITER_TILE:
@@ -442,6 +451,19 @@ lpc_status lpc_tune(lpc_ctx *ctx, int32_t key, int64_t value) {
       return LPC_OK;
   }
   return LPC_EINVAL;
+}
+
+lpc_status lpc_resident_trace(lpc_ctx *ctx, int32_t on, uint64_t *stamps_out_host, void *stream) {
+  if (!ctx) return LPC_ENULL;
+  if (!ctx->res_capable) return LPC_EUNSUPPORTED;
+  if (stamps_out_host) {
+    hipStream_t st = as_stream(stream);
+    LPC_TRY_HIP(hipMemcpyAsync(stamps_out_host, ctx->s.res_trace, sizeof(uint64_t) * 16 * (size_t)ctx->cfg.m,
+                               hipMemcpyDeviceToHost, st));
+    LPC_TRY_HIP(hipStreamSynchronize(st));
+  }
+  ctx->res_trace_on = on != 0;
+  return LPC_OK;
 }
 
 lpc_status lpc_profile_enable(lpc_ctx *ctx, int32_t on) {
@@ -656,6 +678,18 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     const bool two = fused && c->iter_form == 1 && c->iter2_capable;
     const bool cols = fused && c->iter_form == 2 && c->cols_capable && zs != nullptr;
     const bool sparse = c->csr_sparse && !tracing;
+    if (fused && c->iter_form == 3 && c->res_capable && zs != nullptr) {
+      // all m inner iterations in one resident launch
+      ResidentStep rs{};
+      rs.z_snap = zs; rs.mu = s.mu; rs.w_snap = w_snap; rs.w = s.w; rs.alpc = false;
+      rs.key = key_of(c, epoch, 0); rs.step = g.eta; rs.theta = 1.0f;
+      {
+        ProfScope ps(c, LPC_PROF_RESIDENT, st);
+        LPC_TRY_HIP(launch_resident_epoch(c, rs, st));
+      }
+      LPC_TRY_HIP(launch_copy(w_snap, s.w, c->d, st));  // x~ <- x_m
+      return LPC_OK;
+    }
     if (two) LPC_TRY_HIP(launch_fused_iter_reset(c, st));
     if (sparse) {
       // the sparse passes rely on U, the bitmap and the packed words being zero where nothing was written
@@ -746,6 +780,23 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
     // three launches per inner iteration: the rows of the N workers AND of the shared batch J, their fold
     // (+ statistic partials), and the exchange with Alg. 2 steps 13-15 and the next step 6 as its epilogue
     LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
+    if (c->iter_form == 3 && c->res_capable && zs != nullptr) {
+      // all m inner iterations in one resident launch; the weights of Alg. 2 step 15 follow the same recurrence there
+      ResidentStep rs{};
+      rs.z_snap = zs; rs.mu = s.mu; rs.w_snap = w_snap; rs.w = s.w; rs.y = y; rs.z = z; rs.ysum = s.ysum; rs.alpc = true;
+      rs.key = key_of(c, epoch, 0); rs.step_y = step_y; rs.alpha = ap.alpha; rs.tau1 = ap.tau1; rs.tau2 = ap.tau2;
+      rs.theta = ap.theta;
+      {
+        ProfScope ps(c, LPC_PROF_RESIDENT, st);
+        LPC_TRY_HIP(launch_resident_epoch(c, rs, st));
+      }
+      for (int32_t t = 0; t < g.m; ++t) {
+        wsum += weight;
+        weight *= (double)ap.theta;
+      }
+      LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
+      return LPC_OK;
+    }
     if (c->iter_form == 2 && c->cols_capable && zs != nullptr) {
       // two launches per inner iteration, as for Alg. 1; x and z alternate between two buffers each
       float *xa = s.w, *xb = s.w2, *za = z, *zb = s.z2;

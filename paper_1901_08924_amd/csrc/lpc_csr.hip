@@ -28,11 +28,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kGroup = 16;                     // lanes per row
 
-__device__ __forceinline__ float loss_slope(int32_t loss, float z, float y) {
-  if (loss == LPC_LOSS_LOGISTIC) return -y / (1.0f + expf(y * z));
-  return z - y;
-}
-
 __device__ __forceinline__ float loss_value(int32_t loss, float z, float y) {
   if (loss == LPC_LOSS_LOGISTIC) {
     const float t = -y * z;

@@ -43,11 +43,6 @@ struct DenseArgs {
   int32_t shared_rel;  // relative worker index that draws the shared batch J instead (-1: none)
 };
 
-__device__ __forceinline__ float loss_slope(int32_t loss, float z, float y) {
-  if (loss == LPC_LOSS_LOGISTIC) return -y / (1.0f + expf(y * z));
-  return z - y;
-}
-
 __device__ __forceinline__ float loss_value(int32_t loss, float z, float y) {
   if (loss == LPC_LOSS_LOGISTIC) {
     const float t = -y * z;

@@ -124,6 +124,58 @@ __device__ __forceinline__ double wave_max(double v) {
   return fmax(fmax(read_lane(v, 0), read_lane(v, 16)), fmax(read_lane(v, 32), read_lane(v, 48)));
 }
 
+// ---- pieces shared by the quantizer's launches and the resident inner loop ---------------------------------------
+// (the translation units that use them are compiled with floating-point contraction off)
+struct QuantSpec {
+  int32_t bits;
+  int32_t clip_mode;
+  float clip;
+  int32_t enabled;
+};
+
+// eq. (3): delta = lambda*|u|_inf/(2^(b-1)-1); in c*sigma mode
+// lambda = min(1, c*sigma/|u|_inf) with sigma the population standard deviation.
+__device__ inline QParams make_qparams(const QuantSpec &qs, double amax_d, double sum, double sumsq, int64_t d) {
+  QParams q;
+  const float amax = (float)amax_d;
+  float lambda;
+  if (qs.clip_mode == LPC_CLIP_LAMBDA) {
+    lambda = qs.clip;
+  } else if (amax > 0.0f) {
+    const double mean = sum / (double)d;
+    double var = sumsq / (double)d - mean * mean;
+    if (var < 0.0) var = 0.0;
+    const double ratio = (double)qs.clip * sqrt(var) / (double)amax;
+    lambda = ratio < 1.0 ? (float)ratio : 1.0f;
+  } else {
+    lambda = 1.0f;
+  }
+  const float thresh = lambda * amax;
+  const float levels = (float)((1 << (qs.bits - 1)) - 1);
+  const float delta = thresh / levels;
+  const float rdelta = (float)(1.0 / (double)delta);
+  const bool live = delta > 0.0f && isfinite(rdelta);
+  q.delta = live ? delta : 0.0f;
+  q.rdelta = live ? rdelta : 0.0f;
+  q.thresh = thresh;
+  q.neg_edge = -(float)(1 << (qs.bits - 1)) * delta;
+  return q;
+}
+
+// prox_{step*h}(w - step*v) for h = lambda1*|.|_1 + (lambda2/2)*|.|^2 (Alg. 1 steps 9-10): thr = step*lambda1,
+// shrink = 1/(1 + step*lambda2)
+__device__ __forceinline__ float prox_scalar(float w, float v, float step, float thr, float shrink) {
+  const float p = w - step * v;
+  const float mag = fabsf(p) - thr;
+  return mag > 0.0f ? copysignf(mag * shrink, p) : 0.0f;
+}
+
+// derivative of the per-sample loss with respect to the margin z = x'w (logistic with labels +-1, or squared)
+__device__ __forceinline__ float loss_slope(int32_t loss, float z, float y) {
+  if (loss == LPC_LOSS_LOGISTIC) return -y / (1.0f + expf(y * z));
+  return z - y;
+}
+
 // ---- partial dot products of sampled rows with one 128-column tile of an iterate -------------------------------
 // (the small-d inner iteration's margins: see the column-tile worker pass in lpc_dense.hip)
 constexpr int kColTile = 128;     // columns per tile / workgroup

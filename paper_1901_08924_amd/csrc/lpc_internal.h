@@ -126,6 +126,14 @@ struct Scratch {
   float *w2;            // [d] second buffer of the inner iterate (form 2 reads one and writes the other)
   float *z2;            // [d] second buffer of ALPC-SVRG's z
   float *pd;            // two sets of [(N+1)*B][tiles] partial dots of the sampled rows with the iterate
+  // resident inner loop (lpc_resident.hip)
+  float *res_part;      // [8][slots][32][d_pad] partial vectors per die, worker slot and compute unit
+  float *res_ubuf;      // [2][N][d_pad] u^i as the dies publish them (two sets, by iteration parity)
+  float *res_jbuf;      // [2][8][d_pad] the dies' partial sums of the shared batch's difference
+  double *res_stat;     // [2][N][32][4] slice statistics
+  float *res_wbuf;      // [8][d_pad] the iterate, one copy per die
+  uint32_t *res_ctl;    // tickets, barrier counters, flags, abort word
+  unsigned long long *res_trace;  // [m][16] time stamps of the resident loop's phases (lpc_resident_trace)
   unsigned long long *iter_slots;  // two sets of [tiles][N][4] statistics exchanged between the workgroups of the
                                    // two-launch inner iteration (all ones = empty)
   uint32_t *touched;    // [N][bitmap_words] sparse inner iteration: one bit per 32-coordinate segment of u^i
@@ -169,11 +177,14 @@ struct lpc_ctx {
   int32_t fold_slices;    // slices of the two-level fold of the snapshot pass's partial rows
   // form of the small-d dense inner iteration (lpc_tune): 0 = rows, fold, exchange (three launches); 1 = rows,
   // then fold + exchange in one launch whose workgroups wait for each other's statistics; 2 = column tiles fed by
-  // partial dot products, then the exchange, which also leaves the next iteration's partial dots (two launches)
+  // partial dot products, then the exchange, which also leaves the next iteration's partial dots (two launches);
+  // 3 = all m iterations in one resident launch (lpc_resident.hip)
   int32_t iter_form = 0;
   bool at_snapshot = false;    // set by lpc_epoch while it issues t = 0 of Alg. 1, where x_0 is the snapshot itself
   bool iter2_capable = false;  // the context's scratch holds what form 1 needs
   bool cols_capable = false;   // ... what form 2 needs
+  bool res_capable = false;    // ... what form 3 (the resident inner loop) needs
+  bool res_trace_on = false;   // the next resident launches leave their phase time stamps
   int32_t iter_tile = 128, iter_threads = 512;  // launch shape of the second one
   uint32_t spin_limit = 1u << 15;               // polls a workgroup of it waits for the others' statistics
   bool csc_ready = false;  // the column-major tail copy exists (CSR snapshot pass without atomics)
@@ -219,6 +230,25 @@ hipError_t launch_dense_dots(const lpc_ctx *c, const float *w, StreamKey key, in
 hipError_t launch_dense_cols(const lpc_ctx *c, const float *z_snap, const float *pd, StreamKey key, uint32_t tag,
                              int32_t worker_begin, int32_t nvec, bool last_is_shared, float *U, int64_t ldu,
                              bool want_stats, int32_t stat_vec0, hipStream_t st);
+
+// The inner loop of an epoch as one resident launch (lpc_resident.hip)
+struct ResidentStep {
+  const float *z_snap, *mu, *w_snap;
+  float *w;              // in: the first iterate; out: the last
+  float *y, *z, *ysum;   // Alg. 2, 3 only
+  bool alpc;
+  StreamKey key;         // of iteration 0
+  float step;            // Alg. 1: eta
+  float step_y, alpha, tau1, tau2, theta;
+};
+bool resident_supported(const lpc_ctx *c);
+size_t resident_part_floats(const lpc_ctx *c);
+size_t resident_ubuf_floats(const lpc_ctx *c);
+size_t resident_jbuf_floats(const lpc_ctx *c);
+size_t resident_stat_doubles(const lpc_ctx *c);
+size_t resident_wbuf_floats(const lpc_ctx *c);
+size_t resident_ctl_words();
+hipError_t launch_resident_epoch(const lpc_ctx *c, const ResidentStep &rs, hipStream_t st);
 
 // CSR GLM passes (lpc_csr.hip)
 int csr_head_columns(int64_t d);

@@ -31,13 +31,6 @@ constexpr int kSegFloats = 32;
 constexpr int kPitch = 36;
 constexpr int kTileFloats = kThreads * kSegFloats;  // 8192 coordinates per workgroup
 
-struct QuantSpec {
-  int32_t bits;
-  int32_t clip_mode;
-  float clip;
-  int32_t enabled;
-};
-
 struct StatSinks {
   double *stat_part;
   double *stats;
@@ -47,35 +40,6 @@ struct StatSinks {
   double *stats_out;  // caller's buffer or nullptr
   int32_t stat_slots;
 };
-
-// eq. (3): delta = lambda*|u|_inf/(2^(b-1)-1); in c*sigma mode
-// lambda = min(1, c*sigma/|u|_inf) with sigma the population standard deviation.
-__device__ inline QParams make_qparams(const QuantSpec &qs, double amax_d, double sum, double sumsq, int64_t d) {
-  QParams q;
-  const float amax = (float)amax_d;
-  float lambda;
-  if (qs.clip_mode == LPC_CLIP_LAMBDA) {
-    lambda = qs.clip;
-  } else if (amax > 0.0f) {
-    const double mean = sum / (double)d;
-    double var = sumsq / (double)d - mean * mean;
-    if (var < 0.0) var = 0.0;
-    const double ratio = (double)qs.clip * sqrt(var) / (double)amax;
-    lambda = ratio < 1.0 ? (float)ratio : 1.0f;
-  } else {
-    lambda = 1.0f;
-  }
-  const float thresh = lambda * amax;
-  const float levels = (float)((1 << (qs.bits - 1)) - 1);
-  const float delta = thresh / levels;
-  const float rdelta = (float)(1.0 / (double)delta);
-  const bool live = delta > 0.0f && isfinite(rdelta);
-  q.delta = live ? delta : 0.0f;
-  q.rdelta = live ? rdelta : 0.0f;
-  q.thresh = thresh;
-  q.neg_edge = -(float)(1 << (qs.bits - 1)) * delta;
-  return q;
-}
 
 __device__ inline QParams qparams_from_delta(const QuantSpec &qs, float delta) {
   QParams q;
@@ -475,12 +439,6 @@ __device__ __forceinline__ void unpack_accumulate(const uint32_t *__restrict__ s
   uint32_t words[B];
   load_words<B>(src, words);
   accumulate_words<B>(words, delta, acc);
-}
-
-__device__ __forceinline__ float prox_scalar(float w, float v, float step, float thr, float shrink) {
-  const float p = w - step * v;
-  const float mag = fabsf(p) - thr;
-  return mag > 0.0f ? copysignf(mag * shrink, p) : 0.0f;
 }
 
 struct ProxArgs {

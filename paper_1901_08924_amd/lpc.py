@@ -61,6 +61,7 @@ EXPORTS = {
     "lpc_prox_step": (C.c_int, [_vp, _vp, _vp, _vp, C.c_float, _vp]),
     "lpc_epoch": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp]),
     "lpc_epoch_traced": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp, C.POINTER(C.c_uint64), _vp]),
+    "lpc_resident_trace": (C.c_int, [_vp, C.c_int32, _vp, _vp]),
     "lpc_bits_per_iteration": (C.c_int, [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_uint64)]),
     "lpc_epoch_report": (C.c_int, [_vp, _vp, _vp, _vp, C.c_uint32, _vp, _vp]),
     "lpc_clip_sweep": (C.c_int, [_vp, _vp, C.c_int32, C.POINTER(C.c_float), C.c_int32, C.c_uint32, _vp, _vp, _vp,
@@ -80,7 +81,7 @@ EXPORTS = {
     "lpc_profile_read": (C.c_int, [_vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int32), _vp]),
 }
 TUNE_ITER_FORM, TUNE_ITER_TILE, TUNE_ITER_THREADS, TUNE_SPIN_LIMIT = 0, 1, 2, 3
-PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange")
+PROF_CLASSES = ("full_rows", "full_fold", "vr_rows", "vr_fold", "exchange", "resident")
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblpc_hip.so")
 
@@ -315,6 +316,15 @@ class Context:
 
     def profile_enable(self, on):
         _chk(lib.lpc_profile_enable(self._h, 1 if on else 0), "lpc_profile_enable")
+
+    def resident_trace(self, on, read=False, stream=None):
+        """Switches the phase time stamps of the resident inner loop on or off; with read=True first returns the last
+        launch's stamps as m rows of 16 counter readings (100 MHz)."""
+        out = None
+        if read:
+            out = (C.c_uint64 * (16 * self.config.m))()
+        _chk(lib.lpc_resident_trace(self._h, 1 if on else 0, out, _stream(stream)), "lpc_resident_trace")
+        return [list(out[16 * t:16 * t + 16]) for t in range(self.config.m)] if read else None
 
     def profile_read(self, stream=None):
         """{class: (total ms, launches, exact)} since the last read; exact = every record was one kernel timed by
