@@ -413,6 +413,15 @@ lpc_status lpc_create(lpc_ctx **ctx_out, const lpc_problem *problem, const lpc_c
     delete c;
     return LPC_EDEVICE;
   }
+  if (c->res_capable) {
+    // the resident loop's tagged words: no tag of a launch is zero, so zeroed words never pass for written ones
+    const size_t words = ((char *)c->s.res_ctl - (char *)c->s.res_ubuf) / sizeof(uint32_t);
+    if (launch_fill_u32(reinterpret_cast<uint32_t *>(c->s.res_ubuf), 0u, (int64_t)words, nullptr) != hipSuccess ||
+        hipStreamSynchronize(nullptr) != hipSuccess) {
+      delete c;
+      return LPC_EDEVICE;
+    }
+  }
   if (c->csr && build_csc_tail(c, nullptr) != hipSuccess) {
     delete c;
     return LPC_EDEVICE;
@@ -683,6 +692,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       ResidentStep rs{};
       rs.z_snap = zs; rs.mu = s.mu; rs.w_snap = w_snap; rs.w = s.w; rs.alpc = false;
       rs.key = key_of(c, epoch, 0); rs.step = g.eta; rs.theta = 1.0f;
+      rs.tag0 = c->res_tag; c->res_tag += (uint32_t)g.m + 1u;
       {
         ProfScope ps(c, LPC_PROF_RESIDENT, st);
         LPC_TRY_HIP(launch_resident_epoch(c, rs, st));
@@ -786,6 +796,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       rs.z_snap = zs; rs.mu = s.mu; rs.w_snap = w_snap; rs.w = s.w; rs.y = y; rs.z = z; rs.ysum = s.ysum; rs.alpc = true;
       rs.key = key_of(c, epoch, 0); rs.step_y = step_y; rs.alpha = ap.alpha; rs.tau1 = ap.tau1; rs.tau2 = ap.tau2;
       rs.theta = ap.theta;
+      rs.tag0 = c->res_tag; c->res_tag += (uint32_t)g.m + 1u;
       {
         ProfScope ps(c, LPC_PROF_RESIDENT, st);
         LPC_TRY_HIP(launch_resident_epoch(c, rs, st));

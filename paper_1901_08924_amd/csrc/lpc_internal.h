@@ -128,10 +128,10 @@ struct Scratch {
   float *pd;            // two sets of [(N+1)*B][tiles] partial dots of the sampled rows with the iterate
   // resident inner loop (lpc_resident.hip)
   float *res_part;      // [8][slots][32][d_pad] partial vectors per die, worker slot and compute unit
-  float *res_ubuf;      // [2][N][d_pad] u^i as the dies publish them (two sets, by iteration parity)
-  float *res_jbuf;      // [2][8][d_pad] the dies' partial sums of the shared batch's difference
-  double *res_stat;     // [2][N][32][4] slice statistics
-  float *res_wbuf;      // [8][d_pad] the iterate, one copy per die
+  float *res_ubuf;      // [2][N][d_pad] (value, tag) words: u^i as the dies publish them (two sets, by iteration parity)
+  float *res_jbuf;      // [2][8][d_pad] words: the dies' partial sums of the shared batch's difference
+  double *res_stat;     // [2][N][32][8] words: slice statistics
+  float *res_wbuf;      // [8][d_pad] words: the iterate, one copy per die
   uint32_t *res_ctl;    // tickets, barrier counters, flags, abort word
   unsigned long long *res_trace;  // [m][16] time stamps of the resident loop's phases (lpc_resident_trace)
   unsigned long long *iter_slots;  // two sets of [tiles][N][4] statistics exchanged between the workgroups of the
@@ -185,6 +185,7 @@ struct lpc_ctx {
   bool cols_capable = false;   // ... what form 2 needs
   bool res_capable = false;    // ... what form 3 (the resident inner loop) needs
   bool res_trace_on = false;   // the next resident launches leave their phase time stamps
+  uint32_t res_tag = 0;        // tags handed to resident launches so far (each launch takes m + 1)
   int32_t iter_tile = 128, iter_threads = 512;  // launch shape of the second one
   uint32_t spin_limit = 1u << 15;               // polls a workgroup of it waits for the others' statistics
   bool csc_ready = false;  // the column-major tail copy exists (CSR snapshot pass without atomics)
@@ -238,6 +239,7 @@ struct ResidentStep {
   float *y, *z, *ysum;   // Alg. 2, 3 only
   bool alpc;
   StreamKey key;         // of iteration 0
+  uint32_t tag0;         // tags of the launch's words start above this number (grows from launch to launch)
   float step;            // Alg. 1: eta
   float step_y, alpha, tau1, tau2, theta;
 };
