@@ -95,13 +95,13 @@ size_t layout(lpc_ctx *c, char *base) {
   s.csc_rows = (int32_t *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(int32_t));
   s.csc_vals = (float *)take((c->csr ? (size_t)c->prob.nnz : 4) * sizeof(float));
   s.csc_coef = (float *)take((c->csr ? (size_t)c->n : 4) * sizeof(float));
-  s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * c->cfg.N * c->cfg.B : 1) * sizeof(RowPlan));
+  s.csr_plan = (RowPlan *)take((c->csr_sparse ? (size_t)c->cfg.m * N1 * c->cfg.B : 1) * sizeof(RowPlan));
   s.warm_sink = (float *)take(sizeof(float));
-  s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)c->cfg.N * c->bitmap_words : 4) * sizeof(uint32_t));
+  s.touched = (uint32_t *)take((c->csr_sparse ? (size_t)N1 * c->bitmap_words : 4) * sizeof(uint32_t));
   {
     const size_t extra = c->csr_sparse ? (size_t)(csr_sparse_parts(c->cfg.B) - 1) : 0;
-    s.sparse_planes = (float *)take((extra ? (size_t)c->cfg.N * extra * c->d_pad : 4) * sizeof(float));
-    s.touched_parts = (uint32_t *)take((extra ? (size_t)c->cfg.N * extra * c->bitmap_words : 4) * sizeof(uint32_t));
+    s.sparse_planes = (float *)take((extra ? (size_t)N1 * extra * c->d_pad : 4) * sizeof(float));
+    s.touched_parts = (uint32_t *)take((extra ? (size_t)N1 * extra * c->bitmap_words : 4) * sizeof(uint32_t));
   }
   s.report_delta = (float *)take((size_t)c->cfg.m * c->cfg.N * sizeof(float));
   s.report_nclip = (uint32_t *)take((size_t)c->cfg.m * c->cfg.N * sizeof(uint32_t));
@@ -163,16 +163,16 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->full_grad_wgs = csr_full_grad_wgs(c->n_full);
     c->vr_parts = 1;
     c->part_floats = (size_t)c->full_grad_wgs * csr_head_columns(c->d);
-    // Alg. 1 with per-worker scale factors keeps u^i sparse when a worker's batch touches a small part of the
+    // u^i (and the shared batch's difference of Alg. 2) stays sparse when a batch touches a small part of the
     // d columns (about B*nnz/n entries against d coordinates)
     c->sparse_head = csr_head_columns(c->d);
     c->bitmap_words = (c->d_pad / 32 + 31) / 32;
     const double touched = (double)cfg->B * (double)p->nnz / (double)p->n;
-    c->csr_sparse = c->quant && cfg->algo == LPC_ALGO_LPC && cfg->scheme == LPC_SCHEME_A && cfg->N <= 64 &&
+    c->csr_sparse = c->quant && cfg->N <= 64 &&
                     p->d >= 4 * (int64_t)c->sparse_head && touched * 8.0 <= (double)p->d &&
                     csr_sparse_parts(cfg->B) <= 8;  // tail planes per worker the statistics pass can merge
     if (c->csr_sparse) {
-      const size_t head_parts = (size_t)cfg->N * csr_sparse_parts(cfg->B) * c->sparse_head;
+      const size_t head_parts = (size_t)(cfg->N + 1) * csr_sparse_parts(cfg->B) * c->sparse_head;
       if (head_parts > c->part_floats) c->part_floats = head_parts;
     }
   } else if (c->grad_ok) {
@@ -711,7 +711,7 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
       LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
       // the epoch's draws with each row's extent, label and snapshot margin, looked up once
-      LPC_TRY_HIP(launch_csr_plan(c, zs, key_of(c, epoch, 0), st));
+      LPC_TRY_HIP(launch_csr_plan(c, zs, key_of(c, epoch, 0), false, st));
     }
     if (cols) {
       // two launches per inner iteration: column tiles of u^i from the partial dots; exchange + prox + the next
@@ -743,15 +743,25 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       if (sparse) {
         {
           ProfScope ps(c, LPC_PROF_VR_ROWS, st);
-          LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, s.csr_plan + (int64_t)t * g.N * g.B, st));
+          LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, s.csr_plan + (int64_t)t * g.N * g.B, g.N, st));
         }
         {
           ProfScope ps(c, LPC_PROF_VR_FOLD, st);
-          LPC_TRY_HIP(launch_sparse_stats(c, st));
+          LPC_TRY_HIP(launch_sparse_stats(c, g.N, st));
         }
         ProfScope ps(c, LPC_PROF_EXCHANGE, st);
-        LPC_TRY_HIP(launch_sparse_quantize(c, key, st));
-        LPC_TRY_HIP(launch_sparse_receive_prox(c, s.mu, g.eta, s.w, st));
+        if (g.scheme == LPC_SCHEME_A) {
+          LPC_TRY_HIP(launch_sparse_quantize(c, key, false, st));
+          LPC_TRY_HIP(launch_sparse_receive_prox(c, s.mu, g.eta, s.w, st));
+        } else {
+          // schemes (b), (c): one scale factor for all workers, integer sums at the receiver (and eq. (5) for (c));
+          // the receiver is the dense one, so the consumed words and the bitmap are cleared by fills
+          LPC_TRY_HIP(launch_sparse_quantize(c, key, true, st));
+          LPC_TRY_HIP(launch_dequantize_shared(c, s.packed, s.delta, g.scheme == LPC_SCHEME_C, key, s.u_avg, st));
+          LPC_TRY_HIP(launch_prox(c, s.w, s.u_avg, s.mu, g.eta, st));
+          LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
+          LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)g.N * c->bitmap_words, st));
+        }
       } else if (two) {
         // two launches per inner iteration: rows; fold + exchange + prox
         {
@@ -872,6 +882,51 @@ lpc_status lpc_epoch(lpc_ctx *ctx, float *w_snap, float *y, float *z, uint32_t e
       ProfScope ps(c, LPC_PROF_EXCHANGE, st, true);
       LPC_TRY_HIP(launch_fused_exchange_alpc(c, s.U, (int32_t)((c->d_pad + 63) / 64), key, s.packed, s.delta, al,
                                              st));
+      wsum += weight;
+      weight *= (double)ap.theta;
+    }
+    LPC_TRY_HIP(launch_scale_to(c, s.ysum, (float)(1.0 / wsum), w_snap, st));
+    return LPC_OK;
+  }
+  if (c->csr_sparse && !tracing) {
+    // Sparse inner iteration for Alg. 2 / 3: the N workers' vectors and the shared batch's full-precision difference
+    // (vector N) stay sparse through the worker and statistics passes; the workers' are quantized (own scale
+    // factors, or the shared one of schemes (b), (c)), the receiver is the dense one, and one pass over d takes
+    // Alg. 2 steps 13-15 with the next step 6 and clears the shared batch's vector.
+    const int32_t nvec = g.N + 1;
+    const int32_t extra = csr_sparse_parts(g.B) - 1;
+    LPC_TRY_HIP(launch_zero(s.U, (int64_t)nvec * c->d_pad, st));
+    if (extra > 0) {
+      LPC_TRY_HIP(launch_zero(s.sparse_planes, (int64_t)nvec * extra * c->d_pad, st));
+      LPC_TRY_HIP(launch_fill_u32(s.touched_parts, 0u, (int64_t)nvec * extra * c->bitmap_words, st));
+    }
+    LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)nvec * c->bitmap_words, st));
+    LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
+    LPC_TRY_HIP(launch_csr_plan(c, zs, key_of(c, epoch, 0), true, st));
+    LPC_TRY_HIP(launch_alpc_couple(c, z, w_snap, y, ap.tau1, ap.tau2, s.w, st));
+    for (int32_t t = 0; t < g.m; ++t) {
+      const StreamKey key = key_of(c, epoch, (uint32_t)t);
+      {
+        ProfScope ps(c, LPC_PROF_VR_ROWS, st);
+        LPC_TRY_HIP(launch_csr_vr_sparse(c, s.w, w_snap, zs, key, s.csr_plan + (int64_t)t * nvec * g.B, nvec, st));
+      }
+      {
+        ProfScope ps(c, LPC_PROF_VR_FOLD, st);
+        LPC_TRY_HIP(launch_sparse_stats(c, nvec, st));
+      }
+      ProfScope ps(c, LPC_PROF_EXCHANGE, st);
+      LPC_TRY_HIP(launch_sparse_quantize(c, key, g.scheme != LPC_SCHEME_A, st));
+      if (g.scheme == LPC_SCHEME_A) LPC_TRY_HIP(launch_dequantize_avg(c, s.packed, s.delta, s.u_avg, st));
+      else LPC_TRY_HIP(launch_dequantize_shared(c, s.packed, s.delta, g.scheme == LPC_SCHEME_C, key, s.u_avg, st));
+      AlpcStep al{};
+      al.x = s.w; al.u_hat = u_hat; al.w_snap = w_snap; al.mu = s.mu;
+      al.y = y; al.z = z; al.ysum = s.ysum; al.x_next = s.w;
+      al.step_y = step_y; al.alpha = ap.alpha; al.weight = (float)weight; al.tau1 = ap.tau1; al.tau2 = ap.tau2;
+      al.first = t == 0 ? 1 : 0;
+      LPC_TRY_HIP(launch_alpc_update_couple(c, al, st));
+      // the consumed words and all bitmaps (the shared batch's included) start the next iteration at zero
+      LPC_TRY_HIP(launch_fill_u32(s.packed, 0u, (int64_t)g.N * c->W, st));
+      LPC_TRY_HIP(launch_fill_u32(s.touched, 0u, (int64_t)nvec * c->bitmap_words, st));
       wsum += weight;
       weight *= (double)ap.theta;
     }

@@ -62,6 +62,7 @@ struct CsrArgs {
   StreamKey key;
   uint32_t tag;
   int32_t worker_begin, B;
+  int32_t shared_rel;   // plan of an epoch: the vector that draws the shared batch J (-1: none)
   float scale;
 };
 
@@ -576,8 +577,10 @@ __global__ void csr_plan_kernel(CsrArgs a, int32_t m, int32_t N, RowPlan *__rest
   StreamKey key = a.key;
   key.iter = (uint32_t)(idx / per_iter);
   const int64_t rem = idx % per_iter;
-  const uint32_t worker = (uint32_t)(rem / a.B), pos = (uint32_t)(rem % a.B);
-  const int64_t r = sample_row(key, a.tag, worker, pos, a.n);
+  const uint32_t vec = (uint32_t)(rem / a.B), pos = (uint32_t)(rem % a.B);
+  // vector shared_rel, if any, draws the shared batch J of Alg. 2 (double sampling)
+  const bool shared = (int32_t)vec == a.shared_rel;
+  const int64_t r = sample_row(key, shared ? kTagShared : a.tag, shared ? kSharedWorkerField : vec, pos, a.n);
   RowPlan p;
   p.lo = a.row_ptr[r]; p.hi = a.row_ptr[r + 1];
   p.y = a.y[r];
@@ -733,18 +736,20 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 // five, make this pass 7 us slower and the statistics pass 3.4 us faster)
 int csr_sparse_parts(int32_t B) { return (B + kRowGroups - 1) / kRowGroups; }
 
-hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, hipStream_t st) {
+hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, bool plus_shared, hipStream_t st) {
   CsrArgs a{};
   a.row_ptr = c->prob.row_ptr; a.y = c->prob.y; a.z_snap = z_snap;
   a.n = c->n; a.B = c->cfg.B; a.key = key0; a.tag = kTagBatch;
-  const int64_t total = (int64_t)c->cfg.m * c->cfg.N * c->cfg.B;
-  hipLaunchKernelGGL(csr_plan_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, c->cfg.m, c->cfg.N,
+  const int32_t nvec = c->cfg.N + (plus_shared ? 1 : 0);
+  a.shared_rel = plus_shared ? c->cfg.N : -1;
+  const int64_t total = (int64_t)c->cfg.m * nvec * c->cfg.B;
+  hipLaunchKernelGGL(csr_plan_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, c->cfg.m, nvec,
                      c->s.csr_plan);
   return hipGetLastError();
 }
 
 hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
-                                StreamKey key, const RowPlan *plan, hipStream_t st) {
+                                StreamKey key, const RowPlan *plan, int32_t nvec, hipStream_t st) {
   CsrArgs a{};
   a.plan = plan;
   a.row_ptr = c->prob.row_ptr; a.col_idx = c->prob.col_idx; a.vals = c->prob.vals; a.y = c->prob.y;
@@ -757,7 +762,7 @@ hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w
   a.parts = csr_sparse_parts(c->cfg.B);
   a.rows_per_part = kRowGroups;
   a.planes = c->s.sparse_planes; a.touched_parts = c->s.touched_parts;
-  const dim3 grid((unsigned)(c->cfg.N * a.parts));
+  const dim3 grid((unsigned)(nvec * a.parts));  // the rows of vector k are plan[k*B ..]
   const size_t lds = (size_t)a.head * sizeof(float);
   if (z_snap) hipLaunchKernelGGL((csr_vr_ordered_kernel<true, true>), grid, dim3(kSparseThreads), lds, st, a);
   else hipLaunchKernelGGL((csr_vr_ordered_kernel<false, true>), grid, dim3(kSparseThreads), lds, st, a);

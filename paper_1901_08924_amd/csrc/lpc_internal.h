@@ -260,11 +260,13 @@ hipError_t build_csc_tail(lpc_ctx *c, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
 int csr_sparse_parts(int32_t B);
-hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, hipStream_t st);
+// plus_shared: every iteration's plan holds one more vector, the shared batch J of Alg. 2 (N+1 vectors of B rows)
+hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, bool plus_shared, hipStream_t st);
 hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
-                                StreamKey key, const RowPlan *plan, hipStream_t st);
-hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st);
-hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st);
+                                StreamKey key, const RowPlan *plan, int32_t nvec, hipStream_t st);
+hipError_t launch_sparse_stats(const lpc_ctx *c, int32_t nvec, hipStream_t st);
+// share_delta: every worker quantizes with the largest of the N scale factors (Sec. 4.2 schemes (b), (c))
+hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, bool share_delta, hipStream_t st);
 hipError_t launch_sparse_receive_prox(const lpc_ctx *c, const float *mu, float step, float *w, hipStream_t st);
 hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
                               StreamKey key, uint32_t tag, int32_t worker_begin, int32_t worker_end, float *U,
@@ -366,6 +368,8 @@ hipError_t launch_alpc_couple(const lpc_ctx *c, const float *z, const float *w_s
 hipError_t launch_alpc_update(const lpc_ctx *c, const float *x, const float *u_avg, const float *u_hat,
                               const float *mu, float step_y, float alpha, float weight, bool first, float *y,
                               float *z, float *ysum, hipStream_t st);
+// Alg. 2 steps 13-15 and the next step 6 over d coordinates, reading the average from the context's u_avg; clears u_hat
+hipError_t launch_alpc_update_couple(const lpc_ctx *c, const AlpcStep &al, hipStream_t st);
 hipError_t launch_scale_to(const lpc_ctx *c, const float *src, float scale, float *dst, hipStream_t st);
 hipError_t launch_objective_reg(const lpc_ctx *c, const float *w, double *acc, hipStream_t st);
 // evaluators (Sec. 3.3 gradient mapping; Sec. 6.1 entropy coding of the code stream)

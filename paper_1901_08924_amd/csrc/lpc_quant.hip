@@ -845,7 +845,7 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
 template <int B>
 __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a, StatSinks sk, QuantSpec qs,
                                                                    int32_t nslots, int64_t d, StreamKey key,
-                                                                   uint32_t *__restrict__ packed,
+                                                                   int32_t share, uint32_t *__restrict__ packed,
                                                                    float *__restrict__ delta_out) {
   __shared__ int32_t codes[4][32][32];  // per wavefront: 32 segments x 32 codes
   __shared__ int32_t lists[4][kWaveSegs];
@@ -887,8 +887,18 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
   if (tid < 64) {
     double amax, sum, sumsq, bad;
     fold_stat_slots(sk.stat_part + (int64_t)worker * sk.stat_slots * 4, nslots, tid, amax, sum, sumsq, bad);
+    // schemes (b), (c) of Sec. 4.2: every worker quantizes with the largest of the N scale factors; each workgroup
+    // derives it from all the workers' statistic partials (the same folds in the same order everywhere)
+    float dmax = 0.0f;
+    if (share) {
+      for (int32_t i = 0; i < a.N; ++i) {
+        double am_i, s_i, s2_i, b_i;
+        fold_stat_slots(sk.stat_part + (int64_t)i * sk.stat_slots * 4, nslots, tid, am_i, s_i, s2_i, b_i);
+        dmax = fmaxf(dmax, make_qparams(qs, am_i, s_i, s2_i, d).delta);
+      }
+    }
     if (tid == 0) {
-      const QParams q = make_qparams(qs, amax, sum, sumsq, d);
+      const QParams q = share ? qparams_from_delta(qs, dmax) : make_qparams(qs, amax, sum, sumsq, d);
       q_sh = q;
       if (blockIdx.x == 0) {
         double *o = sk.stats + (int64_t)worker * 4;
@@ -1632,6 +1642,27 @@ __global__ void alpc_update_kernel(const float *__restrict__ x, const float *__r
   ysum[j] = first ? weight * yn : ysum[j] + weight * yn;
 }
 
+// Alg. 2 steps 13-15 and the next step 6 for the sparse inner iteration: as alpc_update_kernel followed by
+// alpc_couple_kernel, and the shared batch's difference u_hat (dense storage, non-zero in the head columns and the
+// touched tail segments only) is set back to zero where it was not, ready for the next iteration's scatter.
+__global__ void alpc_update_couple_kernel(const float *__restrict__ x, const float *__restrict__ u_avg,
+                                          float *__restrict__ u_hat, const float *__restrict__ mu,
+                                          const float *__restrict__ ws, float step_y, float thr_y, float shrink_y,
+                                          float alpha, float thr_z, float shrink_z, float weight, int first, float t1,
+                                          float t2, float t3, float *__restrict__ y, float *__restrict__ z,
+                                          float *__restrict__ ysum, float *__restrict__ x_next, int64_t d) {
+  const int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= d) return;
+  const float m = mu[j], uh = u_hat[j];
+  const float yn = prox_scalar(x[j], u_avg[j] + m, step_y, thr_y, shrink_y);
+  const float zn = prox_scalar(z[j], uh + m, alpha, thr_z, shrink_z);
+  if (uh != 0.0f) u_hat[j] = 0.0f;
+  y[j] = yn;
+  z[j] = zn;
+  ysum[j] = first ? weight * yn : ysum[j] + weight * yn;
+  x_next[j] = (t1 * zn + t2 * ws[j]) + t3 * yn;
+}
+
 // f_out = scale * sum of the loss partials (one workgroup, fixed order)
 __global__ __launch_bounds__(kThreads) void sum_loss_kernel(const double *__restrict__ part, int32_t n, double scale,
                                                             double *__restrict__ f_out) {
@@ -1886,19 +1917,19 @@ int32_t sparse_stat_slots(const lpc_ctx *c) { return c->sparse_head / (4 * kThre
 }  // namespace
 
 // statistic partials of the N sparse vectors left by launch_csr_vr_sparse
-hipError_t launch_sparse_stats(const lpc_ctx *c, hipStream_t st) {
-  hipLaunchKernelGGL(sparse_stats_kernel, dim3((unsigned)sparse_stat_slots(c), (unsigned)c->cfg.N), dim3(kThreads), 0,
+hipError_t launch_sparse_stats(const lpc_ctx *c, int32_t nvec, hipStream_t st) {
+  hipLaunchKernelGGL(sparse_stats_kernel, dim3((unsigned)sparse_stat_slots(c), (unsigned)nvec), dim3(kThreads), 0,
                      st, sparse_args_of(c), sinks_of(c, nullptr));
   return hipGetLastError();
 }
 
-hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, hipStream_t st) {
+hipError_t launch_sparse_quantize(const lpc_ctx *c, StreamKey key, bool share_delta, hipStream_t st) {
   // 32 head segments per workgroup, then the tail workgroups
   const dim3 grid((unsigned)(c->sparse_head / (32 * kSegFloats) + sparse_tail_wgs(c)), (unsigned)c->cfg.N);
   const int32_t slots = sparse_stat_slots(c);
 #define CALL(BITS)                                                                                             \
   hipLaunchKernelGGL(sparse_quantize_kernel<BITS>, grid, dim3(kThreads), 0, st, sparse_args_of(c), sinks_of(c, nullptr), \
-                     spec_of(c), slots, c->d, key, c->s.packed, c->s.delta)
+                     spec_of(c), slots, c->d, key, share_delta ? 1 : 0, c->s.packed, c->s.delta)
   LPC_DISPATCH_BITS(c->cfg.bits, CALL)
 #undef CALL
   return hipGetLastError();
@@ -2175,6 +2206,17 @@ hipError_t launch_alpc_update(const lpc_ctx *c, const float *x, const float *u_a
   prox_consts(c, alpha, &thr_z, &shrink_z);
   hipLaunchKernelGGL(alpc_update_kernel, grid1d(c->d, 256), dim3(256), 0, st, x, u_avg, u_hat, mu, step_y, thr_y,
                      shrink_y, alpha, thr_z, shrink_z, weight, first ? 1 : 0, y, z, ysum, c->d);
+  return hipGetLastError();
+}
+
+hipError_t launch_alpc_update_couple(const lpc_ctx *c, const AlpcStep &al, hipStream_t st) {
+  float thr_y, shrink_y, thr_z, shrink_z;
+  prox_consts(c, al.step_y, &thr_y, &shrink_y);
+  prox_consts(c, al.alpha, &thr_z, &shrink_z);
+  const float t3 = (float)(1.0 - (double)al.tau1 - (double)al.tau2);
+  hipLaunchKernelGGL(alpc_update_couple_kernel, grid1d(c->d, 256), dim3(256), 0, st, al.x, c->s.u_avg,
+                     const_cast<float *>(al.u_hat), al.mu, al.w_snap, al.step_y, thr_y, shrink_y, al.alpha, thr_z,
+                     shrink_z, al.weight, al.first, al.tau1, al.tau2, t3, al.y, al.z, al.ysum, al.x_next, c->d);
   return hipGetLastError();
 }
 

@@ -150,3 +150,62 @@ def test_sparse_inner_iteration_matches_the_oracle_coordinate_by_coordinate(bits
     assert diff.max() <= 0.05 * scale
     # the same support (the L1 prox zeroes exactly the same coordinates, up to those few)
     assert np.count_nonzero((w_o == 0) != (w_g == 0)) <= 2e-3 * sp.d
+
+
+@pytest.mark.parametrize("scheme,bits,clip_mode,clip", [(lpco.SCHEME_B, 3, 0, 1.0), (lpco.SCHEME_C, 4, 0, 0.9),
+                                                         (lpco.SCHEME_B, 2, 1, 2.0)])
+def test_sparse_inner_iteration_with_a_shared_scale_factor(scheme, bits, clip_mode, clip):
+    """Sec. 4.2 (b), (c) on CSR rows that touch few columns: the sparse worker, statistics and quantizer passes with
+    delta = max_i delta_i, then the integer-sum receiver (eq. (5) for scheme (c)).  Coordinate-level agreement
+    with the oracle as for scheme (a); the same bits run to run."""
+    import torch
+    sp = lpc_synth.make("c3", n=4096, d=50_000, nnz_mean=20, N=4, B=16)
+    over = dict(bits=bits, clip_mode=clip_mode, clip=clip, m=6, scheme=scheme)
+    hist, w_o, w_g = _run_both(sp, 2, **over)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    scale = max(np.abs(w_o).max(), 1e-12)
+    diff = np.abs(w_g - w_o)
+    assert np.count_nonzero(w_o) > 1000 and np.count_nonzero(w_o[8192:]) > 100
+    assert (diff > 1e-5 * scale).mean() <= 2e-3
+    assert diff.max() <= 0.05 * scale
+    _h, _w, w_again = _run_both(sp, 2, **over)
+    assert np.array_equal(w_g, w_again)
+
+
+@pytest.mark.parametrize("algo,scheme,bits,clip_mode,clip,B", [
+    (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, 16), (lpco.ALGO_ALPC_SC, lpco.SCHEME_A, 4, 1, 2.0, 16),
+    (lpco.ALGO_ALPC_GC, lpco.SCHEME_B, 4, 0, 0.9, 16), (lpco.ALGO_ALPC_GC, lpco.SCHEME_C, 2, 0, 1.0, 16),
+    (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, 70)])        # B = 70: two workgroups (planes) per vector
+def test_sparse_inner_iteration_of_alpc_svrg(algo, scheme, bits, clip_mode, clip, B):
+    """Alg. 2 / Alg. 3 on CSR rows that touch few columns: the workers' vectors AND the shared batch's
+    full-precision difference take the sparse worker and statistics passes; coordinate-level agreement of x~, y and z
+    with the oracle (up to a few flipped rounding decisions) and the same bits run to run."""
+    sp = lpc_synth.make("c3", n=4096, d=50_000, nnz_mean=20, N=4, B=B)
+    over = dict(algo=algo, scheme=scheme, bits=bits, clip_mode=clip_mode, clip=clip, m=6, tau2=0.5, L=0.25,
+                sigma=1e-3 if algo == lpco.ALGO_ALPC_SC else 0.0)
+    runs = []
+    for _ in range(2):
+        ctx = gpu_context(sp, **over)
+        w_g, y_g, z_g = to_dev(sp.w0), to_dev(sp.w0), to_dev(sp.w0)
+        for s in range(2):
+            ctx.epoch(w_g, s, y_g, z_g)
+        assert ctx.take_device_flags() == 0
+        P_g = ctx.objective(w_g)
+        ctx.close()
+        runs.append((w_g.cpu().numpy(), y_g.cpu().numpy(), z_g.cpu().numpy(), P_g))
+    p, _k = oracle_problem(sp)
+    cfg = oracle_config(sp, **over)
+    w_o, y_o, z_o = sp.w0.copy(), sp.w0.copy(), sp.w0.copy()
+    for s in range(2):
+        lpco.epoch(p, cfg, w_o, s, y_o, z_o)
+    P_o = lpco.objective(p, w_o)
+    assert abs(runs[0][3] - P_o) <= 1e-4 * abs(P_o)
+    for got, want in zip(runs[0][:3], (w_o, y_o, z_o)):
+        scale = max(np.abs(want).max(), 1e-12)
+        diff = np.abs(got - want)
+        assert np.count_nonzero(want) > 1000
+        assert (diff > 1e-5 * scale).mean() <= 2e-3
+        assert diff.max() <= 0.05 * scale
+    for a, b in zip(runs[0][:3], runs[1][:3]):
+        assert np.array_equal(a, b)
