@@ -75,6 +75,68 @@ def algorithmic_work(sp, dp, nnz):
             "resident": (sp.m * (4.0 * nvec * B * d + 8.0 * nvec * B + N * (bits * dp / 8.0 + 4.0)), "bytes")}
 
 
+# Vector-unit bound of the dense quantizer (Sec. 3.2 rules (1), (2) with one Philox4x32-10 block per four coordinates).
+# Instruction mix of the kernel's check-free tile path, per coordinate (b = 4): 4.5 64-bit integer products
+# (v_mad_u64_u32: 144 per 32-coordinate segment, 18 per block) and 21.25 other vector instructions (680 per
+# segment: 8.5 xor of the generator, 9 of the rounding rule, the rest packing and addresses).  Rates measured on this chip
+# with saturating kernels of independent instructions (8 wavefronts per SIMD): 23.5 T lane-instructions/s for the 64-bit
+# product, 62 T/s for 32-bit add / xor / fma.
+QUANT_MAD64_PER_COORD, QUANT_VALU_PER_COORD = 4.5, 21.25
+MAD64_RATE, VALU_RATE = 23.5e12, 62.0e12
+
+
+def quantizer_rooflines(ctx, sp):
+    """lpc_vector_stats, lpc_quantize_clip and lpc_dequantize_avg each timed alone on N Gaussian vectors of the
+    workload's length (HIP events around 10 launches): rate against the HBM bound and, for the quantizer, against the
+    vector-unit bound derived above; `frac` is against the tighter of the two."""
+    import torch
+    from paper_1901_08924_amd import lpc
+    dev = torch.device("cuda:0")
+    N, d, bits = sp.N, sp.d, sp.bits
+    dp = lpc.d_pad(d)
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    U = torch.randn(N, dp, device=dev, generator=g)
+    U[:, d:] = 0
+    stats = torch.zeros(N, 4, dtype=torch.float64, device=dev)
+    packed = torch.zeros(N, ctx.W, dtype=torch.int32, device=dev)
+    delta = torch.zeros(N, dtype=torch.float32, device=dev)
+    u_avg = torch.zeros(d, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps   # us per call
+
+    out = {}
+    coords = float(N) * dp
+    us = timed(lambda: ctx.vector_stats(U, N, stats))
+    out["vector_stats"] = {"us": us, "algorithmic_bytes": 4.0 * coords, "hbm_bound_us": 4.0 * coords / (HBM_PEAK_GBPS * 1e3),
+                           "frac": 4.0 * coords / (HBM_PEAK_GBPS * 1e3) / us,
+                           "note": "two launches (partials, fold); events around both"}
+    us = timed(lambda: ctx.quantize_clip(U, stats, None, 0, 1, packed, delta, None))
+    qbytes = coords * (4.0 + bits / 8.0)
+    hbm_us = qbytes / (HBM_PEAK_GBPS * 1e3)
+    alu_us = coords * (QUANT_MAD64_PER_COORD / MAD64_RATE + QUANT_VALU_PER_COORD / VALU_RATE) * 1e6
+    out["quantize_pack"] = {"us": us, "algorithmic_bytes": qbytes, "hbm_bound_us": hbm_us, "alu_bound_us": alu_us,
+                            "frac_of_hbm_bound": hbm_us / us, "frac_of_alu_bound": alu_us / us,
+                            "frac": max(hbm_us, alu_us) / us, "coordinates_per_s": coords / (us * 1e-6),
+                            "note": "parameter launch + quantizer (the epoch's instantiation: no clip counts, unconditional draws)"}
+    us = timed(lambda: ctx.dequantize_avg(packed, delta, u_avg))
+    rbytes = N * bits * dp / 8.0 + 4.0 * d
+    out["dequantize_avg"] = {"us": us, "algorithmic_bytes": rbytes, "hbm_bound_us": rbytes / (HBM_PEAK_GBPS * 1e3),
+                             "frac": rbytes / (HBM_PEAK_GBPS * 1e3) / us}
+    del U, packed, u_avg
+    torch.cuda.empty_cache()
+    return out
+
+
 def measured_traffic(workload):
     """HBM bytes per launch and kernel class from the stored rocprofv3 counter summary of this workload
     (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel), or {} when no summary is kept for it."""
@@ -332,6 +394,8 @@ def run_workload(name, steps, warmup, args, achievable):
                                       "unit": "GB/s" if kind == "bytes" else "TFLOP/s",
                                       "frac_of_peak": rate / (1e9 * HBM_PEAK_GBPS if kind == "bytes"
                                                               else 1e12 * MFMA_FP32_PEAK_TFLOPS)})
+    if name == "c5" and not args.small:
+        rec["exchange_steps"] = quantizer_rooflines(ctx, sp)
     ctx.close()
     del ctx, w, ya, za
     torch.cuda.empty_cache()
