@@ -345,10 +345,18 @@ lpc_status lpc_debug_gemm(const float *A, const float *B, float *C, int32_t M, i
  *       tiles: a workgroup completes one tile of one u^i, taking each sampled row's margin as the sum of partial
  *       dot products that the previous launch left; the exchange launch then also leaves the partial dots of
  *       the next iteration's rows with the new iterate.
- *     Measured on MI355X both two-launch forms are slower than form 0 (the first pays for device-scope atomics,
- *     the second for reading the sampled rows twice); they are kept as tested alternatives.
- *     Forms 0 and 1 give the same bits as each other; form 2 adds the same numbers in another order (the margins
- *     in tiles), so its u^i differ from theirs in the last bits.
+ *     3: one cooperative launch for all m inner iterations of an epoch (Alg. 1 steps 5-11 or Alg. 2 steps 5-15
+ *       with scheme (a), a dense generalized linear model with n_full == n, d a multiple of 4, 16-byte aligned
+ *       rows, a chip of 256 compute units).  256 workgroups stay resident; worker i's rows are read by the
+ *       compute units of die i mod 8; partial vectors, folded slices, statistics and iterates pass between
+ *       workgroups through device memory as (value, tag) words; one barrier per die and iteration.  Every wait is
+ *       bounded by LPC_TUNE_SPIN_LIMIT; a wait that gives up raises an abort word that all workgroups see, the
+ *       launch ends, the iterate is unspecified and lpc_take_device_flags reports LPC_EDEVICE.
+ *     Measured on MI355X forms 1-3 are slower than form 0 (form 1 pays for device-scope atomics, form 2 for reading
+ *     the sampled rows twice, form 3 for dependent instruction chains that a single resident workgroup per compute
+ *     unit cannot overlap); they are kept as tested alternatives.
+ *     Forms 0 and 1 give the same bits as each other; forms 2 and 3 add the same numbers in another order, so
+ *     their u^i differ in the last bits.  Every form gives the same bits from run to run.
  *   LPC_TUNE_ITER_TILE: form 1: coordinates per workgroup of the second launch, 64 or 128;
  *   LPC_TUNE_ITER_THREADS: form 1: its threads per workgroup, 256 or 512;
  *   LPC_TUNE_SPIN_LIMIT: form 1: polls before a workgroup gives up waiting (it then finishes normally with what it
