@@ -76,13 +76,17 @@ def algorithmic_work(sp, dp, nnz):
 
 
 # Vector-unit bound of the dense quantizer (Sec. 3.2 rules (1), (2) with one Philox4x32-10 block per four coordinates).
-# Instruction mix of the kernel's check-free tile path, per coordinate (b = 4): 4.5 64-bit integer products
-# (v_mad_u64_u32: 144 per 32-coordinate segment, 18 per block) and 21.25 other vector instructions (680 per
-# segment: 8.5 xor of the generator, 9 of the rounding rule, the rest packing and addresses).  Rates measured on this chip
-# with saturating kernels of independent instructions (8 wavefronts per SIMD): 23.5 T lane-instructions/s for the 64-bit
-# product, 62 T/s for 32-bit add / xor / fma.
-QUANT_MAD64_PER_COORD, QUANT_VALU_PER_COORD = 4.5, 21.25
-MAD64_RATE, VALU_RATE = 23.5e12, 62.0e12
+# Instruction mix of the word-per-thread kernel, per coordinate (b = 4): 4.5 64-bit integer products (v_mad_u64_u32:
+# 18 per generator block), 4.5 three-input exclusive-ors (v_bitop3_b32) and 13.25 other vector instructions (0.75
+# two-input xor of the generator's first rounds, 10 of the rounding rule, the rest packing and addresses).  Rates measured on
+# this chip with saturating kernels of independent instructions (8 wavefronts per SIMD): 33 T lane-instructions/s for
+# the 64-bit product with a zero addend, 60 T/s for 32-bit add / xor / fma with vector-register operands (37 T/s when
+# an operand is a scalar register).  A register-only loop of one generator block plus the rounding rule of four
+# coordinates runs at 1.98 T coordinates/s (317 cycles per wavefront and block at 2.4 GHz), the generator alone at
+# 3.2 T/s: the second figure of the record (`alu_loop_us`).
+QUANT_MAD64_PER_COORD, QUANT_VALU_PER_COORD = 4.5, 17.75
+MAD64_RATE, VALU_RATE = 33.0e12, 60.0e12
+QUANT_LOOP_COORDS_PER_S = 1.98e12
 
 
 def quantizer_rooflines(ctx, sp):
@@ -125,6 +129,7 @@ def quantizer_rooflines(ctx, sp):
     hbm_us = qbytes / (HBM_PEAK_GBPS * 1e3)
     alu_us = coords * (QUANT_MAD64_PER_COORD / MAD64_RATE + QUANT_VALU_PER_COORD / VALU_RATE) * 1e6
     out["quantize_pack"] = {"us": us, "algorithmic_bytes": qbytes, "hbm_bound_us": hbm_us, "alu_bound_us": alu_us,
+                            "alu_loop_us": coords / QUANT_LOOP_COORDS_PER_S * 1e6,
                             "frac_of_hbm_bound": hbm_us / us, "frac_of_alu_bound": alu_us / us,
                             "frac": max(hbm_us, alu_us) / us, "coordinates_per_s": coords / (us * 1e-6),
                             "note": "parameter launch + quantizer (the epoch's instantiation: no clip counts, unconditional draws)"}

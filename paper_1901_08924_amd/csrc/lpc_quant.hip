@@ -149,36 +149,39 @@ __global__ __launch_bounds__(64 * NWF) void reduce_parts_kernel(const float *__r
   if (want_stats != kStatsNone) publish_stats(sk, vec_begin + vec, blockIdx.x, amax, sum, sumsq, bad);
 }
 
-// statistics of rows of an existing matrix; each workgroup takes `chunk` columns
+// statistics of rows of an existing matrix; each workgroup takes `chunk` columns (a multiple of 4; rows are 16-byte
+// aligned), four 16-byte loads in flight per thread
 __global__ __launch_bounds__(kThreads) void vector_stats_kernel(const float *__restrict__ U, int64_t ld, int64_t d,
                                                                 int64_t chunk, int32_t vec_begin, StatSinks sk) {
   __shared__ double red[4][4];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t vec = blockIdx.y;
-  const float *u = U + (int64_t)vec * ld;
   const int64_t lo = (int64_t)blockIdx.x * chunk;
   const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
-  double amax = 0.0, sum = 0.0, sumsq = 0.0, bad = 0.0;
+  const float *u = U + (int64_t)vec * ld + lo;
+  const int64_t len = hi - lo, n4 = len / 4;
+  double sum = 0.0, sumsq = 0.0;
   float fmx = 0.0f;
-  // chunk is a multiple of 4 and rows are 16-byte aligned: 16-byte loads, scalar tail at the end of the row
-  for (int64_t j = lo + 4 * (int64_t)tid; j < hi; j += 4 * kThreads) {
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (j + 4 <= hi) {
-      const float4 t = *reinterpret_cast<const float4 *>(u + j);
-      v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    } else {
-      for (int k = 0; k < 4 && j + k < hi; ++k) v[k] = u[j + k];
+  uint32_t nbad = 0;
+  auto take = [&](float x) {
+    const bool fin = isfinite(x);
+    const float y = fin ? x : 0.0f;  // a zero adds nothing to any of the three
+    nbad += fin ? 0u : 1u;
+    fmx = fmaxf(fmx, fabsf(y)); sum += (double)y; sumsq += (double)y * (double)y;
+  };
+  for (int64_t i = tid; i < n4; i += 4 * kThreads) {
+    float4 t[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t k = i + q * kThreads;
+      t[q] = *reinterpret_cast<const float4 *>(u + 4 * (k < n4 ? k : i));
+      if (k >= n4) t[q] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (isfinite(v[k])) {
-        fmx = fmaxf(fmx, fabsf(v[k])); sum += (double)v[k]; sumsq += (double)v[k] * (double)v[k];
-      } else {
-        bad += 1.0;
-      }
-    }
+    for (int q = 0; q < 4; ++q) { take(t[q].x); take(t[q].y); take(t[q].z); take(t[q].w); }
   }
-  amax = (double)fmx;
+  if (tid < (int)(len - 4 * n4)) take(u[4 * n4 + tid]);  // the last one to three columns of the row
+  double amax = (double)fmx, bad = (double)nbad;
   amax = wave_max(amax); sum = wave_sum(sum); sumsq = wave_sum(sumsq); bad = wave_sum(bad);
   if (lane == 0) { red[wv][0] = amax; red[wv][1] = sum; red[wv][2] = sumsq; red[wv][3] = bad; }
   __syncthreads();
@@ -390,6 +393,92 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const float *__restr
   if (COUNT) {
     clipped = wave_sum(clipped);
     if ((tid & 63) == 0 && clipped) atomicAdd(&n_clipped[worker], clipped);
+  }
+}
+
+// Quantize + pack for the bit widths whose words hold whole groups of four codes (B = 2, 4, 8): one packed word per
+// thread.  A thread reads the 32/B consecutive coordinates of its word straight from memory (8/B loads of 16 bytes),
+// draws their 8/B Philox blocks and stores the word; a wavefront's stores are 256 contiguous bytes.  No LDS and no
+// barrier, so the registers alone bound the number of resident wavefronts.  The pass is bound by the vector unit:
+// one generator block (18 64-bit multiply-adds, 35 exclusive-ors) and about 45 other instructions per four
+// coordinates; with neither loads nor stores it runs 6 % faster.  Measured and dropped: workgroups that walk the
+// message with a grid stride and request their next word's coordinates ahead (8 to 10 % slower than a thread per
+// word: fresh workgroups cost less than the loop).  Codes, draws and bit layout are those of quantize_kernel.
+// grid = (words of a message / kThreads, N workers).
+template <int B, bool COUNT, bool SKIP>
+__global__ __launch_bounds__(kThreads) void quantize_word_kernel(const float *__restrict__ U, int64_t d, int64_t d_pad,
+                                                                 const QParams *__restrict__ qp, StreamKey key,
+                                                                 uint32_t *__restrict__ packed, int64_t W,
+                                                                 float *__restrict__ delta_out,
+                                                                 uint32_t *__restrict__ n_clipped) {
+  static_assert(B == 2 || B == 4 || B == 8, "a word holds whole groups of four codes");
+  constexpr int kCoords = 32 / B;  // coordinates per word
+  constexpr int kBlocks = kCoords / 4;
+  constexpr uint32_t mask = (1u << B) - 1u;
+  const uint32_t worker = blockIdx.y;
+  const QParams q = qp[worker];
+  if (blockIdx.x == 0 && threadIdx.x == 0) delta_out[worker] = q.delta;
+  const int64_t t = (int64_t)blockIdx.x * kThreads + threadIdx.x;  // word of the message
+  uint32_t clipped = 0;
+  if (t < W) {  // W * kCoords == d_pad: every load stays inside the vector's d_pad floats
+    const float *u = U + (int64_t)worker * d_pad;
+    float4 v[kBlocks];
+#pragma unroll
+    for (int k = 0; k < kBlocks; ++k) v[k] = *reinterpret_cast<const float4 *>(u + t * kCoords + 4 * k);
+    const int64_t j0 = t * kCoords;
+    if (j0 + kCoords > d) {  // the zero padding of the last segment carries code 0 whatever the buffer holds
+#pragma unroll
+      for (int k = 0; k < kBlocks; ++k) {
+        const int64_t j = j0 + 4 * k;
+        if (j + 0 >= d) v[k].x = 0.f;
+        if (j + 1 >= d) v[k].y = 0.f;
+        if (j + 2 >= d) v[k].z = 0.f;
+        if (j + 3 >= d) v[k].w = 0.f;
+      }
+    }
+    uint32_t word = 0u;
+    if constexpr (!COUNT && !SKIP) {
+      // The arithmetic of quantize_four with a code travelling as code + 2^(B-1), a B-bit non-negative number that
+      // one shift-or places in the word; flipping bit B-1 of every field at the end gives the two's-complement
+      // fields.
+      constexpr uint32_t kBias = 1u << (B - 1);
+      constexpr uint32_t kFlip = (uint32_t)(0xFFFFFFFFull / mask) * kBias;  // bit B-1 of every field
+      const float lo = -(float)(1 << (B - 1)), hi = (float)((1 << (B - 1)) - 1);
+#pragma unroll
+      for (int k = 0; k < kBlocks; ++k) {
+        const float vals[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+        float base[4], frac[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float sc = fminf(fmaxf(vals[c] * q.rdelta, lo), hi);
+          base[c] = floorf(sc);
+          frac[c] = sc - base[c];
+        }
+        const Philox4 blk = stream_block(key, kTagQuant, worker, (uint32_t)(j0 / 4 + k));
+        const uint32_t rnd[4] = {blk.x, blk.y, blk.z, blk.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float unif = (float)(rnd[c] >> 8) * 0x1.0p-24f;
+          const uint32_t biased = (uint32_t)((int32_t)base[c] + (int32_t)kBias + ((unif < frac[c]) ? 1 : 0));
+          word |= biased << ((4 * k + c) * B);
+        }
+      }
+      word ^= kFlip;
+      if (!(q.delta > 0.0f)) word = 0u;  // an all-zero vector: every code is 0, also where the vector holds a NaN
+    } else {
+#pragma unroll
+      for (int k = 0; k < kBlocks; ++k) {
+        int32_t code[4];
+        clipped += quantize_four<B, COUNT, SKIP>(v[k], q, key, worker, (uint32_t)(j0 / 4 + k), code);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) word |= ((uint32_t)code[c] & mask) << ((4 * k + c) * B);
+      }
+    }
+    packed[(int64_t)worker * W + t] = word;
+  }
+  if (COUNT) {
+    clipped = wave_sum(clipped);
+    if ((threadIdx.x & 63) == 0 && clipped) atomicAdd(&n_clipped[worker], clipped);
   }
 }
 
@@ -1817,18 +1906,31 @@ namespace {
 template <int B>
 void quantize_launch(const lpc_ctx *c, const float *U, StreamKey key, uint32_t *packed, float *delta_out,
                      uint32_t *n_clipped, hipStream_t st) {
-  const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats), (unsigned)c->cfg.N);
   // evaluation runs and callers of lpc_quantize_clip want the clip counts; the epoch's own launches do not, and
   // on dense vectors they also draw unconditionally
-  if (n_clipped)
-    hipLaunchKernelGGL((quantize_kernel<B, true, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams,
-                       key, packed, c->W, delta_out, n_clipped);
-  else if (c->csr)
-    hipLaunchKernelGGL((quantize_kernel<B, false, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad, c->s.qparams,
-                       key, packed, c->W, delta_out, n_clipped);
-  else
-    hipLaunchKernelGGL((quantize_kernel<B, false, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
-                       c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+  if constexpr (B == 2 || B == 4 || B == 8) {
+    const dim3 grid((unsigned)((c->W + kThreads - 1) / kThreads), (unsigned)c->cfg.N);
+    if (n_clipped)
+      hipLaunchKernelGGL((quantize_word_kernel<B, true, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+    else if (c->csr)
+      hipLaunchKernelGGL((quantize_word_kernel<B, false, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+    else
+      hipLaunchKernelGGL((quantize_word_kernel<B, false, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+  } else {
+    const dim3 grid((unsigned)((c->d_pad + kTileFloats - 1) / kTileFloats), (unsigned)c->cfg.N);
+    if (n_clipped)
+      hipLaunchKernelGGL((quantize_kernel<B, true, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+    else if (c->csr)
+      hipLaunchKernelGGL((quantize_kernel<B, false, true>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+    else
+      hipLaunchKernelGGL((quantize_kernel<B, false, false>), grid, dim3(kThreads), 0, st, U, c->d, c->d_pad,
+                         c->s.qparams, key, packed, c->W, delta_out, n_clipped);
+  }
 }
 
 template <int B, bool PROX>
