@@ -84,6 +84,36 @@ def test_quantize_pack_bit_exact(d, N, bits, clip_mode, clip):
     ctx.close()
 
 
+@pytest.mark.parametrize("d,N,bits,clip", [(4096, 8, 4, 0.9), (8192 * 3 + 37, 3, 4, 1.0), (100_003, 4, 2, 1.0),
+                                           (20_000, 2, 8, 0.75), (45, 3, 2, 1.0), (1001, 5, 8, 0.3)])
+def test_quantize_pack_without_clip_counts_bit_exact(d, N, bits, clip):
+    """The instantiation the epochs use (no clip counts, a draw for every group of four) for the bit widths that pack
+    one word per thread: ragged last segments, garbage in the padding, an all-zero vector, and coordinates just
+    below zero, whose position on the grid rounds up to the next integer."""
+    import torch
+    ctx, _ = _ctx(d, N, bits, 0, clip, seed=11)
+    U = _u(N, d, seed=3 * d + bits)
+    U[0, :] = 0.0                                     # u_0 = 0: every code 0
+    tiny = np.float32(-1e-12) * np.abs(U[1]).max()
+    U[1, 5:d:97] = tiny                              # s in (-2^-25, 0): s - floor(s) rounds to 1
+    U[1, 6:d:97] = -tiny
+    dU = to_dev(U)
+    dU[:, d:] = -77.0
+    stats = torch.zeros(N, 4, dtype=torch.float64, device="cuda")
+    ctx.vector_stats(dU, N, stats)
+    for epoch, it in [(0, 0), (2, 9)]:
+        po, do, _co, _rc = lpco.quantize_clip(U, d, bits, 0, clip, seed=11, epoch=epoch, iter_=it)
+        packed = torch.full((N, ctx.W), -1, dtype=torch.int32, device="cuda")
+        delta = torch.zeros(N, dtype=torch.float32, device="cuda")
+        ctx.quantize_clip(dU, stats, None, epoch, it, packed, delta, None)
+        assert np.array_equal(delta.cpu().numpy(), do)
+        got = packed.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, po)
+        assert not got[0].any()
+    assert ctx.take_device_flags() == 0
+    ctx.close()
+
+
 def test_quantizer_degenerate_inputs():
     import torch
     d, N, bits = 1000, 3, 3
