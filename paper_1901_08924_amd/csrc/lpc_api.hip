@@ -177,7 +177,8 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     }
   } else if (c->grad_ok) {
     c->full_grad_wgs = dense_full_grad_wgs(c->n_full, c->d, c->cus);
-    c->vr_parts = dense_vr_parts(c->d, cfg->N, cfg->B, c->cus);
+    c->vr_parts = dense_vr_parts(c->d, p->ldx, p->X, cfg->N + (cfg->algo != LPC_ALGO_LPC ? 1 : 0), cfg->B, c->cus,
+                                 c->n_full == c->n);
     const size_t a1 = (size_t)c->full_grad_wgs * c->d;
     const size_t a2 = (size_t)(cfg->N + 1) * c->vr_parts * c->d;
     c->part_floats = a1 > a2 ? a1 : a2;

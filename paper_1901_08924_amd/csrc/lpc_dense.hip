@@ -382,6 +382,24 @@ bool pick_shape(int64_t d, int64_t ldx, const void *X, Shape *s) {
 template <int VEC, int K, int T, int MODE>
 void launch_shape(const DenseArgs &a, int grid, int rows_hint, hipStream_t st) {
   constexpr int RMAX = (K >= 8) ? 1 : ((K * VEC >= 16 && MODE == 2) ? 2 : 4);
+  if constexpr (MODE == 1 && K * VEC <= 16 && T >= 256) {  // the worker pass with cached margins: up to eight rows at once
+    if (rows_hint >= 8) {
+      LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, 8, MODE>), dim3((unsigned)grid), dim3(T), st, a);
+      return;
+    }
+    if (rows_hint >= 6) {
+      LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, 6, MODE>), dim3((unsigned)grid), dim3(T), st, a);
+      return;
+    }
+    if (rows_hint == 5) {
+      LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, 5, MODE>), dim3((unsigned)grid), dim3(T), st, a);
+      return;
+    }
+    if (rows_hint == 3) {
+      LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, 3, MODE>), dim3((unsigned)grid), dim3(T), st, a);
+      return;
+    }
+  }
   if (RMAX >= 4 && rows_hint >= 4) {
     LPC_LAUNCH_TIMED((dense_rows_kernel<VEC, K, T, (RMAX >= 4 ? 4 : RMAX), MODE>), dim3((unsigned)grid), dim3(T), st, a);
   } else if (RMAX >= 2 && rows_hint >= 2) {
@@ -441,16 +459,40 @@ int dense_full_grad_wgs(int64_t n, int64_t d, int cus) {
   return (int)wgs;
 }
 
-// Partial rows per worker in the worker pass.  The pass is latency-bound (a few MB per launch), so
-// the sampled rows are spread over about one workgroup per CU: 1, 2 or 4 rows per workgroup.
-int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus) {
-  (void)d;
-  int64_t rows = (int64_t)N * B / cus;
-  // measured: below four sampled rows per CU two rows per workgroup beat four (more workgroups pulling rows
-  // outweigh the extra partial rows the fold has to read); at four rows per CU four per workgroup win (worker
-  // pass +0.8 us, fold -1.3 us)
-  int rpw = rows >= 4 ? 4 : (rows >= 2 ? 2 : 1);
-  return (B + rpw - 1) / rpw;
+// Partial rows per vector in the worker pass (nvec vectors: the N workers and, for Alg. 2 / 3, the shared batch).
+// The pass is latency-bound (a few MB per launch): what counts is the largest number of rows any one CU has to
+// pull, then how few workgroups and partial rows there are.  A workgroup's rows belong to one
+// vector, so with r rows per workgroup there are nvec * ceil(B / r) workgroups and the busiest CU holds
+// ceil(workgroups / cus) * r rows.  Measured on d = 8192, N = 16 + the shared batch, B = 64 (1088 rows on 256 CUs):
+// four rows per workgroup are 272 workgroups, sixteen CUs get two of them and the pass takes 13.2 us; five rows are
+// 221 workgroups, one per CU, 10.9 us; six 11.5 us; eight 16.3 us; one row per workgroup (1088 workgroups, the
+// same five rows on the busiest CU, 64 partial rows per vector) is slower than all of them.  With two sampled rows
+// per CU two rows per workgroup beat four, which the same ordering reproduces.  `many`: the kernel can hold 3, 5, 6 or 8 rows in registers at once
+// (cached margins, 16-byte loads, at most 16 floats per thread and row).
+int dense_vr_parts(int64_t d, int64_t ldx, const void *X, int32_t nvec, int32_t B, int cus, bool cached) {
+  Shape s;
+  bool many = cached && pick_shape(d, ldx, X, &s);
+  if (many) {
+    if (s.k == 4 && s.t == 256) { s.t = 512; s.k = 2; }  // as launch_dense_vr_grad reshapes it
+    many = s.vec == 4 && s.k * s.vec <= 16 && s.t >= 256;
+  }
+  const int64_t rows = (int64_t)nvec * B;
+  if (!many || rows > (int64_t)8 * cus) {
+    const int64_t per_cu = rows / cus;
+    const int rpw = per_cu >= 4 ? 4 : (per_cu >= 2 ? 2 : 1);
+    return (B + rpw - 1) / rpw;
+  }
+  static const int cand[] = {1, 2, 3, 4, 5, 6, 8};
+  int best = 1;
+  int64_t best_load = INT64_MAX;
+  for (int r : cand) {
+    const int64_t wgs = (int64_t)nvec * ((B + r - 1) / r);
+    const int64_t load = ((wgs + cus - 1) / cus) * r;
+    if (load <= best_load) {  // ties: more rows per workgroup (fewer workgroups and partial rows)
+      best = r; best_load = load;
+    }
+  }
+  return (B + best - 1) / best;
 }
 
 hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,

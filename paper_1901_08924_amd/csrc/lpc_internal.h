@@ -214,7 +214,7 @@ lpc_status check_config(const lpc_problem *p, const lpc_config *c);
 // Dense GLM passes (lpc_dense.hip)
 bool dense_supported(int64_t d, int64_t ldx, const void *X);
 int dense_full_grad_wgs(int64_t n, int64_t d, int cus);
-int dense_vr_parts(int64_t d, int32_t N, int32_t B, int cus);
+int dense_vr_parts(int64_t d, int64_t ldx, const void *X, int32_t nvec, int32_t B, int cus, bool cached);
 hipError_t launch_dense_full_grad(const lpc_ctx *c, const float *w, float *z, bool want_loss, int64_t n_rows,
                                   hipStream_t st);
 // plus_shared: one more vector after the workers', drawn from the shared batch J (double sampling)

@@ -1,6 +1,8 @@
 """The entry point that allocates nothing (lpc_exchange_static, for callers that cannot call hipMalloc) against
 lpc_exchange: the same packed words, scale factors and average, bit for bit, on two calls in a row, the second
 with a smaller input (the static scratch keeps the first call's contents)."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -24,9 +26,11 @@ def _pair(d, N, bits, clip_mode, clip, seed, epoch, it):
         delta = torch.full((N,), -1.0, dtype=torch.float32, device="cuda")
         avg = torch.full((d,), -1.0, dtype=torch.float32, device="cuda")
         if static:
-            before = torch.cuda.memory_allocated()
+            # torch's allocator sees no request during the call (frees by the garbage collector do not count)
+            gc.collect()
+            before = torch.cuda.memory_stats()["allocation.all.allocated"]
             lpc.exchange_static(d, N, bits, clip_mode, clip, seed, dU, epoch, it, packed, delta, avg)
-            assert torch.cuda.memory_allocated() == before
+            assert torch.cuda.memory_stats()["allocation.all.allocated"] == before
         else:
             ctx.exchange(dU, epoch, it, packed, delta, avg)
         torch.cuda.synchronize()
