@@ -601,7 +601,9 @@ __global__ void zero_kernel(float4 *__restrict__ dst, int64_t n4) {
 int csr_head_columns(int64_t d) { return (int)(d < 8192 ? d : 8192); }
 
 int csr_full_grad_wgs(int64_t n) {
-  int64_t wgs = 512;  // two resident 1024-thread workgroups per CU
+  // one 1024-thread workgroup per CU: with the registers the ordered scatter needs, a CU holds one at a time, and
+  // 256 workgroups leave half the partial rows of 512 (measured: 296 against 309 us for the pass)
+  int64_t wgs = 256;
   const int64_t by_rows = (n + 63) / 64;
   if (wgs > by_rows) wgs = by_rows;
   if (wgs >= 32) wgs = wgs / 16 * 16;
