@@ -59,7 +59,11 @@ def test_full_gradient_partial_snapshot_and_strided_rows():
 
 
 @pytest.mark.parametrize("name,n,d,N,B", [("c1", 1024, 64, 4, 16), ("c2", 4096, 4096, 8, 64), ("c4", 2048, 8192, 3, 10),
-                                           ("c1", 500, 100, 2, 7), ("c4", 512, 777, 5, 1)])
+                                           ("c1", 500, 100, 2, 7), ("c4", 512, 777, 5, 1),
+                                           # launch shapes of the worker pass with 3, 5, 6 and 8 rows per workgroup
+                                           # (chosen so that no CU holds more rows than it must on 256 CUs)
+                                           ("c4", 4096, 2048, 8, 64), ("c4", 4096, 2048, 16, 64),
+                                           ("c2", 4096, 2048, 16, 96), ("c2", 4096, 2048, 16, 128)])
 @pytest.mark.parametrize("cached", [True, False])
 def test_worker_vr_gradient(name, n, d, N, B, cached):
     import torch
