@@ -72,7 +72,7 @@ __device__ __forceinline__ float group_sum(float v) {
   return row16_sum(v);
 }
 
-constexpr int kFullThreads = 1024;  // snapshot pass: threads per workgroup
+constexpr int kFullThreads = 512;  // snapshot pass: threads per workgroup
 
 struct RowExtent {
   int32_t lo, hi;
@@ -112,9 +112,11 @@ struct RowRecord {
 };
 
 // Snapshot pass.  Workgroup b takes rows [b*rows_per_wg, ...); group g of it every kFullGroups-th row.
-// Built to keep many rows in flight: 1024 threads (64 row groups) share one LDS head, two such workgroups
+// Built to keep many rows in flight: 512 threads (32 row groups) share one LDS head, two such workgroups
 // fit a CU, the first 64 pairs of a row (most rows have no more) are requested one row ahead and the extent
-// of a row two rows ahead.
+// of a row two rows ahead.  (1024 threads per workgroup: with the registers the rotation below needs a CU held one
+// such workgroup at a time, and sixteen wavefronts per rotation instead of eight: 297 against 280 us for the pass
+// on n = d = 2^20.)
 // The head columns' LDS accumulation is made independent of scheduling by a fixed rotation: a wavefront keeps
 // the pairs and slopes of kTurnRounds rounds of its rows in registers and adds them into the LDS accumulator only
 // when the counter `turn` reads block*NW + w (block = round / kTurnRounds, w = its index), then advances the
@@ -601,9 +603,7 @@ __global__ void zero_kernel(float4 *__restrict__ dst, int64_t n4) {
 int csr_head_columns(int64_t d) { return (int)(d < 8192 ? d : 8192); }
 
 int csr_full_grad_wgs(int64_t n) {
-  // one 1024-thread workgroup per CU: with the registers the ordered scatter needs, a CU holds one at a time, and
-  // 256 workgroups leave half the partial rows of 512 (measured: 296 against 309 us for the pass)
-  int64_t wgs = 256;
+  int64_t wgs = 512;  // two resident 512-thread workgroups per CU (256: 305 us, 768: 345 us, 1024: 294 us against 280 us)
   const int64_t by_rows = (n + 63) / 64;
   if (wgs > by_rows) wgs = by_rows;
   if (wgs >= 32) wgs = wgs / 16 * 16;
