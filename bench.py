@@ -370,9 +370,10 @@ def run_workload(name, steps, warmup, args, achievable):
                                            "what": "1 GiB device-to-device copy on this machine, read + write",
                                            "frac_of_it": kd["achieved"] / achievable["achieved_GBps"]}
     if dom == "vr_rows" and kd["bound"] == "hbm" and kd["avg_us"] < 20:
-        roofline["note"] = ("one launch moves only %.1f MB, so it is bound by launch and dependency latency, not by "
-                            "HBM; the HBM-bound kernel of the step is the snapshot pass (kernels.full_rows)"
-                            % (kd["algorithmic_bytes"] / 1e6))
+        roofline["note"] = ("one launch moves only %.1f MB: it is bound by launch and dependency latency and by the "
+                            "rows the busiest compute unit has to pull (its workgroups are sized so that this number "
+                            "is as small as the batch allows), not by the chip's HBM; the HBM-bound kernel of the "
+                            "step is the snapshot pass (kernels.full_rows)" % (kd["algorithmic_bytes"] / 1e6))
     t_full_ms = (prof["full_rows"][0] + prof["full_fold"][0]) / max(1, prof["full_rows"][1])
     rec = {
         "value": iters_per_sec,
