@@ -441,6 +441,7 @@ constexpr int kRowGroups = (kSparseThreads - 64 * kScatterWaves) / kGroup;  // r
 
 template <bool CACHED, bool SPARSE>
 __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs a) {
+  touch_kernel_arguments<(int)(sizeof(CsrArgs))>();
   extern __shared__ float head_acc[];  // SPARSE: a.head floats
   __shared__ RowRecord rec[2][kRowGroups];
   __shared__ int2 stage[2][kRowGroups][64];  // a row's first 64 (column, coef * value) pairs

@@ -95,6 +95,7 @@ __device__ __forceinline__ void store_chunk(float *p, const Chunk<VEC> &c) {
 // snapshot margins.  MODE 2: worker pass that recomputes the snapshot margins (two dot products).
 template <int VEC, int K, int T, int R, int MODE>
 __global__ __launch_bounds__(T) void dense_rows_kernel(DenseArgs a) {
+  touch_kernel_arguments<(int)(sizeof(DenseArgs))>();
   constexpr int NW = T / 64;
   constexpr int NDOT = (MODE == 2) ? 2 : 1;
   __shared__ float red[2][NW][R * NDOT];

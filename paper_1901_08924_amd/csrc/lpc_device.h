@@ -49,6 +49,21 @@ __device__ __forceinline__ int64_t sample_row(const StreamKey &k, uint32_t tag, 
   return (int64_t)(((uint64_t)stream_word(k, tag, worker, pos) * (uint64_t)n) >> 32);
 }
 
+// Requests every 64-byte line of the kernel's argument block with one burst of scalar loads and waits for them
+// once.  A kernel whose arguments are a large structure otherwise fetches its fields where it first needs them: the
+// compiler places those scalar loads block by block, each first touch of a line is a round trip to memory (the
+// host wrote the block, so no cache holds it), and a latency-bound kernel starts with several of them in a row.
+// BYTES = size of the argument block (the kernel's parameters in declaration order).
+template <int BYTES>
+__device__ __forceinline__ void touch_kernel_arguments() {
+  typedef const uint32_t __attribute__((address_space(4))) *KernargWords;
+  KernargWords ka = (KernargWords)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t seen = 0;
+#pragma unroll
+  for (int k = 0; k < (BYTES + 63) / 64; ++k) seen |= ka[k * 16 < BYTES / 4 ? k * 16 : BYTES / 4 - 1];
+  asm volatile("" ::"s"(seen));
+}
+
 // ---- wavefront (64 lanes) reductions: every lane ends with the same bits ----
 // Lanes exchange values with data-parallel-primitive moves inside their row of 16 (no trip through the
 // LDS crossbar): after xor-1, xor-2, half-mirror and mirror steps every lane of a row holds the row's

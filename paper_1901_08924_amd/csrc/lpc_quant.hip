@@ -90,6 +90,7 @@ __device__ inline void publish_stats(const StatSinks &sk, int32_t vec, int32_t s
 // one wavefront per vector: fold its partials, store the statistics and the quantizer parameters
 __global__ __launch_bounds__(64) void finalize_stats_kernel(StatSinks sk, QuantSpec qs, int32_t vec_begin,
                                                             int32_t nslots, int64_t d) {
+  touch_kernel_arguments<(int)(sizeof(StatSinks) + sizeof(QuantSpec) + 16)>();
   const int32_t rel = blockIdx.x, vec = vec_begin + rel;
   double a, s, s2, b;
   fold_stat_slots(sk.stat_part + (int64_t)vec * sk.stat_slots * 4, nslots, threadIdx.x, a, s, s2, b);
@@ -115,6 +116,7 @@ __global__ __launch_bounds__(64 * NWF) void reduce_parts_kernel(const float *__r
                                                                 int64_t d, int64_t d_pad, float scale,
                                                                 float *__restrict__ out, int64_t ld_out,
                                                                 int32_t vec_begin, int32_t want_stats, StatSinks sk) {
+  touch_kernel_arguments<(int)(64 + sizeof(StatSinks))>();
   __shared__ float red[NWF][64];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int32_t vec = blockIdx.y;
@@ -645,6 +647,7 @@ __global__ __launch_bounds__(kQuarterThreads) void dequantize_quarter_kernel(con
                                                                            const float *__restrict__ delta,
                                                                            int32_t N, int64_t d, int64_t d_pad,
                                                                            float *__restrict__ u_avg, ProxArgs pa) {
+  touch_kernel_arguments<(int)(56 + sizeof(ProxArgs))>();
   static_assert(32 % (8 * B) == 0, "eight codes in one word");
   const int64_t q = (int64_t)blockIdx.x * kQuarterThreads + threadIdx.x;
   const int64_t j = q * 8;
@@ -823,6 +826,7 @@ __device__ __forceinline__ int32_t compact_marked_planes(uint32_t *bm0, uint32_t
 // of the worker pass (fixed order, one float4 per thread, coalesced) into U; in the others every wavefront
 // visits the marked ones of its kWaveSegs tail segments.
 __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, StatSinks sk) {
+  touch_kernel_arguments<(int)(sizeof(SparseArgs) + sizeof(StatSinks))>();
   __shared__ double red[4][4];
   __shared__ int32_t list[4][kWaveSegs];
   __shared__ uint32_t masks[4][kWaveSegs];
@@ -936,6 +940,7 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
                                                                    int32_t nslots, int64_t d, StreamKey key,
                                                                    int32_t share, uint32_t *__restrict__ packed,
                                                                    float *__restrict__ delta_out) {
+  touch_kernel_arguments<(int)(sizeof(SparseArgs) + sizeof(StatSinks) + sizeof(QuantSpec) + 48)>();
   __shared__ int32_t codes[4][32][32];  // per wavefront: 32 segments x 32 codes
   __shared__ int32_t lists[4][kWaveSegs];
   __shared__ QParams q_sh;
@@ -1109,6 +1114,7 @@ __device__ __forceinline__ void warm_next_rows(const FusedArgs &a, int ntiles) {
 }
 
 __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs a) {
+  touch_kernel_arguments<(int)(sizeof(FusedArgs))>();
   constexpr int GROUPS = kFusedThreads / 32, NW = kFusedThreads / 64;  // 32-lane groups (a worker each per round), wavefronts
   __shared__ QParams qp[kFusedMaxN];
   __shared__ int32_t codes[kFusedMaxN][kFusedCoords];
