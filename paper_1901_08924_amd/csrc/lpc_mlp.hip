@@ -82,6 +82,7 @@ struct LastArgs {
 
 template <int R>
 __global__ __launch_bounds__(64 * kLastRows / R) void last_layer_kernel(LastArgs g) {
+  touch_kernel_arguments<(int)(sizeof(LastArgs))>();
   constexpr int kThreadsLast = 64 * kLastRows / R;
   extern __shared__ float Wt[];  // [C][K + 4], then bias [C]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

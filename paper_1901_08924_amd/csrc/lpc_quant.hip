@@ -413,6 +413,7 @@ __global__ __launch_bounds__(kThreads) void quantize_word_kernel(const float *__
                                                                  uint32_t *__restrict__ packed, int64_t W,
                                                                  float *__restrict__ delta_out,
                                                                  uint32_t *__restrict__ n_clipped) {
+  touch_kernel_arguments<(int)(80)>();
   static_assert(B == 2 || B == 4 || B == 8, "a word holds whole groups of four codes");
   constexpr int kCoords = 32 / B;  // coordinates per word
   constexpr int kBlocks = kCoords / 4;
