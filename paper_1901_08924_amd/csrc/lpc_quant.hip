@@ -892,13 +892,26 @@ __global__ __launch_bounds__(kThreads) void sparse_stats_kernel(SparseArgs a, St
         }
       }
       if (__ballot(rest_any != 0u) != 0ull) {
-        for (int32_t p = 1; p < a.parts; ++p) {
+        // every further plane's copy is requested before the first is added (one trip to memory, not one per plane:
+        // the segments of the frequent low columns lie in most planes); the additions keep plane order
+        float4 t[kMaxPlanes - 1][4];
+#pragma unroll
+        for (int p = 1; p < kMaxPlanes; ++p) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const uint32_t rest = mk[q] & (mk[q] - 1u);
-            if ((rest >> p) & 1u) {
-              const float4 t = *reinterpret_cast<const float4 *>(pl + (int64_t)(p - 1) * a.d_pad + at[q]);
-              v[q].x += t.x; v[q].y += t.y; v[q].z += t.z; v[q].w += t.w;
+            t[p - 1][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p < a.parts && ((rest >> p) & 1u))
+              t[p - 1][q] = *reinterpret_cast<const float4 *>(pl + (int64_t)(p - 1) * a.d_pad + at[q]);
+          }
+        }
+#pragma unroll
+        for (int p = 1; p < kMaxPlanes; ++p) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint32_t rest = mk[q] & (mk[q] - 1u);
+            if (p < a.parts && ((rest >> p) & 1u)) {
+              v[q].x += t[p - 1][q].x; v[q].y += t[p - 1][q].y; v[q].z += t[p - 1][q].z; v[q].w += t[p - 1][q].w;
             }
           }
         }
