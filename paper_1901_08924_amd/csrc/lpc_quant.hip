@@ -967,16 +967,16 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
   uint32_t *out = packed + (int64_t)worker * a.W;
   int32_t *list = lists[wv];
   int32_t n = 0;
-  float4 v[4];
+  float4 v[4], vn[4];
   // a batch = up to 32 listed segments of this wavefront: slot 8q + sub for q < 4; the tail's are zeroed as read
-  auto load_batch = [&](int32_t i0) {
+  auto load_batch = [&](int32_t i0, float4 (&dst)[4]) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int32_t i = i0 + 8 * q + sub;
-      v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+      dst[q] = make_float4(0.f, 0.f, 0.f, 0.f);
       if (i < n) {
         float *u = urow + (int64_t)list[i] * kSegFloats + part * 4;
-        v[q] = *reinterpret_cast<const float4 *>(u);
+        dst[q] = *reinterpret_cast<const float4 *>(u);
         *reinterpret_cast<float4 *>(u) = make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
@@ -990,7 +990,7 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
     n = compact_marked(a.touched + (int64_t)worker * a.bitmap_words, a.bitmap_words, first_word, stride,
                                     a.d_pad / kSegFloats, lane, list);
     __builtin_amdgcn_wave_barrier();
-    load_batch(0);  // on its way while the statistics are folded
+    load_batch(0, v);  // on its way while the statistics are folded
   }
   if (tid < 64) {
     double amax, sum, sumsq, bad;
@@ -1028,7 +1028,7 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
     for (int t = lane; t < 8 * B; t += 64) out[seg0 * B + t] = assemble_word<B>(codes[wv][t / B], t % B);
   } else {
     for (int32_t i0 = 0; i0 < n; i0 += 32) {
-      if (i0 > 0) load_batch(i0);
+      if (i0 + 32 < n) load_batch(i0 + 32, vn);  // the next batch is on its way while this one is quantized
 #pragma unroll
       for (int qi = 0; qi < 4; ++qi) {
         const int32_t i = i0 + 8 * qi + sub;
@@ -1045,6 +1045,8 @@ __global__ __launch_bounds__(kThreads) void sparse_quantize_kernel(SparseArgs a,
         out[(int64_t)list[i0 + sl] * B + w] = assemble_word<B>(codes[wv][sl], w);
       }
       __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = vn[q];
     }
   }
 }
