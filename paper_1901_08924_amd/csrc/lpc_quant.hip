@@ -1219,20 +1219,24 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
 #pragma unroll
       for (int q = 0; q < 4; ++q) { am[q] = fmax(am[q], lo[q].x); s[q] += lo[q].y; s2[q] += hi[q].x; b[q] += hi[q].y; }
     }
+    // every lane ends with the four vectors' statistics; lane q then derives the quantizer's parameters of vector q
+    // of this wavefront, so the (double-precision) derivation runs once for the four and not once after another
+    double am_m = 0.0, s_m = 0.0, s2_m = 0.0, b_m = 0.0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int32_t i = i0 + NW * q;
-      if (i >= a.N) break;  // uniform over the wavefront
+      if (i0 + NW * q >= a.N) break;  // uniform over the wavefront
       const double am_w = wave_max(am[q]), s_w = wave_sum(s[q]), s2_w = wave_sum(s2[q]), b_w = wave_sum(b[q]);
-      if (lane == 0) {
-        const QParams q_i = make_qparams(a.qs, am_w, s_w, s2_w, a.d);
-        qp[i] = q_i;
-        if (blockIdx.x == 0) {  // tile 0's writer
-          a.delta_out[i] = q_i.delta;
-          double *o = a.stats + (int64_t)i * 4;
-          o[0] = am_w; o[1] = s_w; o[2] = s2_w; o[3] = b_w;
-          if (b_w > 0.0) atomicOr(&a.flags[0], 1u);
-        }
+      if (lane == q) { am_m = am_w; s_m = s_w; s2_m = s2_w; b_m = b_w; }
+    }
+    if (lane < 4 && i0 + NW * lane < a.N) {
+      const int32_t i = i0 + NW * lane;
+      const QParams q_i = make_qparams(a.qs, am_m, s_m, s2_m, a.d);
+      qp[i] = q_i;
+      if (blockIdx.x == 0) {  // tile 0's writer
+        a.delta_out[i] = q_i.delta;
+        double *o = a.stats + (int64_t)i * 4;
+        o[0] = am_m; o[1] = s_m; o[2] = s2_m; o[3] = b_m;
+        if (b_m > 0.0) atomicOr(&a.flags[0], 1u);
       }
     }
   }
@@ -1281,19 +1285,22 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
     }
   }
   __syncthreads();
-  // pack: one thread per output word of the tile
-  {
+  // pack: one thread per output word of the tile.  The wavefronts past the first two take the words, so that they
+  // run beside the update below (threads 0-127) and not ahead of it on the same threads; index / bits is taken with
+  // a 16.16 reciprocal (exact below 4096; the indices here stay below 1024).
+  if (tid >= kFusedCoords) {
     const int32_t bits = a.bits;
     const uint32_t mask = (1u << bits) - 1u;
+    const uint32_t inv = (65536u + (uint32_t)bits - 1u) / (uint32_t)bits;
     const int32_t words_per_worker = 4 * bits;
     const int64_t seg0 = tile0 / kSegFloats;
-    for (int32_t idx = tid; idx < a.N * words_per_worker; idx += kFusedThreads) {
-      const int32_t i = idx / words_per_worker, rem = idx % words_per_worker;
-      const int32_t sgm = rem / bits, wd = rem % bits;
+    for (int32_t idx = tid - kFusedCoords; idx < a.N * words_per_worker; idx += kFusedThreads - kFusedCoords) {
+      const int32_t i = (int32_t)((((uint32_t)idx >> 2) * inv) >> 16), rem = idx - i * words_per_worker;
+      const int32_t sgm = (int32_t)(((uint32_t)rem * inv) >> 16), wd = rem - sgm * bits;
       if ((seg0 + sgm) * kSegFloats >= a.d_pad || !writer) continue;
       const int32_t bit0 = 32 * wd;
       uint32_t word = 0u;
-      for (int32_t c = bit0 / bits; c < 32 && c * bits < bit0 + 32; ++c) {
+      for (int32_t c = (int32_t)(((uint32_t)bit0 * inv) >> 16); c < 32 && c * bits < bit0 + 32; ++c) {
         const uint32_t field = (uint32_t)codes[i][32 * sgm + c] & mask;
         const int32_t sh = c * bits - bit0;
         word |= sh >= 0 ? (field << sh) : (field >> (-sh));
@@ -1307,7 +1314,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_exchange_kernel(FusedArgs
     float next = 0.0f;
     if (j < a.d) {
       float acc = 0.0f;
-      for (int32_t i = 0; i < a.N; ++i) acc = __builtin_fmaf(qp[i].delta, (float)codes[i][tid], acc);
+      for (int32_t i0 = 0; i0 < a.N; i0 += 8) {  // eight workers' operands are read from LDS before the first is used
+        float dl[8];
+        int32_t cd[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int32_t i = i0 + k < a.N ? i0 + k : a.N - 1;
+          dl[k] = qp[i].delta;
+          cd[k] = codes[i][tid];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (i0 + k < a.N) acc = __builtin_fmaf(dl[k], (float)cd[k], acc);
+      }
       const float avg = acc * (1.0f / (float)a.N);
       if (a.u_avg_out && writer) a.u_avg_out[j] = avg;
       if (a.do_prox) {
