@@ -165,7 +165,7 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     c->part_floats = (size_t)c->full_grad_wgs * csr_head_columns(c->d);
     // u^i (and the shared batch's difference of Alg. 2) stays sparse when a batch touches a small part of the
     // d columns (about B*nnz/n entries against d coordinates)
-    c->sparse_head = csr_head_columns(c->d);
+    c->sparse_head = csr_sparse_head_columns(c->d);
     c->bitmap_words = (c->d_pad / 32 + 31) / 32;
     const double touched = (double)cfg->B * (double)p->nnz / (double)p->n;
     c->csr_sparse = c->quant && cfg->N <= 64 &&

@@ -442,7 +442,7 @@ constexpr int kRowGroups = (kSparseThreads - 64 * kScatterWaves) / kGroup;  // r
 template <bool CACHED, bool SPARSE>
 __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs a) {
   touch_kernel_arguments<(int)(sizeof(CsrArgs))>();
-  extern __shared__ float head_acc[];  // SPARSE: a.head floats
+  extern __shared__ __align__(16) float head_acc[];  // SPARSE: a.head floats
   __shared__ RowRecord rec[2][kRowGroups];
   __shared__ int2 stage[2][kRowGroups][64];  // a row's first 64 (column, coef * value) pairs
   const int tid = threadIdx.x, gl = tid & (kGroup - 1), lane = tid & 63, wv = tid >> 6;
@@ -451,10 +451,15 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
   const int32_t pos1 = pos0 + a.rows_per_part < a.B ? pos0 + a.rows_per_part : a.B;
   const uint32_t worker = (a.tag == kTagShared) ? kSharedWorkerField : (uint32_t)(a.worker_begin + wrel);
   const int32_t rounds = (pos1 - pos0 + kRowGroups - 1) / kRowGroups;
-  if (SPARSE) {
-    for (int32_t j = tid; j < a.head; j += kSparseThreads) head_acc[j] = 0.0f;
-    __syncthreads();
-  }
+  // SPARSE: the head accumulator starts at zero (a.head is a multiple of 4096); the row wavefronts clear their share
+  // behind their first requests
+  auto clear_head = [&]() {
+    if (SPARSE) {
+      for (int32_t j = tid * 4; j < a.head; j += kSparseThreads * 4)
+        *reinterpret_cast<float4 *>(head_acc + j) = make_float4(0.f, 0.f, 0.f, 0.f);
+      __syncthreads();
+    }
+  };
   if (wv >= kScatterWaves) {
     // ---- row wavefronts ------------------------------------------------------------------------------------
     const int grp = (tid - 64 * kScatterWaves) / kGroup;
@@ -482,6 +487,7 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
     int32_t c[4];
     float v[4];
     fetch_pairs(cur, c, v);
+    clear_head();
     for (int32_t round = 0; round < rounds; ++round) {
       // this row's gathers first, then the requests for the rounds ahead stay in flight behind them
       float wv4[4], wsv[4];
@@ -527,6 +533,7 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
     if (SPARSE && part > 0) u = a.planes + ((int64_t)wrel * (a.parts - 1) + (part - 1)) * a.d_pad;
     uint32_t *bm = SPARSE ? a.touched + (int64_t)wrel * a.bitmap_words : nullptr;
     if (SPARSE && part > 0) bm = a.touched_parts + ((int64_t)wrel * (a.parts - 1) + (part - 1)) * a.bitmap_words;
+    clear_head();
     for (int32_t round = 0; round < rounds; ++round) {
       __syncthreads();  // barrier `round`
       // rows in batch-position order, eight staged rows read at a time; `mine` selects this wavefront's columns
@@ -566,7 +573,8 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
   if (SPARSE) {
     __syncthreads();
     float *dst = a.part + (int64_t)blockIdx.x * a.head;
-    for (int32_t j = tid; j < a.head; j += kSparseThreads) dst[j] = head_acc[j];
+    for (int32_t j = tid * 4; j < a.head; j += kSparseThreads * 4)
+      *reinterpret_cast<float4 *>(dst + j) = *reinterpret_cast<const float4 *>(head_acc + j);
   }
 }
 
@@ -738,6 +746,15 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 // (measured on n = d = 2^20, N = 16, B = 256: two rounds per workgroup, hence three planes per worker instead of
 // five, make this pass 7 us slower and the statistics pass 3.4 us faster)
 int csr_sparse_parts(int32_t B) { return (B + kRowGroups - 1) / kRowGroups; }
+
+// Leading columns the sparse inner iteration treats densely.  Twice the snapshot pass's head when d is large: the
+// bitmap words right behind an 8192-column head are nearly full in every iteration, and the wavefronts of the
+// statistics pass and of the quantizer that own them then need a second step of 32 segments, which sets the
+// length of both launches.
+int csr_sparse_head_columns(int64_t d) {
+  const int h = csr_head_columns(d);
+  return d >= 16 * (int64_t)h ? 2 * h : h;
+}
 
 hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, bool plus_shared, hipStream_t st) {
   CsrArgs a{};

@@ -260,6 +260,7 @@ hipError_t build_csc_tail(lpc_ctx *c, hipStream_t st);
 hipError_t launch_csr_full_grad(const lpc_ctx *c, const float *w, float *mu, float *z, bool want_loss, int64_t n_rows,
                                 hipStream_t st);
 int csr_sparse_parts(int32_t B);
+int csr_sparse_head_columns(int64_t d);
 // plus_shared: every iteration's plan holds one more vector, the shared batch J of Alg. 2 (N+1 vectors of B rows)
 hipError_t launch_csr_plan(const lpc_ctx *c, const float *z_snap, StreamKey key0, bool plus_shared, hipStream_t st);
 hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w_snap, const float *z_snap,
