@@ -429,22 +429,43 @@ __global__ void csr_tail_kernel(const float *__restrict__ tail, float scale, int
 // positions of one worker: wavefronts 0 and 1 scatter, the kRowGroups groups of the others take the rows.
 //   SPARSE = false: one workgroup per worker; u^i is the worker's zeroed row of U; the two scatter wavefronts
 //     split the columns by parity.
-//   SPARSE = true:  u^i stays sparse, and a worker's batch is cut into `parts` workgroups.  Head columns
-//     accumulate in LDS (scatter wavefront 0) and leave as the workgroup's head row (a.part); a tail column
+//   SPARSE = true:  u^i stays sparse, and a worker's batch is cut into `parts` workgroups of one round each.  Head
+//     columns accumulate in LDS (scatter wavefront 0) and leave as the workgroup's head row (a.part); a tail column
 //     (scatter wavefront 1) is added to the workgroup's own plane of the worker's tail -- plane 0 is the worker's
 //     row of U, plane p > 0 lies in a.planes -- which is all zero outside the segments touched in this
 //     iteration, and its 32-coordinate segment is marked in the worker's bitmap.  The statistics pass adds head
 //     rows and planes in workgroup order, so the result is one fixed sum whatever the timing.
+//     A scatter wavefront pays per instruction, not per active lane, and a row has only about six tail entries: the
+//     row groups count their tail entries, take their offsets from the counts of the rows before them, and write
+//     one dense list in batch-position order, which the tail wavefront applies 64 entries at a time.  Two entries
+//     of one instruction must not meet in one accumulator (the order of the two additions would be open): every
+//     lane enters its list position into a small hash table with an atomic minimum on the accumulator's slot, the
+//     lanes that find their own position there add and clear the slot, the others try again -- so entries of one
+//     accumulator are added in list order, one instruction apart.  (The head entries stay row by row: such a list
+//     of them, with the table's LDS round trips for every 64 entries, made the launch 3 us longer.)
 constexpr int kSparseThreads = 1024;
 constexpr int kScatterWaves = 2;
 constexpr int kRowGroups = (kSparseThreads - 64 * kScatterWaves) / kGroup;  // rows per round: 56
+// SPARSE: the kHotCols leading columns take almost half of all entries, and LDS float atomics run at about three
+// cycles per lane, which would set the length of the scatter.  A row group leaves its values for these columns in a
+// dense row of `hot` instead (plain stores), and one wavefront sums the rows' copies in batch-position order.
+constexpr int kHotCols = 64;
+constexpr int kPairCap = kRowGroups * 64;  // SPARSE: room for the list of tail entries
+constexpr int kHashSlots = 2048;
 
 template <bool CACHED, bool SPARSE>
 __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs a) {
   touch_kernel_arguments<(int)(sizeof(CsrArgs))>();
   extern __shared__ __align__(16) float head_acc[];  // SPARSE: a.head floats
-  __shared__ RowRecord rec[2][kRowGroups];
-  __shared__ int2 stage[2][kRowGroups][64];  // a row's first 64 (column, coef * value) pairs
+  __shared__ RowRecord rec[SPARSE ? 1 : 2][kRowGroups];
+  // a row's first 64 (column, coef * value) pairs, double-buffered over the rounds unless SPARSE (one round per
+  // workgroup); SPARSE: column -1 where the pair went to `hot` or to the list of tail entries
+  __shared__ int2 stage[SPARSE ? 1 : 2][kRowGroups][64];
+  __shared__ int2 tail_list[SPARSE ? kPairCap : 1];
+  __shared__ float hot[SPARSE ? kRowGroups : 1][kHotCols];
+  __shared__ int32_t cnt[SPARSE ? kRowGroups : 1];  // a row's tail entries among its first 64
+  __shared__ uint32_t hsh[SPARSE ? kHashSlots : 1];
+  float hot_sum = 0.0f;
   const int tid = threadIdx.x, gl = tid & (kGroup - 1), lane = tid & 63, wv = tid >> 6;
   const int32_t wrel = blockIdx.x / a.parts, part = blockIdx.x % a.parts;
   const int32_t pos0 = part * a.rows_per_part;
@@ -457,6 +478,7 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
     if (SPARSE) {
       for (int32_t j = tid * 4; j < a.head; j += kSparseThreads * 4)
         *reinterpret_cast<float4 *>(head_acc + j) = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int32_t j = tid; j < kHashSlots; j += kSparseThreads) hsh[j] = 0xffffffffu;  // free
       __syncthreads();
     }
   };
@@ -518,11 +540,45 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
       const float z = group_sum(s);
       const float zs = CACHED ? cur.z : group_sum(s2);
       const float coef = (loss_slope(a.loss, z, cur.y) - loss_slope(a.loss, zs, cur.y)) * a.scale;
+      if constexpr (SPARSE) {
+        // class of each of the row's first 64 entries: 3 hot, 1 other head, 2 tail, 0 past the row's end
+        const int32_t len = cur.hi - cur.lo;
+        *reinterpret_cast<float4 *>(&hot[grp][gl * 4]) = make_float4(0.f, 0.f, 0.f, 0.f);  // kHotCols = 4 * kGroup
+        const int sh = lane & 48;  // this group's first lane in the wavefront
+        int32_t cls[4], rt[4], nt = 0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        stage[round & 1][grp][q * kGroup + gl] = make_int2(c[q], __float_as_int(coef * v[q]));
-      if (gl == 0) rec[round & 1][grp] = RowRecord{cur.lo, cur.hi - cur.lo, coef};
-      __syncthreads();  // barrier `round`: the round's records and staged pairs are complete
+        for (int q = 0; q < 4; ++q) {
+          cls[q] = q * kGroup + gl >= len ? 0 : c[q] < kHotCols ? 3 : c[q] < a.head ? 1 : 2;
+          if (cls[q] == 3) hot[grp][c[q]] = coef * v[q];
+          stage[0][grp][q * kGroup + gl] = make_int2(cls[q] == 1 ? c[q] : -1, __float_as_int(coef * v[q]));
+          const uint32_t gt = (uint32_t)(__ballot(cls[q] == 2) >> sh) & 0xffffu;
+          rt[q] = nt + __popc(gt & ((1u << gl) - 1u)); nt += __popc(gt);
+        }
+        if (gl == 0) {
+          cnt[grp] = nt;
+          rec[0][grp] = RowRecord{cur.lo, len, coef};
+        }
+        __syncthreads();  // the rows' counts and staged head pairs are complete
+        int32_t bt = 0;
+        for (int k = gl; k < grp; k += kGroup) bt += cnt[k];
+        bt = row16_sum(bt);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (cls[q] == 2) tail_list[bt + rt[q]] = make_int2(c[q], __float_as_int(coef * v[q]));
+        __syncthreads();  // the list of tail entries is complete
+        if (wv == kScatterWaves) {  // first row wavefront: lane c sums hot column c over the rows, in order
+          float acc = 0.0f;
+#pragma unroll 8
+          for (int r = 0; r < kRowGroups; ++r) acc += hot[r][lane];
+          hot_sum = acc;
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          stage[round & 1][grp][q * kGroup + gl] = make_int2(c[q], __float_as_int(coef * v[q]));
+        if (gl == 0) rec[round & 1][grp] = RowRecord{cur.lo, cur.hi - cur.lo, coef};
+        __syncthreads();  // barrier `round`: the round's records and staged pairs are complete
+      }
       cur = nxt; nxt = nxt2;
 #pragma unroll
       for (int q = 0; q < 4; ++q) { c[q] = cn[q]; v[q] = vn[q]; }
@@ -535,9 +591,74 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
     if (SPARSE && part > 0) bm = a.touched_parts + ((int64_t)wrel * (a.parts - 1) + (part - 1)) * a.bitmap_words;
     clear_head();
     for (int32_t round = 0; round < rounds; ++round) {
-      __syncthreads();  // barrier `round`
-      // rows in batch-position order, eight staged rows read at a time; `mine` selects this wavefront's columns
-      auto walk = [&](auto mine, auto add) {
+      if constexpr (SPARSE) {
+        __syncthreads();  // the rows' counts and staged head pairs are complete
+        __syncthreads();  // the list of tail entries is complete
+        if (wv == 0) {
+          // head: rows in batch-position order, eight staged rows at a time, the next eight requested ahead
+          const uint64_t long_rows = __ballot((lane < kRowGroups ? rec[0][lane].len : 0) > 64);
+          static_assert(kRowGroups % 8 == 0, "the walk takes eight rows at a time");
+          int2 t[8], tn[8];
+#pragma unroll
+          for (int q = 0; q < 8; ++q) t[q] = stage[0][q][lane];
+          for (int32_t row0 = 0; row0 < kRowGroups; row0 += 8) {
+            if (row0 + 8 < kRowGroups) {
+#pragma unroll
+              for (int q = 0; q < 8; ++q) tn[q] = stage[0][row0 + 8 + q][lane];
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              if (t[q].x >= 0) atomicAdd(&head_acc[t[q].x], __int_as_float(t[q].y));
+              if ((long_rows >> (row0 + q)) & 1ull) {  // uniform and rare: the rest of a long row comes from memory
+                const RowRecord m = rec[0][row0 + q];
+                for (int32_t k = 64 + lane; k < m.len; k += 64) {
+                  const int32_t col = a.col_idx[m.lo + k];
+                  if (col < a.head) atomicAdd(&head_acc[col], m.coef * a.vals[m.lo + k]);
+                }
+              }
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t[q] = tn[q];
+          }
+        } else {
+          const int32_t total = (int32_t)wave_sum((uint32_t)(lane < kRowGroups ? cnt[lane] : 0));
+          uint64_t long_rows = __ballot((lane < kRowGroups ? rec[0][lane].len : 0) > 64);
+          auto add = [&](int32_t col, float g) {
+            atomicAdd(&u[col], g);
+            atomicOr(&bm[col >> 10], 1u << ((col >> 5) & 31));
+          };
+          for (int32_t i0 = 0; i0 < total; i0 += 64) {
+            const int32_t idx = i0 + lane;
+            bool pending = idx < total;
+            const int2 pr = pending ? tail_list[idx] : make_int2(0, 0);
+            const uint32_t slot = ((uint32_t)pr.x ^ ((uint32_t)pr.x >> 11)) & (kHashSlots - 1);
+            while (__ballot(pending) != 0ull) {  // uniform; every turn retires at least the smallest pending position
+              if (pending) atomicMin(&hsh[slot], (uint32_t)idx);
+              __builtin_amdgcn_wave_barrier();
+              const bool won =
+                  pending && __hip_atomic_load(&hsh[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT) == (uint32_t)idx;
+              __builtin_amdgcn_wave_barrier();
+              if (won) {
+                add(pr.x, __int_as_float(pr.y));
+                __hip_atomic_store(&hsh[slot], 0xffffffffu, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                pending = false;
+              }
+              __builtin_amdgcn_wave_barrier();
+            }
+          }
+          // what rows longer than 64 entries hold past their first 64 comes from memory, after the list, row by row
+          while (long_rows != 0ull) {
+            const RowRecord m = rec[0][__builtin_ctzll(long_rows)];
+            long_rows &= long_rows - 1ull;
+            for (int32_t k = 64 + lane; k < m.len; k += 64) {
+              const int32_t col = a.col_idx[m.lo + k];
+              if (col >= a.head) add(col, m.coef * a.vals[m.lo + k]);
+            }
+          }
+        }
+      } else {
+        __syncthreads();  // barrier `round`
+        // rows in batch-position order, eight staged rows read at a time; wavefront wv takes the columns of its parity
         const int buf = round & 1;
         for (int32_t row0 = 0; row0 < kRowGroups; row0 += 8) {
           RowRecord m[8];
@@ -549,28 +670,19 @@ __global__ __launch_bounds__(kSparseThreads) void csr_vr_ordered_kernel(CsrArgs 
           }
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
-            if (lane < m[q].len && mine(t[q].x)) add(t[q].x, __int_as_float(t[q].y));
+            if (lane < m[q].len && (t[q].x & (kScatterWaves - 1)) == wv) atomicAdd(&u[t[q].x], __int_as_float(t[q].y));
             for (int32_t k = 64 + lane; k < m[q].len; k += 64) {  // the rest of a long row comes from memory
               const int32_t col = a.col_idx[m[q].lo + k];
-              if (mine(col)) add(col, m[q].coef * a.vals[m[q].lo + k]);
+              if ((col & (kScatterWaves - 1)) == wv) atomicAdd(&u[col], m[q].coef * a.vals[m[q].lo + k]);
             }
           }
         }
-      };
-      if (SPARSE && wv == 0) {
-        walk([&](int32_t col) { return col < a.head; }, [&](int32_t col, float g) { atomicAdd(&head_acc[col], g); });
-      } else if (SPARSE) {
-        walk([&](int32_t col) { return col >= a.head; }, [&](int32_t col, float g) {
-          atomicAdd(&u[col], g);
-          atomicOr(&bm[col >> 10], 1u << ((col >> 5) & 31));
-        });
-      } else {
-        walk([&](int32_t col) { return (col & (kScatterWaves - 1)) == wv; },
-             [&](int32_t col, float g) { atomicAdd(&u[col], g); });
       }
     }
   }
   if (SPARSE) {
+    __syncthreads();
+    if (wv == kScatterWaves) head_acc[lane] += hot_sum;  // behind what a long row's further entries left there
     __syncthreads();
     float *dst = a.part + (int64_t)blockIdx.x * a.head;
     for (int32_t j = tid * 4; j < a.head; j += kSparseThreads * 4)
@@ -780,7 +892,7 @@ hipError_t launch_csr_vr_sparse(const lpc_ctx *c, const float *w, const float *w
   a.key = key; a.tag = kTagBatch; a.worker_begin = 0; a.B = c->cfg.B;
   a.scale = (float)(1.0 / (double)c->cfg.B);
   a.parts = csr_sparse_parts(c->cfg.B);
-  a.rows_per_part = kRowGroups;
+  a.rows_per_part = kRowGroups;  // one round per workgroup: the kernel's `hot` rows are single-buffered
   a.planes = c->s.sparse_planes; a.touched_parts = c->s.touched_parts;
   const dim3 grid((unsigned)(nvec * a.parts));  // the rows of vector k are plan[k*B ..]
   const size_t lds = (size_t)a.head * sizeof(float);

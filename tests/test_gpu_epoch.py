@@ -152,6 +152,26 @@ def test_sparse_inner_iteration_matches_the_oracle_coordinate_by_coordinate(bits
     assert np.count_nonzero((w_o == 0) != (w_g == 0)) <= 2e-3 * sp.d
 
 
+@pytest.mark.parametrize("nnz_mean,B", [(80, 16), (160, 70)])
+def test_sparse_inner_iteration_with_long_rows_and_the_wide_head(nnz_mean, B):
+    """d >= 2^17: the sparse passes treat 16384 leading columns densely.  Rows longer than 64 entries: the worker
+    pass stages a row's first 64 pairs and takes the rest from memory (head and tail wavefronts both), B = 70 adds
+    a second workgroup per worker, hence a second tail plane.  Same agreement with the dense oracle as above."""
+    sp = lpc_synth.make("c3", n=2048, d=140_000, nnz_mean=nnz_mean, N=4, B=B)
+    rp = sp.csr[0]
+    assert (np.diff(rp) > 64).mean() > 0.1
+    hist, w_o, w_g = _run_both(sp, 2, bits=3, m=5)
+    for P_o, P_g, _ in hist:
+        assert abs(P_g - P_o) <= 1e-4 * abs(P_o)
+    scale = max(np.abs(w_o).max(), 1e-12)
+    diff = np.abs(w_g - w_o)
+    assert np.count_nonzero(w_o[:64]) > 32 and np.count_nonzero(w_o[64:16384]) > 1000
+    assert np.count_nonzero(w_o[16384:]) > 100
+    assert (diff > 1e-5 * scale).mean() <= 2e-3
+    assert diff.max() <= 0.05 * scale
+    assert np.count_nonzero((w_o == 0) != (w_g == 0)) <= 2e-3 * sp.d
+
+
 @pytest.mark.parametrize("scheme,bits,clip_mode,clip", [(lpco.SCHEME_B, 3, 0, 1.0), (lpco.SCHEME_C, 4, 0, 0.9),
                                                          (lpco.SCHEME_B, 2, 1, 2.0)])
 def test_sparse_inner_iteration_with_a_shared_scale_factor(scheme, bits, clip_mode, clip):
