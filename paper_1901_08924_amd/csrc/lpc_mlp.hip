@@ -245,6 +245,64 @@ __global__ __launch_bounds__(256) void colsum_kernel(float *__restrict__ D0, con
   }
 }
 
+// colsum_kernel for every layer of the worker pass in one launch (all deltas exist once the backward pass is
+// through, and each of these launches is short enough to be bound by its launch): blockIdx.x runs over the
+// layers' 64-column blocks, first[l] being layer l's first.  Same arithmetic per column as colsum_kernel.
+constexpr int kColsumMaxLayers = 8;
+struct ColsumLayers {
+  float *D0[kColsumMaxLayers];
+  const float *D1[kColsumMaxLayers];
+  float *out[kColsumMaxLayers];
+  int cols[kColsumMaxLayers], first[kColsumMaxLayers + 1], sum_back[kColsumMaxLayers];
+  int n, K;
+  float alpha;
+  int64_t out_stride;
+};
+
+__global__ __launch_bounds__(256) void colsum_layers_kernel(ColsumLayers g) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  int l = 0;
+#pragma unroll
+  for (int k = 1; k < kColsumMaxLayers; ++k)
+    if (k < g.n && (int)blockIdx.x >= g.first[k]) l = k;
+  // the layer's fields, selected without indexing the argument arrays by a run-time value
+  float *D0 = g.D0[0], *out = g.out[0];
+  const float *D1 = g.D1[0];
+  int cols = g.cols[0], first = g.first[0], sum_back = g.sum_back[0];
+#pragma unroll
+  for (int k = 1; k < kColsumMaxLayers; ++k)
+    if (k == l) { D0 = g.D0[k]; D1 = g.D1[k]; out = g.out[k]; cols = g.cols[k]; first = g.first[k]; sum_back = g.sum_back[k]; }
+  const int c = ((int)blockIdx.x - first) * 64 + lane;
+  const int b = blockIdx.y, K = g.K;
+  float s = 0.0f;
+  if (c < cols) {
+    float *p0 = D0 + (int64_t)b * K * cols + c;
+    const float *p1 = D1 + (int64_t)b * K * cols + c;
+    for (int k = wv; k < K; k += 32) {  // eight rows of each set in flight per step
+      float v0[8], v1[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool ok = k + 4 * j < K;
+        v0[j] = ok ? p0[(int64_t)(k + 4 * j) * cols] : 0.0f;
+        v1[j] = ok ? p1[(int64_t)(k + 4 * j) * cols] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float t = v0[j] + v1[j];
+        s += t;
+        if (sum_back && k + 4 * j < K) p0[(int64_t)(k + 4 * j) * cols] = t;
+      }
+    }
+  }
+  red[wv][lane] = s;
+  __syncthreads();
+  if (wv == 0 && c < cols) {
+    const float t = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    out[(int64_t)b * g.out_stride + c] = g.alpha * t;
+  }
+}
+
 // out[j] (+)= alpha * (P[0][j] + P[1][j] + ... + P[nb-1][j]) for j < count, the partial vectors `stride` floats
 // apart; summed in block order.  count and the pointers are multiples of four floats / 16 bytes.
 __global__ __launch_bounds__(256) void fold_blocks_kernel(const float *__restrict__ P, int nb, int64_t stride,
@@ -540,13 +598,28 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   const int32_t vec0 = (tag == kTagShared) ? c->cfg.N : worker_begin;
   int32_t slot = 0;
   StatRange ranges{};
+  // bias: column sums of the two delta sets over the worker's rows; for the first layer, whose input rows are
+  // the same for both sets, the pass also leaves the sum of the two deltas in set 0 (one contraction below).
+  // One launch for all layers when the net has at most kColsumMaxLayers.
+  const bool biases_at_once = nn.L <= kColsumMaxLayers;
+  if (biases_at_once) {
+    ColsumLayers cl{};
+    cl.n = nn.L; cl.K = B; cl.alpha = alpha; cl.out_stride = c->d_pad;
+    int blocks = 0;
+    for (int l = 0; l < nn.L; ++l) {
+      cl.D0[l] = nn.del(l + 1, 0); cl.D1[l] = nn.del(l + 1, 1); cl.out[l] = U + c->mlp_boff[l];
+      cl.cols[l] = nn.dims[l + 1]; cl.sum_back[l] = l == 0 ? 1 : 0; cl.first[l] = blocks;
+      blocks += (nn.dims[l + 1] + 63) / 64;
+    }
+    cl.first[nn.L] = blocks;
+    hipLaunchKernelGGL(colsum_layers_kernel, dim3((unsigned)blocks, (unsigned)nw), dim3(256), 0, st, cl);
+  }
   for (int l = nn.L - 1; l >= 0; --l) {
     const int out = nn.dims[l + 1], in = nn.dims[l];
-    // bias: column sums of the two delta sets over the worker's rows; for the first layer, whose input rows are
-    // the same for both sets, the pass also leaves the sum of the two deltas in set 0 (one contraction below)
-    hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), (unsigned)nw), dim3(256), 0, st,
-                       nn.del(l + 1, 0), (const float *)nn.del(l + 1, 1), B, out, alpha, 0, U + c->mlp_boff[l],
-                       c->d_pad, l == 0 ? 1 : 0);
+    if (!biases_at_once)
+      hipLaunchKernelGGL(colsum_kernel, dim3((unsigned)((out + 63) / 64), (unsigned)nw), dim3(256), 0, st,
+                         nn.del(l + 1, 0), (const float *)nn.del(l + 1, 1), B, out, alpha, 0, U + c->mlp_boff[l],
+                         c->d_pad, l == 0 ? 1 : 0);
     GemmArgs g{};
     g.transA = 1;
     g.C = U + c->mlp_woff[l]; g.ldc = out; g.strideC = c->d_pad;
