@@ -194,7 +194,8 @@ lpc_status fill_ctx(lpc_ctx *c, const lpc_problem *p, const lpc_config *cfg) {
     // vector (and per layer computed on the vector units): small layers need more slots than d_pad/64
     int64_t need = 0;
     for (int l = 0; l < p->mlp_nlayers; ++l)
-      need += (int64_t)(c->mlp_dims[l] / 128 + 1) * (c->mlp_dims[l + 1] / 64 + 1) + 2;
+      need += (int64_t)(c->mlp_dims[l] / 128 + 1) * (c->mlp_dims[l + 1] / 64 + 1) + 2 +
+              (c->mlp_dims[l + 1] + 63) / 64 + (c->mlp_dims[l] + 63) / 64;  // + bias blocks, + a vector-unit product's
     if (need > c->stat_slots) c->stat_slots = (int32_t)need;
   }
   c->iter2_capable = fused_iter_supported(c);

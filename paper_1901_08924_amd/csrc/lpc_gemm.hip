@@ -212,10 +212,9 @@ __device__ __forceinline__ void store_tile(const GemmArgs &g, const floatx16 (&a
 // The tile's statistics: wavefront reductions, then the wavefronts in order through `red` (LDS, 4 doubles per
 // wavefront, not in use by anyone else); slot `tile` of batch item bz receives them.  Contains a barrier.
 __device__ __forceinline__ void tile_statistics(const GemmArgs &g, double *red, int tid, int64_t bz, int64_t tile,
-                                                float fmx, float ssum, float ssq, float sbad) {
+                                                float fmx, double ssum, double ssq, double sbad) {
   const int lane = tid & 63, wave = tid >> 6;
-  const double a_w = (double)wave_max(fmx), s_w = wave_sum((double)ssum), q_w = wave_sum((double)ssq),
-               b_w = wave_sum((double)sbad);
+  const double a_w = (double)wave_max(fmx), s_w = wave_sum(ssum), q_w = wave_sum(ssq), b_w = wave_sum(sbad);
   if (lane == 0) { red[wave * 4 + 0] = a_w; red[wave * 4 + 1] = s_w; red[wave * 4 + 2] = q_w; red[wave * 4 + 3] = b_w; }
   __syncthreads();
   if (tid == 0) {
@@ -430,13 +429,14 @@ __global__ __launch_bounds__(512) void gemm_mfma8_kernel(GemmArgs g) {
 constexpr int kSkinnyN = 16;
 constexpr int kSkinnyLdsFloats = 16384;  // 64 KB
 
-__device__ __forceinline__ void skinny_store(const GemmArgs &g, float *C, int64_t bz, int row, int col, float acc) {
+__device__ __forceinline__ float skinny_store(const GemmArgs &g, float *C, int64_t bz, int row, int col, float acc) {
   const int64_t off = (int64_t)row * g.ldc + col;
   float val = g.alpha * acc + (g.bias ? g.bias[bz * g.strideBias + col] : 0.0f);
   if (g.relu) val = val > 0.0f ? val : 0.0f;
   if (g.relu_mask) val = g.relu_mask[off + (C - g.C)] > 0.0f ? val : 0.0f;
   if (g.accumulate) val += C[off];
   C[off] = val;
+  return val;
 }
 
 // C = A*B, A [M][K] row-major.  A wavefront takes one row of A at a time (16 rows per workgroup): its lanes
@@ -589,6 +589,13 @@ int gemm_tiles(const GemmArgs &g) {
   return ((g.N + BN - 1) / BN) * ((g.M + BM - 1) / BM);
 }
 
+// whether launch_gemm takes gemm_skinny_tn_short_kernel, which can leave statistic partials like the matrix-core
+// kernels (g.stat_part), and how many: one per workgroup of a batch item
+bool gemm_takes_skinny_short(const GemmArgs &g) {
+  return !gemm_takes_matrix_cores(g) && g.transA && g.K <= 128;
+}
+int gemm_skinny_short_slots(const GemmArgs &g) { return (g.M + 63) / 64; }
+
 // The same product when K <= 128 (a worker's rows of one batch): every row of A and B that the workgroup needs
 // is requested before anything is consumed, one round trip instead of one per operand and parameter set.
 // Rows are taken in the order of gemm_skinny_tn_kernel, so the sums are the same to the bit.
@@ -651,13 +658,25 @@ __global__ __launch_bounds__(256) void gemm_skinny_tn_short_kernel(GemmArgs g) {
   for (int c = 0; c < kSkinnyN; ++c) red[(wave * 64 + lane) * kSkinnyN + c] = acc[c];
   __syncthreads();
   float *C = g.C + bz * g.strideC;
+  // g.stat_part: the workgroup also leaves the statistics of what it stores, as slot stat_slot0 + blockIdx.x
+  float fmx = 0.0f;
+  double ssum = 0.0, ssq = 0.0, sbad = 0.0;
   for (int i = tid; i < 64 * kSkinnyN; i += 256) {
     const int l = i >> 4, c = i & 15, row = blockIdx.x * 64 + l;
     if (row < g.M && c < g.N) {
       const float r = ((red[(0 * 64 + l) * kSkinnyN + c] + red[(1 * 64 + l) * kSkinnyN + c]) +
                        red[(2 * 64 + l) * kSkinnyN + c]) + red[(3 * 64 + l) * kSkinnyN + c];
-      skinny_store(g, C, bz, row, c, r);
+      const float val = skinny_store(g, C, bz, row, c, r);
+      if (isfinite(val)) {
+        fmx = fmaxf(fmx, fabsf(val)); ssum += (double)val; ssq += (double)val * (double)val;
+      } else {
+        sbad += 1.0;
+      }
     }
+  }
+  if (g.stat_part) {  // uniform
+    __shared__ double stat_red[16];
+    tile_statistics(g, stat_red, tid, bz, blockIdx.x, fmx, ssum, ssq, sbad);
   }
 }
 

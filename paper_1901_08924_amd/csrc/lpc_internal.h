@@ -276,7 +276,9 @@ hipError_t launch_csr_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
 // MLP instance (lpc_gemm.hip, lpc_mlp.hip)
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t st);
 bool gemm_takes_matrix_cores(const GemmArgs &g);  // false: the vector-unit path (no statistic partials)
-int gemm_tiles(const GemmArgs &g);                 // statistic partials a matrix-core launch writes per batch item
+int gemm_tiles(const GemmArgs &g);
+bool gemm_takes_skinny_short(const GemmArgs &g);
+int gemm_skinny_short_slots(const GemmArgs &g);                 // statistic partials a matrix-core launch writes per batch item
 // Rows per block of the MLP snapshot pass's reductions over rows (bias column sums, weight gradients formed on
 // the vector units): a chunk is cut into blocks that are summed side by side, one partial per block, and the
 // partials are folded by a second, small column sum; a lone launch over thousands of rows would occupy 1-16 CUs.

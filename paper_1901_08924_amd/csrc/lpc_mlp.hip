@@ -257,6 +257,11 @@ struct ColsumLayers {
   int n, K;
   float alpha;
   int64_t out_stride;
+  // not null: block x of batch item b also leaves the statistics of its 64 sums (Sec. 3.2 needs those of u^i) as
+  // slot stat_slot0 + x of the item's partials
+  double *stat_part;
+  int64_t stat_batch_stride;
+  int32_t stat_slot0;
 };
 
 __global__ __launch_bounds__(256) void colsum_layers_kernel(ColsumLayers g) {
@@ -297,9 +302,21 @@ __global__ __launch_bounds__(256) void colsum_layers_kernel(ColsumLayers g) {
   }
   red[wv][lane] = s;
   __syncthreads();
-  if (wv == 0 && c < cols) {
-    const float t = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
-    out[(int64_t)b * g.out_stride + c] = g.alpha * t;
+  if (wv == 0) {  // the whole wavefront
+    float val = 0.0f;
+    if (c < cols) {
+      val = g.alpha * (((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
+      out[(int64_t)b * g.out_stride + c] = val;
+    }
+    if (g.stat_part) {  // uniform; a lane past the layer's columns holds 0, which adds nothing
+      const bool fin = isfinite(val);
+      const double a_w = (double)wave_max(fin ? fabsf(val) : 0.0f), s_w = wave_sum(fin ? (double)val : 0.0),
+                   q_w = wave_sum(fin ? (double)val * (double)val : 0.0), b_w = wave_sum(fin ? 0.0 : 1.0);
+      if (lane == 0) {
+        double *p = g.stat_part + (int64_t)b * g.stat_batch_stride + ((int64_t)g.stat_slot0 + blockIdx.x) * 4;
+        p[0] = a_w; p[1] = s_w; p[2] = q_w; p[3] = b_w;
+      }
+    }
   }
 }
 
@@ -591,17 +608,18 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
   e = backward_data(nn, w, wstride, 2, c->s.mlp_xb, in0, c->s.mlp_yb, rows, nullptr, st);
   if (e != hipSuccess) return e;
   const float alpha = (float)(1.0 / (double)B);
-  // Statistics of u^i (Sec. 3.2 needs |u|_inf before anything can be quantized): the matrix-core products leave
-  // one partial per output tile from their epilogues, the few columns written by other kernels (biases, a
-  // last layer on the vector units) get a small reduction of their own; no extra pass over U.
-  const bool want_stats = stats_mode != kStatsNone;
-  const int32_t vec0 = (tag == kTagShared) ? c->cfg.N : worker_begin;
-  int32_t slot = 0;
-  StatRange ranges{};
+  // Statistics of u^i (Sec. 3.2 needs |u|_inf before anything can be quantized): the kernels that write u^i leave
+  // them as partials -- the matrix-core products one per output tile from their epilogues, the bias sums and the
+  // short products on the vector units one per workgroup; only what other kernels write (deep nets' biases, long
+  // products on the vector units) gets a small reduction of its own.  No extra pass over U.
   // bias: column sums of the two delta sets over the worker's rows; for the first layer, whose input rows are
   // the same for both sets, the pass also leaves the sum of the two deltas in set 0 (one contraction below).
   // One launch for all layers when the net has at most kColsumMaxLayers.
   const bool biases_at_once = nn.L <= kColsumMaxLayers;
+  const bool want_stats = stats_mode != kStatsNone;
+  const int32_t vec0 = (tag == kTagShared) ? c->cfg.N : worker_begin;
+  int32_t slot = 0;
+  StatRange ranges{};
   if (biases_at_once) {
     ColsumLayers cl{};
     cl.n = nn.L; cl.K = B; cl.alpha = alpha; cl.out_stride = c->d_pad;
@@ -612,6 +630,12 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
       blocks += (nn.dims[l + 1] + 63) / 64;
     }
     cl.first[nn.L] = blocks;
+    if (want_stats) {  // the launch leaves the statistics of the bias entries it writes
+      cl.stat_part = c->s.stat_part + (int64_t)vec0 * c->stat_slots * 4;
+      cl.stat_batch_stride = (int64_t)c->stat_slots * 4;
+      cl.stat_slot0 = slot;
+      slot += blocks;
+    }
     hipLaunchKernelGGL(colsum_layers_kernel, dim3((unsigned)blocks, (unsigned)nw), dim3(256), 0, st, cl);
   }
   for (int l = nn.L - 1; l >= 0; --l) {
@@ -637,12 +661,12 @@ hipError_t launch_mlp_vr_grad(const lpc_ctx *c, const float *w, const float *w_s
       }
     }
     if (want_stats) {
-      ranges.begin[ranges.n] = c->mlp_boff[l]; ranges.len[ranges.n] = out; ++ranges.n;
-      if (gemm_takes_matrix_cores(g)) {
+      if (!biases_at_once) { ranges.begin[ranges.n] = c->mlp_boff[l]; ranges.len[ranges.n] = out; ++ranges.n; }
+      if (gemm_takes_matrix_cores(g) || gemm_takes_skinny_short(g)) {
         g.stat_part = c->s.stat_part + (int64_t)vec0 * c->stat_slots * 4;
         g.stat_batch_stride = (int64_t)c->stat_slots * 4;
         g.stat_slot0 = slot;
-        slot += gemm_tiles(g);
+        slot += gemm_takes_matrix_cores(g) ? gemm_tiles(g) : gemm_skinny_short_slots(g);
       } else {
         ranges.begin[ranges.n] = c->mlp_woff[l]; ranges.len[ranges.n] = (int64_t)in * out; ++ranges.n;
       }
