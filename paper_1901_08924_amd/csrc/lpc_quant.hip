@@ -57,7 +57,20 @@ __device__ inline QParams qparams_from_delta(const QuantSpec &qs, float delta) {
 __device__ inline void fold_stat_slots(const double *p, int32_t nslots, int lane, double &a, double &s,
                                        double &s2, double &b) {
   a = 0.0; s = 0.0; s2 = 0.0; b = 0.0;
-  for (int32_t k = lane; k < nslots; k += 64) {
+  int32_t k = lane;
+  // many slots (the MLP has several hundred): four of a lane's slots are requested before the first is added, in
+  // the same order
+  for (; k + 192 < nslots; k += 256) {
+    double2 lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      lo[q] = *reinterpret_cast<const double2 *>(p + (k + 64 * q) * 4);
+      hi[q] = *reinterpret_cast<const double2 *>(p + (k + 64 * q) * 4 + 2);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { a = fmax(a, lo[q].x); s += lo[q].y; s2 += hi[q].x; b += hi[q].y; }
+  }
+  for (; k < nslots; k += 64) {
     const double2 lo = *reinterpret_cast<const double2 *>(p + k * 4);
     const double2 hi = *reinterpret_cast<const double2 *>(p + k * 4 + 2);
     a = fmax(a, lo.x);
