@@ -172,14 +172,15 @@ def test_sparse_inner_iteration_with_long_rows_and_the_wide_head(nnz_mean, B):
     assert np.count_nonzero((w_o == 0) != (w_g == 0)) <= 2e-3 * sp.d
 
 
-@pytest.mark.parametrize("scheme,bits,clip_mode,clip", [(lpco.SCHEME_B, 3, 0, 1.0), (lpco.SCHEME_C, 4, 0, 0.9),
-                                                         (lpco.SCHEME_B, 2, 1, 2.0)])
-def test_sparse_inner_iteration_with_a_shared_scale_factor(scheme, bits, clip_mode, clip):
+@pytest.mark.parametrize("scheme,bits,clip_mode,clip,d", [
+    (lpco.SCHEME_B, 3, 0, 1.0, 50_000), (lpco.SCHEME_C, 4, 0, 0.9, 50_000), (lpco.SCHEME_B, 2, 1, 2.0, 50_000),
+    (lpco.SCHEME_C, 3, 0, 1.0, 140_000)])                      # d >= 2^17: 16384 dense head columns
+def test_sparse_inner_iteration_with_a_shared_scale_factor(scheme, bits, clip_mode, clip, d):
     """Sec. 4.2 (b), (c) on CSR rows that touch few columns: the sparse worker, statistics and quantizer passes with
     delta = max_i delta_i, then the integer-sum receiver (eq. (5) for scheme (c)).  Coordinate-level agreement
     with the oracle as for scheme (a); the same bits run to run."""
     import torch
-    sp = lpc_synth.make("c3", n=4096, d=50_000, nnz_mean=20, N=4, B=16)
+    sp = lpc_synth.make("c3", n=4096, d=d, nnz_mean=20, N=4, B=16)
     over = dict(bits=bits, clip_mode=clip_mode, clip=clip, m=6, scheme=scheme)
     hist, w_o, w_g = _run_both(sp, 2, **over)
     for P_o, P_g, _ in hist:
@@ -196,12 +197,14 @@ def test_sparse_inner_iteration_with_a_shared_scale_factor(scheme, bits, clip_mo
 @pytest.mark.parametrize("algo,scheme,bits,clip_mode,clip,B", [
     (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, 16), (lpco.ALGO_ALPC_SC, lpco.SCHEME_A, 4, 1, 2.0, 16),
     (lpco.ALGO_ALPC_GC, lpco.SCHEME_B, 4, 0, 0.9, 16), (lpco.ALGO_ALPC_GC, lpco.SCHEME_C, 2, 0, 1.0, 16),
-    (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, 70)])        # B = 70: two workgroups (planes) per vector
+    (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, 70),         # B = 70: two workgroups (planes) per vector
+    (lpco.ALGO_ALPC_GC, lpco.SCHEME_A, 3, 0, 1.0, -70)])       # ... and d >= 2^17: 16384 dense head columns
 def test_sparse_inner_iteration_of_alpc_svrg(algo, scheme, bits, clip_mode, clip, B):
     """Alg. 2 / Alg. 3 on CSR rows that touch few columns: the workers' vectors AND the shared batch's
     full-precision difference take the sparse worker and statistics passes; coordinate-level agreement of x~, y and z
     with the oracle (up to a few flipped rounding decisions) and the same bits run to run."""
-    sp = lpc_synth.make("c3", n=4096, d=50_000, nnz_mean=20, N=4, B=B)
+    d, B = (140_000, -B) if B < 0 else (50_000, B)
+    sp = lpc_synth.make("c3", n=4096, d=d, nnz_mean=20, N=4, B=B)
     over = dict(algo=algo, scheme=scheme, bits=bits, clip_mode=clip_mode, clip=clip, m=6, tau2=0.5, L=0.25,
                 sigma=1e-3 if algo == lpco.ALGO_ALPC_SC else 0.0)
     runs = []
